@@ -1,0 +1,196 @@
+"""numpy-facing loader for the CPU oracle (``dvdq_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product package imports this module;
+only tests, the smoke check and the benchmark's CPU-baseline leg do.  The C file
+is compiled with plain gcc (-O2, OpenMP over token rows, no fast-math, no FMA
+contraction) into ``oracle/libdvdq_oracle.so`` the first time it is needed or
+when the source is newer than the library.
+
+Every wrapper below only marshals arrays; the arithmetic lives in the C file,
+where each function cites the passage of the method it restates.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dvdq_oracle.c")
+_LIB = os.path.join(_HERE, "libdvdq_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc.  Returns the library path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call([
+            "gcc", "-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
+            "-fPIC", "-shared", "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm",
+        ])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = C.CDLL(build())
+        i64, i32, vp = C.c_int64, C.c_int, C.c_void_p
+        lib.dvdq_oracle_hadamard.argtypes = [i32, vp]
+        lib.dvdq_oracle_rotate.argtypes = [vp, i64, i64, i32, vp]
+        lib.dvdq_oracle_quantize.argtypes = [vp, i64, i64, i32, vp, vp]
+        lib.dvdq_oracle_rotate_quant.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
+        lib.dvdq_oracle_unpack_w4.argtypes = [vp, i64, i64, vp]
+        lib.dvdq_oracle_pack_w4.argtypes = [vp, i64, i64, vp]
+        lib.dvdq_oracle_int_gemm.argtypes = [vp, vp, i64, i64, i64, vp]
+        lib.dvdq_oracle_epilogue.argtypes = [vp, vp, vp, vp, i64, i64, vp]
+        lib.dvdq_oracle_w4ax_gemm.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp]
+        lib.dvdq_oracle_qlinear.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, vp, vp, vp, vp]
+        lib.dvdq_oracle_f64_to_bf16.argtypes = [vp, i64, vp]
+        for f in ("hadamard", "rotate", "quantize", "rotate_quant", "w4ax_gemm", "qlinear"):
+            getattr(lib, "dvdq_oracle_" + f).restype = i32
+        for f in ("unpack_w4", "pack_w4", "int_gemm", "epilogue", "f64_to_bf16"):
+            getattr(lib, "dvdq_oracle_" + f).restype = None
+        _lib = lib
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _arr(a, dtype, ndim=None):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    if ndim is not None and a.ndim != ndim:
+        raise ValueError(f"expected {ndim}-d array, got shape {a.shape}")
+    return a
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError(f"oracle {what} failed with code {rc}")
+
+
+def num_threads() -> int:
+    """Threads the OpenMP loops will use (for the benchmark's report)."""
+    n = os.environ.get("OMP_NUM_THREADS")
+    return int(n) if n else (os.cpu_count() or 1)
+
+
+def hadamard(B: int) -> np.ndarray:
+    H = np.empty((B, B), dtype=np.float64)
+    _check(_load().dvdq_oracle_hadamard(B, _p(H)), "hadamard")
+    return H
+
+
+def rotate(x_bf16: np.ndarray, had_block: int) -> np.ndarray:
+    x = _arr(x_bf16, np.uint16, 2)
+    M, K = x.shape
+    out = np.empty((M, K), dtype=np.float64)
+    _check(_load().dvdq_oracle_rotate(_p(x), M, K, had_block, _p(out)), "rotate")
+    return out
+
+
+def quantize(xrot: np.ndarray, act_bits: int):
+    xr = _arr(xrot, np.float64, 2)
+    M, K = xr.shape
+    codes = np.empty((M, K), dtype=np.int8)
+    scale = np.empty(M, dtype=np.float32)
+    _check(_load().dvdq_oracle_quantize(_p(xr), M, K, act_bits, _p(codes), _p(scale)), "quantize")
+    return codes, scale
+
+
+def rotate_quant(x_bf16: np.ndarray, had_block: int, act_bits: int, return_rotated: bool = False):
+    x = _arr(x_bf16, np.uint16, 2)
+    M, K = x.shape
+    codes = np.empty((M, K), dtype=np.int8)
+    scale = np.empty(M, dtype=np.float32)
+    xr = np.empty((M, K), dtype=np.float64) if return_rotated else None
+    _check(_load().dvdq_oracle_rotate_quant(_p(x), M, K, had_block, act_bits, _p(codes), _p(scale), _p(xr)),
+           "rotate_quant")
+    return (codes, scale, xr) if return_rotated else (codes, scale)
+
+
+def unpack_w4(w_packed: np.ndarray) -> np.ndarray:
+    w = _arr(w_packed, np.uint8, 2)
+    N, K2 = w.shape
+    out = np.empty((N, 2 * K2), dtype=np.int8)
+    _load().dvdq_oracle_unpack_w4(_p(w), N, 2 * K2, _p(out))
+    return out
+
+
+def pack_w4(codes: np.ndarray) -> np.ndarray:
+    c = _arr(codes, np.int8, 2)
+    N, K = c.shape
+    if K % 2:
+        raise ValueError("K must be even")
+    out = np.empty((N, K // 2), dtype=np.uint8)
+    _load().dvdq_oracle_pack_w4(_p(c), N, K, _p(out))
+    return out
+
+
+def int_gemm(codes: np.ndarray, w_codes: np.ndarray) -> np.ndarray:
+    q, w = _arr(codes, np.int8, 2), _arr(w_codes, np.int8, 2)
+    (M, K), (N, K2) = q.shape, w.shape
+    if K != K2:
+        raise ValueError("K mismatch")
+    acc = np.empty((M, N), dtype=np.int64)
+    _load().dvdq_oracle_int_gemm(_p(q), _p(w), M, N, K, _p(acc))
+    return acc
+
+
+def epilogue(acc: np.ndarray, x_scale: np.ndarray, w_scale: np.ndarray, bias_bf16=None) -> np.ndarray:
+    a = _arr(acc, np.int64, 2)
+    M, N = a.shape
+    xs, ws = _arr(x_scale, np.float32, 1), _arr(w_scale, np.float32, 1)
+    b = None if bias_bf16 is None else _arr(bias_bf16, np.uint16, 1)
+    if xs.size != M or ws.size != N or (b is not None and b.size != N):
+        raise ValueError("scale/bias length mismatch")
+    y = np.empty((M, N), dtype=np.uint16)
+    _load().dvdq_oracle_epilogue(_p(a), _p(xs), _p(ws), _p(b), M, N, _p(y))
+    return y
+
+
+def w4ax_gemm(codes, x_scale, w_packed, w_scale, bias_bf16=None, return_acc: bool = False):
+    q = _arr(codes, np.int8, 2)
+    w = _arr(w_packed, np.uint8, 2)
+    (M, K), N = q.shape, w.shape[0]
+    if w.shape[1] * 2 != K:
+        raise ValueError("K mismatch")
+    xs, ws = _arr(x_scale, np.float32, 1), _arr(w_scale, np.float32, 1)
+    b = None if bias_bf16 is None else _arr(bias_bf16, np.uint16, 1)
+    y = np.empty((M, N), dtype=np.uint16)
+    acc = np.empty((M, N), dtype=np.int64) if return_acc else None
+    _check(_load().dvdq_oracle_w4ax_gemm(_p(q), _p(xs), _p(w), _p(ws), _p(b), M, N, K, _p(y), _p(acc)),
+           "w4ax_gemm")
+    return (y, acc) if return_acc else y
+
+
+def qlinear(x_bf16, w_packed, w_scale, had_block: int, act_bits: int, bias_bf16=None):
+    """Whole layer.  Returns dict(y=bf16 bits, codes, x_scale, acc)."""
+    x = _arr(x_bf16, np.uint16, 2)
+    w = _arr(w_packed, np.uint8, 2)
+    (M, K), N = x.shape, w.shape[0]
+    if w.shape[1] * 2 != K:
+        raise ValueError("K mismatch")
+    ws = _arr(w_scale, np.float32, 1)
+    b = None if bias_bf16 is None else _arr(bias_bf16, np.uint16, 1)
+    y = np.empty((M, N), dtype=np.uint16)
+    codes = np.empty((M, K), dtype=np.int8)
+    scale = np.empty(M, dtype=np.float32)
+    acc = np.empty((M, N), dtype=np.int64)
+    _check(_load().dvdq_oracle_qlinear(_p(x), _p(w), _p(ws), _p(b), M, N, K, had_block, act_bits,
+                                       _p(y), _p(codes), _p(scale), _p(acc)), "qlinear")
+    return dict(y=y, codes=codes, x_scale=scale, acc=acc)
+
+
+def f64_to_bf16(a: np.ndarray) -> np.ndarray:
+    v = _arr(a, np.float64)
+    out = np.empty(v.shape, dtype=np.uint16)
+    _load().dvdq_oracle_f64_to_bf16(_p(v), v.size, _p(out))
+    return out

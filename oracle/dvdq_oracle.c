@@ -1,0 +1,257 @@
+/*
+ * CPU oracle for the rotated, auto-scaled, low-bit quantized linear layer.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a deliberately plain,
+ * slow, fp64 / int64 restatement of what the layer computes, written so that a
+ * reader can check it against the method section by eye.  It shares no code,
+ * header, table or helper with the GPU library and is never called by it; only
+ * the tests, the smoke check and the benchmark's CPU-baseline leg use it.
+ *
+ * What it computes, step by step (method Sec. 3.2, the ARQ equation
+ *   X^ = Q(X H Lambda^-1),  Y = X^ Lambda W^^T ;  dequantization as in Sec. 3.1):
+ *
+ *   1. X~ = X * blockdiag(H_B)          dense fp64 matrix product, no butterfly
+ *   2. s_m = max_k |x~_mk| / qmax       one online scale per token row
+ *   3. q_mk = clamp(rint(x~_mk / s_m))  symmetric codes, round-half-to-even
+ *   4. acc_mn = sum_k q_mk * w_nk       exact integer sum (int64)
+ *   5. y_mn = bf16(acc_mn * s_m * ws_n [+ bias_n])
+ *
+ * Readings taken where the text leaves a choice (per-token scale granularity,
+ * symmetric range +-(2^(b-1)-1), Sylvester ordering of H, tie rule, nibble
+ * order) are listed in the repository's design notes; each function below says
+ * which one it relies on.
+ *
+ * Parity status: every function here is pinned by CPU tests against closed
+ * forms, hand-derived examples, a library Hadamard matrix, and brute force on
+ * tiny shapes.  Nothing about video quality is pinned (it needs the real model).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ---------------------------------------------------------------- bf16 */
+
+/* bf16 bit pattern -> double (exact). */
+static double bf16_to_f64(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+/* double -> bf16 bit pattern with a single round-to-nearest-even
+ * (not via float, which would round twice). */
+static uint16_t f64_to_bf16(double v)
+{
+    if (isnan(v)) return 0x7FC0;
+    if (isinf(v)) return v > 0 ? 0x7F80 : 0xFF80;
+    if (v == 0.0) return signbit(v) ? 0x8000 : 0x0000;
+    int e = ilogb(v);                 /* v = m * 2^e, 1 <= |m| < 2 */
+    if (e < -126) e = -126;           /* subnormal bf16 range: fixed quantum */
+    double quantum = ldexp(1.0, e - 7);
+    double r = nearbyint(v / quantum) * quantum;   /* both scalings are exact */
+    float f = (float)r;               /* r has <= 8 significant bits: exact, or inf on overflow */
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    return (uint16_t)(u >> 16);
+}
+
+void dvdq_oracle_f64_to_bf16(const double *in, int64_t n, uint16_t *out)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = f64_to_bf16(in[i]);
+}
+
+/* ---------------------------------------------------------------- Hadamard */
+
+/* Dense normalized Walsh-Hadamard matrix of order B (a power of two) by the
+ * Sylvester recursion H_1 = [1], H_2n = [[H_n, H_n], [H_n, -H_n]], scaled by
+ * 1/sqrt(B) so that H H^T = I (the orthogonality the rotation relies on,
+ * Sec. 3.2).  Row-major, B*B doubles.  Returns 0, or -1 if B is not a power of two. */
+int dvdq_oracle_hadamard(int B, double *H)
+{
+    if (B < 1 || (B & (B - 1)) != 0) return -1;
+    H[0] = 1.0;
+    for (int n = 1; n < B; n *= 2) {
+        /* grow the top-left n x n block (stride B) into 2n x 2n */
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j) {
+                double h = H[(size_t)i * B + j];
+                H[(size_t)i * B + (j + n)] = h;
+                H[(size_t)(i + n) * B + j] = h;
+                H[(size_t)(i + n) * B + (j + n)] = -h;
+            }
+    }
+    double norm = 1.0 / sqrt((double)B);
+    for (size_t i = 0; i < (size_t)B * B; ++i) H[i] *= norm;
+    return 0;
+}
+
+/* X~ = X * blockdiag(H_B, ..., H_B): every contiguous group of B channels of a
+ * token row is multiplied by H_B (Sec. 3.2, X~ = XH; block-diagonal reading for
+ * channel counts that are not a power of two).  x: bf16 bits [M,K]; xrot: fp64 [M,K].
+ * Returns 0, -1 bad B, -2 B does not divide K. */
+int dvdq_oracle_rotate(const uint16_t *x, int64_t M, int64_t K, int B, double *xrot)
+{
+    if (B < 1 || (B & (B - 1)) != 0) return -1;
+    if (K % B != 0) return -2;
+    double *H = (double *)malloc(sizeof(double) * (size_t)B * B);
+    if (!H) return -3;
+    dvdq_oracle_hadamard(B, H);
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        double *xin = (double *)malloc(sizeof(double) * (size_t)B);
+        for (int64_t g = 0; g < K / B; ++g) {
+            const uint16_t *xb = x + m * K + g * B;
+            double *ob = xrot + m * K + g * B;
+            for (int i = 0; i < B; ++i) xin[i] = bf16_to_f64(xb[i]);
+            for (int j = 0; j < B; ++j) {
+                double s = 0.0;
+                for (int i = 0; i < B; ++i) s += xin[i] * H[(size_t)i * B + j];
+                ob[j] = s;
+            }
+        }
+        free(xin);
+    }
+    free(H);
+    return 0;
+}
+
+/* ---------------------------------------------------------------- quantizer */
+
+/* Steps 2-3 on already rotated rows.  qmax = 2^(bits-1) - 1.  The scale is
+ * rounded once to fp32 (that fp32 number is the scale the layer hands on) and
+ * the codes are taken against exactly that number.  A zero row gives scale 0
+ * and all-zero codes. */
+int dvdq_oracle_quantize(const double *xrot, int64_t M, int64_t K, int bits,
+                         int8_t *codes, float *x_scale)
+{
+    if (bits < 2 || bits > 8) return -1;
+    const double qmax = (double)((1 << (bits - 1)) - 1);
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        const double *r = xrot + m * K;
+        double amax = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            double a = fabs(r[k]);
+            if (a > amax) amax = a;
+        }
+        float s = (float)(amax / qmax);      /* round-to-nearest-even to fp32 */
+        x_scale[m] = s;
+        if (!(s > 0.0f)) {
+            for (int64_t k = 0; k < K; ++k) codes[m * K + k] = 0;
+            continue;
+        }
+        double sd = (double)s;
+        for (int64_t k = 0; k < K; ++k) {
+            double q = nearbyint(r[k] / sd);  /* default FP environment: ties to even */
+            if (q > qmax) q = qmax;
+            if (q < -qmax) q = -qmax;
+            codes[m * K + k] = (int8_t)q;
+        }
+    }
+    return 0;
+}
+
+/* Steps 1-3 in one call.  xrot_out may be NULL. */
+int dvdq_oracle_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int B, int bits,
+                             int8_t *codes, float *x_scale, double *xrot_out)
+{
+    double *xr = xrot_out ? xrot_out : (double *)malloc(sizeof(double) * (size_t)M * K);
+    if (!xr) return -3;
+    int rc = dvdq_oracle_rotate(x, M, K, B, xr);
+    if (rc == 0) rc = dvdq_oracle_quantize(xr, M, K, bits, codes, x_scale);
+    if (!xrot_out) free(xr);
+    return rc;
+}
+
+/* ---------------------------------------------------------------- weights */
+
+/* Canonical packed INT4 -> int8 codes.  Byte j of a row carries channel 2j in
+ * bits 0-3 and channel 2j+1 in bits 4-7, each a 4-bit two's-complement number. */
+void dvdq_oracle_unpack_w4(const uint8_t *packed, int64_t N, int64_t K, int8_t *codes)
+{
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t j = 0; j < K / 2; ++j) {
+            int lo = packed[n * (K / 2) + j] & 0xF;
+            int hi = (packed[n * (K / 2) + j] >> 4) & 0xF;
+            codes[n * K + 2 * j] = (int8_t)(lo >= 8 ? lo - 16 : lo);
+            codes[n * K + 2 * j + 1] = (int8_t)(hi >= 8 ? hi - 16 : hi);
+        }
+}
+
+/* Inverse of the above, for the pack/unpack round-trip pin. */
+void dvdq_oracle_pack_w4(const int8_t *codes, int64_t N, int64_t K, uint8_t *packed)
+{
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t j = 0; j < K / 2; ++j) {
+            int lo = codes[n * K + 2 * j] & 0xF;
+            int hi = codes[n * K + 2 * j + 1] & 0xF;
+            packed[n * (K / 2) + j] = (uint8_t)(lo | (hi << 4));
+        }
+}
+
+/* ---------------------------------------------------------------- GEMM */
+
+/* Step 4: acc[m,n] = sum_k q[m,k] * w[n,k], the plain definition, in int64. */
+void dvdq_oracle_int_gemm(const int8_t *q, const int8_t *w, int64_t M, int64_t N, int64_t K,
+                          int64_t *acc)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t s = 0;
+            for (int64_t k = 0; k < K; ++k)
+                s += (int64_t)q[m * K + k] * (int64_t)w[n * K + k];
+            acc[m * N + n] = s;
+        }
+}
+
+/* Step 5: rescale by the token scale (Lambda) and the weight step size (Delta),
+ * add the optional bias, round once to bf16.  bias may be NULL. */
+void dvdq_oracle_epilogue(const int64_t *acc, const float *x_scale, const float *w_scale,
+                          const uint16_t *bias, int64_t M, int64_t N, uint16_t *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            double v = (double)acc[m * N + n] * (double)x_scale[m] * (double)w_scale[n];
+            if (bias) v += bf16_to_f64(bias[n]);
+            y[m * N + n] = f64_to_bf16(v);
+        }
+}
+
+/* Steps 4-5 from codes (the GEMM half of the layer). acc_out may be NULL. */
+int dvdq_oracle_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w_packed,
+                          const float *w_scale, const uint16_t *bias,
+                          int64_t M, int64_t N, int64_t K, uint16_t *y, int64_t *acc_out)
+{
+    if (K % 2) return -2;
+    int8_t *w = (int8_t *)malloc((size_t)N * K);
+    int64_t *acc = acc_out ? acc_out : (int64_t *)malloc(sizeof(int64_t) * (size_t)M * N);
+    if (!w || !acc) { free(w); if (!acc_out) free(acc); return -3; }
+    dvdq_oracle_unpack_w4(w_packed, N, K, w);
+    dvdq_oracle_int_gemm(codes, w, M, N, K, acc);
+    dvdq_oracle_epilogue(acc, x_scale, w_scale, bias, M, N, y);
+    free(w);
+    if (!acc_out) free(acc);
+    return 0;
+}
+
+/* The whole layer, steps 1-5.  codes_out / scale_out / acc_out may be NULL. */
+int dvdq_oracle_qlinear(const uint16_t *x, const uint8_t *w_packed, const float *w_scale,
+                        const uint16_t *bias, int64_t M, int64_t N, int64_t K, int B, int bits,
+                        uint16_t *y, int8_t *codes_out, float *scale_out, int64_t *acc_out)
+{
+    int8_t *codes = codes_out ? codes_out : (int8_t *)malloc((size_t)M * K);
+    float *scale = scale_out ? scale_out : (float *)malloc(sizeof(float) * (size_t)M);
+    int rc = -3;
+    if (codes && scale) {
+        rc = dvdq_oracle_rotate_quant(x, M, K, B, bits, codes, scale, NULL);
+        if (rc == 0) rc = dvdq_oracle_w4ax_gemm(codes, scale, w_packed, w_scale, bias, M, N, K, y, acc_out);
+    }
+    if (!codes_out) free(codes);
+    if (!scale_out) free(scale);
+    return rc;
+}
