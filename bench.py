@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized-linear hot path on one MI355X.
+
+A step is one pass of the whole path -- dvdq_qlinear: block-Hadamard rotation,
+per-token auto-scale, quantization, INT4 x INTb GEMM, dequantizing epilogue --
+over one batch of synthetic activations of the small-video-DiT QKV projection
+(M=32760 tokens, K=1536, N=4608, W4A4, Hadamard block 256).  Inputs are resident
+in HBM before the timed region; weights are pre-packed offline.
+
+Prints ONE JSON line: whole-path throughput in TOP/s (2*M*N*K per step), the
+roofline of the dominant kernel (the INT8-MFMA GEMM) from per-launch HIP-event
+timings, the same for the HBM-bound rotate+quantize kernel, and the CPU oracle
+timed on this machine's host cores on a bounded token sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5000.0     # published dense INT8 matrix peak, MI355X
+HBM_PEAK_GBPS = 8000.0           # published HBM3E bandwidth, MI355X
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", type=int, default=1, help="index into the five configs (default: the headline one)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--bufs", type=int, default=3, help="input/output buffer sets rotated through (cache defeat)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build targets one GPU; the path shards by tokens with no collective, "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import dvdq_inputs as di
+    import paper_2505_18663_amd as dvdq
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dvdq.lib()   # fail loudly if the HIP library is missing
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    wl = di.WORKLOADS[args.workload]
+    M, K, N, B, bits = wl.M, wl.K, wl.N, wl.had_block, wl.act_bits
+    xb = di.make_x(wl)
+    wp, ws, _ = di.make_weights(wl)
+    nb = max(1, args.bufs)
+    x0 = torch.from_numpy(xb.view(np.int16)).view(torch.bfloat16).to(dev)
+    xs = [x0] + [x0.clone() for _ in range(nb - 1)]
+    w_native = dvdq.w4_prepack(torch.from_numpy(wp).to(dev))
+    ws_dev = torch.from_numpy(ws).to(dev)
+    need = dvdq.qlinear_workspace_bytes(M, K, bits)
+    wsp = [torch.empty((need,), dtype=torch.uint8, device=dev) for _ in range(nb)]
+    ys = [torch.empty((M, N), dtype=torch.bfloat16, device=dev) for _ in range(nb)]
+    torch.cuda.synchronize()
+
+    def step(i):
+        j = i % nb
+        dvdq.qlinear(xs[j], w_native, ws_dev, B, bits, dvdq.W_NATIVE, y=ys[j], workspace=wsp[j])
+
+    # ---- timed region: whole path
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t_step = (time.perf_counter() - t0) / args.steps
+    ops = 2.0 * M * N * K
+    tops = ops / t_step / 1e12
+
+    # ---- per-kernel launch durations (HIP events on the launch stream)
+    def time_launches(fn, n):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for i in range(min(args.warmup, 5)):
+            fn(i)
+        torch.cuda.synchronize()
+        for i in range(n):
+            ev[i][0].record()
+            fn(i)
+            ev[i][1].record()
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in ev)
+        return sum(ms) / len(ms), ms[len(ms) // 2]
+
+    views = [dvdq.workspace_views(w_, M, K, bits) for w_ in wsp]
+
+    def rq(i):
+        j = i % nb
+        dvdq.rotate_quant(xs[j], B, bits, codes=views[j][0], x_scale=views[j][1])
+
+    def gemm(i):
+        j = i % nb
+        dvdq.w4ax_gemm(views[j][0], views[j][1], w_native, ws_dev, bits, dvdq.W_NATIVE, y=ys[j])
+
+    rq_avg, rq_med = time_launches(rq, args.steps)
+    gemm_avg, gemm_med = time_launches(gemm, args.steps)
+    rq_bytes = 2.0 * M * K + 1.0 * M * K + 4.0 * M          # bf16 in, int8 codes out, fp32 scales out
+    rq_gbps = rq_bytes / (rq_avg * 1e-3) / 1e9
+    gemm_tops = ops / (gemm_avg * 1e-3) / 1e12
+
+    # ---- calibration: what this chip sustains for a plain copy and a register-only INT8 MFMA loop
+    src = torch.empty((256 << 20,), dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    copy_avg, _ = time_launches(lambda i: dvdq.bench_copy(src, dst), 10)
+    copy_gbps = 2.0 * src.numel() / (copy_avg * 1e-3) / 1e9
+    sink = torch.zeros((4,), dtype=torch.int32, device=dev)
+    mfma_ops = [0.0]
+
+    def mfma(i):
+        mfma_ops[0] = dvdq.bench_mfma_i8(2000, sink)
+    mfma_avg, _ = time_launches(mfma, 5)
+    mfma_ceiling = mfma_ops[0] / (mfma_avg * 1e-3) / 1e12
+    del src, dst
+
+    out = {
+        "metric": "fused W4A4 qlinear TOPS & % INT8-MFMA peak; rotate+quant HBM GB/s",
+        "value": round(tops, 2), "unit": "TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(t_step * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8 x int4 -> int32 (bf16 in/out)", "data": "synthetic",
+        "config": {"workload": wl.name, "M": M, "K": K, "N": N, "had_block": B, "act_bits": bits,
+                   "w_layout": "native", "buffers_rotated": nb},
+        "frac_int8_mfma_peak": round(tops / INT8_MFMA_PEAK_TOPS, 4),
+        "roofline": {"kernel": "w4ax_gemm", "bound": "mfma", "achieved": round(gemm_tops, 2),
+                     "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(gemm_tops / INT8_MFMA_PEAK_TOPS, 4),
+                     "traffic": None, "avg_launch_ms": round(gemm_avg, 4), "median_launch_ms": round(gemm_med, 4),
+                     "measured_mfma_ceiling_tops": round(mfma_ceiling, 1)},
+        "roofline_rotate_quant": {"kernel": "rotate_quant", "bound": "hbm", "achieved": round(rq_gbps, 1),
+                                  "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(rq_gbps / HBM_PEAK_GBPS, 4),
+                                  "traffic": None, "avg_launch_ms": round(rq_avg, 4),
+                                  "median_launch_ms": round(rq_med, 4), "algorithmic_bytes": rq_bytes,
+                                  "measured_copy_gbps": round(copy_gbps, 1)},
+    }
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded token sample
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = di.sample_rows(M, 256)
+        xs_rows = np.ascontiguousarray(xb[rows])
+        oracle.qlinear(xs_rows[:8], wp, ws, B, bits)       # load / warm the library
+        t0 = time.perf_counter()
+        oracle.qlinear(xs_rows, wp, ws, B, bits)
+        t_cpu = time.perf_counter() - t0
+        out["cpu_baseline"] = {
+            "value": round(2.0 * rows.size * N * K / t_cpu / 1e12, 5), "unit": "TOP/s",
+            "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{rows.size} of {M} token rows (first 256 + last 256), whole layer, {t_cpu:.2f} s; "
+                      f"work is linear in rows, full-size time extrapolates to {t_cpu * M / rows.size:.1f} s",
+        }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

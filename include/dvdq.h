@@ -1,0 +1,131 @@
+/*
+ * dvdq -- the quantized linear layer of a video DiT on MI355X (gfx950).
+ *
+ * C ABI of the hot path of DVD-Quant's quantized inference: one linear layer
+ *
+ *     X~ = X H            online block Walsh-Hadamard rotation      (Sec. 3.2, ARQ)
+ *     s  = max|X~| / qmax  online auto-scale, one per token row      (Sec. 3.2, ARQ equation)
+ *     X^ = Q(X~ / s)      symmetric low-bit codes                   (Sec. 3.2, ARQ equation)
+ *     Y  = s * (X^ W^^T) * Delta    low-bit GEMM and rescale        (Sec. 3.2 ARQ equation, Sec. 3.1 DeQuant)
+ *
+ * with W^ the offline-quantized INT4 weights (codes + one step size Delta per
+ * output channel), already expressed in the rotated basis (W H, Sec. 3.2).
+ * The activation bit-width is an argument: delta-Guided Bit Switching (Sec. 3.3)
+ * picks it per denoising step outside this library.
+ *
+ * Conventions shared by every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     never allocates, frees or keeps device memory and holds no global state.
+ *   - `hip_stream` is the caller's hipStream_t (NULL = the default stream).  All
+ *     work is enqueued on it; calls return without synchronizing.
+ *   - Inputs are read-only; outputs must not overlap inputs or each other.
+ *   - Base pointers must be 16-byte aligned (DVDQ_ERR_ALIGN otherwise).
+ *   - Return value: DVDQ_OK (0) or a dvdq_status code.  Argument errors are found
+ *     on the host before anything is enqueued.  Nothing is printed, nothing throws.
+ *   - NaN / Inf in X: no fault, result unspecified.
+ *   - Tensors are dense row-major.  bf16 is passed as `void*` to 16-bit patterns.
+ *
+ * Activation codes: int8 container, one code per byte, values in
+ * [-qmax, qmax], qmax = 2^(act_bits-1) - 1  (7, 31 or 127 for 4, 6, 8 bits).
+ *
+ * Weight codes, canonical layout (DVDQ_W_CANONICAL): uint8 [N, K/2]; byte j of
+ * row n holds channel 2j in bits 0-3 and channel 2j+1 in bits 4-7, each a 4-bit
+ * two's-complement number (offline quantizers produce [-7, 7]; -8 is accepted).
+ * Native layout (DVDQ_W_NATIVE): the opaque buffer written by dvdq_w4_prepack,
+ * dvdq_w4_native_bytes(N, K) bytes; same information, ordered for the GEMM kernel.
+ */
+#ifndef DVDQ_H
+#define DVDQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DVDQ_OK = 0,
+    DVDQ_ERR_NULL = 1,        /* a required pointer is NULL */
+    DVDQ_ERR_SHAPE = 2,       /* M, N, K, had_block inconsistent (non-positive, K % had_block, K odd, ...) */
+    DVDQ_ERR_UNSUPPORTED = 3, /* valid request outside what the kernels implement */
+    DVDQ_ERR_WORKSPACE = 4,   /* workspace too small */
+    DVDQ_ERR_ALIGN = 5,       /* a base pointer is not 16-byte aligned */
+    DVDQ_ERR_HIP = 6          /* a kernel launch failed (hipGetLastError) */
+} dvdq_status;
+
+enum { DVDQ_W_CANONICAL = 0, DVDQ_W_NATIVE = 1 };
+
+/*
+ * Rotate + auto-scale + quantize (Sec. 3.2: X~ = XH by fast Hadamard transform,
+ * per-row s = ||x~||_inf / qmax, codes = round-half-even(x~ / s) clamped to +-qmax).
+ *
+ *   x_bf16   in   bf16 [M, K]
+ *   had_block     size B of the normalized Walsh-Hadamard blocks (natural/Sylvester
+ *                 order, H[i,j] = (-1)^popcount(i&j)/sqrt(B)); every contiguous group
+ *                 of B channels is rotated on its own.  Power of two, 1 <= B <= 512,
+ *                 B divides K.  B = 1 means no rotation.
+ *   act_bits      4, 6 or 8
+ *   codes    out  int8 [M, K]
+ *   x_scale  out  fp32 [M]; 0 for an all-zero row (its codes are all 0)
+ *
+ * K must be a multiple of 8 (DVDQ_ERR_SHAPE) and at most 65536 (DVDQ_ERR_UNSUPPORTED).
+ */
+int dvdq_rotate_quant(const void *x_bf16, int64_t M, int64_t K, int had_block, int act_bits,
+                      int8_t *codes, float *x_scale, void *hip_stream);
+
+/*
+ * Low-bit GEMM with exact int32 accumulation and the dequantizing epilogue
+ * (Sec. 3.2: Y = X^ Lambda W^^T; Sec. 3.1 DeQuant with zero-point 0):
+ *
+ *     acc[m,n] = sum_k codes[m,k] * w[n,k]                       (exact, int32)
+ *     y[m,n]   = bf16( float(acc[m,n]) * x_scale[m] * w_scale[n] + bias[n] )
+ *
+ *   codes     in   int8 [M, K], |code| <= 2^(act_bits-1) - 1 (not checked)
+ *   x_scale   in   fp32 [M]
+ *   w         in   packed INT4 weights, layout per `w_layout`
+ *   w_scale   in   fp32 [N]
+ *   bias_bf16 in   bf16 [N] or NULL
+ *   act_bits       4, 6 or 8 (bounds the accumulator: qmax * 8 * K must stay below 2^31,
+ *                  DVDQ_ERR_UNSUPPORTED otherwise)
+ *   y_bf16    out  bf16 [M, N]
+ *   acc_out   out  int32 [M, N] or NULL; when given, receives the raw accumulators
+ *                  (parity hook; costs extra bandwidth)
+ *
+ * K must be a multiple of 64 (DVDQ_ERR_SHAPE).  Any M >= 1, N >= 1; ragged tiles
+ * are handled inside.
+ */
+int dvdq_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
+                   const void *bias_bf16, int64_t M, int64_t N, int64_t K, int act_bits, int w_layout,
+                   void *y_bf16, int32_t *acc_out, void *hip_stream);
+
+/*
+ * The whole layer in one call: dvdq_rotate_quant followed by dvdq_w4ax_gemm on
+ * the same stream.  `workspace` (device, 256-byte aligned) must hold at least
+ * dvdq_qlinear_workspace_bytes(M, K, act_bits) bytes; after the call completes it
+ * contains the activation codes (int8 [M, K]) at offset 0 and the token scales
+ * (fp32 [M]) at offset dvdq_qlinear_scale_offset(M, K, act_bits), so callers and
+ * tests can inspect them.  Arguments as in the two calls above.
+ */
+int dvdq_qlinear(const void *x_bf16, const uint8_t *w, const float *w_scale, const void *bias_bf16,
+                 int64_t M, int64_t N, int64_t K, int had_block, int act_bits, int w_layout,
+                 void *y_bf16, void *workspace, size_t workspace_bytes, void *hip_stream);
+size_t dvdq_qlinear_workspace_bytes(int64_t M, int64_t K, int act_bits);
+size_t dvdq_qlinear_scale_offset(int64_t M, int64_t K, int act_bits);
+
+/*
+ * One-time, offline: reorder canonical packed weights into the GEMM kernel's
+ * native layout (the rotated, quantized weights of Sec. 3.2 are fixed after
+ * quantization, so this runs once per layer).  w_native must hold
+ * dvdq_w4_native_bytes(N, K) bytes.  K multiple of 64.
+ */
+int dvdq_w4_prepack(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, void *hip_stream);
+size_t dvdq_w4_native_bytes(int64_t N, int64_t K);
+
+const char *dvdq_status_string(int status);
+int dvdq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DVDQ_H */

@@ -1,0 +1,34 @@
+/*
+ * Measurement helpers exported by libdvdq next to the layer itself.  They are
+ * not part of the quantized linear layer; the benchmark uses them to calibrate
+ * its rooflines on the machine it runs on:
+ *   - a plain copy kernel of known size (reference reading for the HBM traffic
+ *     counters and for achievable copy bandwidth),
+ *   - a register-only INT8 MFMA loop (the matrix-core rate the chip sustains when
+ *     nothing but MFMA issue limits it).
+ * Same conventions as dvdq.h: device pointers owned by the caller, work enqueued
+ * on the caller's stream, DVDQ_OK or a dvdq_status code returned.
+ */
+#ifndef DVDQ_BENCH_H
+#define DVDQ_BENCH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* dst[i] = src[i] for `bytes` bytes (multiple of 16; both pointers 16-byte aligned). */
+int dvdq_bench_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
+
+/* Every wave of a full-chip launch issues `iters` x 16 independent 32x32x32 INT8 MFMAs on
+ * registers; `sink` (device, >= 4 bytes) receives a value that depends on the
+ * result so the loop is not removed.  *ops_out (host pointer, may be NULL) receives the
+ * number of integer operations (2 per multiply-add) the launch performs. */
+int dvdq_bench_mfma_i8(int iters, int32_t *sink, double *ops_out, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DVDQ_BENCH_H */

@@ -1,0 +1,235 @@
+"""Python binding of libdvdq (ctypes).  Argument marshalling only: every step of
+the quantized linear layer runs in the HIP kernels behind the C ABI declared in
+``include/dvdq.h``.  PyTorch supplies device memory and streams, nothing else.
+
+There is no CPU fallback: if ``libdvdq.so`` has not been built
+(``python -m paper_2505_18663_amd.build``) importing a function works but the first
+call raises ``DvdqLibraryMissing``.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+__all__ = [
+    "DvdqError", "DvdqLibraryMissing", "lib", "library_path", "version", "status_string",
+    "rotate_quant", "w4ax_gemm", "qlinear", "qlinear_workspace_bytes", "qlinear_scale_offset",
+    "w4_prepack", "w4_native_bytes", "bench_copy", "bench_mfma_i8",
+    "W_CANONICAL", "W_NATIVE", "EXPORTED_SYMBOLS",
+]
+
+W_CANONICAL, W_NATIVE = 0, 1
+
+EXPORTED_SYMBOLS = (
+    "dvdq_rotate_quant", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_qlinear_workspace_bytes",
+    "dvdq_qlinear_scale_offset", "dvdq_w4_prepack", "dvdq_w4_native_bytes", "dvdq_status_string",
+    "dvdq_version", "dvdq_bench_copy", "dvdq_bench_mfma_i8",
+)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libdvdq.so")
+_lib = None
+
+
+class DvdqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: dvdq status {status} ({status_string(status)})")
+
+
+class DvdqLibraryMissing(RuntimeError):
+    pass
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> C.CDLL:
+    """Load libdvdq.so (once) and declare the C prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise DvdqLibraryMissing(
+            f"{_LIB_PATH} not found: build it with `python -m paper_2505_18663_amd.build` "
+            "(hipcc, gfx950).  There is no fallback path.")
+    L = C.CDLL(_LIB_PATH)
+    i64, i32, vp, sz = C.c_int64, C.c_int, C.c_void_p, C.c_size_t
+    L.dvdq_rotate_quant.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
+    L.dvdq_w4ax_gemm.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, vp, vp, vp]
+    L.dvdq_qlinear.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, vp, sz, vp]
+    L.dvdq_qlinear_workspace_bytes.argtypes = [i64, i64, i32]
+    L.dvdq_qlinear_scale_offset.argtypes = [i64, i64, i32]
+    L.dvdq_w4_prepack.argtypes = [vp, i64, i64, vp, vp]
+    L.dvdq_w4_native_bytes.argtypes = [i64, i64]
+    L.dvdq_status_string.argtypes = [i32]
+    L.dvdq_version.argtypes = []
+    L.dvdq_bench_copy.argtypes = [vp, vp, sz, vp]
+    L.dvdq_bench_mfma_i8.argtypes = [i32, vp, C.POINTER(C.c_double), vp]
+    for f in ("dvdq_rotate_quant", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_w4_prepack", "dvdq_version",
+              "dvdq_bench_copy", "dvdq_bench_mfma_i8"):
+        getattr(L, f).restype = i32
+    for f in ("dvdq_qlinear_workspace_bytes", "dvdq_qlinear_scale_offset", "dvdq_w4_native_bytes"):
+        getattr(L, f).restype = sz
+    L.dvdq_status_string.restype = C.c_char_p
+    _lib = L
+    return L
+
+
+def version() -> int:
+    return lib().dvdq_version()
+
+
+def status_string(status: int) -> str:
+    return lib().dvdq_status_string(int(status)).decode()
+
+
+# ------------------------------------------------------------------ marshalling helpers
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _need(t, dtype, shape, name):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name}: expected a CUDA/HIP tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name}: expected dtype {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+    return t
+
+
+def _check(rc, where):
+    if rc != 0:
+        raise DvdqError(rc, where)
+
+
+# ------------------------------------------------------------------ the layer
+def rotate_quant(x, had_block: int, act_bits: int, codes=None, x_scale=None, stream=None):
+    """x: bf16 [M, K] -> (codes int8 [M, K], x_scale fp32 [M]).  See dvdq_rotate_quant."""
+    L = lib()
+    _need(x, torch.bfloat16, None, "x")
+    M, K = x.shape
+    if codes is None:
+        codes = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    if x_scale is None:
+        x_scale = torch.empty((M,), dtype=torch.float32, device=x.device)
+    _need(codes, torch.int8, (M, K), "codes")
+    _need(x_scale, torch.float32, (M,), "x_scale")
+    _check(L.dvdq_rotate_quant(_ptr(x), M, K, had_block, act_bits, _ptr(codes), _ptr(x_scale), _stream(stream)),
+           "dvdq_rotate_quant")
+    return codes, x_scale
+
+
+def w4ax_gemm(codes, x_scale, w, w_scale, act_bits: int, w_layout: int = W_CANONICAL, bias=None,
+              y=None, acc_out=None, want_acc: bool = False, stream=None):
+    """codes int8 [M, K], w uint8 packed INT4 [N, K/2] (or native) -> y bf16 [M, N].
+    With want_acc (or acc_out given) also returns the int32 accumulators."""
+    L = lib()
+    _need(codes, torch.int8, None, "codes")
+    M, K = codes.shape
+    _need(w_scale, torch.float32, None, "w_scale")
+    N = w_scale.shape[0]
+    _need(x_scale, torch.float32, (M,), "x_scale")
+    _need(w, torch.uint8, None, "w")
+    if w_layout == W_CANONICAL and tuple(w.shape) != (N, K // 2):
+        raise ValueError(f"w: expected shape {(N, K // 2)}, got {tuple(w.shape)}")
+    if w_layout == W_NATIVE and w.numel() < L.dvdq_w4_native_bytes(N, K):
+        raise ValueError("w: native buffer too small")
+    if bias is not None:
+        _need(bias, torch.bfloat16, (N,), "bias")
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=codes.device)
+    _need(y, torch.bfloat16, (M, N), "y")
+    if want_acc and acc_out is None:
+        acc_out = torch.empty((M, N), dtype=torch.int32, device=codes.device)
+    if acc_out is not None:
+        _need(acc_out, torch.int32, (M, N), "acc_out")
+    _check(L.dvdq_w4ax_gemm(_ptr(codes), _ptr(x_scale), _ptr(w), _ptr(w_scale), _ptr(bias), M, N, K, act_bits,
+                            w_layout, _ptr(y), _ptr(acc_out), _stream(stream)), "dvdq_w4ax_gemm")
+    return (y, acc_out) if acc_out is not None else y
+
+
+def qlinear_workspace_bytes(M: int, K: int, act_bits: int) -> int:
+    return lib().dvdq_qlinear_workspace_bytes(M, K, act_bits)
+
+
+def qlinear_scale_offset(M: int, K: int, act_bits: int) -> int:
+    return lib().dvdq_qlinear_scale_offset(M, K, act_bits)
+
+
+def qlinear(x, w, w_scale, had_block: int, act_bits: int, w_layout: int = W_CANONICAL, bias=None,
+            y=None, workspace=None, stream=None):
+    """The whole layer.  Returns (y bf16 [M, N], workspace uint8); the workspace holds the
+    codes at offset 0 and the token scales at qlinear_scale_offset(M, K, act_bits)."""
+    L = lib()
+    _need(x, torch.bfloat16, None, "x")
+    M, K = x.shape
+    _need(w_scale, torch.float32, None, "w_scale")
+    N = w_scale.shape[0]
+    _need(w, torch.uint8, None, "w")
+    if w_layout == W_CANONICAL and tuple(w.shape) != (N, K // 2):
+        raise ValueError(f"w: expected shape {(N, K // 2)}, got {tuple(w.shape)}")
+    if bias is not None:
+        _need(bias, torch.bfloat16, (N,), "bias")
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    _need(y, torch.bfloat16, (M, N), "y")
+    need = L.dvdq_qlinear_workspace_bytes(M, K, act_bits)
+    if workspace is None:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=x.device)
+    _need(workspace, torch.uint8, None, "workspace")
+    _check(L.dvdq_qlinear(_ptr(x), _ptr(w), _ptr(w_scale), _ptr(bias), M, N, K, had_block, act_bits, w_layout,
+                          _ptr(y), _ptr(workspace), workspace.numel(), _stream(stream)), "dvdq_qlinear")
+    return y, workspace
+
+
+def workspace_views(workspace, M: int, K: int, act_bits: int):
+    """(codes int8 [M, K], x_scale fp32 [M]) views into a qlinear workspace."""
+    off = qlinear_scale_offset(M, K, act_bits)
+    codes = workspace[:M * K].view(torch.int8).view(M, K)
+    scale = workspace[off:off + 4 * M].view(torch.float32)
+    return codes, scale
+
+
+def w4_native_bytes(N: int, K: int) -> int:
+    return lib().dvdq_w4_native_bytes(N, K)
+
+
+def w4_prepack(w_canonical, w_native=None, stream=None):
+    """uint8 [N, K/2] canonical -> opaque native buffer for the GEMM kernel (offline, once)."""
+    L = lib()
+    _need(w_canonical, torch.uint8, None, "w_canonical")
+    N, K2 = w_canonical.shape
+    K = 2 * K2
+    need = L.dvdq_w4_native_bytes(N, K)
+    if w_native is None:
+        w_native = torch.empty((max(need, 1),), dtype=torch.uint8, device=w_canonical.device)
+    _need(w_native, torch.uint8, None, "w_native")
+    if w_native.numel() < need:
+        raise ValueError("w_native too small")
+    _check(L.dvdq_w4_prepack(_ptr(w_canonical), N, K, _ptr(w_native), _stream(stream)), "dvdq_w4_prepack")
+    return w_native
+
+
+# ------------------------------------------------------------------ calibration helpers
+def bench_copy(src, dst, stream=None):
+    nbytes = src.numel() * src.element_size()
+    _check(lib().dvdq_bench_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "dvdq_bench_copy")
+
+
+def bench_mfma_i8(iters: int, sink, stream=None) -> float:
+    ops = C.c_double(0.0)
+    _check(lib().dvdq_bench_mfma_i8(iters, _ptr(sink), C.byref(ops), _stream(stream)), "dvdq_bench_mfma_i8")
+    return ops.value

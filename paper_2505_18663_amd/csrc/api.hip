@@ -1,0 +1,132 @@
+// C ABI of libdvdq: argument validation on the host, then kernel launches.
+// Every check happens before anything is enqueued; no entry point allocates,
+// frees or synchronizes.
+#include "dvdq_internal.h"
+
+namespace {
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int log2_exact(int v) {
+    if (v < 1 || (v & (v - 1)) != 0) return -1;
+    int l = 0;
+    while ((1 << l) < v) ++l;
+    return l;
+}
+
+inline bool bits_ok(int b) { return b == 4 || b == 6 || b == 8; }
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int check_rotate_quant(const void *x, int64_t M, int64_t K, int had_block, int act_bits, const void *codes,
+                       const void *x_scale, int *log2b) {
+    if (!x || !codes || !x_scale) return DVDQ_ERR_NULL;
+    if (M < 1 || K < 1 || (K % 8) != 0) return DVDQ_ERR_SHAPE;
+    *log2b = log2_exact(had_block);
+    if (*log2b < 0 || (K % had_block) != 0) return DVDQ_ERR_SHAPE;
+    if (!bits_ok(act_bits) || had_block > 512 || K > 65536 || M > 0x7FFFFFFF) return DVDQ_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(codes) || !aligned16(x_scale)) return DVDQ_ERR_ALIGN;
+    return DVDQ_OK;
+}
+
+int check_gemm(const void *codes, const void *x_scale, const void *w, const void *w_scale, const void *bias,
+               int64_t M, int64_t N, int64_t K, int act_bits, int w_layout, const void *y, const void *acc_out) {
+    if (!codes || !x_scale || !w || !w_scale || !y) return DVDQ_ERR_NULL;
+    if (M < 1 || N < 1 || K < 1 || (K % 64) != 0) return DVDQ_ERR_SHAPE;
+    if (!bits_ok(act_bits) || (w_layout != DVDQ_W_CANONICAL && w_layout != DVDQ_W_NATIVE)) return DVDQ_ERR_UNSUPPORTED;
+    if (M > 0x7FFFFFFF || N > 0x7FFFFFFF || K > 0x7FFFFFFF) return DVDQ_ERR_UNSUPPORTED;
+    // the kernel accumulates 16 * sum(code * w): |code| <= qmax, |w| <= 8
+    const int64_t qmax = (1 << (act_bits - 1)) - 1;
+    if (16 * qmax * 8 * K >= (int64_t)1 << 31) return DVDQ_ERR_UNSUPPORTED;
+    if (!aligned16(codes) || !aligned16(x_scale) || !aligned16(w) || !aligned16(w_scale) || !aligned16(y) ||
+        (bias && !aligned16(bias)) || (acc_out && !aligned16(acc_out)))
+        return DVDQ_ERR_ALIGN;
+    return DVDQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int dvdq_rotate_quant(const void *x_bf16, int64_t M, int64_t K, int had_block, int act_bits, int8_t *codes,
+                      float *x_scale, void *hip_stream) {
+    int log2b = 0;
+    const int rc = check_rotate_quant(x_bf16, M, K, had_block, act_bits, codes, x_scale, &log2b);
+    if (rc != DVDQ_OK) return rc;
+    return dvdq::launch_rotate_quant(static_cast<const uint16_t *>(x_bf16), M, K, log2b, act_bits, codes, x_scale,
+                                     static_cast<hipStream_t>(hip_stream));
+}
+
+int dvdq_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
+                   const void *bias_bf16, int64_t M, int64_t N, int64_t K, int act_bits, int w_layout,
+                   void *y_bf16, int32_t *acc_out, void *hip_stream) {
+    const int rc = check_gemm(codes, x_scale, w, w_scale, bias_bf16, M, N, K, act_bits, w_layout, y_bf16, acc_out);
+    if (rc != DVDQ_OK) return rc;
+    return dvdq::launch_w4ax_gemm(codes, x_scale, w, w_scale, static_cast<const uint16_t *>(bias_bf16), M, N, K,
+                                  w_layout, static_cast<uint16_t *>(y_bf16), acc_out,
+                                  static_cast<hipStream_t>(hip_stream));
+}
+
+size_t dvdq_qlinear_scale_offset(int64_t M, int64_t K, int act_bits) {
+    (void)act_bits;  // codes use an int8 container for every supported width
+    if (M < 1 || K < 1) return 0;
+    return round_up((size_t)M * (size_t)K, 256);
+}
+
+size_t dvdq_qlinear_workspace_bytes(int64_t M, int64_t K, int act_bits) {
+    if (M < 1 || K < 1) return 0;
+    return dvdq_qlinear_scale_offset(M, K, act_bits) + round_up(sizeof(float) * (size_t)M, 256);
+}
+
+int dvdq_qlinear(const void *x_bf16, const uint8_t *w, const float *w_scale, const void *bias_bf16, int64_t M,
+                 int64_t N, int64_t K, int had_block, int act_bits, int w_layout, void *y_bf16, void *workspace,
+                 size_t workspace_bytes, void *hip_stream) {
+    if (!workspace) return DVDQ_ERR_NULL;
+    if (M < 1 || K < 1) return DVDQ_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return DVDQ_ERR_ALIGN;
+    int8_t *codes = static_cast<int8_t *>(workspace);
+    float *x_scale = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) +
+                                               dvdq_qlinear_scale_offset(M, K, act_bits));
+    int log2b = 0;
+    int rc = check_rotate_quant(x_bf16, M, K, had_block, act_bits, codes, x_scale, &log2b);
+    if (rc != DVDQ_OK) return rc;
+    rc = check_gemm(codes, x_scale, w, w_scale, bias_bf16, M, N, K, act_bits, w_layout, y_bf16, nullptr);
+    if (rc != DVDQ_OK) return rc;
+    if (workspace_bytes < dvdq_qlinear_workspace_bytes(M, K, act_bits)) return DVDQ_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    rc = dvdq::launch_rotate_quant(static_cast<const uint16_t *>(x_bf16), M, K, log2b, act_bits, codes, x_scale,
+                                   stream);
+    if (rc != DVDQ_OK) return rc;
+    return dvdq::launch_w4ax_gemm(codes, x_scale, w, w_scale, static_cast<const uint16_t *>(bias_bf16), M, N, K,
+                                  w_layout, static_cast<uint16_t *>(y_bf16), nullptr, stream);
+}
+
+size_t dvdq_w4_native_bytes(int64_t N, int64_t K) {
+    if (N < 1 || K < 1 || (K % 64) != 0) return 0;
+    return (size_t)N * (size_t)K / 2;
+}
+
+int dvdq_w4_prepack(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, void *hip_stream) {
+    if (!w_canonical || !w_native) return DVDQ_ERR_NULL;
+    if (N < 1 || K < 1 || (K % 64) != 0) return DVDQ_ERR_SHAPE;
+    if (N > 0x7FFFFFFF || K > 0x7FFFFFFF) return DVDQ_ERR_UNSUPPORTED;
+    if (!aligned16(w_canonical) || !aligned16(w_native)) return DVDQ_ERR_ALIGN;
+    return dvdq::launch_w4_prepack(w_canonical, N, K, w_native, static_cast<hipStream_t>(hip_stream));
+}
+
+const char *dvdq_status_string(int status) {
+    switch (status) {
+        case DVDQ_OK: return "ok";
+        case DVDQ_ERR_NULL: return "a required pointer is NULL";
+        case DVDQ_ERR_SHAPE: return "inconsistent shape arguments";
+        case DVDQ_ERR_UNSUPPORTED: return "request outside what the kernels implement";
+        case DVDQ_ERR_WORKSPACE: return "workspace too small";
+        case DVDQ_ERR_ALIGN: return "pointer not sufficiently aligned";
+        case DVDQ_ERR_HIP: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int dvdq_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,24 @@
+// Internal declarations shared by the translation units of libdvdq (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/dvdq.h"
+
+namespace dvdq {
+
+// Launchers: arguments are already validated by the C-ABI layer in api.hip.
+// Each returns DVDQ_OK or DVDQ_ERR_HIP.
+int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block, int act_bits,
+                        int8_t *codes, float *x_scale, hipStream_t stream);
+
+int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
+                     const uint16_t *bias, int64_t M, int64_t N, int64_t K, int w_layout,
+                     uint16_t *y, int32_t *acc_out, hipStream_t stream);
+
+int launch_w4_prepack(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, hipStream_t stream);
+
+inline int check_launch() { return hipGetLastError() == hipSuccess ? DVDQ_OK : DVDQ_ERR_HIP; }
+
+}  // namespace dvdq

@@ -1,0 +1,77 @@
+"""Parity criteria shared by the GPU tests (kept apart from the oracle: this is the
+judging logic, not an implementation of the layer).
+
+Bars (stated in the tests that call these):
+  * int32 accumulators: bit-exact on identical codes.
+  * activation codes: bit-exact, except elements whose exact rotated value lies
+    within one fp32 ulp of the row maximum (in code units: qmax * 2^-23) of a
+    rounding boundary -- widened by the row's own scale difference, which is
+    itself limited to 2 fp32 ulps -- each off by exactly 1, and at most
+    ceil(1e-5 * elements) of them.
+  * token scales: within 2 fp32 ulps.
+  * bf16 outputs on identical accumulators and scales: within 1 bf16 ulp
+    everywhere, max relative error <= 1e-2, mean relative error <= 1e-3.
+"""
+import math
+
+import numpy as np
+
+import dvdq_inputs as di
+
+
+def ulp_diff_f32(a, b):
+    ia = np.ascontiguousarray(a, dtype=np.float32).view(np.int32).astype(np.int64)
+    ib = np.ascontiguousarray(b, dtype=np.float32).view(np.int32).astype(np.int64)
+    return np.abs(ia - ib)        # inputs here are non-negative scales: bit patterns are ordered
+
+
+def check_codes_and_scales(codes_gpu, scale_gpu, codes_ref, scale_ref, xrot_ref, act_bits, label=""):
+    """Returns a dict of counters; raises AssertionError on any violation."""
+    qmax = 2 ** (act_bits - 1) - 1
+    d_ulp = ulp_diff_f32(scale_gpu, scale_ref)
+    assert d_ulp.max(initial=0) <= 2, f"{label}: token scale off by {d_ulp.max()} fp32 ulps (bar: 2)"
+    zero = scale_ref == 0
+    assert np.array_equal(scale_gpu[zero], scale_ref[zero]), f"{label}: zero rows must give scale 0"
+    mism = codes_gpu != codes_ref
+    n_mis = int(mism.sum())
+    budget = math.ceil(1e-5 * codes_ref.size)
+    out = dict(elements=int(codes_ref.size), mismatches=n_mis, budget=budget,
+               max_scale_ulp=int(d_ulp.max(initial=0)), max_boundary_dist_ulps=0.0)
+    if n_mis == 0:
+        return out
+    rows, cols = np.nonzero(mism)
+    g = codes_gpu[rows, cols].astype(np.int64)
+    r = codes_ref[rows, cols].astype(np.int64)
+    assert np.all(np.abs(g - r) == 1), f"{label}: a code differs by more than 1"
+    t = xrot_ref[rows, cols] / scale_ref[rows].astype(np.float64)     # exact value in code units
+    boundary = np.minimum(g, r) + 0.5
+    dist = np.abs(t - boundary)
+    unit = qmax * 2.0 ** -23                                          # one fp32 ulp of the row maximum
+    tol = unit * (1.0 + d_ulp[rows])
+    out["max_boundary_dist_ulps"] = float((dist / unit).max())
+    bad = dist > tol
+    assert not bad.any(), (f"{label}: {int(bad.sum())} code mismatches are not within one fp32 ulp of a rounding "
+                           f"boundary (worst {float((dist / unit).max()):.3f} ulps)")
+    assert n_mis <= budget, f"{label}: {n_mis} boundary flips exceed the budget of {budget}"
+    return out
+
+
+def bf16_ulp_distance(a_bits, b_bits):
+    """Distance in bf16 ulps between two arrays of bf16 bit patterns (sign-magnitude aware)."""
+    def key(u):
+        u = np.ascontiguousarray(u, dtype=np.uint16).astype(np.int32)
+        return np.where(u & 0x8000, -(u & 0x7FFF), u & 0x7FFF)
+    return np.abs(key(a_bits) - key(b_bits))
+
+
+def check_y(y_gpu_bits, y_ref_bits, label=""):
+    """bf16 outputs computed from identical accumulators and scales."""
+    d = bf16_ulp_distance(y_gpu_bits, y_ref_bits)
+    assert d.max(initial=0) <= 1, f"{label}: output differs by {d.max()} bf16 ulps (bar: 1)"
+    yg = di.bf16_bits_to_f32(y_gpu_bits).astype(np.float64)
+    yr = di.bf16_bits_to_f32(y_ref_bits).astype(np.float64)
+    rho = np.sqrt((yr ** 2).mean(axis=1, keepdims=True))              # floor for outputs near zero
+    rel = np.abs(yg - yr) / np.maximum(np.abs(yr), np.maximum(rho, 1e-30))
+    assert rel.max(initial=0) <= 1e-2, f"{label}: max relative error {rel.max():.3e} > 1e-2"
+    assert rel.mean() <= 1e-3, f"{label}: mean relative error {rel.mean():.3e} > 1e-3"
+    return dict(max_rel=float(rel.max(initial=0)), mean_rel=float(rel.mean()), ulp1=int((d == 1).sum()))

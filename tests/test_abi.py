@@ -1,0 +1,105 @@
+"""The C-ABI library: it loads, exports every symbol the headers declare, and its
+host-side argument checks answer before anything touches a GPU.  CPU-only (no
+compute call is made here)."""
+import ctypes as C
+import glob
+import os
+import re
+
+import pytest
+
+import paper_2505_18663_amd as dvdq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    names = set()
+    for h in glob.glob(os.path.join(ROOT, "include", "*.h")):
+        text = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names |= set(re.findall(r"\b(dvdq_[a-z0-9_]+)\s*\(", text))
+    return names
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = dvdq.lib()
+    decl = declared_symbols()
+    assert decl, "no declarations found"
+    for name in decl:
+        assert hasattr(L, name), f"{name} declared in include/ but not exported"
+    assert decl == set(dvdq.EXPORTED_SYMBOLS)
+    assert dvdq.version() >= 100
+    assert dvdq.status_string(0) == "ok" and "NULL" in dvdq.status_string(1)
+
+
+FAKE = C.c_void_p(0x1000)       # non-NULL, 16-byte aligned; never dereferenced: every call below fails validation
+ODD = C.c_void_p(0x1008)
+
+
+def test_rotate_quant_argument_errors():
+    f = dvdq.lib().dvdq_rotate_quant
+    assert f(None, 4, 256, 256, 4, FAKE, FAKE, None) == 1
+    assert f(FAKE, 4, 256, 256, 4, None, FAKE, None) == 1
+    assert f(FAKE, 0, 256, 256, 4, FAKE, FAKE, None) == 2          # M < 1
+    assert f(FAKE, 4, 252, 4, 4, FAKE, FAKE, None) == 2            # K not a multiple of 8
+    assert f(FAKE, 4, 768, 512, 4, FAKE, FAKE, None) == 2          # block does not divide K
+    assert f(FAKE, 4, 768, 96, 4, FAKE, FAKE, None) == 2           # block not a power of two
+    assert f(FAKE, 4, 2048, 1024, 4, FAKE, FAKE, None) == 3        # block > 512
+    assert f(FAKE, 4, 256, 256, 5, FAKE, FAKE, None) == 3          # bits
+    assert f(FAKE, 4, 131072, 256, 4, FAKE, FAKE, None) == 3       # K too large
+    assert f(ODD, 4, 256, 256, 4, FAKE, FAKE, None) == 5
+
+
+def test_gemm_argument_errors():
+    f = dvdq.lib().dvdq_w4ax_gemm
+    ok = dict(M=4, N=8, K=64)
+    assert f(None, FAKE, FAKE, FAKE, None, 4, 8, 64, 4, 0, FAKE, None, None) == 1
+    assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 8, 64, 4, 0, None, None, None) == 1
+    assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 0, 64, 4, 0, FAKE, None, None) == 2
+    assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 8, 96, 4, 0, FAKE, None, None) == 2     # K % 64
+    assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 8, 64, 3, 0, FAKE, None, None) == 3
+    assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 8, 64, 4, 7, FAKE, None, None) == 3     # layout
+    assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 8, 64 * 4096, 8, 0, FAKE, None, None) == 3   # accumulator bound
+    assert f(FAKE, FAKE, ODD, FAKE, None, 4, 8, 64, 4, 0, FAKE, None, None) == 5
+    assert f(FAKE, FAKE, FAKE, FAKE, ODD, 4, 8, 64, 4, 0, FAKE, None, None) == 5
+    assert ok
+
+
+def test_qlinear_workspace_and_argument_errors():
+    L = dvdq.lib()
+    M, K = 32760, 1536
+    off = dvdq.qlinear_scale_offset(M, K, 4)
+    need = dvdq.qlinear_workspace_bytes(M, K, 4)
+    assert off >= M * K and off % 256 == 0 and need >= off + 4 * M
+    assert dvdq.qlinear_workspace_bytes(0, K, 4) == 0
+    f = L.dvdq_qlinear
+    assert f(FAKE, FAKE, FAKE, None, M, 64, K, 256, 4, 0, FAKE, None, need, None) == 1
+    assert f(FAKE, FAKE, FAKE, None, M, 64, K, 256, 4, 0, FAKE, C.c_void_p(0x1010), need, None) == 5
+    assert f(FAKE, FAKE, FAKE, None, M, 64, K, 256, 4, 0, FAKE, C.c_void_p(0x1100), need - 1, None) == 4
+    assert f(FAKE, FAKE, FAKE, None, M, 64, K, 1024, 4, 0, FAKE, C.c_void_p(0x1100), need, None) == 2   # 1024 does not divide 1536
+    assert f(FAKE, FAKE, FAKE, None, 8, 64, 2048, 1024, 4, 0, FAKE, C.c_void_p(0x1100), 1 << 20, None) == 3
+    assert f(None, FAKE, FAKE, None, M, 64, K, 256, 4, 0, FAKE, C.c_void_p(0x1100), need, None) == 1
+
+
+def test_prepack_argument_errors_and_size():
+    L = dvdq.lib()
+    assert dvdq.w4_native_bytes(4608, 1536) >= 4608 * 1536 // 2
+    assert dvdq.w4_native_bytes(8, 96) == 0
+    assert L.dvdq_w4_prepack(None, 8, 64, FAKE, None) == 1
+    assert L.dvdq_w4_prepack(FAKE, 8, 96, FAKE, None) == 2
+    assert L.dvdq_w4_prepack(FAKE, 8, 64, ODD, None) == 5
+
+
+def test_bench_helpers_argument_errors():
+    L = dvdq.lib()
+    assert L.dvdq_bench_copy(None, FAKE, 64, None) == 1
+    assert L.dvdq_bench_copy(FAKE, FAKE, 24, None) == 2
+    assert L.dvdq_bench_mfma_i8(0, FAKE, None, None) == 2
+    assert L.dvdq_bench_mfma_i8(4, None, None, None) == 1
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros((4, 256), dtype=torch.bfloat16)
+    with pytest.raises(TypeError):
+        dvdq.rotate_quant(x, 256, 4)
