@@ -16,7 +16,7 @@ import torch
 __all__ = [
     "DvdqError", "DvdqLibraryMissing", "lib", "library_path", "version", "status_string",
     "rotate_quant", "w4ax_gemm", "qlinear", "qlinear_workspace_bytes", "qlinear_scale_offset",
-    "w4_prepack", "w4_native_bytes", "bench_copy", "bench_mfma_i8",
+    "w4_prepack", "w4_native_bytes", "bench_copy", "bench_mfma_i8", "bench_set_gemm_variant",
     "W_CANONICAL", "W_NATIVE", "EXPORTED_SYMBOLS",
 ]
 
@@ -25,7 +25,7 @@ W_CANONICAL, W_NATIVE = 0, 1
 EXPORTED_SYMBOLS = (
     "dvdq_rotate_quant", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_qlinear_workspace_bytes",
     "dvdq_qlinear_scale_offset", "dvdq_w4_prepack", "dvdq_w4_native_bytes", "dvdq_status_string",
-    "dvdq_version", "dvdq_bench_copy", "dvdq_bench_mfma_i8",
+    "dvdq_version", "dvdq_bench_copy", "dvdq_bench_mfma_i8", "dvdq_bench_set_gemm_variant",
 )
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -69,6 +69,8 @@ def lib() -> C.CDLL:
     L.dvdq_version.argtypes = []
     L.dvdq_bench_copy.argtypes = [vp, vp, sz, vp]
     L.dvdq_bench_mfma_i8.argtypes = [i32, vp, C.POINTER(C.c_double), vp]
+    L.dvdq_bench_set_gemm_variant.argtypes = [i32]
+    L.dvdq_bench_set_gemm_variant.restype = i32
     for f in ("dvdq_rotate_quant", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_w4_prepack", "dvdq_version",
               "dvdq_bench_copy", "dvdq_bench_mfma_i8"):
         getattr(L, f).restype = i32
@@ -233,3 +235,7 @@ def bench_mfma_i8(iters: int, sink, stream=None) -> float:
     ops = C.c_double(0.0)
     _check(lib().dvdq_bench_mfma_i8(iters, _ptr(sink), C.byref(ops), _stream(stream)), "dvdq_bench_mfma_i8")
     return ops.value
+
+
+def bench_set_gemm_variant(variant: int) -> None:
+    _check(lib().dvdq_bench_set_gemm_variant(int(variant)), "dvdq_bench_set_gemm_variant")

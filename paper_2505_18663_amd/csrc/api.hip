@@ -103,7 +103,7 @@ int dvdq_qlinear(const void *x_bf16, const uint8_t *w, const float *w_scale, con
 
 size_t dvdq_w4_native_bytes(int64_t N, int64_t K) {
     if (N < 1 || K < 1 || (K % 64) != 0) return 0;
-    return (size_t)N * (size_t)K / 2;
+    return dvdq::w4_native_bytes(N, K);
 }
 
 int dvdq_w4_prepack(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, void *hip_stream) {

@@ -60,4 +60,9 @@ int dvdq_bench_mfma_i8(int iters, int32_t *sink, double *ops_out, void *hip_stre
     return dvdq::check_launch();
 }
 
+int dvdq_bench_set_gemm_variant(int variant) {
+    dvdq::set_gemm_variant(variant);
+    return DVDQ_OK;
+}
+
 }  // extern "C"

@@ -17,6 +17,13 @@ int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w
                      const uint16_t *bias, int64_t M, int64_t N, int64_t K, int w_layout,
                      uint16_t *y, int32_t *acc_out, hipStream_t stream);
 
+int launch_w4ax_gemm_canonical(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
+                               const uint16_t *bias, int64_t M, int64_t N, int64_t K, uint16_t *y, int32_t *acc_out,
+                               hipStream_t stream);
+
+size_t w4_native_bytes(int64_t N, int64_t K);
+void set_gemm_variant(int v);  // benchmark sweeps only; -1 = choose by shape
+
 int launch_w4_prepack(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, hipStream_t stream);
 
 inline int check_launch() { return hipGetLastError() == hipSuccess ? DVDQ_OK : DVDQ_ERR_HIP; }

@@ -1,20 +1,29 @@
-// W4Ax GEMM for gfx950: int8 activation codes x packed INT4 weights on the INT8
-// matrix cores, exact int32 accumulation, dequantizing epilogue to bf16
-// (Sec. 3.2: Y = X^ Lambda W^^T; Sec. 3.1 DeQuant with zero-point 0).
+// W4Ax GEMM for gfx950, fast path for pre-packed ("native") weights: int8
+// activation codes x packed INT4 weights on the INT8 matrix cores, exact int32
+// accumulation, dequantizing epilogue to bf16 (Sec. 3.2: Y = X^ Lambda W^^T;
+// Sec. 3.1 DeQuant with zero-point 0).
 //
-// Weight nibbles are widened to int8 lanes holding 16*code (mask / shift-by-4 of the
-// packed word: the nibble lands in the top half of its byte with the right sign), so
-// the MFMA accumulates 16*acc exactly; the factor is removed by an arithmetic shift
-// before the accumulator is exposed or scaled.  |16 * acc| <= 16 * 127 * 8 * K must
-// stay below 2^31, which the API layer checks.
+// Data movement.  Both operands travel HBM/L2 -> LDS with LDS-direct loads
+// (16 bytes per lane, no VGPR staging) through a ring of STAGES buffers; K is
+// consumed in slices of 128.  Completion is tracked by hand with s_waitcnt vmcnt
+// because the compiler does not order LDS reads after LDS-direct loads.
+//   codes  : [row][128 B], the 16-byte chunk index xor-ed with (row & 7), so the
+//            8 lanes that read the same chunk of 8 consecutive rows hit 8 bank groups;
+//            a wave's load instruction covers 8 full 128-byte rows.
+//   weights: stay packed (two codes per byte) in LDS; the native layout is the LDS
+//            image itself, so a slice is one linear, fully coalesced copy:
+//            [k128 slice][32-row group][k32 step][k16 half][row][8 B].
+//            The 8 bytes hold 16 consecutive channels; byte b of dword d carries
+//            channel 8d+b in its low and channel 8d+b+4 in its high nibble, so that
+//            (p << 4) & 0xF0F0F0F0 and p & 0xF0F0F0F0 are int8 lanes of 16*code in
+//            channel order.  The MFMA then accumulates 16*acc exactly; the factor
+//            is folded into the token scale (a power of two) or shifted out.
 //
-// Tiling: a workgroup of 4 waves (2 x 2) computes a BM x BN tile of Y; each wave a
-// (BM/2) x (BN/2) sub-tile out of 32x32x32 MFMAs.  The weight tile is the MFMA's
-// row operand and the code tile its column operand, so a lane ends up with 4
-// consecutive output channels of one token: one 8-byte bf16 store.  K is consumed in
-// slices of 64 through double-buffered LDS; global loads for slice t+1 are in flight
-// while slice t is multiplied.  LDS rows are 64 bytes with the 16-byte chunk index
-// xor-ed by (row >> 1) & 3 so that 8 consecutive rows hit distinct bank groups.
+// Compute.  A workgroup of WAVES_M x WAVES_N waves owns a BM x BN tile; a wave a
+// (BM/WAVES_M) x (BN/WAVES_N) sub-tile of 32x32x32 MFMAs.  The weight fragment is
+// the MFMA's row operand and the code fragment its column operand, so a lane holds
+// 4 consecutive output channels of one token; lane halves are exchanged
+// (v_permlane32_swap) so that every lane stores 16 contiguous bytes of bf16.
 #include "dvdq_internal.h"
 
 namespace dvdq {
@@ -23,23 +32,12 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int kBK = 64;  // K slice per main-loop step (bytes of int8 codes)
+constexpr int kBK = 128;      // K slice (bytes of int8 codes per row)
+constexpr int kGroup = 32;    // weight rows per native-layout group
+constexpr int kGroupBytes = kGroup * kBK / 2;  // 2048: one group, one K slice, packed
+constexpr int kNPad = 256;    // native layout pads N to a multiple of this
 
-__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 3); }
-
-// 8 packed nibbles -> two dwords of int8 lanes (16*code), channels in natural order.
-template <bool NATIVE>
-__device__ __forceinline__ void widen8(uint32_t p, uint32_t &d0, uint32_t &d1) {
-    const uint32_t lo = (p << 4) & 0xF0F0F0F0u;  // nibbles 0,2,4,6
-    const uint32_t hi = p & 0xF0F0F0F0u;         // nibbles 1,3,5,7
-    if (NATIVE) {  // native order stores channels (0,4,1,5,2,6,3,7) in nibbles 0..7
-        d0 = lo;
-        d1 = hi;
-    } else {       // canonical: nibble i is channel i -> interleave bytes of lo and hi
-        d0 = __builtin_amdgcn_perm(hi, lo, 0x05010400u);
-        d1 = __builtin_amdgcn_perm(hi, lo, 0x07030602u);
-    }
-}
+#define DVDQ_LDS(p) ((__attribute__((address_space(3))) void *)(p))
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
     typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
@@ -47,69 +45,84 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
     return __builtin_bit_cast(uint32_t, p);
 }
 
-template <int BM, int BN, bool NATIVE>
-__global__ __launch_bounds__(256) void w4ax_gemm_kernel(
+// vmcnt-only wait (leave expcnt / lgkmcnt alone): gfx9 encoding, vmcnt = {imm[15:14], imm[3:0]}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is 6 bits");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// Enqueue the LDS-direct loads of K slice `kt` into ring buffer `buf` (this wave's share).
+template <int A_DMA, int W_DMA, int A_STAGE, int STAGE>
+__device__ __forceinline__ void issue_stage(int kt, int buf, uint8_t *smem, int wave, const int8_t *(&a_src)[A_DMA],
+                                            int (&a_koff)[A_DMA], int K, const uint8_t *w_src,
+                                            int64_t w_slice_stride) {
+    uint8_t *sa = smem + buf * STAGE, *sw = sa + A_STAGE;
+#pragma unroll
+    for (int i = 0; i < A_DMA; ++i) {
+        // a slice that runs past K (K % 128 == 64) re-reads valid bytes; its weights are zero
+        const int koff = min(kt * kBK + a_koff[i], K - 16);
+        __builtin_amdgcn_global_load_lds(const_cast<int8_t *>(a_src[i] + koff), DVDQ_LDS(sa + (wave * A_DMA + i) * 1024), 16, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < W_DMA; ++i)
+        __builtin_amdgcn_global_load_lds(const_cast<uint8_t *>(w_src + kt * w_slice_stride + i * 1024),
+                                         DVDQ_LDS(sw + (wave * W_DMA + i) * 1024), 16, 0, 0);
+}
+
+}  // namespace
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int OCC>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_kernel(
     const int8_t *__restrict__ codes, const float *__restrict__ x_scale, const uint8_t *__restrict__ w,
     const float *__restrict__ w_scale, const uint16_t *__restrict__ bias, int M, int N, int K,
-    uint16_t *__restrict__ y, int32_t *__restrict__ acc_out, int tiles_m, int tiles_n) {
-    constexpr int WM = BM / 2, WN = BN / 2;      // wave sub-tile
-    constexpr int TM = WM / 32, TN = WN / 32;    // MFMA tiles per wave
-    constexpr int A_LOADS = BM * kBK / 16 / 256; // 16-byte code loads per thread per slice
-    constexpr int W_LOADS = BN * (kBK / 2) / 16 / 256;
-    static_assert(A_LOADS >= 1 && W_LOADS >= 1, "tile too small for 256 threads");
+    uint16_t *__restrict__ y, int32_t *__restrict__ acc_out, int tiles_m, int tiles_n, int group_n) {
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave sub-tile
+    constexpr int TM = WM / 32, TN = WN / 32;            // MFMA tiles per wave
+    constexpr int A_STAGE = BM * kBK, W_STAGE = BN * kBK / 2, STAGE = A_STAGE + W_STAGE;
+    constexpr int A_DMA = A_STAGE / 1024 / NW;           // LDS-direct loads per wave per slice (1 KB each)
+    constexpr int W_DMA = W_STAGE / 1024 / NW;
+    constexpr int DMA = A_DMA + W_DMA;
+    static_assert(A_DMA * 1024 * NW == A_STAGE && W_DMA * 1024 * NW == W_STAGE, "tile does not split over the waves");
+    static_assert(STAGES >= 2 && (STAGES - 1) * DMA < 64, "too many loads in flight for vmcnt");
 
     extern __shared__ __align__(16) uint8_t smem[];
-    uint8_t *sA = smem;                       // [2][BM][64]
-    uint8_t *sW = smem + 2 * BM * kBK;        // [2][BN][64]
 
-    // XCD-aware tile order: consecutive workgroup ids land on different XCDs, so give
-    // each XCD one contiguous range of tiles (they share code panels in that XCD's L2).
+    // Tile order.  Workgroup ids are dealt round-robin to the 8 XCDs, so give each XCD
+    // a contiguous range of tiles.  Inside the range tiles run over `group_n` output
+    // column tiles fastest, then over token tiles, then over column groups: workgroups
+    // resident together share code panels and a bounded set of weight panels in L2.
     const int total = tiles_m * tiles_n;
-    int tile = blockIdx.x;
+    int t = blockIdx.x;
     const int per_xcd = total / 8;
-    if (tile < per_xcd * 8) tile = (tile % 8) * per_xcd + tile / 8;
-    const int tile_m = tile / tiles_n, tile_n = tile - tile_m * tiles_n;
+    if (t < per_xcd * 8) t = (t % 8) * per_xcd + t / 8;
+    const int per_group = tiles_m * group_n;
+    const int grp = t / per_group;
+    const int in_grp = t - grp * per_group;
+    const int gw = min(group_n, tiles_n - grp * group_n);  // columns in this (possibly last, narrower) group
+    const int tile_m = in_grp / gw, tile_n = grp * group_n + (in_grp - tile_m * gw);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = (wave & 1) * WM, wn = (wave >> 1) * WN;
+    const int wm = (wave % WAVES_M) * WM, wn = (wave / WAVES_M) * WN;
+    const int KT = (K + kBK - 1) / kBK;
+    const int G = ((N + kNPad - 1) / kNPad) * (kNPad / kGroup);  // 32-row groups in the padded weight buffer
 
-    // global -> register staging
-    uint4 ra[A_LOADS], rw[W_LOADS];
-    const int KT = K / kBK;
-    auto load_slice = [&](int kt) {
+    // ---- LDS-direct load addressing (per lane, per load slot)
+    // codes: load slot i of this wave fills LDS rows 8b .. 8b+7 of the stage, b = wave * A_DMA + i
+    const int8_t *a_src[A_DMA];
+    int a_koff[A_DMA];
 #pragma unroll
-        for (int i = 0; i < A_LOADS; ++i) {
-            const int idx = tid + i * 256, row = idx >> 2, chunk = idx & 3;
-            const int gm = min(m0 + row, M - 1);
-            ra[i] = *reinterpret_cast<const uint4 *>(codes + (int64_t)gm * K + kt * kBK + chunk * 16);
-        }
-#pragma unroll
-        for (int i = 0; i < W_LOADS; ++i) {
-            const int idx = tid + i * 256, row = idx >> 1, half = idx & 1;
-            const int gn = min(n0 + row, N - 1);
-            rw[i] = *reinterpret_cast<const uint4 *>(w + (int64_t)gn * (K / 2) + kt * (kBK / 2) + half * 16);
-        }
-    };
-    auto store_slice = [&](int buf) {
-        uint8_t *a = sA + buf * BM * kBK, *b = sW + buf * BN * kBK;
-#pragma unroll
-        for (int i = 0; i < A_LOADS; ++i) {
-            const int idx = tid + i * 256, row = idx >> 2, chunk = idx & 3;
-            *reinterpret_cast<uint4 *>(a + row * kBK + swz(row, chunk) * 16) = ra[i];
-        }
-#pragma unroll
-        for (int i = 0; i < W_LOADS; ++i) {
-            const int idx = tid + i * 256, row = idx >> 1, half = idx & 1;
-            uint4 c0, c1;
-            widen8<NATIVE>(rw[i].x, c0.x, c0.y);
-            widen8<NATIVE>(rw[i].y, c0.z, c0.w);
-            widen8<NATIVE>(rw[i].z, c1.x, c1.y);
-            widen8<NATIVE>(rw[i].w, c1.z, c1.w);
-            *reinterpret_cast<uint4 *>(b + row * kBK + swz(row, 2 * half) * 16) = c0;
-            *reinterpret_cast<uint4 *>(b + row * kBK + swz(row, 2 * half + 1) * 16) = c1;
-        }
-    };
+    for (int i = 0; i < A_DMA; ++i) {
+        const int row = (wave * A_DMA + i) * 8 + (lane >> 3);
+        const int chunk = (lane & 7) ^ (row & 7);
+        a_src[i] = codes + (int64_t)min(m0 + row, M - 1) * K;
+        a_koff[i] = chunk * 16;
+    }
+    // weights: the stage image is one linear run of W_STAGE bytes in the native buffer
+    const uint8_t *w_src = w + (int64_t)(n0 / kGroup) * kGroupBytes + (wave * W_DMA) * 1024 + lane * 16;
+    const int64_t w_slice_stride = (int64_t)G * kGroupBytes;
 
     v16i acc[TN][TM];
 #pragma unroll
@@ -119,27 +132,40 @@ __global__ __launch_bounds__(256) void w4ax_gemm_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    load_slice(0);
-    store_slice(0);
-    __syncthreads();
+    // ---- fragment addressing
+    const int frow = lane & 31, fhalf = lane >> 5;
+    int a_row_off[TM];
+#pragma unroll
+    for (int j = 0; j < TM; ++j) a_row_off[j] = (wm + j * 32 + frow) * kBK;
+    const int a_xor = lane & 7;  // == row & 7: wm and 32 j are multiples of 8
+    const int w_off = (wn / kGroup) * kGroupBytes + fhalf * 256 + frow * 8;
 
-    const int frow = lane & 31, fchunk = lane >> 5;  // fragment row / 16-byte half within a K=32 step
+    // ---- prologue: fill STAGES-1 buffers
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s)
+        if (s < KT) issue_stage<A_DMA, W_DMA, A_STAGE, STAGE>(s, s, smem, wave, a_src, a_koff, K, w_src, w_slice_stride);
+
     for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) load_slice(kt + 1);
-        const uint8_t *a = sA + buf * BM * kBK, *b = sW + buf * BN * kBK;
+        // slice kt has landed once at most the loads of the (STAGES-2) younger slices are outstanding
+        if (kt + STAGES - 2 < KT) wait_vmcnt<(STAGES - 2) * DMA>(); else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();   // everyone's part of slice kt is in LDS; everyone is done reading slice kt-1
+        if (kt + STAGES - 1 < KT) issue_stage<A_DMA, W_DMA, A_STAGE, STAGE>(kt + STAGES - 1, (kt + STAGES - 1) % STAGES, smem, wave, a_src, a_koff, K, w_src,
+                                                        w_slice_stride);
+
+        const uint8_t *sa = smem + (kt % STAGES) * STAGE, *sw = sa + A_STAGE;
 #pragma unroll
         for (int ks = 0; ks < kBK / 32; ++ks) {
             v4i fa[TM], fw[TN];
 #pragma unroll
-            for (int j = 0; j < TM; ++j) {
-                const int row = wm + j * 32 + frow;
-                fa[j] = *reinterpret_cast<const v4i *>(a + row * kBK + swz(row, ks * 2 + fchunk) * 16);
-            }
+            for (int j = 0; j < TM; ++j)
+                fa[j] = *reinterpret_cast<const v4i *>(sa + a_row_off[j] + (((ks * 2 + fhalf) ^ a_xor) << 4));
 #pragma unroll
             for (int i = 0; i < TN; ++i) {
-                const int row = wn + i * 32 + frow;
-                fw[i] = *reinterpret_cast<const v4i *>(b + row * kBK + swz(row, ks * 2 + fchunk) * 16);
+                const uint2 p = *reinterpret_cast<const uint2 *>(sw + w_off + i * kGroupBytes + ks * 512);
+                fw[i][0] = (int)((p.x << 4) & 0xF0F0F0F0u);
+                fw[i][1] = (int)(p.x & 0xF0F0F0F0u);
+                fw[i][2] = (int)((p.y << 4) & 0xF0F0F0F0u);
+                fw[i][3] = (int)(p.y & 0xF0F0F0F0u);
             }
 #pragma unroll
             for (int i = 0; i < TN; ++i)
@@ -147,52 +173,78 @@ __global__ __launch_bounds__(256) void w4ax_gemm_kernel(
                 for (int j = 0; j < TM; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[i], fa[j], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < KT) store_slice(buf ^ 1);
-        __syncthreads();
     }
 
-    // Epilogue.  Accumulator register r of MFMA tile (i, j) in lane l is
-    //   n = n0 + wn + 32 i + 8 (r / 4) + 4 (l / 32) + (r % 4),   m = m0 + wm + 32 j + (l % 32).
-    const bool vec_ok = (N & 3) == 0;
+    // ---- epilogue.  Accumulator register r = 4 g + q of MFMA tile (i, j) in lane l is
+    //   n = n0 + wn + 32 i + 8 g + 4 (l / 32) + q,   m = m0 + wm + 32 j + (l % 32),  value 16 * acc.
+    const bool vec8 = (N & 7) == 0;
 #pragma unroll
     for (int j = 0; j < TM; ++j) {
-        const int m = m0 + wm + j * 32 + (lane & 31);
-        if (m >= M) continue;
-        const float xs = x_scale[m];
+        const int m = m0 + wm + j * 32 + frow;
+        const bool m_ok = m < M;
+        const float xs16 = m_ok ? x_scale[m] * 0.0625f : 0.f;   // folds the factor 16 of the widened weights
 #pragma unroll
         for (int i = 0; i < TN; ++i) {
+            const int nb = n0 + wn + i * 32;   // this MFMA tile's first output channel
+            if (acc_out && m_ok) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = n0 + wn + i * 32 + g * 8 + (lane >> 5) * 4;
-                if (n >= N) continue;
-                int a4[4];
+                for (int g = 0; g < 4; ++g) {
+                    const int n = nb + g * 8 + fhalf * 4;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) a4[r] = acc[i][j][g * 4 + r] >> 4;  // exact: low 4 bits are zero
-                if (vec_ok) {  // n + 3 < N because N % 4 == 0 and n % 4 == 0
-                    const float4 ws = *reinterpret_cast<const float4 *>(w_scale + n);
-                    float o[4] = {(float)a4[0] * xs * ws.x, (float)a4[1] * xs * ws.y, (float)a4[2] * xs * ws.z,
-                                  (float)a4[3] * xs * ws.w};
-                    if (bias) {
-                        const uint2 bb = *reinterpret_cast<const uint2 *>(bias + n);
-                        o[0] += __uint_as_float(bb.x << 16);
-                        o[1] += __uint_as_float(bb.x & 0xFFFF0000u);
-                        o[2] += __uint_as_float(bb.y << 16);
-                        o[3] += __uint_as_float(bb.y & 0xFFFF0000u);
+                    for (int q = 0; q < 4; ++q)
+                        if (n + q < N) acc_out[(int64_t)m * N + n + q] = acc[i][j][g * 4 + q] >> 4;
+                }
+            }
+            if (vec8) {
+                uint32_t pk[4][2];
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = nb + g * 8 + fhalf * 4;
+                    float o[4];
+                    if (n < N) {  // N % 8 == 0 and n % 4 == 0: n + 3 < N as well
+                        const float4 ws = *reinterpret_cast<const float4 *>(w_scale + n);
+                        o[0] = (float)acc[i][j][g * 4 + 0] * xs16 * ws.x;
+                        o[1] = (float)acc[i][j][g * 4 + 1] * xs16 * ws.y;
+                        o[2] = (float)acc[i][j][g * 4 + 2] * xs16 * ws.z;
+                        o[3] = (float)acc[i][j][g * 4 + 3] * xs16 * ws.w;
+                        if (bias) {
+                            const uint2 bb = *reinterpret_cast<const uint2 *>(bias + n);
+                            o[0] += __uint_as_float(bb.x << 16);
+                            o[1] += __uint_as_float(bb.x & 0xFFFF0000u);
+                            o[2] += __uint_as_float(bb.y << 16);
+                            o[3] += __uint_as_float(bb.y & 0xFFFF0000u);
+                        }
+                    } else {
+                        o[0] = o[1] = o[2] = o[3] = 0.f;
                     }
-                    uint2 out;
-                    out.x = pack_bf16x2(o[0], o[1]);
-                    out.y = pack_bf16x2(o[2], o[3]);
-                    *reinterpret_cast<uint2 *>(y + (int64_t)m * N + n) = out;
-                    if (acc_out)
-                        *reinterpret_cast<int4 *>(acc_out + (int64_t)m * N + n) = make_int4(a4[0], a4[1], a4[2], a4[3]);
-                } else {
+                    pk[g][0] = pack_bf16x2(o[0], o[1]);
+                    pk[g][1] = pack_bf16x2(o[2], o[3]);
+                }
+                // lanes l and l+32 hold channels (8g .. 8g+3) and (8g+4 .. 8g+7): swap the upper
+                // half of tile g with the lower half of tile g+1 so each lane owns 8 consecutive channels
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        if (n + r >= N) break;
-                        float o = (float)a4[r] * xs * w_scale[n + r];
-                        if (bias) o += __uint_as_float((uint32_t)bias[n + r] << 16);
-                        y[(int64_t)m * N + n + r] = (uint16_t)(pack_bf16x2(o, 0.f) & 0xFFFFu);
-                        if (acc_out) acc_out[(int64_t)m * N + n + r] = a4[r];
+                for (int g = 0; g < 4; g += 2) {
+#pragma unroll
+                    for (int d = 0; d < 2; ++d) {
+                        auto r = __builtin_amdgcn_permlane32_swap(pk[g][d], pk[g + 1][d], false, false);
+                        pk[g][d] = r[0];
+                        pk[g + 1][d] = r[1];
+                    }
+                    const int n = nb + g * 8 + fhalf * 8;
+                    if (m_ok && n < N)
+                        *reinterpret_cast<uint4 *>(y + (int64_t)m * N + n) =
+                            make_uint4(pk[g][0], pk[g][1], pk[g + 1][0], pk[g + 1][1]);
+                }
+            } else if (m_ok) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = nb + g * 8 + fhalf * 4;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        if (n + q >= N) break;
+                        float o = (float)acc[i][j][g * 4 + q] * xs16 * w_scale[n + q];
+                        if (bias) o += __uint_as_float((uint32_t)bias[n + q] << 16);
+                        y[(int64_t)m * N + n + q] = (uint16_t)(pack_bf16x2(o, 0.f) & 0xFFFFu);
                     }
                 }
             }
@@ -200,55 +252,87 @@ __global__ __launch_bounds__(256) void w4ax_gemm_kernel(
     }
 }
 
-// canonical [N, K/2] -> native: same geometry, nibbles of every 32-bit word reordered
-// from channel order (0..7) to (0,4,1,5,2,6,3,7) so that widening needs no byte shuffle.
-__global__ void w4_prepack_kernel(const uint32_t *__restrict__ src, uint32_t *__restrict__ dst, int64_t words) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= words) return;
-    const uint32_t p = src[i];
+namespace {
+
+// canonical [N, K/2] -> native layout (see the top of this file).  One thread per
+// output dword (8 channels).  Rows >= N and channels >= K are written as zero.
+__global__ __launch_bounds__(256) void w4_prepack_kernel(const uint8_t *__restrict__ src, uint32_t *__restrict__ dst,
+                                                         int N, int K, int G, int KT) {
+    const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t words = (int64_t)KT * G * (kGroupBytes / 4);
+    if (o >= words) return;
+    int64_t v = o;
+    const int d = (int)(v & 1); v >>= 1;
+    const int r = (int)(v & 31); v >>= 5;
+    const int half = (int)(v & 1); v >>= 1;
+    const int ks = (int)(v & 3); v >>= 2;
+    const int g = (int)(v % G);
+    const int kt = (int)(v / G);
+    const int n = g * kGroup + r;
+    const int k = kt * kBK + ks * 32 + half * 16 + d * 8;
+    uint32_t p = 0;
+    if (n < N && k < K) p = *reinterpret_cast<const uint32_t *>(src + (int64_t)n * (K / 2) + k / 2);
+    // nibble i of p is channel k+i; wanted: byte b = channel b (low nibble) | channel b+4 (high nibble)
     uint32_t q = 0;
-    const int order[8] = {0, 4, 1, 5, 2, 6, 3, 7};
 #pragma unroll
-    for (int nib = 0; nib < 8; ++nib) q |= ((p >> (4 * order[nib])) & 0xFu) << (4 * nib);
-    dst[i] = q;
+    for (int b = 0; b < 4; ++b) {
+        q |= ((p >> (4 * b)) & 0xFu) << (8 * b);
+        q |= ((p >> (4 * (b + 4))) & 0xFu) << (8 * b + 4);
+    }
+    dst[o] = q;
 }
 
-template <int BM, int BN>
-int launch_tile(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
-                const uint16_t *bias, int M, int N, int K, int w_layout, uint16_t *y, int32_t *acc_out,
-                hipStream_t stream) {
+int g_variant = -1;  // -1: pick by shape; set by the benchmark's sweep hook
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int OCC>
+int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
+                  const uint16_t *bias, int M, int N, int K, uint16_t *y, int32_t *acc_out, hipStream_t stream) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    const size_t smem = 2 * (size_t)(BM + BN) * kBK;
-    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
-    if (w_layout == DVDQ_W_NATIVE) {
-        auto k = w4ax_gemm_kernel<BM, BN, true>;
-        hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        hipLaunchKernelGGL(k, grid, block, smem, stream, codes, x_scale, w, w_scale, bias, M, N, K, y, acc_out,
-                           tiles_m, tiles_n);
-    } else {
-        auto k = w4ax_gemm_kernel<BM, BN, false>;
-        hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        hipLaunchKernelGGL(k, grid, block, smem, stream, codes, x_scale, w, w_scale, bias, M, N, K, y, acc_out,
-                           tiles_m, tiles_n);
-    }
+    // keep the weight panels of one column group around 2 MB (half an XCD's L2)
+    int group_n = (int)((2 << 20) / ((int64_t)BN * K / 2));
+    group_n = group_n < 1 ? 1 : (group_n > tiles_n ? tiles_n : group_n);
+    const size_t smem = (size_t)STAGES * (BM * kBK + BN * kBK / 2);
+    auto k = w4ax_gemm_native_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, OCC>;
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipLaunchKernelGGL(k, dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WAVES_M * WAVES_N), smem, stream, codes,
+                       x_scale, w, w_scale, bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n);
     return check_launch();
 }
 
 }  // namespace
 
+void set_gemm_variant(int v) { g_variant = v; }
+
 int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                      const uint16_t *bias, int64_t M, int64_t N, int64_t K, int w_layout, uint16_t *y,
                      int32_t *acc_out, hipStream_t stream) {
-    return launch_tile<256, 256>(codes, x_scale, w, w_scale, bias, (int)M, (int)N, (int)K, w_layout, y, acc_out,
-                                 stream);
+    if (w_layout == DVDQ_W_CANONICAL)
+        return launch_w4ax_gemm_canonical(codes, x_scale, w, w_scale, bias, M, N, K, y, acc_out, stream);
+    const int m = (int)M, n = (int)N, k = (int)K;
+#define DVDQ_GEMM_ARGS codes, x_scale, w, w_scale, bias, m, n, k, y, acc_out, stream
+    switch (g_variant) {
+        case 1: return launch_native<256, 256, 2, 2, 3, 1>(DVDQ_GEMM_ARGS);
+        case 2: return launch_native<128, 256, 2, 2, 2, 2>(DVDQ_GEMM_ARGS);
+        case 3: return launch_native<256, 256, 4, 2, 3, 1>(DVDQ_GEMM_ARGS);
+        case 4: return launch_native<256, 128, 2, 2, 2, 2>(DVDQ_GEMM_ARGS);
+        case 5: return launch_native<256, 256, 2, 2, 2, 1>(DVDQ_GEMM_ARGS);
+        default: return launch_native<128, 256, 2, 2, 2, 2>(DVDQ_GEMM_ARGS);
+    }
+#undef DVDQ_GEMM_ARGS
+}
+
+size_t w4_native_bytes(int64_t N, int64_t K) {
+    const int64_t npad = (N + kNPad - 1) / kNPad * kNPad, kpad = (K + kBK - 1) / kBK * kBK;
+    return (size_t)(npad * kpad / 2);
 }
 
 int launch_w4_prepack(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, hipStream_t stream) {
-    const int64_t words = N * K / 8;
-    const int threads = 256;
-    const int64_t blocks = (words + threads - 1) / threads;
-    hipLaunchKernelGGL(w4_prepack_kernel, dim3((unsigned)blocks), dim3(threads), 0, stream,
-                       reinterpret_cast<const uint32_t *>(w_canonical), reinterpret_cast<uint32_t *>(w_native), words);
+    const int G = (int)((N + kNPad - 1) / kNPad * (kNPad / kGroup));
+    const int KT = (int)((K + kBK - 1) / kBK);
+    const int64_t words = (int64_t)KT * G * (kGroupBytes / 4);
+    const int64_t blocks = (words + 255) / 256;
+    hipLaunchKernelGGL(w4_prepack_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, w_canonical,
+                       reinterpret_cast<uint32_t *>(w_native), (int)N, (int)K, G, KT);
     return check_launch();
 }
 
