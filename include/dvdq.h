@@ -92,8 +92,8 @@ int dvdq_rotate_quant(const void *x_bf16, int64_t M, int64_t K, int had_block, i
  *   acc_out   out  int32 [M, N] or NULL; when given, receives the raw accumulators
  *                  (parity hook; costs extra bandwidth)
  *
- * K must be a multiple of 64 (DVDQ_ERR_SHAPE).  Any M >= 1, N >= 1; ragged tiles
- * are handled inside.
+ * K must be a multiple of 64 (DVDQ_ERR_SHAPE), and of 128 with the native layout
+ * (DVDQ_ERR_UNSUPPORTED otherwise).  Any M >= 1, N >= 1; ragged tiles are handled inside.
  */
 int dvdq_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                    const void *bias_bf16, int64_t M, int64_t N, int64_t K, int act_bits, int w_layout,
@@ -117,7 +117,8 @@ size_t dvdq_qlinear_scale_offset(int64_t M, int64_t K, int act_bits);
  * One-time, offline: reorder canonical packed weights into the GEMM kernel's
  * native layout (the rotated, quantized weights of Sec. 3.2 are fixed after
  * quantization, so this runs once per layer).  w_native must hold
- * dvdq_w4_native_bytes(N, K) bytes.  K multiple of 64.
+ * dvdq_w4_native_bytes(N, K) bytes.  K must be a multiple of 128 (DVDQ_ERR_UNSUPPORTED
+ * otherwise; dvdq_w4_native_bytes then returns 0).
  */
 int dvdq_w4_prepack(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, void *hip_stream);
 size_t dvdq_w4_native_bytes(int64_t N, int64_t K);

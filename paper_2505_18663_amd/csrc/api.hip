@@ -34,6 +34,7 @@ int check_gemm(const void *codes, const void *x_scale, const void *w, const void
     if (!codes || !x_scale || !w || !w_scale || !y) return DVDQ_ERR_NULL;
     if (M < 1 || N < 1 || K < 1 || (K % 64) != 0) return DVDQ_ERR_SHAPE;
     if (!bits_ok(act_bits) || (w_layout != DVDQ_W_CANONICAL && w_layout != DVDQ_W_NATIVE)) return DVDQ_ERR_UNSUPPORTED;
+    if (w_layout == DVDQ_W_NATIVE && (K % 128) != 0) return DVDQ_ERR_UNSUPPORTED;
     if (M > 0x7FFFFFFF || N > 0x7FFFFFFF || K > 0x7FFFFFFF) return DVDQ_ERR_UNSUPPORTED;
     // the kernel accumulates 16 * sum(code * w): |code| <= qmax, |w| <= 8
     const int64_t qmax = (1 << (act_bits - 1)) - 1;
@@ -102,13 +103,14 @@ int dvdq_qlinear(const void *x_bf16, const uint8_t *w, const float *w_scale, con
 }
 
 size_t dvdq_w4_native_bytes(int64_t N, int64_t K) {
-    if (N < 1 || K < 1 || (K % 64) != 0) return 0;
+    if (N < 1 || K < 1 || (K % 128) != 0) return 0;
     return dvdq::w4_native_bytes(N, K);
 }
 
 int dvdq_w4_prepack(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, void *hip_stream) {
     if (!w_canonical || !w_native) return DVDQ_ERR_NULL;
-    if (N < 1 || K < 1 || (K % 64) != 0) return DVDQ_ERR_SHAPE;
+    if (N < 1 || K < 1 || (K % 2) != 0) return DVDQ_ERR_SHAPE;
+    if ((K % 128) != 0) return DVDQ_ERR_UNSUPPORTED;
     if (N > 0x7FFFFFFF || K > 0x7FFFFFFF) return DVDQ_ERR_UNSUPPORTED;
     if (!aligned16(w_canonical) || !aligned16(w_native)) return DVDQ_ERR_ALIGN;
     return dvdq::launch_w4_prepack(w_canonical, N, K, w_native, static_cast<hipStream_t>(hip_stream));

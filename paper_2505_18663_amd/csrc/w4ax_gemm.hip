@@ -7,9 +7,9 @@
 // (16 bytes per lane, no VGPR staging) through a ring of STAGES buffers; K is
 // consumed in slices of 128.  Completion is tracked by hand with s_waitcnt vmcnt
 // because the compiler does not order LDS reads after LDS-direct loads.
-//   codes  : [row][128 B], the 16-byte chunk index xor-ed with (row & 7), so the
-//            8 lanes that read the same chunk of 8 consecutive rows hit 8 bank groups;
-//            a wave's load instruction covers 8 full 128-byte rows.
+//   codes  : [row][128 B], the 16-byte chunk index xor-ed with (row & 7), so the 8 lanes
+//            that read the same chunk of 8 consecutive rows cover a whole 128-byte LDS
+//            bank line; a wave's load instruction covers 8 full 128-byte rows.
 //   weights: stay packed (two codes per byte) in LDS; the native layout is the LDS
 //            image itself, so a slice is one linear, fully coalesced copy:
 //            [k128 slice][32-row group][k32 step][k16 half][row][8 B].
@@ -52,27 +52,50 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-// Enqueue the LDS-direct loads of K slice `kt` into ring buffer `buf` (this wave's share).
-template <int A_DMA, int W_DMA, int A_STAGE, int STAGE>
-__device__ __forceinline__ void issue_stage(int kt, int buf, uint8_t *smem, int wave, const int8_t *(&a_src)[A_DMA],
-                                            int (&a_koff)[A_DMA], int K, const uint8_t *w_src,
-                                            int64_t w_slice_stride) {
-    uint8_t *sa = smem + buf * STAGE, *sw = sa + A_STAGE;
-#pragma unroll
-    for (int i = 0; i < A_DMA; ++i) {
-        // a slice that runs past K (K % 128 == 64) re-reads valid bytes; its weights are zero
-        const int koff = min(kt * kBK + a_koff[i], K - 16);
-        __builtin_amdgcn_global_load_lds(const_cast<int8_t *>(a_src[i] + koff), DVDQ_LDS(sa + (wave * A_DMA + i) * 1024), 16, 0, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < W_DMA; ++i)
-        __builtin_amdgcn_global_load_lds(const_cast<uint8_t *>(w_src + kt * w_slice_stride + i * 1024),
-                                         DVDQ_LDS(sw + (wave * W_DMA + i) * 1024), 16, 0, 0);
+// One LDS-direct load: 16 bytes per lane from global address `sbase` + `voff` (sbase
+// wave-uniform, voff per lane) to LDS address `lds_base` + 16 * lane (lds_base
+// wave-uniform).  Written as inline assembly so that the compiler's waitcnt insertion
+// does not know about it: with the builtin it makes every later LDS read wait for ALL
+// outstanding LDS-direct loads (it cannot tell the ring buffers apart), which
+// serializes the pipeline.  Completion is awaited by hand (wait_vmcnt) before the
+// workgroup barrier that publishes a buffer.
+__device__ __forceinline__ void lds_direct_load16(const void *sbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(voff), "s"(sbase), "s"(lds_base)
+                 : "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void *p) {
+    return (uint32_t)(uintptr_t)DVDQ_LDS(p);
+}
+
+// make a 64-bit pointer provably wave-uniform (lives in SGPRs)
+template <typename T>
+__device__ __forceinline__ const T *uniform_ptr(const T *p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const T *>(((uint64_t)hi << 32) | lo);
 }
 
 }  // namespace
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int OCC>
+// Tile order.  Tiles are numbered so that `group_n` output-column tiles run fastest,
+// then token tiles, then column groups: tiles with neighbouring numbers share code
+// panels and a bounded set of weight panels, which is what stays in an XCD's L2.
+__device__ __forceinline__ void tile_origin(int t, int tiles_m, int tiles_n, int group_n, int BM, int BN, int &m0,
+                                            int &n0) {
+    const int per_group = tiles_m * group_n;
+    const int grp = t / per_group;
+    const int in_grp = t - grp * per_group;
+    const int gw = min(group_n, tiles_n - grp * group_n);  // columns in this (possibly last, narrower) group
+    const int tile_m = in_grp / gw;
+    m0 = tile_m * BM;
+    n0 = (grp * group_n + (in_grp - tile_m * gw)) * BN;
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int OCC, int DBG = 0>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_kernel(
     const int8_t *__restrict__ codes, const float *__restrict__ x_scale, const uint8_t *__restrict__ w,
     const float *__restrict__ w_scale, const uint16_t *__restrict__ bias, int M, int N, int K,
@@ -84,45 +107,64 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     constexpr int A_DMA = A_STAGE / 1024 / NW;           // LDS-direct loads per wave per slice (1 KB each)
     constexpr int W_DMA = W_STAGE / 1024 / NW;
     constexpr int DMA = A_DMA + W_DMA;
+    // With 3 or more buffers the slice after the current one is already published, so the
+    // first fragments of slice q+1 are fetched while the last MFMAs of slice q run.
+    constexpr int AHEAD = STAGES >= 3 ? 1 : 0;
     static_assert(A_DMA * 1024 * NW == A_STAGE && W_DMA * 1024 * NW == W_STAGE, "tile does not split over the waves");
     static_assert(STAGES >= 2 && (STAGES - 1) * DMA < 64, "too many loads in flight for vmcnt");
 
     extern __shared__ __align__(16) uint8_t smem[];
+    const uint32_t smem_base = lds_address(smem);
 
-    // Tile order.  Workgroup ids are dealt round-robin to the 8 XCDs, so give each XCD
-    // a contiguous range of tiles.  Inside the range tiles run over `group_n` output
-    // column tiles fastest, then over token tiles, then over column groups: workgroups
-    // resident together share code panels and a bounded set of weight panels in L2.
-    const int total = tiles_m * tiles_n;
-    int t = blockIdx.x;
-    const int per_xcd = total / 8;
-    if (t < per_xcd * 8) t = (t % 8) * per_xcd + t / 8;
-    const int per_group = tiles_m * group_n;
-    const int grp = t / per_group;
-    const int in_grp = t - grp * per_group;
-    const int gw = min(group_n, tiles_n - grp * group_n);  // columns in this (possibly last, narrower) group
-    const int tile_m = in_grp / gw, tile_n = grp * group_n + (in_grp - tile_m * gw);
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = (wave % WAVES_M) * WM, wn = (wave / WAVES_M) * WN;
-    const int KT = (K + kBK - 1) / kBK;
+    const int KT = K / kBK;
     const int G = ((N + kNPad - 1) / kNPad) * (kNPad / kGroup);  // 32-row groups in the padded weight buffer
-
-    // ---- LDS-direct load addressing (per lane, per load slot)
-    // codes: load slot i of this wave fills LDS rows 8b .. 8b+7 of the stage, b = wave * A_DMA + i
-    const int8_t *a_src[A_DMA];
-    int a_koff[A_DMA];
-#pragma unroll
-    for (int i = 0; i < A_DMA; ++i) {
-        const int row = (wave * A_DMA + i) * 8 + (lane >> 3);
-        const int chunk = (lane & 7) ^ (row & 7);
-        a_src[i] = codes + (int64_t)min(m0 + row, M - 1) * K;
-        a_koff[i] = chunk * 16;
-    }
-    // weights: the stage image is one linear run of W_STAGE bytes in the native buffer
-    const uint8_t *w_src = w + (int64_t)(n0 / kGroup) * kGroupBytes + (wave * W_DMA) * 1024 + lane * 16;
     const int64_t w_slice_stride = (int64_t)G * kGroupBytes;
+
+    // Persistent workgroups.  Workgroup ids are dealt round-robin to the 8 XCDs; the j-th
+    // tile of workgroup b is number j * grid + (b % 8) * (grid / 8) + b / 8, so the
+    // workgroups of one XCD work on one contiguous run of tile numbers at a time.
+    const int total = tiles_m * tiles_n;
+    const int grid = gridDim.x;  // multiple of 8
+    const int first_tile = (blockIdx.x % 8) * (grid / 8) + blockIdx.x / 8;
+    const int my_tiles = first_tile < total ? (total - 1 - first_tile) / grid + 1 : 0;
+    const int items = my_tiles * KT;  // one item = one K slice of one tile
+
+    // ---- LDS-direct load addressing: wave-uniform base pointer + per-lane 32-bit offset.
+    // codes: load slot i of this wave fills LDS rows 8b .. 8b+7 of the stage, b = wave * A_DMA + i;
+    // LDS position p of a row holds the row's 16-byte chunk p ^ (row & 7).
+    int a_row[A_DMA];
+    uint32_t a_voff[A_DMA];
+#pragma unroll
+    for (int i = 0; i < A_DMA; ++i) a_row[i] = (wave * A_DMA + i) * 8 + (lane >> 3);
+    // weights: a stage image is one linear run of W_STAGE bytes in the native buffer
+    const uint32_t w_voff = (uint32_t)(wave * W_DMA) * 1024 + lane * 16;
+    const int8_t *a_base = codes;   // start of the tile's first code row, advanced by 128 per slice
+    const uint8_t *w_base = w;      // start of the tile's weight image in slice 0, advanced per slice
+    int issue_tile = 0, issue_kt = 0;   // next item to enqueue
+    auto issue_next = [&] __device__(int buf) {
+        if (issue_kt == 0) {
+            int m0, n0;
+            tile_origin(first_tile + issue_tile * grid, tiles_m, tiles_n, group_n, BM, BN, m0, n0);
+            a_base = uniform_ptr(codes + (int64_t)m0 * K);
+            w_base = uniform_ptr(w + (int64_t)(n0 / kGroup) * kGroupBytes);
+#pragma unroll
+            for (int i = 0; i < A_DMA; ++i) {
+                const int row = min(a_row[i], M - 1 - m0);   // rows past M re-read the last valid row
+                a_voff[i] = (uint32_t)row * K + (((lane & 7) ^ (a_row[i] & 7)) << 4);
+            }
+        }
+        const uint32_t sa = smem_base + buf * STAGE, sw = sa + A_STAGE;
+#pragma unroll
+        for (int i = 0; i < A_DMA; ++i) lds_direct_load16(a_base, a_voff[i], sa + (wave * A_DMA + i) * 1024);
+#pragma unroll
+        for (int i = 0; i < W_DMA; ++i) lds_direct_load16(w_base, w_voff + i * 1024, sw + (wave * W_DMA + i) * 1024);
+        a_base += kBK;
+        w_base += w_slice_stride;
+        if (++issue_kt == KT) { issue_kt = 0; ++issue_tile; }
+    };
 
     v16i acc[TN][TM];
 #pragma unroll
@@ -132,7 +174,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    // ---- fragment addressing
+    // ---- fragment addressing: MFMA operand row = lane % 32, K half = lane / 32
     const int frow = lane & 31, fhalf = lane >> 5;
     int a_row_off[TM];
 #pragma unroll
@@ -140,113 +182,160 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     const int a_xor = lane & 7;  // == row & 7: wm and 32 j are multiples of 8
     const int w_off = (wn / kGroup) * kGroupBytes + fhalf * 256 + frow * 8;
 
-    // ---- prologue: fill STAGES-1 buffers
+    // fragments of one K=32 step: TM code fragments (16 B) and TN packed weight fragments (8 B)
+    struct Frags { v4i a[TM]; uint2 w[TN]; };
+    auto load_frags = [&] __device__(Frags &f, int buf, int ks) {
+        const uint8_t *sa = smem + buf * STAGE, *sw = sa + A_STAGE;
 #pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s)
-        if (s < KT) issue_stage<A_DMA, W_DMA, A_STAGE, STAGE>(s, s, smem, wave, a_src, a_koff, K, w_src, w_slice_stride);
-
-    for (int kt = 0; kt < KT; ++kt) {
-        // slice kt has landed once at most the loads of the (STAGES-2) younger slices are outstanding
-        if (kt + STAGES - 2 < KT) wait_vmcnt<(STAGES - 2) * DMA>(); else wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();   // everyone's part of slice kt is in LDS; everyone is done reading slice kt-1
-        if (kt + STAGES - 1 < KT) issue_stage<A_DMA, W_DMA, A_STAGE, STAGE>(kt + STAGES - 1, (kt + STAGES - 1) % STAGES, smem, wave, a_src, a_koff, K, w_src,
-                                                        w_slice_stride);
-
-        const uint8_t *sa = smem + (kt % STAGES) * STAGE, *sw = sa + A_STAGE;
-#pragma unroll
-        for (int ks = 0; ks < kBK / 32; ++ks) {
-            v4i fa[TM], fw[TN];
-#pragma unroll
-            for (int j = 0; j < TM; ++j)
-                fa[j] = *reinterpret_cast<const v4i *>(sa + a_row_off[j] + (((ks * 2 + fhalf) ^ a_xor) << 4));
-#pragma unroll
-            for (int i = 0; i < TN; ++i) {
-                const uint2 p = *reinterpret_cast<const uint2 *>(sw + w_off + i * kGroupBytes + ks * 512);
-                fw[i][0] = (int)((p.x << 4) & 0xF0F0F0F0u);
-                fw[i][1] = (int)(p.x & 0xF0F0F0F0u);
-                fw[i][2] = (int)((p.y << 4) & 0xF0F0F0F0u);
-                fw[i][3] = (int)(p.y & 0xF0F0F0F0u);
-            }
-#pragma unroll
-            for (int i = 0; i < TN; ++i)
-#pragma unroll
-                for (int j = 0; j < TM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[i], fa[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TM; ++j) {
+            if (DBG & 4) { f.a[j][0] = lane + buf; f.a[j][1] = j; f.a[j][2] = ks; f.a[j][3] = 3; continue; }
+            f.a[j] = *reinterpret_cast<const v4i *>(sa + a_row_off[j] + (((ks * 2 + fhalf) ^ a_xor) << 4));
         }
-    }
-
-    // ---- epilogue.  Accumulator register r = 4 g + q of MFMA tile (i, j) in lane l is
-    //   n = n0 + wn + 32 i + 8 g + 4 (l / 32) + q,   m = m0 + wm + 32 j + (l % 32),  value 16 * acc.
-    const bool vec8 = (N & 7) == 0;
-#pragma unroll
-    for (int j = 0; j < TM; ++j) {
-        const int m = m0 + wm + j * 32 + frow;
-        const bool m_ok = m < M;
-        const float xs16 = m_ok ? x_scale[m] * 0.0625f : 0.f;   // folds the factor 16 of the widened weights
 #pragma unroll
         for (int i = 0; i < TN; ++i) {
-            const int nb = n0 + wn + i * 32;   // this MFMA tile's first output channel
-            if (acc_out && m_ok) {
+            if (DBG & 4) { f.w[i].x = lane * 3 + buf + i; f.w[i].y = ks; continue; }
+            f.w[i] = *reinterpret_cast<const uint2 *>(sw + w_off + i * kGroupBytes + ks * 512);
+        }
+    };
+    auto mma_step = [&] __device__(const Frags &f) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = nb + g * 8 + fhalf * 4;
+        for (int i = 0; i < TN; ++i) {
+            v4i fw;   // int8 lanes of 16 * code, channel order
+            fw[0] = (int)((f.w[i].x << 4) & 0xF0F0F0F0u);
+            fw[1] = (int)(f.w[i].x & 0xF0F0F0F0u);
+            fw[2] = (int)((f.w[i].y << 4) & 0xF0F0F0F0u);
+            fw[3] = (int)(f.w[i].y & 0xF0F0F0F0u);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        if (n + q < N) acc_out[(int64_t)m * N + n + q] = acc[i][j][g * 4 + q] >> 4;
+            for (int j = 0; j < TM; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw, f.a[j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    // ---- prologue: fill STAGES-1 buffers; with look-ahead also publish slice 0 and fetch its first fragments
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s)
+        if (s < items && !(DBG & 1)) issue_next(s);
+    Frags f0, f1;
+    if (AHEAD && items > 0) {
+        if (STAGES - 2 < items) wait_vmcnt<(STAGES - 2) * DMA>(); else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        load_frags(f0, 0, 0);
+    }
+
+    int kt = 0, tile_j = 0;
+    for (int q = 0; q < items; ++q) {
+        // Publish slice q + AHEAD: it has landed once at most the loads of the
+        // (STAGES - 2 - AHEAD) younger slices are outstanding (a wave's vector memory
+        // operations complete in issue order).  The barrier also means that everyone is
+        // done reading slice q-1, whose buffer the next load overwrites.
+        if (!(DBG & 2)) {
+            if (q + STAGES - 2 < items) wait_vmcnt<(STAGES - 2 - AHEAD) * DMA>(); else wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+        }
+        if (q + STAGES - 1 < items && !(DBG & 1)) issue_next((q + STAGES - 1) % STAGES);
+
+        // Software pipeline over the four K=32 steps of the slice: the fragments of step s+1 are
+        // requested before the MFMAs of step s are issued.  The scheduling barriers keep the
+        // compiler from sinking the LDS reads back down to their first use.
+        const int buf = q % STAGES;
+        if (!AHEAD) load_frags(f0, buf, 0);
+        load_frags(f1, buf, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_step(f0);
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(f0, buf, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_step(f1);
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(f1, buf, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_step(f0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (AHEAD) load_frags(f0, (q + 1) % STAGES, 0);   // after the last slice: stale but in-bounds, unused
+        __builtin_amdgcn_sched_barrier(0);
+        mma_step(f1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (++kt < KT) continue;
+
+        // ---- epilogue of tile tile_j.  Accumulator register r = 4 g + e of MFMA tile (i, j) in lane l is
+        //   n = n0 + wn + 32 i + 8 g + 4 (l / 32) + e,   m = m0 + wm + 32 j + (l % 32),  value 16 * acc.
+        int m0, n0;
+        tile_origin(first_tile + tile_j * grid, tiles_m, tiles_n, group_n, BM, BN, m0, n0);
+        kt = 0;
+        ++tile_j;
+        const bool vec8 = (N & 7) == 0;
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int m = m0 + wm + j * 32 + frow;
+            const bool m_ok = m < M;
+            const float xs16 = m_ok ? x_scale[m] * 0.0625f : 0.f;   // folds the factor 16 of the widened weights
+#pragma unroll
+            for (int i = 0; i < TN; ++i) {
+                const int nb = n0 + wn + i * 32;   // this MFMA tile's first output channel
+                if (acc_out && m_ok) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int n = nb + g * 8 + fhalf * 4;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (n + e < N) acc_out[(int64_t)m * N + n + e] = acc[i][j][g * 4 + e] >> 4;
+                    }
                 }
-            }
-            if (vec8) {
-                uint32_t pk[4][2];
+                if (vec8) {
+                    uint32_t pk[4][2];
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = nb + g * 8 + fhalf * 4;
-                    float o[4];
-                    if (n < N) {  // N % 8 == 0 and n % 4 == 0: n + 3 < N as well
-                        const float4 ws = *reinterpret_cast<const float4 *>(w_scale + n);
-                        o[0] = (float)acc[i][j][g * 4 + 0] * xs16 * ws.x;
-                        o[1] = (float)acc[i][j][g * 4 + 1] * xs16 * ws.y;
-                        o[2] = (float)acc[i][j][g * 4 + 2] * xs16 * ws.z;
-                        o[3] = (float)acc[i][j][g * 4 + 3] * xs16 * ws.w;
-                        if (bias) {
-                            const uint2 bb = *reinterpret_cast<const uint2 *>(bias + n);
-                            o[0] += __uint_as_float(bb.x << 16);
-                            o[1] += __uint_as_float(bb.x & 0xFFFF0000u);
-                            o[2] += __uint_as_float(bb.y << 16);
-                            o[3] += __uint_as_float(bb.y & 0xFFFF0000u);
+                    for (int g = 0; g < 4; ++g) {
+                        const int n = nb + g * 8 + fhalf * 4;
+                        float o[4];
+                        if (n < N) {  // N % 8 == 0 and n % 4 == 0: n + 3 < N as well
+                            const float4 ws = *reinterpret_cast<const float4 *>(w_scale + n);
+                            o[0] = (float)acc[i][j][g * 4 + 0] * xs16 * ws.x;
+                            o[1] = (float)acc[i][j][g * 4 + 1] * xs16 * ws.y;
+                            o[2] = (float)acc[i][j][g * 4 + 2] * xs16 * ws.z;
+                            o[3] = (float)acc[i][j][g * 4 + 3] * xs16 * ws.w;
+                            if (bias) {
+                                const uint2 bb = *reinterpret_cast<const uint2 *>(bias + n);
+                                o[0] += __uint_as_float(bb.x << 16);
+                                o[1] += __uint_as_float(bb.x & 0xFFFF0000u);
+                                o[2] += __uint_as_float(bb.y << 16);
+                                o[3] += __uint_as_float(bb.y & 0xFFFF0000u);
+                            }
+                        } else {
+                            o[0] = o[1] = o[2] = o[3] = 0.f;
                         }
-                    } else {
-                        o[0] = o[1] = o[2] = o[3] = 0.f;
+                        pk[g][0] = pack_bf16x2(o[0], o[1]);
+                        pk[g][1] = pack_bf16x2(o[2], o[3]);
                     }
-                    pk[g][0] = pack_bf16x2(o[0], o[1]);
-                    pk[g][1] = pack_bf16x2(o[2], o[3]);
-                }
-                // lanes l and l+32 hold channels (8g .. 8g+3) and (8g+4 .. 8g+7): swap the upper
-                // half of tile g with the lower half of tile g+1 so each lane owns 8 consecutive channels
+                    // lanes l and l+32 hold channels (8g .. 8g+3) and (8g+4 .. 8g+7): swap the upper
+                    // half of tile g with the lower half of tile g+1 so each lane owns 8 consecutive channels
 #pragma unroll
-                for (int g = 0; g < 4; g += 2) {
+                    for (int g = 0; g < 4; g += 2) {
 #pragma unroll
-                    for (int d = 0; d < 2; ++d) {
-                        auto r = __builtin_amdgcn_permlane32_swap(pk[g][d], pk[g + 1][d], false, false);
-                        pk[g][d] = r[0];
-                        pk[g + 1][d] = r[1];
+                        for (int d = 0; d < 2; ++d) {
+                            auto r = __builtin_amdgcn_permlane32_swap(pk[g][d], pk[g + 1][d], false, false);
+                            pk[g][d] = r[0];
+                            pk[g + 1][d] = r[1];
+                        }
+                        const int n = nb + g * 8 + fhalf * 8;
+                        if (m_ok && n < N && (!(DBG & 8) || pk[g][0] == 0x12345678u))
+                            *reinterpret_cast<uint4 *>(y + (int64_t)m * N + n) =
+                                make_uint4(pk[g][0], pk[g][1], pk[g + 1][0], pk[g + 1][1]);
                     }
-                    const int n = nb + g * 8 + fhalf * 8;
-                    if (m_ok && n < N)
-                        *reinterpret_cast<uint4 *>(y + (int64_t)m * N + n) =
-                            make_uint4(pk[g][0], pk[g][1], pk[g + 1][0], pk[g + 1][1]);
-                }
-            } else if (m_ok) {
+                } else if (m_ok) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = nb + g * 8 + fhalf * 4;
+                    for (int g = 0; g < 4; ++g) {
+                        const int n = nb + g * 8 + fhalf * 4;
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        if (n + q >= N) break;
-                        float o = (float)acc[i][j][g * 4 + q] * xs16 * w_scale[n + q];
-                        if (bias) o += __uint_as_float((uint32_t)bias[n + q] << 16);
-                        y[(int64_t)m * N + n + q] = (uint16_t)(pack_bf16x2(o, 0.f) & 0xFFFFu);
+                        for (int e = 0; e < 4; ++e) {
+                            if (n + e >= N) break;
+                            float o = (float)acc[i][j][g * 4 + e] * xs16 * w_scale[n + e];
+                            if (bias) o += __uint_as_float((uint32_t)bias[n + e] << 16);
+                            y[(int64_t)m * N + n + e] = (uint16_t)(pack_bf16x2(o, 0.f) & 0xFFFFu);
+                        }
                     }
                 }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
             }
         }
     }
@@ -284,18 +373,20 @@ __global__ __launch_bounds__(256) void w4_prepack_kernel(const uint8_t *__restri
 
 int g_variant = -1;  // -1: pick by shape; set by the benchmark's sweep hook
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int OCC>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int OCC, int DBG = 0>
 int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                   const uint16_t *bias, int M, int N, int K, uint16_t *y, int32_t *acc_out, hipStream_t stream) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    // keep the weight panels of one column group around 2 MB (half an XCD's L2)
-    int group_n = (int)((2 << 20) / ((int64_t)BN * K / 2));
-    group_n = group_n < 1 ? 1 : (group_n > tiles_n ? tiles_n : group_n);
+    const int group_n = tiles_n < 8 ? tiles_n : 8;
+    const int total = tiles_m * tiles_n;
+    // persistent: OCC workgroups per compute unit (256 CUs), grid a multiple of the 8 XCDs
+    int grid = 256 * OCC;
+    if (total < grid) grid = (total + 7) / 8 * 8;
     const size_t smem = (size_t)STAGES * (BM * kBK + BN * kBK / 2);
-    auto k = w4ax_gemm_native_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, OCC>;
+    auto k = w4ax_gemm_native_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, OCC, DBG>;
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    hipLaunchKernelGGL(k, dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WAVES_M * WAVES_N), smem, stream, codes,
-                       x_scale, w, w_scale, bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n);
+    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), smem, stream, codes, x_scale, w,
+                       w_scale, bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n);
     return check_launch();
 }
 
@@ -311,12 +402,17 @@ int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w
     const int m = (int)M, n = (int)N, k = (int)K;
 #define DVDQ_GEMM_ARGS codes, x_scale, w, w_scale, bias, m, n, k, y, acc_out, stream
     switch (g_variant) {
-        case 1: return launch_native<256, 256, 2, 2, 3, 1>(DVDQ_GEMM_ARGS);
+        case 1: return launch_native<256, 256, 4, 2, 3, 1>(DVDQ_GEMM_ARGS);
         case 2: return launch_native<128, 256, 2, 2, 2, 2>(DVDQ_GEMM_ARGS);
-        case 3: return launch_native<256, 256, 4, 2, 3, 1>(DVDQ_GEMM_ARGS);
+        case 3: return launch_native<256, 256, 2, 4, 3, 1>(DVDQ_GEMM_ARGS);
         case 4: return launch_native<256, 128, 2, 2, 2, 2>(DVDQ_GEMM_ARGS);
-        case 5: return launch_native<256, 256, 2, 2, 2, 1>(DVDQ_GEMM_ARGS);
-        default: return launch_native<128, 256, 2, 2, 2, 2>(DVDQ_GEMM_ARGS);
+        case 5: return launch_native<256, 256, 2, 2, 3, 1>(DVDQ_GEMM_ARGS);
+        case 11: return launch_native<256, 256, 4, 2, 3, 1, 1>(DVDQ_GEMM_ARGS);
+        case 13: return launch_native<256, 256, 4, 2, 3, 1, 3>(DVDQ_GEMM_ARGS);
+        case 14: return launch_native<256, 256, 4, 2, 3, 1, 4>(DVDQ_GEMM_ARGS);
+        case 17: return launch_native<256, 256, 4, 2, 3, 1, 7>(DVDQ_GEMM_ARGS);
+        case 18: return launch_native<256, 256, 4, 2, 3, 1, 8>(DVDQ_GEMM_ARGS);
+        default: return launch_native<256, 256, 4, 2, 3, 1>(DVDQ_GEMM_ARGS);
     }
 #undef DVDQ_GEMM_ARGS
 }

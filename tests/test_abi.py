@@ -60,6 +60,7 @@ def test_gemm_argument_errors():
     assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 8, 64, 3, 0, FAKE, None, None) == 3
     assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 8, 64, 4, 7, FAKE, None, None) == 3     # layout
     assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 8, 64 * 4096, 8, 0, FAKE, None, None) == 3   # accumulator bound
+    assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 8, 192, 4, 1, FAKE, None, None) == 3    # native layout needs K % 128 == 0
     assert f(FAKE, FAKE, ODD, FAKE, None, 4, 8, 64, 4, 0, FAKE, None, None) == 5
     assert f(FAKE, FAKE, FAKE, FAKE, ODD, 4, 8, 64, 4, 0, FAKE, None, None) == 5
     assert ok
@@ -84,10 +85,11 @@ def test_qlinear_workspace_and_argument_errors():
 def test_prepack_argument_errors_and_size():
     L = dvdq.lib()
     assert dvdq.w4_native_bytes(4608, 1536) >= 4608 * 1536 // 2
-    assert dvdq.w4_native_bytes(8, 96) == 0
+    assert dvdq.w4_native_bytes(8, 96) == 0 and dvdq.w4_native_bytes(8, 192) == 0
     assert L.dvdq_w4_prepack(None, 8, 64, FAKE, None) == 1
-    assert L.dvdq_w4_prepack(FAKE, 8, 96, FAKE, None) == 2
-    assert L.dvdq_w4_prepack(FAKE, 8, 64, ODD, None) == 5
+    assert L.dvdq_w4_prepack(FAKE, 8, 95, FAKE, None) == 2
+    assert L.dvdq_w4_prepack(FAKE, 8, 192, FAKE, None) == 3
+    assert L.dvdq_w4_prepack(FAKE, 8, 128, ODD, None) == 5
 
 
 def test_bench_helpers_argument_errors():

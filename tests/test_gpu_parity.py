@@ -119,7 +119,8 @@ def rand_gemm_inputs(rng, M, N, K, bits):
     (128, 256, 256, 4, "native", True),
     (1, 1, 64, 4, "canonical", False),
     (37, 50, 128, 6, "canonical", True),       # N % 4 != 0: scalar store path
-    (300, 520, 192, 8, "native", False),       # ragged in M and N, several tiles
+    (300, 520, 384, 8, "native", False),       # ragged in M and N, several tiles
+    (300, 520, 192, 8, "canonical", False),    # K not a multiple of 128: canonical layout only
     (513, 260, 1536, 4, "native", True),
     (256, 768, 13824, 4, "native", False),     # deepest K of the workloads
     (70, 300, 704, 8, "canonical", True),
