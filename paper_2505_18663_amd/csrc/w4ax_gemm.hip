@@ -66,6 +66,11 @@ __device__ __forceinline__ void lds_direct_load16(const void *sbase, uint32_t vo
                  : "memory");
 }
 
+// chunk swizzle of a code row in LDS (see the kernel): 128-byte rows use row & 7, 64-byte rows
+// (two rows per 128-byte bank line) use (row >> 1) & 3
+template <int BK>
+__device__ __forceinline__ int swz_bk(int row) { return BK == 128 ? (row & 7) : ((row >> 1) & 3); }
+
 __device__ __forceinline__ uint32_t lds_address(const void *p) {
     return (uint32_t)(uintptr_t)DVDQ_LDS(p);
 }
@@ -95,7 +100,7 @@ __device__ __forceinline__ void tile_origin(int t, int tiles_m, int tiles_n, int
     n0 = (grp * group_n + (in_grp - tile_m * gw)) * BN;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int OCC, int DBG = 0>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int OCC, int DBG = 0>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_kernel(
     const int8_t *__restrict__ codes, const float *__restrict__ x_scale, const uint8_t *__restrict__ w,
     const float *__restrict__ w_scale, const uint16_t *__restrict__ bias, int M, int N, int K,
@@ -103,23 +108,30 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave sub-tile
     constexpr int TM = WM / 32, TN = WN / 32;            // MFMA tiles per wave
-    constexpr int A_STAGE = BM * kBK, W_STAGE = BN * kBK / 2, STAGE = A_STAGE + W_STAGE;
-    constexpr int A_DMA = A_STAGE / 1024 / NW;           // LDS-direct loads per wave per slice (1 KB each)
+    constexpr int KS = BK / 32;                          // MFMA K steps per item
+    constexpr int A_STAGE = BM * BK, W_STAGE = BN * BK / 2, STAGE = A_STAGE + W_STAGE;
+    constexpr int A_DMA = A_STAGE / 1024 / NW;           // LDS-direct loads per wave per item (1 KB each)
     constexpr int W_DMA = W_STAGE / 1024 / NW;
     constexpr int DMA = A_DMA + W_DMA;
-    // With 3 or more buffers the slice after the current one is already published, so the
-    // first fragments of slice q+1 are fetched while the last MFMAs of slice q run.
+    constexpr int CHUNKS = BK / 16;                      // 16-byte chunks per code row in LDS
+    constexpr int ROWS_PER_DMA = 1024 / BK;              // code rows one wave-wide load covers
+    constexpr int W_GROUP = kGroup * BK / 2;             // bytes of one 32-row weight group per item
+    // With 3 or more buffers the item after the current one is already published, so the
+    // first fragments of item q+1 are fetched while the last MFMAs of item q run.
     constexpr int AHEAD = STAGES >= 3 ? 1 : 0;
-    static_assert(A_DMA * 1024 * NW == A_STAGE && W_DMA * 1024 * NW == W_STAGE, "tile does not split over the waves");
+    static_assert(BK == 64 || BK == 128, "K slice per item");
+    static_assert(A_DMA >= 1 && W_DMA >= 1 && A_DMA * 1024 * NW == A_STAGE && W_DMA * 1024 * NW == W_STAGE,
+                  "tile does not split over the waves");
     static_assert(STAGES >= 2 && (STAGES - 1) * DMA < 64, "too many loads in flight for vmcnt");
 
     extern __shared__ __align__(16) uint8_t smem[];
     const uint32_t smem_base = lds_address(smem);
 
+    auto swz = [] __device__(int row) { return swz_bk<BK>(row); };
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = (wave % WAVES_M) * WM, wn = (wave / WAVES_M) * WN;
-    const int KT = K / kBK;
+    const int KT = K / BK;
     const int G = ((N + kNPad - 1) / kNPad) * (kNPad / kGroup);  // 32-row groups in the padded weight buffer
     const int64_t w_slice_stride = (int64_t)G * kGroupBytes;
 
@@ -131,39 +143,59 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     const int first_tile = (blockIdx.x % 8) * (grid / 8) + blockIdx.x / 8;
     const int my_tiles = first_tile < total ? (total - 1 - first_tile) / grid + 1 : 0;
     const int items = my_tiles * KT;  // one item = one K slice of one tile
+    if (items == 0) return;           // (whole workgroup: nothing below is reached, no barrier is missed)
 
     // ---- LDS-direct load addressing: wave-uniform base pointer + per-lane 32-bit offset.
-    // codes: load slot i of this wave fills LDS rows 8b .. 8b+7 of the stage, b = wave * A_DMA + i;
-    // LDS position p of a row holds the row's 16-byte chunk p ^ (row & 7).
+    // codes: load slot i of this wave fills ROWS_PER_DMA consecutive LDS rows of the stage;
+    // LDS position p of a row holds the row's 16-byte chunk p ^ swz(row), where swz spreads
+    // the 8 rows that one quarter-wave reads over the 8 16-byte slots of a 128-byte bank line.
     int a_row[A_DMA];
     uint32_t a_voff[A_DMA];
 #pragma unroll
-    for (int i = 0; i < A_DMA; ++i) a_row[i] = (wave * A_DMA + i) * 8 + (lane >> 3);
-    // weights: a stage image is one linear run of W_STAGE bytes in the native buffer
-    const uint32_t w_voff = (uint32_t)(wave * W_DMA) * 1024 + lane * 16;
-    const int8_t *a_base = codes;   // start of the tile's first code row, advanced by 128 per slice
-    const uint8_t *w_base = w;      // start of the tile's weight image in slice 0, advanced per slice
-    int issue_tile = 0, issue_kt = 0;   // next item to enqueue
-    auto issue_next = [&] __device__(int buf) {
-        if (issue_kt == 0) {
+    for (int i = 0; i < A_DMA; ++i) a_row[i] = (wave * A_DMA + i) * ROWS_PER_DMA + lane / CHUNKS;
+    // weights: per item and 32-row group a contiguous run of W_GROUP bytes in the native buffer
+    uint32_t w_voff[W_DMA];
+#pragma unroll
+    for (int i = 0; i < W_DMA; ++i) {
+        const int byte = (wave * W_DMA + i) * 1024 + lane * 16;     // offset in the stage's weight image
+        w_voff[i] = (byte / W_GROUP) * kGroupBytes + (byte % W_GROUP);
+    }
+    const int8_t *a_base = codes;   // start of the tile's first code row, advanced by BK per item
+    const uint8_t *w_base = w;      // start of the tile's weight image for the item
+    int issue_tile = 0, issue_kt = 0, issued = 0;   // next item to enqueue
+    uint32_t issue_sa = 0;                          // LDS address of the buffer being filled
+    // The loads of one item are enqueued one at a time (issue_one) so they can be spread
+    // between the MFMAs of the slice being multiplied.  Past the last item the same slice
+    // is enqueued again (harmless, keeps the load count per item uniform for vmcnt).
+    auto issue_prepare = [&] __device__(int buf) {
+        if (issue_kt == 0 && issued < items) {
             int m0, n0;
             tile_origin(first_tile + issue_tile * grid, tiles_m, tiles_n, group_n, BM, BN, m0, n0);
+            if (DBG & 16) { m0 = (blockIdx.x & 7) * BM; n0 = 0; }
             a_base = uniform_ptr(codes + (int64_t)m0 * K);
             w_base = uniform_ptr(w + (int64_t)(n0 / kGroup) * kGroupBytes);
 #pragma unroll
             for (int i = 0; i < A_DMA; ++i) {
                 const int row = min(a_row[i], M - 1 - m0);   // rows past M re-read the last valid row
-                a_voff[i] = (uint32_t)row * K + (((lane & 7) ^ (a_row[i] & 7)) << 4);
+                a_voff[i] = (uint32_t)row * K + (((lane % CHUNKS) ^ swz(a_row[i])) << 4);
             }
         }
-        const uint32_t sa = smem_base + buf * STAGE, sw = sa + A_STAGE;
-#pragma unroll
-        for (int i = 0; i < A_DMA; ++i) lds_direct_load16(a_base, a_voff[i], sa + (wave * A_DMA + i) * 1024);
-#pragma unroll
-        for (int i = 0; i < W_DMA; ++i) lds_direct_load16(w_base, w_voff + i * 1024, sw + (wave * W_DMA + i) * 1024);
-        a_base += kBK;
-        w_base += w_slice_stride;
-        if (++issue_kt == KT) { issue_kt = 0; ++issue_tile; }
+        issue_sa = smem_base + buf * STAGE;
+    };
+    auto issue_one = [&] __device__(int idx) {
+        if (DBG & 1) return;
+        if (idx < A_DMA)
+            lds_direct_load16(a_base, a_voff[idx], issue_sa + (wave * A_DMA + idx) * 1024);
+        else
+            lds_direct_load16(w_base, w_voff[idx - A_DMA], issue_sa + A_STAGE + (wave * W_DMA + idx - A_DMA) * 1024);
+    };
+    auto issue_advance = [&] __device__() {
+        if (++issued < items && !(DBG & 16)) {
+            a_base += BK;
+            // items alternate between the halves of a 128-channel slice of the native layout when BK = 64
+            w_base += (BK == 128 || (issue_kt & 1)) ? w_slice_stride - (kBK - BK) * (kGroup / 2) : (int64_t)W_GROUP;
+            if (++issue_kt == KT) { issue_kt = 0; ++issue_tile; }
+        }
     };
 
     v16i acc[TN][TM];
@@ -178,9 +210,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     const int frow = lane & 31, fhalf = lane >> 5;
     int a_row_off[TM];
 #pragma unroll
-    for (int j = 0; j < TM; ++j) a_row_off[j] = (wm + j * 32 + frow) * kBK;
-    const int a_xor = lane & 7;  // == row & 7: wm and 32 j are multiples of 8
-    const int w_off = (wn / kGroup) * kGroupBytes + fhalf * 256 + frow * 8;
+    for (int j = 0; j < TM; ++j) a_row_off[j] = (wm + j * 32 + frow) * BK;
+    const int a_xor = swz(frow);  // == swz(row): wm and 32 j are multiples of 32
+    const int w_off = (wn / kGroup) * W_GROUP + fhalf * 256 + frow * 8;
 
     // fragments of one K=32 step: TM code fragments (16 B) and TN packed weight fragments (8 B)
     struct Frags { v4i a[TM]; uint2 w[TN]; };
@@ -194,30 +226,35 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
 #pragma unroll
         for (int i = 0; i < TN; ++i) {
             if (DBG & 4) { f.w[i].x = lane * 3 + buf + i; f.w[i].y = ks; continue; }
-            f.w[i] = *reinterpret_cast<const uint2 *>(sw + w_off + i * kGroupBytes + ks * 512);
+            f.w[i] = *reinterpret_cast<const uint2 *>(sw + w_off + i * W_GROUP + ks * 512);
         }
+    };
+    auto mma_part = [&] __device__(const Frags &f, int i) {
+        v4i fw;   // int8 lanes of 16 * code, channel order
+        fw[0] = (int)((f.w[i].x << 4) & 0xF0F0F0F0u);
+        fw[1] = (int)(f.w[i].x & 0xF0F0F0F0u);
+        fw[2] = (int)((f.w[i].y << 4) & 0xF0F0F0F0u);
+        fw[3] = (int)(f.w[i].y & 0xF0F0F0F0u);
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw, f.a[j], acc[i][j], 0, 0, 0);
     };
     auto mma_step = [&] __device__(const Frags &f) {
 #pragma unroll
-        for (int i = 0; i < TN; ++i) {
-            v4i fw;   // int8 lanes of 16 * code, channel order
-            fw[0] = (int)((f.w[i].x << 4) & 0xF0F0F0F0u);
-            fw[1] = (int)(f.w[i].x & 0xF0F0F0F0u);
-            fw[2] = (int)((f.w[i].y << 4) & 0xF0F0F0F0u);
-            fw[3] = (int)(f.w[i].y & 0xF0F0F0F0u);
-#pragma unroll
-            for (int j = 0; j < TM; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw, f.a[j], acc[i][j], 0, 0, 0);
-        }
+        for (int i = 0; i < TN; ++i) mma_part(f, i);
     };
 
     // ---- prologue: fill STAGES-1 buffers; with look-ahead also publish slice 0 and fetch its first fragments
 #pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s)
-        if (s < items && !(DBG & 1)) issue_next(s);
+    for (int s = 0; s < STAGES - 1; ++s) {
+        issue_prepare(s);
+#pragma unroll
+        for (int d = 0; d < DMA; ++d) issue_one(d);
+        issue_advance();
+    }
     Frags f0, f1;
-    if (AHEAD && items > 0) {
-        if (STAGES - 2 < items) wait_vmcnt<(STAGES - 2) * DMA>(); else wait_vmcnt<0>();
+    if (AHEAD) {
+        wait_vmcnt<(STAGES - 2) * DMA>();
         __builtin_amdgcn_s_barrier();
         load_frags(f0, 0, 0);
     }
@@ -227,34 +264,35 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
         // Publish slice q + AHEAD: it has landed once at most the loads of the
         // (STAGES - 2 - AHEAD) younger slices are outstanding (a wave's vector memory
         // operations complete in issue order).  The barrier also means that everyone is
-        // done reading slice q-1, whose buffer the next load overwrites.
+        // done reading slice q-1, whose buffer the next loads overwrite.
         if (!(DBG & 2)) {
-            if (q + STAGES - 2 < items) wait_vmcnt<(STAGES - 2 - AHEAD) * DMA>(); else wait_vmcnt<0>();
+            wait_vmcnt<(STAGES - 2 - AHEAD) * DMA>();
             __builtin_amdgcn_s_barrier();
         }
-        if (q + STAGES - 1 < items && !(DBG & 1)) issue_next((q + STAGES - 1) % STAGES);
+        issue_prepare((q + STAGES - 1) % STAGES);
 
-        // Software pipeline over the four K=32 steps of the slice: the fragments of step s+1 are
-        // requested before the MFMAs of step s are issued.  The scheduling barriers keep the
-        // compiler from sinking the LDS reads back down to their first use.
+        // Software pipeline over the K=32 steps of the item: the fragments of step s+1 (or of
+        // step 0 of the next item) are requested before the MFMAs of step s are issued, and the
+        // LDS-direct loads of item q+STAGES-1 are dealt out between the MFMA groups.  The
+        // scheduling barriers keep the compiler from regrouping any of it.
         const int buf = q % STAGES;
         if (!AHEAD) load_frags(f0, buf, 0);
-        load_frags(f1, buf, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        mma_step(f0);
-        __builtin_amdgcn_sched_barrier(0);
-        load_frags(f0, buf, 2);
-        __builtin_amdgcn_sched_barrier(0);
-        mma_step(f1);
-        __builtin_amdgcn_sched_barrier(0);
-        load_frags(f1, buf, 3);
-        __builtin_amdgcn_sched_barrier(0);
-        mma_step(f0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (AHEAD) load_frags(f0, (q + 1) % STAGES, 0);   // after the last slice: stale but in-bounds, unused
-        __builtin_amdgcn_sched_barrier(0);
-        mma_step(f1);
-        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            Frags &cur = (ks & 1) ? f1 : f0;
+            Frags &nxt = (ks & 1) ? f0 : f1;
+            if (ks + 1 < KS) load_frags(nxt, buf, ks + 1);
+            else if (AHEAD) load_frags(nxt, (q + 1) % STAGES, 0);   // after the last item: stale but in-bounds, unused
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < TN; ++i) {
+                mma_part(cur, i);
+#pragma unroll
+                for (int d = ks * TN + i; d < DMA; d += KS * TN) issue_one(d);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        issue_advance();
         if (++kt < KT) continue;
 
         // ---- epilogue of tile tile_j.  Accumulator register r = 4 g + e of MFMA tile (i, j) in lane l is
@@ -339,6 +377,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
             }
         }
     }
+    wait_vmcnt<0>();   // no LDS-direct load may still be in flight when the workgroup's LDS is released
 }
 
 namespace {
@@ -373,7 +412,7 @@ __global__ __launch_bounds__(256) void w4_prepack_kernel(const uint8_t *__restri
 
 int g_variant = -1;  // -1: pick by shape; set by the benchmark's sweep hook
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int OCC, int DBG = 0>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int OCC, int DBG = 0>
 int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                   const uint16_t *bias, int M, int N, int K, uint16_t *y, int32_t *acc_out, hipStream_t stream) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
@@ -382,8 +421,8 @@ int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, c
     // persistent: OCC workgroups per compute unit (256 CUs), grid a multiple of the 8 XCDs
     int grid = 256 * OCC;
     if (total < grid) grid = (total + 7) / 8 * 8;
-    const size_t smem = (size_t)STAGES * (BM * kBK + BN * kBK / 2);
-    auto k = w4ax_gemm_native_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, OCC, DBG>;
+    const size_t smem = (size_t)STAGES * (BM * BK + BN * BK / 2);
+    auto k = w4ax_gemm_native_kernel<BM, BN, BK, WAVES_M, WAVES_N, STAGES, OCC, DBG>;
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), smem, stream, codes, x_scale, w,
                        w_scale, bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n);
@@ -401,18 +440,27 @@ int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w
         return launch_w4ax_gemm_canonical(codes, x_scale, w, w_scale, bias, M, N, K, y, acc_out, stream);
     const int m = (int)M, n = (int)N, k = (int)K;
 #define DVDQ_GEMM_ARGS codes, x_scale, w, w_scale, bias, m, n, k, y, acc_out, stream
-    switch (g_variant) {
-        case 1: return launch_native<256, 256, 4, 2, 3, 1>(DVDQ_GEMM_ARGS);
-        case 2: return launch_native<128, 256, 2, 2, 2, 2>(DVDQ_GEMM_ARGS);
-        case 3: return launch_native<256, 256, 2, 4, 3, 1>(DVDQ_GEMM_ARGS);
-        case 4: return launch_native<256, 128, 2, 2, 2, 2>(DVDQ_GEMM_ARGS);
-        case 5: return launch_native<256, 256, 2, 2, 3, 1>(DVDQ_GEMM_ARGS);
-        case 11: return launch_native<256, 256, 4, 2, 3, 1, 1>(DVDQ_GEMM_ARGS);
-        case 13: return launch_native<256, 256, 4, 2, 3, 1, 3>(DVDQ_GEMM_ARGS);
-        case 14: return launch_native<256, 256, 4, 2, 3, 1, 4>(DVDQ_GEMM_ARGS);
-        case 17: return launch_native<256, 256, 4, 2, 3, 1, 7>(DVDQ_GEMM_ARGS);
-        case 18: return launch_native<256, 256, 4, 2, 3, 1, 8>(DVDQ_GEMM_ARGS);
-        default: return launch_native<256, 256, 4, 2, 3, 1>(DVDQ_GEMM_ARGS);
+    int v = g_variant;
+    if (v < 0) {
+        // Picked from sweeps over the DiT shapes: deep K amortizes a 256 x 256 tile owned by one
+        // 8-wave workgroup per compute unit; shallower K wants two independent 4-wave workgroups
+        // per compute unit, so that one's epilogue overlaps the other's main loop.
+        if (k >= 8192) v = 3;
+        else if (k <= 2048 && n <= 6144) v = 8;
+        else v = 2;
+    }
+    switch (v) {
+        case 1: return launch_native<256, 256, 128, 4, 2, 3, 1>(DVDQ_GEMM_ARGS);
+        case 2: return launch_native<128, 256, 128, 2, 2, 2, 2>(DVDQ_GEMM_ARGS);
+        case 3: return launch_native<256, 256, 128, 2, 4, 3, 1>(DVDQ_GEMM_ARGS);
+        case 4: return launch_native<256, 128, 128, 2, 2, 2, 2>(DVDQ_GEMM_ARGS);
+        case 5: return launch_native<256, 256, 64, 4, 2, 6, 1>(DVDQ_GEMM_ARGS);
+        case 7: return launch_native<256, 256, 64, 4, 2, 4, 1>(DVDQ_GEMM_ARGS);
+        case 8: return launch_native<128, 256, 64, 2, 2, 4, 2>(DVDQ_GEMM_ARGS);
+        case 9: return launch_native<256, 128, 64, 2, 2, 4, 2>(DVDQ_GEMM_ARGS);
+        case 13: return launch_native<256, 256, 128, 4, 2, 3, 1, 3>(DVDQ_GEMM_ARGS);
+        case 18: return launch_native<256, 256, 128, 4, 2, 3, 1, 8>(DVDQ_GEMM_ARGS);
+        default: return DVDQ_ERR_UNSUPPORTED;
     }
 #undef DVDQ_GEMM_ARGS
 }
