@@ -12,7 +12,7 @@
 //     products are exact and the sums are accumulated in fp32.  No bf16 -> fp32
 //     unpacking is needed and the result lands in the same lane, same order.
 //   * bits 5..8 (strides 32..256) are butterflies between lanes, on fp32 values, with
-//     DPP row operations.  The 16-byte chunks of a unit are dealt to lanes so that
+//     DPP row operations (one fused multiply-add with a DPP operand per value).  The 16-byte chunks of a unit are dealt to lanes so that
 //     bits 5, 6, 7 pair lanes l ^ 1, l ^ 2, l ^ 8 (single DPP operations) and bit 8,
 //     which only 512-blocks transform, pairs l ^ 4 (two masked row shifts).
 //
@@ -20,9 +20,10 @@
 //   l = (c & 3) << 4 | (c >> 2 & 1) | (c >> 3 & 1) << 1 | (c >> 5 & 1) << 2 | (c >> 4 & 1) << 3,
 // i.e. lanes l, l+16, l+32, l+48 hold 64 contiguous bytes and a wave instruction still
 // covers one contiguous kilobyte.  Rows longer than a few units are spread over the
-// waves of a workgroup and the abs-max is combined through LDS.  The 1/sqrt(B)
-// normalization is never applied to the data: it is folded into the scale and into
-// the reciprocal the codes are taken with.
+// waves of a workgroup and the abs-max is combined through LDS.  Workgroups stay
+// resident and stride over the rows, prefetching the next row while one is processed.
+// The 1/sqrt(B) normalization is never applied to the data: it is folded into the
+// scale and into the reciprocal the codes are taken with.
 #include "dvdq_internal.h"
 
 namespace dvdq {
@@ -39,13 +40,41 @@ __device__ __forceinline__ float dpp_mov(float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
 }
 
-// value of lane (l ^ 4): rows shifted left by 4 for the lanes with bit 2 clear (banks 0 and 2),
-// right by 4 for the others (banks 1 and 3)
-__device__ __forceinline__ float dpp_xor4(float v) {
-    const int x = __builtin_bit_cast(int, v);
-    int t = __builtin_amdgcn_update_dpp(0, x, 0x104 /* row_shl:4 */, 0xF, 0x5, false);
-    t = __builtin_amdgcn_update_dpp(t, x, 0x114 /* row_shr:4 */, 0xF, 0xA, false);
-    return __builtin_bit_cast(float, t);
+// One butterfly stage over a lane pairing with a single DPP operand, 8 values, one
+// instruction per value: v = own + sign * partner, sign = +1 in the lane whose stage bit
+// is clear and -1 in the other.  The lane with the bit set therefore holds MINUS the
+// butterfly's difference; the caller tracks that sign and folds it into the quantizer.
+// (The compiler does not fuse a DPP move into an fma, so this is inline assembly.  The
+// leading s_nop covers the 2 wait states a DPP read needs after a VALU write of the same
+// register; the values must have been written by ordinary VALU instructions, never
+// directly by an MFMA, whose longer read-after-write distance only the compiler inserts.)
+#define DVDQ_FMAC_DPP8(CTRL)                                                                                   \
+    asm volatile("s_nop 1\n\t"                                                                                 \
+                 "v_fmac_f32_dpp %0, %0, %8 " CTRL " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"              \
+                 "v_fmac_f32_dpp %1, %1, %8 " CTRL " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"              \
+                 "v_fmac_f32_dpp %2, %2, %8 " CTRL " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"              \
+                 "v_fmac_f32_dpp %3, %3, %8 " CTRL " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"              \
+                 "v_fmac_f32_dpp %4, %4, %8 " CTRL " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"              \
+                 "v_fmac_f32_dpp %5, %5, %8 " CTRL " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"              \
+                 "v_fmac_f32_dpp %6, %6, %8 " CTRL " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"              \
+                 "v_fmac_f32_dpp %7, %7, %8 " CTRL " row_mask:0xf bank_mask:0xf bound_ctrl:1"                  \
+                 : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7]) \
+                 : "v"(sign))
+
+__device__ __forceinline__ void stage_xor2(float (&v)[8], float sign) { DVDQ_FMAC_DPP8("quad_perm:[2,3,0,1]"); }
+__device__ __forceinline__ void stage_xor8(float (&v)[8], float sign) { DVDQ_FMAC_DPP8("row_ror:8"); }
+
+// Butterfly stage over lanes l ^ 4 (no single DPP pattern): rows shifted left by 4 feed the
+// lanes with bit 2 clear (banks 0 and 2: own + partner), rows shifted right by 4 the others
+// (banks 1 and 3: partner - own).  Two instructions per value, exact butterfly signs.
+__device__ __forceinline__ float stage_xor4_one(float v) {
+    float w;
+    asm volatile("s_nop 1\n\t"
+                 "v_add_f32_dpp %0, %1, %1 row_shl:4 row_mask:0xf bank_mask:0x5\n\t"
+                 "v_sub_f32_dpp %0, %1, %1 row_shr:4 row_mask:0xf bank_mask:0xa"
+                 : "=&v"(w)
+                 : "v"(v));
+    return w;
 }
 
 // entry (r, k) of the 32 x 32 matrix that applies H to the index bits in `mask` and the
@@ -63,14 +92,12 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
     double scale_mul,  // 1 / (sqrt(B) * qmax); fp64 so the fp32 scale is rounded once
     float recip_num,   // 1 / sqrt(B)
     int8_t *__restrict__ codes, float *__restrict__ x_scale) {
-    extern __shared__ float s_amax[];  // [rows_per_wg * waves_per_row]
+    extern __shared__ float s_amax[];  // [2][rows_per_wg * waves_per_row], slots alternate per iteration
     constexpr int MASK5 = LOG2B >= 5 ? 31 : ((1 << LOG2B) - 1);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int row_in_wg = wave / waves_per_row;
     const int wsub = wave - row_in_wg * waves_per_row;
-    const int64_t row = (int64_t)blockIdx.x * rows_per_wg + row_in_wg;
-    const bool row_ok = row < M;
     // this lane's 16-byte chunk within a unit
     const int chunk = ((lane >> 4) & 3) | ((lane & 1) << 2) | (((lane >> 1) & 1) << 3) | (((lane >> 3) & 1) << 4) |
                       (((lane >> 2) & 1) << 5);
@@ -89,84 +116,103 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
         }
         tmat[h] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
     }
-    // butterfly signs of the lane-pairing stages: the lane with the stage's bit set takes (partner - own)
-    const float s1 = (lane & 1) ? -1.f : 1.f, s2 = (lane & 2) ? -1.f : 1.f;
-    const float s8 = (lane & 8) ? -1.f : 1.f, s4 = (lane & 4) ? -1.f : 1.f;
+    // butterfly signs of the lane-pairing stages (the lane with the stage's bit set takes the difference)
+    const float s1 = (lane & 1) ? -1.f : 1.f, s2 = (lane & 2) ? -1.f : 1.f, s8 = (lane & 8) ? -1.f : 1.f;
+    // stages xor 2 and xor 8 leave MINUS the difference in the lane with the bit set
+    const float flip = (((LOG2B >= 7) && (lane & 2)) != ((LOG2B >= 8) && (lane & 8))) ? -1.f : 1.f;
 
-    float v[CPW][8];
-    float amax = 0.f;
+    // channel offsets of this lane's chunks; chunks at or past K are padding (zero in, nothing out)
+    int k0[CPW];
 #pragma unroll
-    for (int c = 0; c < CPW; ++c) {
-        const int k0 = (wsub + c * waves_per_row) * kUnit + chunk * 8;
-        uint4 raw = make_uint4(0, 0, 0, 0);
-        if (row_ok && k0 < K) raw = *reinterpret_cast<const uint4 *>(x + row * K + k0);
-        if (LOG2B == 0) {
-            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                v[c][2 * i] = __uint_as_float(w[i] << 16);
-                v[c][2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
-            }
-        } else {
-            const bf16x8 data = __builtin_bit_cast(bf16x8, raw);
-            const v4f zero = {0.f, 0.f, 0.f, 0.f};
-            const v4f d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tmat[0], data, zero, 0, 0, 0);
-            const v4f d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tmat[1], data, zero, 0, 0, 0);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                v[c][i] = d0[i];
-                v[c][4 + i] = d1[i];
-            }
-        }
-    }
-#pragma unroll
-    for (int c = 0; c < CPW; ++c) {
-        if (LOG2B >= 6) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) v[c][i] = fmaf(v[c][i], s1, dpp_mov<0xB1>(v[c][i]));  // quad_perm [1,0,3,2]
-        }
-        if (LOG2B >= 7) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) v[c][i] = fmaf(v[c][i], s2, dpp_mov<0x4E>(v[c][i]));  // quad_perm [2,3,0,1]
-        }
-        if (LOG2B >= 8) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) v[c][i] = fmaf(v[c][i], s8, dpp_mov<0x128>(v[c][i]));  // row_ror:8
-        }
-        if (LOG2B >= 9) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) v[c][i] = fmaf(v[c][i], s4, dpp_xor4(v[c][i]));
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(v[c][i]));
-    }
-#pragma unroll
-    for (int m = 1; m < kWave; m <<= 1) amax = fmaxf(amax, __shfl_xor(amax, m, kWave));
-    if (waves_per_row > 1) {
-        if (lane == 0) s_amax[wave] = amax;
-        __syncthreads();
-        amax = 0.f;
-        for (int i = 0; i < waves_per_row; ++i) amax = fmaxf(amax, s_amax[row_in_wg * waves_per_row + i]);
-    }
-    // scale handed on = amax / (sqrt(B) * qmax); codes = rne(v * (1/sqrt(B)) / scale)
-    const float scale = (float)((double)amax * scale_mul);
-    const float r = scale > 0.f ? recip_num / scale : 0.f;
-    if (row_ok && wsub == 0 && lane == 0) x_scale[row] = scale;
+    for (int c = 0; c < CPW; ++c) k0[c] = (wsub + c * waves_per_row) * kUnit + chunk * 8;
 
-    const float magic = 12582912.f;  // 1.5 * 2^23: adding it rounds to integer, ties to even
+    auto load_row = [&] __device__(uint4 (&raw)[CPW], int64_t row) {
 #pragma unroll
-    for (int c = 0; c < CPW; ++c) {
-        const int k0 = (wsub + c * waves_per_row) * kUnit + chunk * 8;
-        uint32_t b[8];
+        for (int c = 0; c < CPW; ++c) {
+            raw[c] = make_uint4(0, 0, 0, 0);
+            if (row < M && k0[c] < K) raw[c] = *reinterpret_cast<const uint4 *>(x + row * K + k0[c]);
+        }
+    };
+
+    // Workgroups stride over the rows; the next row's loads are in flight while this one is processed.
+    const int64_t row_step = (int64_t)gridDim.x * rows_per_wg;
+    int64_t row = (int64_t)blockIdx.x * rows_per_wg + row_in_wg;
+    uint4 raw[CPW];
+    load_row(raw, row);
+    int slot = 0;
+    for (int64_t base = (int64_t)blockIdx.x * rows_per_wg; base < M; base += row_step, row += row_step, slot ^= 1) {
+        uint4 nxt[CPW];
+        load_row(nxt, row + row_step);
+        const bool row_ok = row < M;
+
+        float v[CPW][8];
+        float amax = 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) b[i] = __float_as_uint(fmaf(v[c][i], r, magic));
-        // low bytes of b[0..3] / b[4..7] -> one dword each
-        uint2 out;
-        out.x = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u),
-                                      __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u), 0x05040100u);
-        out.y = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[7], b[6], 0x0c0c0400u),
-                                      __builtin_amdgcn_perm(b[5], b[4], 0x0c0c0400u), 0x05040100u);
-        if (row_ok && k0 < K) *reinterpret_cast<uint2 *>(codes + row * K + k0) = out;
+        for (int c = 0; c < CPW; ++c) {
+            if (LOG2B == 0) {
+                const uint32_t w[4] = {raw[c].x, raw[c].y, raw[c].z, raw[c].w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    v[c][2 * i] = __uint_as_float(w[i] << 16);
+                    v[c][2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+                }
+            } else {
+                const bf16x8 data = __builtin_bit_cast(bf16x8, raw[c]);
+                const v4f zero = {0.f, 0.f, 0.f, 0.f};
+                const v4f d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tmat[0], data, zero, 0, 0, 0);
+                const v4f d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tmat[1], data, zero, 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    v[c][i] = d0[i];
+                    v[c][4 + i] = d1[i];
+                }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) {
+            if (LOG2B >= 6) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v[c][i] = fmaf(v[c][i], s1, dpp_mov<0xB1>(v[c][i]));  // quad_perm [1,0,3,2]
+            }
+            if (LOG2B >= 7) stage_xor2(v[c], s2);
+            if (LOG2B >= 8) stage_xor8(v[c], s8);
+            if (LOG2B >= 9) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v[c][i] = stage_xor4_one(v[c][i]);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(v[c][i]));
+        }
+#pragma unroll
+        for (int m = 1; m < kWave; m <<= 1) amax = fmaxf(amax, __shfl_xor(amax, m, kWave));
+        if (waves_per_row > 1) {
+            float *slots = s_amax + slot * (rows_per_wg * waves_per_row);
+            if (lane == 0) slots[wave] = amax;
+            __syncthreads();
+            amax = 0.f;
+            for (int i = 0; i < waves_per_row; ++i) amax = fmaxf(amax, slots[row_in_wg * waves_per_row + i]);
+        }
+        // scale handed on = amax / (sqrt(B) * qmax); codes = rne(v * (1/sqrt(B)) / scale)
+        const float scale = (float)((double)amax * scale_mul);
+        const float r = scale > 0.f ? flip * (recip_num / scale) : 0.f;
+        if (row_ok && wsub == 0 && lane == 0) x_scale[row] = scale;
+
+        const float magic = 12582912.f;  // 1.5 * 2^23: adding it rounds to integer, ties to even
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) {
+            uint32_t b[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) b[i] = __float_as_uint(fmaf(v[c][i], r, magic));
+            // low bytes of b[0..3] / b[4..7] -> one dword each
+            uint2 out;
+            out.x = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u),
+                                          __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u), 0x05040100u);
+            out.y = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[7], b[6], 0x0c0c0400u),
+                                          __builtin_amdgcn_perm(b[5], b[4], 0x0c0c0400u), 0x05040100u);
+            if (row_ok && k0[c] < K) *reinterpret_cast<uint2 *>(codes + row * K + k0[c]) = out;
+        }
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) raw[c] = nxt[c];
     }
 }
 
@@ -199,8 +245,14 @@ int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block,
     if (cpw > 8) return DVDQ_ERR_UNSUPPORTED;
     const int rows_per_wg = W >= 4 ? 1 : 4 / W;
     const dim3 block(kWave * W * rows_per_wg);
-    const dim3 grid((unsigned)((M + rows_per_wg - 1) / rows_per_wg));
-    const size_t smem = sizeof(float) * W * rows_per_wg;
+    // resident workgroups: a whole number per compute unit (256 of them), about 16 waves each,
+    // every workgroup striding over the rows
+    const int64_t wgs_needed = (M + rows_per_wg - 1) / rows_per_wg;
+    int wgs_per_cu = 16 / (W * rows_per_wg);
+    if (wgs_per_cu < 1) wgs_per_cu = 1;
+    const int64_t wgs_resident = 256 * (int64_t)wgs_per_cu;
+    const dim3 grid((unsigned)(wgs_needed < wgs_resident ? wgs_needed : wgs_resident));
+    const size_t smem = 2 * sizeof(float) * W * rows_per_wg;
     const double qmax = (double)((1 << (act_bits - 1)) - 1);
     const double norm = 1.0 / sqrt((double)(1 << log2_block));
     const double scale_mul = norm / qmax;
