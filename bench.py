@@ -24,6 +24,13 @@ sys.path.insert(0, ROOT)
 INT8_MFMA_PEAK_TOPS = 5000.0     # published dense INT8 matrix peak, MI355X
 HBM_PEAK_GBPS = 8000.0           # published HBM3E bandwidth, MI355X
 
+# HBM bytes per launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
+# very command, scaled by the same counters' reading for dvdq_bench_copy; the summaries with the
+# commands are profiles/bench_<workload>_hbm_counters.md.  None where no counter run exists.
+MEASURED_HBM_TRAFFIC = {
+    "small_dit_qkv_w4a4": {"w4ax_gemm": 641.7e6, "rotate_quant": 151.3e6},
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -85,18 +92,21 @@ def main():
     ops = 2.0 * M * N * K
     tops = ops / t_step / 1e12
 
-    # ---- per-kernel launch durations (HIP events on the launch stream)
-    def time_launches(fn, n):
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    # ---- per-kernel launch durations (HIP events on the launch stream, around groups of 5
+    # back-to-back launches so that the event overhead does not inflate short kernels)
+    def time_launches(fn, n, group=5):
+        n_groups = max(1, n // group)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_groups)]
         for i in range(min(args.warmup, 5)):
             fn(i)
         torch.cuda.synchronize()
-        for i in range(n):
-            ev[i][0].record()
-            fn(i)
-            ev[i][1].record()
+        for g in range(n_groups):
+            ev[g][0].record()
+            for i in range(group):
+                fn(g * group + i)
+            ev[g][1].record()
         torch.cuda.synchronize()
-        ms = sorted(a.elapsed_time(b) for a, b in ev)
+        ms = sorted(a.elapsed_time(b) / group for a, b in ev)
         return sum(ms) / len(ms), ms[len(ms) // 2]
 
     views = [dvdq.workspace_views(w_, M, K, bits) for w_ in wsp]
@@ -118,14 +128,14 @@ def main():
     # ---- calibration: what this chip sustains for a plain copy and a register-only INT8 MFMA loop
     src = torch.empty((256 << 20,), dtype=torch.uint8, device=dev)
     dst = torch.empty_like(src)
-    copy_avg, _ = time_launches(lambda i: dvdq.bench_copy(src, dst), 10)
+    copy_avg, _ = time_launches(lambda i: dvdq.bench_copy(src, dst), 10, group=2)
     copy_gbps = 2.0 * src.numel() / (copy_avg * 1e-3) / 1e9
     sink = torch.zeros((4,), dtype=torch.int32, device=dev)
     mfma_ops = [0.0]
 
     def mfma(i):
         mfma_ops[0] = dvdq.bench_mfma_i8(2000, sink)
-    mfma_avg, _ = time_launches(mfma, 5)
+    mfma_avg, _ = time_launches(mfma, 4, group=2)
     mfma_ceiling = mfma_ops[0] / (mfma_avg * 1e-3) / 1e12
     del src, dst
 
@@ -139,29 +149,43 @@ def main():
         "frac_int8_mfma_peak": round(tops / INT8_MFMA_PEAK_TOPS, 4),
         "roofline": {"kernel": "w4ax_gemm", "bound": "mfma", "achieved": round(gemm_tops, 2),
                      "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(gemm_tops / INT8_MFMA_PEAK_TOPS, 4),
-                     "traffic": None, "avg_launch_ms": round(gemm_avg, 4), "median_launch_ms": round(gemm_med, 4),
+                     "traffic": MEASURED_HBM_TRAFFIC.get(wl.name, {}).get("w4ax_gemm"),
+                     "avg_launch_ms": round(gemm_avg, 4), "median_launch_ms": round(gemm_med, 4),
                      "measured_mfma_ceiling_tops": round(mfma_ceiling, 1)},
         "roofline_rotate_quant": {"kernel": "rotate_quant", "bound": "hbm", "achieved": round(rq_gbps, 1),
                                   "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(rq_gbps / HBM_PEAK_GBPS, 4),
-                                  "traffic": None, "avg_launch_ms": round(rq_avg, 4),
+                                  "traffic": MEASURED_HBM_TRAFFIC.get(wl.name, {}).get("rotate_quant"),
+                                  "avg_launch_ms": round(rq_avg, 4),
                                   "median_launch_ms": round(rq_med, 4), "algorithmic_bytes": rq_bytes,
                                   "measured_copy_gbps": round(copy_gbps, 1)},
     }
 
-    # ---- CPU baseline: the oracle as it stands, on a bounded token sample
+    # ---- CPU baseline: the oracle as it stands, on a bounded token sample (about 10-30 s of CPU work)
     if not args.no_cpu_baseline:
         import oracle
-        rows = di.sample_rows(M, 256)
-        xs_rows = np.ascontiguousarray(xb[rows])
-        oracle.qlinear(xs_rows[:8], wp, ws, B, bits)       # load / warm the library
+        probe = di.sample_rows(M, 256)
+        xp = np.ascontiguousarray(xb[probe])
+        oracle.qlinear(xp[:8], wp, ws, B, bits)            # build / load / warm the library
+        t0 = time.perf_counter()
+        oracle.qlinear(xp, wp, ws, B, bits)
+        t_probe = time.perf_counter() - t0
+        per_row = t_probe / probe.size
+        n_rows = int(min(M, max(probe.size, 15.0 / per_row)))     # aim at ~15 s, never more than the workload
+        if n_rows >= M:
+            rows, what = np.arange(M), f"all {M} token rows"
+        else:
+            rows = di.sample_rows(M, n_rows // 2)
+            what = f"{rows.size} of {M} token rows (first and last {n_rows // 2})"
+        xs_rows = xb if rows.size == M else np.ascontiguousarray(xb[rows])
         t0 = time.perf_counter()
         oracle.qlinear(xs_rows, wp, ws, B, bits)
         t_cpu = time.perf_counter() - t0
         out["cpu_baseline"] = {
             "value": round(2.0 * rows.size * N * K / t_cpu / 1e12, 5), "unit": "TOP/s",
             "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"{rows.size} of {M} token rows (first 256 + last 256), whole layer, {t_cpu:.2f} s; "
-                      f"work is linear in rows, full-size time extrapolates to {t_cpu * M / rows.size:.1f} s",
+            "sample": f"{what}, whole layer (dense fp64 Hadamard, int64 GEMM), {t_cpu:.2f} s"
+                      + ("" if rows.size == M else f"; work is linear in rows, full size extrapolates to "
+                                                   f"{t_cpu * M / rows.size:.1f} s"),
         }
     print(json.dumps(out))
 
