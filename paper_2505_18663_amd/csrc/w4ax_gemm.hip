@@ -71,6 +71,14 @@ __device__ __forceinline__ void lds_direct_load16(const void *sbase, uint32_t vo
 template <int BK>
 __device__ __forceinline__ int swz_bk(int row) { return BK == 128 ? (row & 7) : ((row >> 1) & 3); }
 
+// Same, 4 bytes per lane (LDS address lds_base + 4 * lane): used for the per-tile scale vectors.
+__device__ __forceinline__ void lds_direct_load4(const void *sbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 :
+                 : "v"(voff), "s"(sbase), "s"(lds_base)
+                 : "memory");
+}
+
 __device__ __forceinline__ uint32_t lds_address(const void *p) {
     return (uint32_t)(uintptr_t)DVDQ_LDS(p);
 }
@@ -119,6 +127,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     // With 3 or more buffers the item after the current one is already published, so the
     // first fragments of item q+1 are fetched while the last MFMAs of item q run.
     constexpr int AHEAD = STAGES >= 3 ? 1 : 0;
+    constexpr int SCALES = (BM + BN) * 4;                // bytes of one tile's token + channel scales in LDS
+    constexpr int STORES = TM * TN * 2;                  // 16-byte store instructions per wave per full tile
+    static_assert((STAGES - 2 - AHEAD) * DMA + STORES < 64, "store-aware wait exceeds vmcnt");
     static_assert(BK == 64 || BK == 128, "K slice per item");
     static_assert(A_DMA >= 1 && W_DMA >= 1 && A_DMA * 1024 * NW == A_STAGE && W_DMA * 1024 * NW == W_STAGE,
                   "tile does not split over the waves");
@@ -178,6 +189,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
             for (int i = 0; i < A_DMA; ++i) {
                 const int row = min(a_row[i], M - 1 - m0);   // rows past M re-read the last valid row
                 a_voff[i] = (uint32_t)row * K + (((lane % CHUNKS) ^ swz(a_row[i])) << 4);
+            }
+            // The tile's scales go to LDS as well ([BM token scales][BN channel scales], two tiles
+            // deep), so that the epilogue needs no vector-memory load: such a load would queue
+            // behind the LDS-direct loads in flight.  Indices past M / N repeat the last valid one.
+            // They are issued ahead of the tile's first data loads and are therefore complete
+            // whenever that item is published.
+            const uint32_t sc = smem_base + STAGES * STAGE + (issue_tile & 1) * SCALES;
+#pragma unroll
+            for (int j = 0; j < (BM + BN) / 64; ++j) {
+                if (j % NW != wave) continue;
+                if (j < BM / 64)
+                    lds_direct_load4(x_scale, (uint32_t)min(m0 + j * 64 + lane, M - 1) * 4, sc + j * 256);
+                else
+                    lds_direct_load4(w_scale, (uint32_t)min(n0 + (j - BM / 64) * 64 + lane, N - 1) * 4, sc + j * 256);
             }
         }
         issue_sa = smem_base + buf * STAGE;
@@ -259,14 +284,22 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
         load_frags(f0, 0, 0);
     }
 
-    int kt = 0, tile_j = 0;
+    int kt = 0, tile_j = 0, store_credit = 0;
     for (int q = 0; q < items; ++q) {
         // Publish slice q + AHEAD: it has landed once at most the loads of the
         // (STAGES - 2 - AHEAD) younger slices are outstanding (a wave's vector memory
         // operations complete in issue order).  The barrier also means that everyone is
         // done reading slice q-1, whose buffer the next loads overwrite.
         if (!(DBG & 2)) {
-            wait_vmcnt<(STAGES - 2 - AHEAD) * DMA>();
+            // Right after the epilogue of a full tile exactly STORES stores are this wave's youngest
+            // operations (for the next STAGES-1-AHEAD items the awaited loads are older than them):
+            // do not wait for their acknowledgement.
+            if (store_credit > 0) {
+                wait_vmcnt<(STAGES - 2 - AHEAD) * DMA + STORES>();
+                --store_credit;
+            } else {
+                wait_vmcnt<(STAGES - 2 - AHEAD) * DMA>();
+            }
             __builtin_amdgcn_s_barrier();
         }
         issue_prepare((q + STAGES - 1) % STAGES);
@@ -302,11 +335,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
         kt = 0;
         ++tile_j;
         const bool vec8 = (N & 7) == 0;
+        const float *s_xs = reinterpret_cast<const float *>(smem + STAGES * STAGE + ((tile_j - 1) & 1) * SCALES);
+        const float *s_ws = s_xs + BM;
+        // every lane of every wave stores all its values: the store count is exact (see the wait above)
+        if (vec8 && !acc_out && !(DBG & 8) && m0 + BM <= M && n0 + BN <= N && KT >= STAGES)
+            store_credit = STAGES - 1 - AHEAD;
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
             const int m = m0 + wm + j * 32 + frow;
             const bool m_ok = m < M;
-            const float xs16 = m_ok ? x_scale[m] * 0.0625f : 0.f;   // folds the factor 16 of the widened weights
+            const float xs16 = s_xs[wm + j * 32 + frow] * 0.0625f;   // folds the factor 16 of the widened weights
 #pragma unroll
             for (int i = 0; i < TN; ++i) {
                 const int nb = n0 + wn + i * 32;   // this MFMA tile's first output channel
@@ -326,7 +364,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
                         const int n = nb + g * 8 + fhalf * 4;
                         float o[4];
                         if (n < N) {  // N % 8 == 0 and n % 4 == 0: n + 3 < N as well
-                            const float4 ws = *reinterpret_cast<const float4 *>(w_scale + n);
+                            const float4 ws = *reinterpret_cast<const float4 *>(s_ws + (n - n0));
                             o[0] = (float)acc[i][j][g * 4 + 0] * xs16 * ws.x;
                             o[1] = (float)acc[i][j][g * 4 + 1] * xs16 * ws.y;
                             o[2] = (float)acc[i][j][g * 4 + 2] * xs16 * ws.z;
@@ -366,7 +404,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             if (n + e >= N) break;
-                            float o = (float)acc[i][j][g * 4 + e] * xs16 * w_scale[n + e];
+                            float o = (float)acc[i][j][g * 4 + e] * xs16 * s_ws[n + e - n0];
                             if (bias) o += __uint_as_float((uint32_t)bias[n + e] << 16);
                             y[(int64_t)m * N + n + e] = (uint16_t)(pack_bf16x2(o, 0.f) & 0xFFFFu);
                         }
@@ -421,7 +459,7 @@ int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, c
     // persistent: OCC workgroups per compute unit (256 CUs), grid a multiple of the 8 XCDs
     int grid = 256 * OCC;
     if (total < grid) grid = (total + 7) / 8 * 8;
-    const size_t smem = (size_t)STAGES * (BM * BK + BN * BK / 2);
+    const size_t smem = (size_t)STAGES * (BM * BK + BN * BK / 2) + 2 * (BM + BN) * 4;
     auto k = w4ax_gemm_native_kernel<BM, BN, BK, WAVES_M, WAVES_N, STAGES, OCC, DBG>;
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), smem, stream, codes, x_scale, w,
@@ -449,6 +487,13 @@ int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w
         else if (k <= 2048 && n <= 6144) v = 8;
         else v = 2;
     }
+    // the two-deep scale buffers of a workgroup need K slices >= ring depth - 1 (see the kernel);
+    // shallow K falls back to the two-buffer variant, which always qualifies
+    {
+        const int bk = (v == 5 || v == 7 || v == 8 || v == 9 || (v >= 80 && v < 90) || v == 815) ? 64 : 128;
+        const int stages = (v == 2 || v == 4) ? 2 : (v == 5 ? 6 : ((v == 7 || v == 8 || v == 9 || (v >= 80 && v < 90) || v == 815) ? 4 : 3));
+        if (k / bk < stages - 1) v = 2;
+    }
     switch (v) {
         case 1: return launch_native<256, 256, 128, 4, 2, 3, 1>(DVDQ_GEMM_ARGS);
         case 2: return launch_native<128, 256, 128, 2, 2, 2, 2>(DVDQ_GEMM_ARGS);
@@ -458,6 +503,11 @@ int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w
         case 7: return launch_native<256, 256, 64, 4, 2, 4, 1>(DVDQ_GEMM_ARGS);
         case 8: return launch_native<128, 256, 64, 2, 2, 4, 2>(DVDQ_GEMM_ARGS);
         case 9: return launch_native<256, 128, 64, 2, 2, 4, 2>(DVDQ_GEMM_ARGS);
+        case 88: return launch_native<128, 256, 64, 2, 2, 4, 2, 8>(DVDQ_GEMM_ARGS);
+        case 81: return launch_native<128, 256, 64, 2, 2, 4, 2, 1>(DVDQ_GEMM_ARGS);
+        case 83: return launch_native<128, 256, 64, 2, 2, 4, 2, 3>(DVDQ_GEMM_ARGS);
+        case 87: return launch_native<128, 256, 64, 2, 2, 4, 2, 7>(DVDQ_GEMM_ARGS);
+        case 815: return launch_native<128, 256, 64, 2, 2, 4, 2, 15>(DVDQ_GEMM_ARGS);
         case 13: return launch_native<256, 256, 128, 4, 2, 3, 1, 3>(DVDQ_GEMM_ARGS);
         case 18: return launch_native<256, 256, 128, 4, 2, 3, 1, 8>(DVDQ_GEMM_ARGS);
         default: return DVDQ_ERR_UNSUPPORTED;
