@@ -52,6 +52,10 @@ def _load():
         lib.dvdq_oracle_w4ax_gemm.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp]
         lib.dvdq_oracle_qlinear.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, vp, vp, vp, vp]
         lib.dvdq_oracle_f64_to_bf16.argtypes = [vp, i64, vp]
+        lib.dvdq_oracle_rel_l1.argtypes = [vp, vp, i64]
+        lib.dvdq_oracle_rel_l1.restype = C.c_double
+        lib.dvdq_oracle_gbs_update.argtypes = [C.c_double, C.c_double, i32, i32, C.POINTER(C.c_double)]
+        lib.dvdq_oracle_gbs_update.restype = i32
         for f in ("hadamard", "rotate", "quantize", "rotate_quant", "w4ax_gemm", "qlinear"):
             getattr(lib, "dvdq_oracle_" + f).restype = i32
         for f in ("unpack_w4", "pack_w4", "int_gemm", "epilogue", "f64_to_bf16"):
@@ -194,3 +198,18 @@ def f64_to_bf16(a: np.ndarray) -> np.ndarray:
     out = np.empty(v.shape, dtype=np.uint16)
     _load().dvdq_oracle_f64_to_bf16(_p(v), v.size, _p(out))
     return out
+
+
+def rel_l1(f_t_bf16: np.ndarray, f_prev_bf16: np.ndarray) -> float:
+    """||F_t - F_{t-1}||_1 / ||F_{t-1}||_1 on bf16 bit patterns (any shape), fp64 sums."""
+    a, b = _arr(f_t_bf16, np.uint16), _arr(f_prev_bf16, np.uint16)
+    if a.shape != b.shape:
+        raise ValueError("shape mismatch")
+    return float(_load().dvdq_oracle_rel_l1(_p(a), _p(b), a.size))
+
+
+def gbs_update(l1: float, delta: float, b_low: int, b_high: int, acc: float):
+    """One controller update.  Returns (bits for the next step, new running sum)."""
+    c_acc = C.c_double(acc)
+    bits = _load().dvdq_oracle_gbs_update(float(l1), float(delta), b_low, b_high, C.byref(c_acc))
+    return bits, c_acc.value

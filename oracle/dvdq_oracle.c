@@ -255,3 +255,36 @@ int dvdq_oracle_qlinear(const uint16_t *x, const uint8_t *w_packed, const float 
     if (!scale_out) free(scale);
     return rc;
 }
+
+/* ---------------------------------------------------------------- delta-Guided Bit Switching (Sec. 3.3) */
+
+/* Relative L1 change between successive model outputs,
+ *   L1(F, t) = ||F_t - F_{t-1}||_1 / ||F_{t-1}||_1,
+ * on bf16 tensors of n elements, summed in fp64.  A zero denominator gives +inf when
+ * the numerator is positive and 0 when both are zero. */
+double dvdq_oracle_rel_l1(const uint16_t *f_t, const uint16_t *f_prev, int64_t n)
+{
+    double num = 0.0, den = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        double a = bf16_to_f64(f_t[i]), b = bf16_to_f64(f_prev[i]);
+        num += fabs(a - b);
+        den += fabs(b);
+    }
+    if (den == 0.0) return num > 0.0 ? INFINITY : 0.0;
+    return num / den;
+}
+
+/* One update of the bit-width controller after a denoising step has produced its
+ * output: the change of that step is added to the running sum kept since the last
+ * reset; while the sum stays below delta the next step runs at b_low, and once it
+ * reaches delta the next step runs at b_high and the sum restarts from zero.
+ * *acc is the running sum (in/out).  Returns the bit-width for the next step. */
+int dvdq_oracle_gbs_update(double l1, double delta, int b_low, int b_high, double *acc)
+{
+    *acc += l1;
+    if (*acc >= delta) {
+        *acc = 0.0;
+        return b_high;
+    }
+    return b_low;
+}
