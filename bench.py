@@ -139,6 +139,14 @@ def main():
     mfma_ceiling = mfma_ops[0] / (mfma_avg * 1e-3) / 1e12
     del src, dst
 
+    # ---- the delta-GBS controller step on a 720p-class latent (16 x 33 x 90 x 160 bf16 values):
+    # two HBM reads of the tensor, one scalar out
+    n_lat = 16 * 33 * 90 * 160
+    f_prev = torch.randn((n_lat,), device=dev).to(torch.bfloat16)
+    f_cur = (f_prev.float() + 0.05 * torch.randn((n_lat,), device=dev)).to(torch.bfloat16)
+    ctl = dvdq.GbsController(delta=0.1)
+    gbs_avg, _ = time_launches(lambda i: ctl.step(f_cur, f_prev), 20, group=10)
+
     out = {
         "metric": "fused W4A4 qlinear TOPS & % INT8-MFMA peak; rotate+quant HBM GB/s",
         "value": round(tops, 2), "unit": "TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -159,6 +167,9 @@ def main():
                                   "median_launch_ms": round(rq_med, 4), "algorithmic_bytes": rq_bytes,
                                   "measured_copy_gbps": round(copy_gbps, 1)},
     }
+
+    out["gbs_controller"] = {"elements": n_lat, "us_per_step": round(gbs_avg * 1e3, 2),
+                             "achieved_gbps": round(4.0 * n_lat / (gbs_avg * 1e-3) / 1e9, 1), "bound": "hbm (launch-bound at this size)"}
 
     # ---- CPU baseline: the oracle as it stands, on a bounded token sample (about 10-30 s of CPU work)
     if not args.no_cpu_baseline:

@@ -123,6 +123,31 @@ size_t dvdq_qlinear_scale_offset(int64_t M, int64_t K, int act_bits);
 int dvdq_w4_prepack(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, void *hip_stream);
 size_t dvdq_w4_native_bytes(int64_t N, int64_t K);
 
+/*
+ * delta-Guided Bit Switching (Sec. 3.3): choose the activation bit-width of the next
+ * denoising step from how much the model output changed.
+ *
+ * `state` is 16 bytes of device memory owned by the caller:
+ *     offset 0   double  running sum of relative L1 changes since the last reset
+ *     offset 8   float   the change L1(F, t) computed by the latest dvdq_gbs_step
+ *     offset 12  int32   bit-width for the next step (read this one scalar back)
+ * dvdq_gbs_reset starts a new sampling run: sum 0, bits = initial_bits (the first
+ * step has no predecessor to compare with; b_high is the safe choice).
+ *
+ * dvdq_gbs_step, called after a denoising step produced f_t (bf16, n elements; f_prev
+ * is the previous step's output): computes
+ *     L1 = sum|f_t - f_prev| / sum|f_prev|          (fp32 per thread, fp64 across threads)
+ * adds it to the running sum, and sets bits = b_low while the sum stays below `delta`,
+ * or bits = b_high and sum = 0 once it reaches `delta` (the B_{t_i} case equation).
+ * A zero denominator gives +inf (or 0 when the numerator is zero too).
+ * `workspace`: device, at least dvdq_gbs_workspace_bytes() bytes, scratch.
+ * delta >= 0; b_low <= b_high, each 4, 6 or 8.  Results are bit-reproducible (no atomics).
+ */
+size_t dvdq_gbs_workspace_bytes(void);
+int dvdq_gbs_reset(void *state, int initial_bits, void *hip_stream);
+int dvdq_gbs_step(const void *f_t_bf16, const void *f_prev_bf16, int64_t n, float delta, int b_low, int b_high,
+                  void *state, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 const char *dvdq_status_string(int status);
 int dvdq_version(void);
 

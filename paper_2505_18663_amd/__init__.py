@@ -16,7 +16,7 @@ import torch
 __all__ = [
     "DvdqError", "DvdqLibraryMissing", "lib", "library_path", "version", "status_string",
     "rotate_quant", "w4ax_gemm", "qlinear", "qlinear_workspace_bytes", "qlinear_scale_offset",
-    "w4_prepack", "w4_native_bytes", "bench_copy", "bench_mfma_i8", "bench_set_gemm_variant",
+    "w4_prepack", "w4_native_bytes", "GbsController", "bench_copy", "bench_mfma_i8", "bench_set_gemm_variant",
     "W_CANONICAL", "W_NATIVE", "EXPORTED_SYMBOLS",
 ]
 
@@ -25,7 +25,7 @@ W_CANONICAL, W_NATIVE = 0, 1
 EXPORTED_SYMBOLS = (
     "dvdq_rotate_quant", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_qlinear_workspace_bytes",
     "dvdq_qlinear_scale_offset", "dvdq_w4_prepack", "dvdq_w4_native_bytes", "dvdq_status_string",
-    "dvdq_version", "dvdq_bench_copy", "dvdq_bench_mfma_i8", "dvdq_bench_set_gemm_variant",
+    "dvdq_version", "dvdq_gbs_workspace_bytes", "dvdq_gbs_reset", "dvdq_gbs_step", "dvdq_bench_copy", "dvdq_bench_mfma_i8", "dvdq_bench_set_gemm_variant",
 )
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -67,6 +67,12 @@ def lib() -> C.CDLL:
     L.dvdq_w4_native_bytes.argtypes = [i64, i64]
     L.dvdq_status_string.argtypes = [i32]
     L.dvdq_version.argtypes = []
+    L.dvdq_gbs_workspace_bytes.argtypes = []
+    L.dvdq_gbs_workspace_bytes.restype = sz
+    L.dvdq_gbs_reset.argtypes = [vp, i32, vp]
+    L.dvdq_gbs_reset.restype = i32
+    L.dvdq_gbs_step.argtypes = [vp, vp, i64, C.c_float, i32, i32, vp, vp, sz, vp]
+    L.dvdq_gbs_step.restype = i32
     L.dvdq_bench_copy.argtypes = [vp, vp, sz, vp]
     L.dvdq_bench_mfma_i8.argtypes = [i32, vp, C.POINTER(C.c_double), vp]
     L.dvdq_bench_set_gemm_variant.argtypes = [i32]
@@ -223,6 +229,36 @@ def w4_prepack(w_canonical, w_native=None, stream=None):
         raise ValueError("w_native too small")
     _check(L.dvdq_w4_prepack(_ptr(w_canonical), N, K, _ptr(w_native), _stream(stream)), "dvdq_w4_prepack")
     return w_native
+
+
+# ------------------------------------------------------------------ delta-GBS controller
+class GbsController:
+    """Device-side state of delta-Guided Bit Switching plus the two C calls.  `step` enqueues the
+    update; `bits()` reads the one scalar back (synchronizes)."""
+
+    def __init__(self, delta: float, b_low: int = 4, b_high: int = 8, device="cuda:0", stream=None):
+        self.delta, self.b_low, self.b_high = float(delta), int(b_low), int(b_high)
+        self.state = torch.zeros((16,), dtype=torch.uint8, device=device)
+        self.workspace = torch.empty((lib().dvdq_gbs_workspace_bytes(),), dtype=torch.uint8, device=device)
+        self.reset(stream=stream)
+
+    def reset(self, stream=None):
+        _check(lib().dvdq_gbs_reset(_ptr(self.state), self.b_high, _stream(stream)), "dvdq_gbs_reset")
+
+    def step(self, f_t, f_prev, stream=None):
+        _need(f_t, torch.bfloat16, None, "f_t")
+        _need(f_prev, torch.bfloat16, tuple(f_t.shape), "f_prev")
+        _check(lib().dvdq_gbs_step(_ptr(f_t), _ptr(f_prev), f_t.numel(), self.delta, self.b_low, self.b_high,
+                                   _ptr(self.state), _ptr(self.workspace), self.workspace.numel(), _stream(stream)),
+               "dvdq_gbs_step")
+
+    def read(self):
+        """(running sum, last relative L1, bits for the next step) -- synchronizes."""
+        raw = self.state.cpu().numpy()
+        return float(raw[:8].view("<f8")[0]), float(raw[8:12].view("<f4")[0]), int(raw[12:16].view("<i4")[0])
+
+    def bits(self) -> int:
+        return self.read()[2]
 
 
 # ------------------------------------------------------------------ calibration helpers

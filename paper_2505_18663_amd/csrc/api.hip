@@ -116,6 +116,27 @@ int dvdq_w4_prepack(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w
     return dvdq::launch_w4_prepack(w_canonical, N, K, w_native, static_cast<hipStream_t>(hip_stream));
 }
 
+size_t dvdq_gbs_workspace_bytes(void) { return dvdq::gbs_workspace_bytes(); }
+
+int dvdq_gbs_reset(void *state, int initial_bits, void *hip_stream) {
+    if (!state) return DVDQ_ERR_NULL;
+    if (!bits_ok(initial_bits)) return DVDQ_ERR_UNSUPPORTED;
+    if (!aligned16(state)) return DVDQ_ERR_ALIGN;
+    return dvdq::launch_gbs_reset(state, initial_bits, static_cast<hipStream_t>(hip_stream));
+}
+
+int dvdq_gbs_step(const void *f_t_bf16, const void *f_prev_bf16, int64_t n, float delta, int b_low, int b_high,
+                  void *state, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (!f_t_bf16 || !f_prev_bf16 || !state || !workspace) return DVDQ_ERR_NULL;
+    if (n < 1 || !(delta >= 0.f)) return DVDQ_ERR_SHAPE;
+    if (!bits_ok(b_low) || !bits_ok(b_high) || b_low > b_high) return DVDQ_ERR_UNSUPPORTED;
+    if (workspace_bytes < dvdq::gbs_workspace_bytes()) return DVDQ_ERR_WORKSPACE;
+    if (!aligned16(f_t_bf16) || !aligned16(f_prev_bf16) || !aligned16(state) || !aligned16(workspace))
+        return DVDQ_ERR_ALIGN;
+    return dvdq::launch_gbs_step(static_cast<const uint16_t *>(f_t_bf16), static_cast<const uint16_t *>(f_prev_bf16), n,
+                                 (double)delta, b_low, b_high, state, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
 const char *dvdq_status_string(int status) {
     switch (status) {
         case DVDQ_OK: return "ok";

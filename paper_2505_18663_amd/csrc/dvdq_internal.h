@@ -26,6 +26,11 @@ void set_gemm_variant(int v);  // benchmark sweeps only; -1 = choose by shape
 
 int launch_w4_prepack(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, hipStream_t stream);
 
+size_t gbs_workspace_bytes();
+int launch_gbs_reset(void *state, int bits, hipStream_t stream);
+int launch_gbs_step(const uint16_t *ft, const uint16_t *fp, int64_t n, double delta, int b_low, int b_high,
+                    void *state, void *workspace, hipStream_t stream);
+
 inline int check_launch() { return hipGetLastError() == hipSuccess ? DVDQ_OK : DVDQ_ERR_HIP; }
 
 }  // namespace dvdq

@@ -92,6 +92,22 @@ def test_prepack_argument_errors_and_size():
     assert L.dvdq_w4_prepack(FAKE, 8, 128, ODD, None) == 5
 
 
+def test_gbs_argument_errors():
+    L = dvdq.lib()
+    ws = L.dvdq_gbs_workspace_bytes()
+    assert ws >= 16
+    assert L.dvdq_gbs_reset(None, 8, None) == 1
+    assert L.dvdq_gbs_reset(FAKE, 5, None) == 3
+    assert L.dvdq_gbs_reset(ODD, 8, None) == 5
+    f = L.dvdq_gbs_step
+    assert f(None, FAKE, 64, 0.1, 4, 8, FAKE, FAKE, ws, None) == 1
+    assert f(FAKE, FAKE, 0, 0.1, 4, 8, FAKE, FAKE, ws, None) == 2
+    assert f(FAKE, FAKE, 64, -1.0, 4, 8, FAKE, FAKE, ws, None) == 2
+    assert f(FAKE, FAKE, 64, 0.1, 8, 4, FAKE, FAKE, ws, None) == 3
+    assert f(FAKE, FAKE, 64, 0.1, 4, 8, FAKE, FAKE, ws - 1, None) == 4
+    assert f(FAKE, ODD, 64, 0.1, 4, 8, FAKE, FAKE, ws, None) == 5
+
+
 def test_bench_helpers_argument_errors():
     L = dvdq.lib()
     assert L.dvdq_bench_copy(None, FAKE, 64, None) == 1
