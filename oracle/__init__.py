@@ -47,6 +47,8 @@ def _load():
         lib.dvdq_oracle_rotate_quant.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
         lib.dvdq_oracle_unpack_w4.argtypes = [vp, i64, i64, vp]
         lib.dvdq_oracle_pack_w4.argtypes = [vp, i64, i64, vp]
+        lib.dvdq_oracle_unpack_a4.argtypes = [vp, i64, i64, vp]
+        lib.dvdq_oracle_pack_a4.argtypes = [vp, i64, i64, vp]
         lib.dvdq_oracle_int_gemm.argtypes = [vp, vp, i64, i64, i64, vp]
         lib.dvdq_oracle_epilogue.argtypes = [vp, vp, vp, vp, i64, i64, vp]
         lib.dvdq_oracle_w4ax_gemm.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp]
@@ -58,7 +60,7 @@ def _load():
         lib.dvdq_oracle_gbs_update.restype = i32
         for f in ("hadamard", "rotate", "quantize", "rotate_quant", "w4ax_gemm", "qlinear"):
             getattr(lib, "dvdq_oracle_" + f).restype = i32
-        for f in ("unpack_w4", "pack_w4", "int_gemm", "epilogue", "f64_to_bf16"):
+        for f in ("unpack_w4", "pack_w4", "unpack_a4", "pack_a4", "int_gemm", "epilogue", "f64_to_bf16"):
             getattr(lib, "dvdq_oracle_" + f).restype = None
         _lib = lib
     return _lib
@@ -135,6 +137,28 @@ def pack_w4(codes: np.ndarray) -> np.ndarray:
         raise ValueError("K must be even")
     out = np.empty((N, K // 2), dtype=np.uint8)
     _load().dvdq_oracle_pack_w4(_p(c), N, K, _p(out))
+    return out
+
+
+def unpack_a4(packed: np.ndarray) -> np.ndarray:
+    """Packed 4-bit activation codes uint8 [M, K/2] -> int8 [M, K]."""
+    p = _arr(packed, np.uint8, 2)
+    M, K2 = p.shape
+    if K2 % 4:
+        raise ValueError("K must be a multiple of 8")
+    out = np.empty((M, 2 * K2), dtype=np.int8)
+    _load().dvdq_oracle_unpack_a4(_p(p), M, 2 * K2, _p(out))
+    return out
+
+
+def pack_a4(codes: np.ndarray) -> np.ndarray:
+    """int8 [M, K] codes in [-8, 7] -> packed uint8 [M, K/2]."""
+    c = _arr(codes, np.int8, 2)
+    M, K = c.shape
+    if K % 8:
+        raise ValueError("K must be a multiple of 8")
+    out = np.empty((M, K // 2), dtype=np.uint8)
+    _load().dvdq_oracle_pack_a4(_p(c), M, K, _p(out))
     return out
 
 

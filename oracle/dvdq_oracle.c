@@ -192,6 +192,35 @@ void dvdq_oracle_pack_w4(const int8_t *codes, int64_t N, int64_t K, uint8_t *pac
         }
 }
 
+/* ---------------------------------------------------------------- packed activation codes */
+
+/* The 4-bit container of activation codes between quantizer and GEMM (an encoding of
+ * this library, not of the method: the codes themselves are the ARQ codes of Sec. 3.2).
+ * A row of K codes becomes K/2 bytes; within each group of 8 channels, byte b (0..3)
+ * carries channel 8g+b in bits 0-3 and channel 8g+b+4 in bits 4-7, two's complement. */
+void dvdq_oracle_unpack_a4(const uint8_t *packed, int64_t M, int64_t K, int8_t *codes)
+{
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t g = 0; g < K / 8; ++g)
+            for (int b = 0; b < 4; ++b) {
+                int byte = packed[m * (K / 2) + 4 * g + b];
+                int lo = byte & 0xF, hi = (byte >> 4) & 0xF;
+                codes[m * K + 8 * g + b] = (int8_t)(lo >= 8 ? lo - 16 : lo);
+                codes[m * K + 8 * g + b + 4] = (int8_t)(hi >= 8 ? hi - 16 : hi);
+            }
+}
+
+void dvdq_oracle_pack_a4(const int8_t *codes, int64_t M, int64_t K, uint8_t *packed)
+{
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t g = 0; g < K / 8; ++g)
+            for (int b = 0; b < 4; ++b) {
+                int lo = codes[m * K + 8 * g + b] & 0xF;
+                int hi = codes[m * K + 8 * g + b + 4] & 0xF;
+                packed[m * (K / 2) + 4 * g + b] = (uint8_t)(lo | (hi << 4));
+            }
+}
+
 /* ---------------------------------------------------------------- GEMM */
 
 /* Step 4: acc[m,n] = sum_k q[m,k] * w[n,k], the plain definition, in int64. */

@@ -194,6 +194,29 @@ def test_pack_unpack_all_pairs_and_generator_agreement():
     assert np.array_equal(oracle.unpack_w4(np.array([[0x8F]], dtype=np.uint8))[0], [-1, -8])
 
 
+def test_packed_activation_container_bytes_roundtrip_and_mask_property():
+    # hand-derived bytes for one group of 8 channels: byte b = channel b | channel b+4 << 4
+    row = np.array([[1, -1, 7, -7, 2, 3, -8, 0]], dtype=np.int8)
+    #                 byte0 = 1 | 2<<4, byte1 = 0xF | 3<<4, byte2 = 7 | 8<<4, byte3 = 9 | 0<<4
+    assert oracle.pack_a4(row).tolist() == [[0x21, 0x3F, 0x87, 0x09]]
+    assert np.array_equal(oracle.unpack_a4(np.array([[0x21, 0x3F, 0x87, 0x09]], dtype=np.uint8)), row)
+    # every code value in every one of the 8 positions of a group, two groups per row
+    rng = np.random.default_rng(77)
+    codes = rng.integers(-8, 8, size=(64, 16)).astype(np.int8)
+    for pos in range(16):
+        codes[:16, pos] = np.arange(-8, 8)
+    packed = oracle.pack_a4(codes)
+    assert packed.shape == (64, 8) and np.array_equal(oracle.unpack_a4(packed), codes)
+    # the property the container exists for: reading a group as one little-endian 32-bit word p,
+    # (p << 4) & 0xF0F0F0F0 and p & 0xF0F0F0F0 are the int8 lanes 16*code of channels 0-3 and 4-7
+    p32 = packed.reshape(64, 2, 4).astype(np.uint32)
+    word = p32[..., 0] | (p32[..., 1] << 8) | (p32[..., 2] << 16) | (p32[..., 3] << 24)
+    lo = ((word << 4) & 0xF0F0F0F0).astype(np.uint32)
+    hi = (word & 0xF0F0F0F0).astype(np.uint32)
+    lanes = np.stack([(lo >> (8 * b)) & 0xFF for b in range(4)] + [(hi >> (8 * b)) & 0xFF for b in range(4)], axis=-1)
+    assert np.array_equal(lanes.astype(np.uint8).view(np.int8).reshape(64, 16).astype(np.int32), 16 * codes.astype(np.int32))
+
+
 # ------------------------------------------------------------------ integer GEMM
 def test_int_gemm_bruteforce_vs_float64():
     rng = np.random.default_rng(30)
