@@ -5,7 +5,8 @@ A step is one pass of the whole path -- dvdq_qlinear: block-Hadamard rotation,
 per-token auto-scale, quantization, INT4 x INTb GEMM, dequantizing epilogue --
 over one batch of synthetic activations of the small-video-DiT QKV projection
 (M=32760 tokens, K=1536, N=4608, W4A4, Hadamard block 256).  Inputs are resident
-in HBM before the timed region; weights are pre-packed offline.
+in HBM before the timed region; weights are pre-packed offline.  Between the two
+kernels 4-bit codes travel packed two per byte (the int8 container otherwise).
 
 Prints ONE JSON line: whole-path throughput in TOP/s (2*M*N*K per step), the
 roofline of the dominant kernel (the INT8-MFMA GEMM) from per-launch HIP-event
@@ -28,7 +29,7 @@ HBM_PEAK_GBPS = 8000.0           # published HBM3E bandwidth, MI355X
 # very command, scaled by the same counters' reading for dvdq_bench_copy; the summaries with the
 # commands are profiles/bench_<workload>_hbm_counters.md.  None where no counter run exists.
 MEASURED_HBM_TRAFFIC = {
-    "small_dit_qkv_w4a4": {"w4ax_gemm": 556.8e6, "rotate_quant": 151.3e6},
+    "small_dit_qkv_w4a4": {"w4ax_gemm": 551.0e6, "rotate_quant": 126.1e6},
 }
 
 
@@ -71,16 +72,24 @@ def main():
     xs = [x0] + [x0.clone() for _ in range(nb - 1)]
     w_native = dvdq.w4_prepack(torch.from_numpy(wp).to(dev))
     ws_dev = torch.from_numpy(ws).to(dev)
-    need = dvdq.qlinear_workspace_bytes(M, K, bits)
+    fmt = dvdq.CODES_PACKED4 if bits == 4 else dvdq.CODES_INT8
+    need = dvdq.qlinear_workspace_bytes(M, K, fmt)
     wsp = [torch.empty((need,), dtype=torch.uint8, device=dev) for _ in range(nb)]
     ys = [torch.empty((M, N), dtype=torch.bfloat16, device=dev) for _ in range(nb)]
     torch.cuda.synchronize()
 
     def step(i):
         j = i % nb
-        dvdq.qlinear(xs[j], w_native, ws_dev, B, bits, dvdq.W_NATIVE, y=ys[j], workspace=wsp[j])
+        dvdq.qlinear(xs[j], w_native, ws_dev, B, bits, dvdq.W_NATIVE, y=ys[j], workspace=wsp[j], codes_format=fmt)
 
-    # ---- timed region: whole path
+    # ---- timed region: whole path.  Before the W warm-up steps the same step runs for about half a
+    # second: coming out of idle the chip needs tens of milliseconds to settle its clocks, and
+    # without this the first timed steps run up to 25 % slower than the steady state.
+    t_ramp = time.perf_counter()
+    while time.perf_counter() - t_ramp < 0.5:
+        for i in range(20):
+            step(i)
+        torch.cuda.synchronize()
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -109,20 +118,50 @@ def main():
         ms = sorted(a.elapsed_time(b) / group for a, b in ev)
         return sum(ms) / len(ms), ms[len(ms) // 2]
 
-    views = [dvdq.workspace_views(w_, M, K, bits) for w_ in wsp]
+    views = [dvdq.workspace_views(w_, M, K, fmt) for w_ in wsp]
 
     def rq(i):
         j = i % nb
-        dvdq.rotate_quant(xs[j], B, bits, codes=views[j][0], x_scale=views[j][1])
+        dvdq.rotate_quant(xs[j], B, bits, codes=views[j][0], x_scale=views[j][1], codes_format=fmt)
 
     def gemm(i):
         j = i % nb
-        dvdq.w4ax_gemm(views[j][0], views[j][1], w_native, ws_dev, bits, dvdq.W_NATIVE, y=ys[j])
+        dvdq.w4ax_gemm(views[j][0], views[j][1], w_native, ws_dev, bits, dvdq.W_NATIVE, y=ys[j], codes_format=fmt)
 
-    rq_avg, rq_med = time_launches(rq, args.steps)
-    gemm_avg, gemm_med = time_launches(gemm, args.steps)
-    rq_bytes = 2.0 * M * K + 1.0 * M * K + 4.0 * M          # bf16 in, int8 codes out, fp32 scales out
+    # The two kernels of the path in the order the fused call runs them, one event after every
+    # kernel: a kernel's duration is the time between the events around it.  Measured in this
+    # context (the quantizer runs while the GEMM's output is still draining from the memory-side
+    # cache; the GEMM finds the codes the quantizer just wrote) the two durations add up to the step.
+    def time_in_context(n):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(2 * n + 1)]
+        for i in range(min(args.warmup, 5)):
+            rq(i)
+            gemm(i)
+        torch.cuda.synchronize()
+        evs[0].record()
+        for i in range(n):
+            rq(i)
+            evs[2 * i + 1].record()
+            gemm(i)
+            evs[2 * i + 2].record()
+        torch.cuda.synchronize()
+        t_rq = sorted(evs[2 * i].elapsed_time(evs[2 * i + 1]) for i in range(n))
+        t_gemm = sorted(evs[2 * i + 1].elapsed_time(evs[2 * i + 2]) for i in range(n))
+        return sum(t_rq) / n, t_rq[n // 2], sum(t_gemm) / n, t_gemm[n // 2]
+
+    rq_avg, rq_med, gemm_avg, gemm_med = time_in_context(args.steps)
+    # the same kernels launched back to back on their own (no other kernel in between)
+    rq_alone, _ = time_launches(rq, args.steps)
+    gemm_alone, _ = time_launches(gemm, args.steps)
+    code_bytes = 0.5 if fmt == dvdq.CODES_PACKED4 else 1.0
+    rq_bytes = 2.0 * M * K + code_bytes * M * K + 4.0 * M      # bf16 in, codes out, fp32 scales out
     rq_gbps = rq_bytes / (rq_avg * 1e-3) / 1e9
+    # the same kernel writing the int8 container (3 bytes per element), for reference
+    codes8 = [torch.empty((M, K), dtype=torch.int8, device=dev) for _ in range(nb)]
+    rq8_avg, _ = time_launches(lambda i: dvdq.rotate_quant(xs[i % nb], B, bits, codes=codes8[i % nb],
+                                                           x_scale=views[i % nb][1]), args.steps)
+    rq8_bytes = 3.0 * M * K + 4.0 * M
+    del codes8
     gemm_tops = ops / (gemm_avg * 1e-3) / 1e12
 
     # ---- calibration: what this chip sustains for a plain copy and a register-only INT8 MFMA loop
@@ -153,19 +192,26 @@ def main():
         "ms_per_step": round(t_step * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int8 x int4 -> int32 (bf16 in/out)", "data": "synthetic",
         "config": {"workload": wl.name, "M": M, "K": K, "N": N, "had_block": B, "act_bits": bits,
-                   "w_layout": "native", "buffers_rotated": nb},
+                   "w_layout": "native", "codes_format": "packed4" if fmt == dvdq.CODES_PACKED4 else "int8",
+                   "buffers_rotated": nb},
         "frac_int8_mfma_peak": round(tops / INT8_MFMA_PEAK_TOPS, 4),
         "roofline": {"kernel": "w4ax_gemm", "bound": "mfma", "achieved": round(gemm_tops, 2),
                      "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(gemm_tops / INT8_MFMA_PEAK_TOPS, 4),
                      "traffic": MEASURED_HBM_TRAFFIC.get(wl.name, {}).get("w4ax_gemm"),
                      "avg_launch_ms": round(gemm_avg, 4), "median_launch_ms": round(gemm_med, 4),
+                     "avg_launch_ms_alone": round(gemm_alone, 4),
                      "measured_mfma_ceiling_tops": round(mfma_ceiling, 1)},
         "roofline_rotate_quant": {"kernel": "rotate_quant", "bound": "hbm", "achieved": round(rq_gbps, 1),
                                   "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(rq_gbps / HBM_PEAK_GBPS, 4),
                                   "traffic": MEASURED_HBM_TRAFFIC.get(wl.name, {}).get("rotate_quant"),
                                   "avg_launch_ms": round(rq_avg, 4),
-                                  "median_launch_ms": round(rq_med, 4), "algorithmic_bytes": rq_bytes,
-                                  "measured_copy_gbps": round(copy_gbps, 1)},
+                                  "median_launch_ms": round(rq_med, 4), "avg_launch_ms_alone": round(rq_alone, 4),
+                                  "algorithmic_bytes": rq_bytes,
+                                  "measured_copy_gbps": round(copy_gbps, 1),
+                                  "int8_container": {"achieved": round(rq8_bytes / (rq8_avg * 1e-3) / 1e9, 1),
+                                                     "frac": round(rq8_bytes / (rq8_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                                                     "avg_launch_ms": round(rq8_avg, 4),
+                                                     "algorithmic_bytes": rq8_bytes}},
     }
 
     out["gbs_controller"] = {"elements": n_lat, "us_per_step": round(gbs_avg * 1e3, 2),

@@ -15,7 +15,8 @@
  *
  * Conventions shared by every entry point
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
- *     never allocates, frees or keeps device memory and holds no global state.
+ *     never allocates, frees or keeps device memory and holds no global state
+ *     (the tile-variant switch of dvdq_bench.h, a measurement hook, aside).
  *   - `hip_stream` is the caller's hipStream_t (NULL = the default stream).  All
  *     work is enqueued on it; calls return without synchronizing.
  *   - Inputs are read-only; outputs must not overlap inputs or each other.
@@ -25,8 +26,15 @@
  *   - NaN / Inf in X: no fault, result unspecified.
  *   - Tensors are dense row-major.  bf16 is passed as `void*` to 16-bit patterns.
  *
- * Activation codes: int8 container, one code per byte, values in
- * [-qmax, qmax], qmax = 2^(act_bits-1) - 1  (7, 31 or 127 for 4, 6, 8 bits).
+ * Activation codes, values in [-qmax, qmax], qmax = 2^(act_bits-1) - 1 (7, 31 or 127
+ * for 4, 6, 8 bits), in one of two containers (`codes_format`):
+ *   DVDQ_CODES_INT8     int8 [M, K], one code per byte.  Every bit-width.
+ *   DVDQ_CODES_PACKED4  uint8 [M, K/2], two 4-bit two's-complement codes per byte, act_bits = 4
+ *                       only.  Channels are interleaved within groups of 8: byte b (0..3) of
+ *                       group g of a row holds channel 8g+b in bits 0-3 and channel 8g+b+4 in
+ *                       bits 4-7.  This is the order in which one shift and two masks turn a
+ *                       32-bit word into int8 lanes in channel order; it halves the bytes the
+ *                       quantizer writes and the GEMM reads.  Both are passed as `int8_t *`.
  *
  * Weight codes, canonical layout (DVDQ_W_CANONICAL): uint8 [N, K/2]; byte j of
  * row n holds channel 2j in bits 0-3 and channel 2j+1 in bits 4-7, each a 4-bit
@@ -55,6 +63,7 @@ typedef enum {
 } dvdq_status;
 
 enum { DVDQ_W_CANONICAL = 0, DVDQ_W_NATIVE = 1 };
+enum { DVDQ_CODES_INT8 = 0, DVDQ_CODES_PACKED4 = 1 };
 
 /*
  * Rotate + auto-scale + quantize (Sec. 3.2: X~ = XH by fast Hadamard transform,
@@ -66,12 +75,14 @@ enum { DVDQ_W_CANONICAL = 0, DVDQ_W_NATIVE = 1 };
  *                 of B channels is rotated on its own.  Power of two, 1 <= B <= 512,
  *                 B divides K.  B = 1 means no rotation.
  *   act_bits      4, 6 or 8
- *   codes    out  int8 [M, K]
+ *   codes_format  container of the codes (see above); DVDQ_CODES_PACKED4 with act_bits != 4 is
+ *                 DVDQ_ERR_UNSUPPORTED
+ *   codes    out  int8 [M, K], or uint8 [M, K/2] when packed
  *   x_scale  out  fp32 [M]; 0 for an all-zero row (its codes are all 0)
  *
  * K must be a multiple of 8 (DVDQ_ERR_SHAPE) and at most 65536 (DVDQ_ERR_UNSUPPORTED).
  */
-int dvdq_rotate_quant(const void *x_bf16, int64_t M, int64_t K, int had_block, int act_bits,
+int dvdq_rotate_quant(const void *x_bf16, int64_t M, int64_t K, int had_block, int act_bits, int codes_format,
                       int8_t *codes, float *x_scale, void *hip_stream);
 
 /*
@@ -81,13 +92,17 @@ int dvdq_rotate_quant(const void *x_bf16, int64_t M, int64_t K, int had_block, i
  *     acc[m,n] = sum_k codes[m,k] * w[n,k]                       (exact, int32)
  *     y[m,n]   = bf16( float(acc[m,n]) * x_scale[m] * w_scale[n] + bias[n] )
  *
- *   codes     in   int8 [M, K], |code| <= 2^(act_bits-1) - 1 (not checked)
+ *   codes     in   int8 [M, K] or packed uint8 [M, K/2] per `codes_format`,
+ *                  |code| <= 2^(act_bits-1) - 1 (not checked)
  *   x_scale   in   fp32 [M]
  *   w         in   packed INT4 weights, layout per `w_layout`
  *   w_scale   in   fp32 [N]
  *   bias_bf16 in   bf16 [N] or NULL
- *   act_bits       4, 6 or 8 (bounds the accumulator: qmax * 8 * K must stay below 2^31,
- *                  DVDQ_ERR_UNSUPPORTED otherwise)
+ *   act_bits       4, 6 or 8 (bounds the accumulator: qmax * 8 * K must stay below 2^27, or
+ *                  2^23 with packed codes, DVDQ_ERR_UNSUPPORTED otherwise: the kernels
+ *                  accumulate 16 * acc, resp. 256 * acc)
+ *   codes_format   DVDQ_CODES_PACKED4 needs act_bits = 4 and the native weight layout
+ *                  (DVDQ_ERR_UNSUPPORTED otherwise)
  *   y_bf16    out  bf16 [M, N]
  *   acc_out   out  int32 [M, N] or NULL; when given, receives the raw accumulators
  *                  (parity hook; costs extra bandwidth)
@@ -96,22 +111,23 @@ int dvdq_rotate_quant(const void *x_bf16, int64_t M, int64_t K, int had_block, i
  * (DVDQ_ERR_UNSUPPORTED otherwise).  Any M >= 1, N >= 1; ragged tiles are handled inside.
  */
 int dvdq_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
-                   const void *bias_bf16, int64_t M, int64_t N, int64_t K, int act_bits, int w_layout,
-                   void *y_bf16, int32_t *acc_out, void *hip_stream);
+                   const void *bias_bf16, int64_t M, int64_t N, int64_t K, int act_bits, int codes_format,
+                   int w_layout, void *y_bf16, int32_t *acc_out, void *hip_stream);
 
 /*
  * The whole layer in one call: dvdq_rotate_quant followed by dvdq_w4ax_gemm on
  * the same stream.  `workspace` (device, 256-byte aligned) must hold at least
- * dvdq_qlinear_workspace_bytes(M, K, act_bits) bytes; after the call completes it
- * contains the activation codes (int8 [M, K]) at offset 0 and the token scales
- * (fp32 [M]) at offset dvdq_qlinear_scale_offset(M, K, act_bits), so callers and
- * tests can inspect them.  Arguments as in the two calls above.
+ * dvdq_qlinear_workspace_bytes(M, K, codes_format) bytes; after the call completes it
+ * contains the activation codes (in the container `codes_format` names) at offset 0
+ * and the token scales (fp32 [M]) at offset dvdq_qlinear_scale_offset(M, K,
+ * codes_format), so callers and tests can inspect them.  `codes_format` is the
+ * container used between the two kernels; arguments as in the two calls above.
  */
 int dvdq_qlinear(const void *x_bf16, const uint8_t *w, const float *w_scale, const void *bias_bf16,
-                 int64_t M, int64_t N, int64_t K, int had_block, int act_bits, int w_layout,
+                 int64_t M, int64_t N, int64_t K, int had_block, int act_bits, int codes_format, int w_layout,
                  void *y_bf16, void *workspace, size_t workspace_bytes, void *hip_stream);
-size_t dvdq_qlinear_workspace_bytes(int64_t M, int64_t K, int act_bits);
-size_t dvdq_qlinear_scale_offset(int64_t M, int64_t K, int act_bits);
+size_t dvdq_qlinear_workspace_bytes(int64_t M, int64_t K, int codes_format);
+size_t dvdq_qlinear_scale_offset(int64_t M, int64_t K, int codes_format);
 
 /*
  * One-time, offline: reorder canonical packed weights into the GEMM kernel's

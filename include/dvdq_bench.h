@@ -29,7 +29,8 @@ int dvdq_bench_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
 int dvdq_bench_mfma_i8(int iters, int32_t *sink, double *ops_out, void *hip_stream);
 
 /* Tile-configuration sweeps: force the native-layout GEMM to use tile variant `variant`
- * (1..4, see the dispatch table in w4ax_gemm.hip); -1 restores the library's own choice.  Process-wide,
+ * (1..4, see the dispatch tables in w4ax_gemm.hip, one per code container; shapes too shallow
+ * in K for a variant's ring fall back to variant 2); -1 restores the library's own choice.  Process-wide,
  * not thread-safe, meant for benchmarking only. */
 int dvdq_bench_set_gemm_variant(int variant);
 

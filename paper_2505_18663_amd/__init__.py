@@ -17,10 +17,11 @@ __all__ = [
     "DvdqError", "DvdqLibraryMissing", "lib", "library_path", "version", "status_string",
     "rotate_quant", "w4ax_gemm", "qlinear", "qlinear_workspace_bytes", "qlinear_scale_offset",
     "w4_prepack", "w4_native_bytes", "GbsController", "bench_copy", "bench_mfma_i8", "bench_set_gemm_variant",
-    "W_CANONICAL", "W_NATIVE", "EXPORTED_SYMBOLS",
+    "W_CANONICAL", "W_NATIVE", "CODES_INT8", "CODES_PACKED4", "EXPORTED_SYMBOLS",
 ]
 
 W_CANONICAL, W_NATIVE = 0, 1
+CODES_INT8, CODES_PACKED4 = 0, 1
 
 EXPORTED_SYMBOLS = (
     "dvdq_rotate_quant", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_qlinear_workspace_bytes",
@@ -58,9 +59,9 @@ def lib() -> C.CDLL:
             "(hipcc, gfx950).  There is no fallback path.")
     L = C.CDLL(_LIB_PATH)
     i64, i32, vp, sz = C.c_int64, C.c_int, C.c_void_p, C.c_size_t
-    L.dvdq_rotate_quant.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
-    L.dvdq_w4ax_gemm.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, vp, vp, vp]
-    L.dvdq_qlinear.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, vp, sz, vp]
+    L.dvdq_rotate_quant.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp]
+    L.dvdq_w4ax_gemm.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, vp, vp]
+    L.dvdq_qlinear.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, i32, vp, vp, sz, vp]
     L.dvdq_qlinear_workspace_bytes.argtypes = [i64, i64, i32]
     L.dvdq_qlinear_scale_offset.argtypes = [i64, i64, i32]
     L.dvdq_w4_prepack.argtypes = [vp, i64, i64, vp, vp]
@@ -124,29 +125,43 @@ def _check(rc, where):
 
 
 # ------------------------------------------------------------------ the layer
-def rotate_quant(x, had_block: int, act_bits: int, codes=None, x_scale=None, stream=None):
-    """x: bf16 [M, K] -> (codes int8 [M, K], x_scale fp32 [M]).  See dvdq_rotate_quant."""
+def _codes_spec(M: int, K: int, codes_format: int):
+    """(dtype, shape) of the tensor that carries the activation codes."""
+    if codes_format == CODES_PACKED4:
+        return torch.uint8, (M, K // 2)
+    return torch.int8, (M, K)
+
+
+def rotate_quant(x, had_block: int, act_bits: int, codes=None, x_scale=None, stream=None,
+                 codes_format: int = CODES_INT8):
+    """x: bf16 [M, K] -> (codes int8 [M, K] or packed uint8 [M, K/2], x_scale fp32 [M]).
+    See dvdq_rotate_quant."""
     L = lib()
     _need(x, torch.bfloat16, None, "x")
     M, K = x.shape
+    cdtype, cshape = _codes_spec(M, K, codes_format)
     if codes is None:
-        codes = torch.empty((M, K), dtype=torch.int8, device=x.device)
+        codes = torch.empty(cshape, dtype=cdtype, device=x.device)
     if x_scale is None:
         x_scale = torch.empty((M,), dtype=torch.float32, device=x.device)
-    _need(codes, torch.int8, (M, K), "codes")
+    _need(codes, cdtype, cshape, "codes")
     _need(x_scale, torch.float32, (M,), "x_scale")
-    _check(L.dvdq_rotate_quant(_ptr(x), M, K, had_block, act_bits, _ptr(codes), _ptr(x_scale), _stream(stream)),
-           "dvdq_rotate_quant")
+    _check(L.dvdq_rotate_quant(_ptr(x), M, K, had_block, act_bits, codes_format, _ptr(codes), _ptr(x_scale),
+                               _stream(stream)), "dvdq_rotate_quant")
     return codes, x_scale
 
 
 def w4ax_gemm(codes, x_scale, w, w_scale, act_bits: int, w_layout: int = W_CANONICAL, bias=None,
-              y=None, acc_out=None, want_acc: bool = False, stream=None):
-    """codes int8 [M, K], w uint8 packed INT4 [N, K/2] (or native) -> y bf16 [M, N].
-    With want_acc (or acc_out given) also returns the int32 accumulators."""
+              y=None, acc_out=None, want_acc: bool = False, stream=None, codes_format: int = CODES_INT8):
+    """codes int8 [M, K] (or packed uint8 [M, K/2]), w uint8 packed INT4 [N, K/2] (or native)
+    -> y bf16 [M, N].  With want_acc (or acc_out given) also returns the int32 accumulators."""
     L = lib()
-    _need(codes, torch.int8, None, "codes")
-    M, K = codes.shape
+    if codes_format == CODES_PACKED4:
+        _need(codes, torch.uint8, None, "codes")
+        M, K = codes.shape[0], 2 * codes.shape[1]
+    else:
+        _need(codes, torch.int8, None, "codes")
+        M, K = codes.shape
     _need(w_scale, torch.float32, None, "w_scale")
     N = w_scale.shape[0]
     _need(x_scale, torch.float32, (M,), "x_scale")
@@ -165,22 +180,22 @@ def w4ax_gemm(codes, x_scale, w, w_scale, act_bits: int, w_layout: int = W_CANON
     if acc_out is not None:
         _need(acc_out, torch.int32, (M, N), "acc_out")
     _check(L.dvdq_w4ax_gemm(_ptr(codes), _ptr(x_scale), _ptr(w), _ptr(w_scale), _ptr(bias), M, N, K, act_bits,
-                            w_layout, _ptr(y), _ptr(acc_out), _stream(stream)), "dvdq_w4ax_gemm")
+                            codes_format, w_layout, _ptr(y), _ptr(acc_out), _stream(stream)), "dvdq_w4ax_gemm")
     return (y, acc_out) if acc_out is not None else y
 
 
-def qlinear_workspace_bytes(M: int, K: int, act_bits: int) -> int:
-    return lib().dvdq_qlinear_workspace_bytes(M, K, act_bits)
+def qlinear_workspace_bytes(M: int, K: int, codes_format: int = CODES_INT8) -> int:
+    return lib().dvdq_qlinear_workspace_bytes(M, K, codes_format)
 
 
-def qlinear_scale_offset(M: int, K: int, act_bits: int) -> int:
-    return lib().dvdq_qlinear_scale_offset(M, K, act_bits)
+def qlinear_scale_offset(M: int, K: int, codes_format: int = CODES_INT8) -> int:
+    return lib().dvdq_qlinear_scale_offset(M, K, codes_format)
 
 
 def qlinear(x, w, w_scale, had_block: int, act_bits: int, w_layout: int = W_CANONICAL, bias=None,
-            y=None, workspace=None, stream=None):
+            y=None, workspace=None, stream=None, codes_format: int = CODES_INT8):
     """The whole layer.  Returns (y bf16 [M, N], workspace uint8); the workspace holds the
-    codes at offset 0 and the token scales at qlinear_scale_offset(M, K, act_bits)."""
+    codes at offset 0 and the token scales at qlinear_scale_offset(M, K, codes_format)."""
     L = lib()
     _need(x, torch.bfloat16, None, "x")
     M, K = x.shape
@@ -194,19 +209,20 @@ def qlinear(x, w, w_scale, had_block: int, act_bits: int, w_layout: int = W_CANO
     if y is None:
         y = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
     _need(y, torch.bfloat16, (M, N), "y")
-    need = L.dvdq_qlinear_workspace_bytes(M, K, act_bits)
+    need = L.dvdq_qlinear_workspace_bytes(M, K, codes_format)
     if workspace is None:
         workspace = torch.empty((need,), dtype=torch.uint8, device=x.device)
     _need(workspace, torch.uint8, None, "workspace")
-    _check(L.dvdq_qlinear(_ptr(x), _ptr(w), _ptr(w_scale), _ptr(bias), M, N, K, had_block, act_bits, w_layout,
-                          _ptr(y), _ptr(workspace), workspace.numel(), _stream(stream)), "dvdq_qlinear")
+    _check(L.dvdq_qlinear(_ptr(x), _ptr(w), _ptr(w_scale), _ptr(bias), M, N, K, had_block, act_bits, codes_format,
+                          w_layout, _ptr(y), _ptr(workspace), workspace.numel(), _stream(stream)), "dvdq_qlinear")
     return y, workspace
 
 
-def workspace_views(workspace, M: int, K: int, act_bits: int):
-    """(codes int8 [M, K], x_scale fp32 [M]) views into a qlinear workspace."""
-    off = qlinear_scale_offset(M, K, act_bits)
-    codes = workspace[:M * K].view(torch.int8).view(M, K)
+def workspace_views(workspace, M: int, K: int, codes_format: int = CODES_INT8):
+    """(codes int8 [M, K] or packed uint8 [M, K/2], x_scale fp32 [M]) views into a qlinear workspace."""
+    off = qlinear_scale_offset(M, K, codes_format)
+    cdtype, cshape = _codes_spec(M, K, codes_format)
+    codes = workspace[:cshape[0] * cshape[1]].view(cdtype).view(cshape)
     scale = workspace[off:off + 4 * M].view(torch.float32)
     return codes, scale
 

@@ -86,13 +86,16 @@ __device__ __forceinline__ uint32_t had5_bf16(int r, int k, int mask) {
 
 // CPW = units per wave.  waves_per_row (W) waves share a row; unit u of the row
 // belongs to wave (u % W) as its (u / W)-th unit.
-template <int LOG2B, int CPW>
+template <int LOG2B, int CPW, bool PACK4>
 __global__ __launch_bounds__(1024) void rotate_quant_kernel(
     const uint16_t *__restrict__ x, int64_t M, int K, int waves_per_row, int rows_per_wg,
     double scale_mul,  // 1 / (sqrt(B) * qmax); fp64 so the fp32 scale is rounded once
     float recip_num,   // 1 / sqrt(B)
+    int via_lds,       // PACK4 only: gather the packed codes through LDS into 16-byte stores (K % 32 == 0)
     int8_t *__restrict__ codes, float *__restrict__ x_scale) {
     extern __shared__ float s_amax[];  // [2][rows_per_wg * waves_per_row], slots alternate per iteration
+    // then, 16-byte aligned, [waves][CPW][64] dwords for gathering packed codes (via_lds)
+    uint32_t *s_pack = reinterpret_cast<uint32_t *>(s_amax) + (2 * rows_per_wg * waves_per_row + 3) / 4 * 4;
     constexpr int MASK5 = LOG2B >= 5 ? 31 : ((1 << LOG2B) - 1);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
@@ -198,18 +201,57 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
         if (row_ok && wsub == 0 && lane == 0) x_scale[row] = scale;
 
         const float magic = 12582912.f;  // 1.5 * 2^23: adding it rounds to integer, ties to even
+        if (PACK4) {
+            // two codes per byte, in the nibble order the GEMM widens with two masks: byte b of a
+            // chunk's dword = code[b] (bits 0-3) | code[b + 4] (bits 4-7), two's complement
+            uint32_t p[CPW];
 #pragma unroll
-        for (int c = 0; c < CPW; ++c) {
-            uint32_t b[8];
+            for (int c = 0; c < CPW; ++c) {
+                uint32_t b[8], u[4];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) b[i] = __float_as_uint(fmaf(v[c][i], r, magic));
-            // low bytes of b[0..3] / b[4..7] -> one dword each
-            uint2 out;
-            out.x = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u),
-                                          __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u), 0x05040100u);
-            out.y = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[7], b[6], 0x0c0c0400u),
-                                          __builtin_amdgcn_perm(b[5], b[4], 0x0c0c0400u), 0x05040100u);
-            if (row_ok && k0[c] < K) *reinterpret_cast<uint2 *>(codes + row * K + k0[c]) = out;
+                for (int i = 0; i < 8; ++i) b[i] = __float_as_uint(fmaf(v[c][i], r, magic));
+#pragma unroll
+                for (int i = 0; i < 4; ++i) u[i] = (b[i] & 0xFu) | (b[i + 4] << 4);
+                p[c] = __builtin_amdgcn_perm(__builtin_amdgcn_perm(u[3], u[2], 0x0c0c0400u),
+                                             __builtin_amdgcn_perm(u[1], u[0], 0x0c0c0400u), 0x05040100u);
+            }
+            if (via_lds) {
+                // K % 32 == 0: a unit's 64 dwords (one per lane, in chunk order) are gathered through
+                // LDS so that 16 lanes store the unit as 16-byte pieces; wave-private LDS, in-order
+                uint32_t *sp = s_pack + wave * (CPW * 64);
+#pragma unroll
+                for (int c = 0; c < CPW; ++c) sp[c * 64 + chunk] = p[c];
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+                for (int idx0 = 0; idx0 < CPW * 16; idx0 += kWave) {
+                    const int idx = idx0 + lane, c = idx >> 4, part = idx & 15;
+                    const int k = (wsub + c * waves_per_row) * kUnit + part * 32;  // first channel of the piece
+                    if (idx < CPW * 16 && row_ok && k < K)
+                        *reinterpret_cast<uint4 *>(codes + (row * K + k) / 2) =
+                            *reinterpret_cast<const uint4 *>(sp + c * 64 + part * 4);
+                }
+                __builtin_amdgcn_wave_barrier();   // the next row's LDS writes stay behind these reads
+            } else {
+#pragma unroll
+                for (int c = 0; c < CPW; ++c)
+                    if (row_ok && k0[c] < K) *reinterpret_cast<uint32_t *>(codes + (row * K + k0[c]) / 2) = p[c];
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < CPW; ++c) {
+                uint32_t b[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) b[i] = __float_as_uint(fmaf(v[c][i], r, magic));
+                // low bytes of b[0..3] / b[4..7] -> one dword each
+                uint2 out;
+                out.x = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u),
+                                              __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u), 0x05040100u);
+                out.y = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[7], b[6], 0x0c0c0400u),
+                                              __builtin_amdgcn_perm(b[5], b[4], 0x0c0c0400u), 0x05040100u);
+                if (row_ok && k0[c] < K) *reinterpret_cast<uint2 *>(codes + row * K + k0[c]) = out;
+            }
         }
 #pragma unroll
         for (int c = 0; c < CPW; ++c) raw[c] = nxt[c];
@@ -218,11 +260,16 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
 
 template <int LOG2B>
 int launch_cpw(int cpw, dim3 grid, dim3 block, size_t smem, hipStream_t stream, const uint16_t *x, int64_t M,
-               int K, int W, int rpw, double scale_mul, float recip_num, int8_t *codes, float *x_scale) {
+               int K, int W, int rpw, double scale_mul, float recip_num, int pack4, int8_t *codes,
+               float *x_scale) {
 #define DVDQ_RQ_CASE(C)                                                                                   \
     case C:                                                                                               \
-        hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C>), grid, block, smem, stream, x, M, K, W, rpw,   \
-                           scale_mul, recip_num, codes, x_scale);                                         \
+        if (pack4)                                                                                        \
+            hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C, true>), grid, block, smem, stream, x, M, K, \
+                               W, rpw, scale_mul, recip_num, pack4 == 2, codes, x_scale);                 \
+        else                                                                                              \
+            hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C, false>), grid, block, smem, stream, x, M,   \
+                               K, W, rpw, scale_mul, recip_num, 0, codes, x_scale);                       \
         break;
     switch (cpw) {
         DVDQ_RQ_CASE(1) DVDQ_RQ_CASE(2) DVDQ_RQ_CASE(3) DVDQ_RQ_CASE(4)
@@ -235,8 +282,9 @@ int launch_cpw(int cpw, dim3 grid, dim3 block, size_t smem, hipStream_t stream, 
 
 }  // namespace
 
-int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block, int act_bits, int8_t *codes,
-                        float *x_scale, hipStream_t stream) {
+int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block, int act_bits, int codes_format,
+                        int8_t *codes, float *x_scale, hipStream_t stream) {
+    const int pack4 = codes_format != DVDQ_CODES_PACKED4 ? 0 : ((K % 32) == 0 ? 2 : 1);
     const int units = (int)((K + kUnit - 1) / kUnit);
     // waves per row: at most 4 units (32 fp32 values per lane) in registers per wave, at most 16 waves
     int W = (units + 3) / 4;
@@ -252,7 +300,8 @@ int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block,
     if (wgs_per_cu < 1) wgs_per_cu = 1;
     const int64_t wgs_resident = 256 * (int64_t)wgs_per_cu;
     const dim3 grid((unsigned)(wgs_needed < wgs_resident ? wgs_needed : wgs_resident));
-    const size_t smem = 2 * sizeof(float) * W * rows_per_wg;
+    size_t smem = 2 * sizeof(float) * W * rows_per_wg;
+    if (pack4 == 2) smem = (smem + 15) / 16 * 16 + (size_t)W * rows_per_wg * cpw * 256;
     const double qmax = (double)((1 << (act_bits - 1)) - 1);
     const double norm = 1.0 / sqrt((double)(1 << log2_block));
     const double scale_mul = norm / qmax;
@@ -260,7 +309,7 @@ int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block,
 #define DVDQ_RQ_B(L)                                                                                        \
     case L:                                                                                                 \
         return launch_cpw<L>(cpw, grid, block, smem, stream, x, M, (int)K, W, rows_per_wg, scale_mul,       \
-                             recip_num, codes, x_scale);
+                             recip_num, pack4, codes, x_scale);
     switch (log2_block) {
         DVDQ_RQ_B(0) DVDQ_RQ_B(1) DVDQ_RQ_B(2) DVDQ_RQ_B(3) DVDQ_RQ_B(4)
         DVDQ_RQ_B(5) DVDQ_RQ_B(6) DVDQ_RQ_B(7) DVDQ_RQ_B(8) DVDQ_RQ_B(9)

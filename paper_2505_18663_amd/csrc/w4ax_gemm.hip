@@ -108,7 +108,7 @@ __device__ __forceinline__ void tile_origin(int t, int tiles_m, int tiles_n, int
     n0 = (grp * group_n + (in_grp - tile_m * gw)) * BN;
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int OCC>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int OCC, bool A4>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_kernel(
     const int8_t *__restrict__ codes, const float *__restrict__ x_scale, const uint8_t *__restrict__ w,
     const float *__restrict__ w_scale, const uint16_t *__restrict__ bias, int M, int N, int K,
@@ -116,21 +116,28 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave sub-tile
     constexpr int TM = WM / 32, TN = WN / 32;            // MFMA tiles per wave
-    constexpr int KS = BK / 32;                          // MFMA K steps per item
-    constexpr int A_STAGE = BM * BK, W_STAGE = BN * BK / 2, STAGE = A_STAGE + W_STAGE;
+    // A4: the codes arrive packed two per byte (same nibble order as the weights) and are
+    // widened to int8 lanes of 16 * code in registers like the weights.  A lane's 16-byte code
+    // fragment then spans 32 channels, so one pipeline step covers 64 channels = 2 MFMAs per tile.
+    constexpr int A_ROW = A4 ? BK / 2 : BK;              // bytes of one code row per item
+    constexpr int NT = A4 ? 2 : 1;                       // MFMAs along K per step and output tile
+    constexpr int KS = BK / (32 * NT);                   // pipeline steps per item
+    constexpr int A_STAGE = BM * A_ROW, W_STAGE = BN * BK / 2, STAGE = A_STAGE + W_STAGE;
     constexpr int A_DMA = A_STAGE / 1024 / NW;           // LDS-direct loads per wave per item (1 KB each)
     constexpr int W_DMA = W_STAGE / 1024 / NW;
     constexpr int DMA = A_DMA + W_DMA;
-    constexpr int CHUNKS = BK / 16;                      // 16-byte chunks per code row in LDS
-    constexpr int ROWS_PER_DMA = 1024 / BK;              // code rows one wave-wide load covers
+    constexpr int CHUNKS = A_ROW / 16;                   // 16-byte chunks per code row in LDS
+    constexpr int ROWS_PER_DMA = 1024 / A_ROW;           // code rows one wave-wide load covers
     constexpr int W_GROUP = kGroup * BK / 2;             // bytes of one 32-row weight group per item
     // With 3 or more buffers the item after the current one is already published, so the
     // first fragments of item q+1 are fetched while the last MFMAs of item q run.
     constexpr int AHEAD = STAGES >= 3 ? 1 : 0;
-    constexpr int SCALES = (BM + BN) * 4;                // bytes of one tile's token + channel scales in LDS
+    // bytes of one tile's epilogue vectors in LDS: token scales, channel scales (fp32), bias (bf16)
+    constexpr int SCALES = (BM + BN) * 4 + BN * 2;
     constexpr int STORES = TM * TN * 2;                  // 16-byte store instructions per wave per full tile
     static_assert((STAGES - 2 - AHEAD) * DMA + STORES < 64, "store-aware wait exceeds vmcnt");
     static_assert(BK == 64 || BK == 128, "K slice per item");
+    static_assert(A_ROW == 64 || A_ROW == 128, "code row bytes per item");
     static_assert(A_DMA >= 1 && W_DMA >= 1 && A_DMA * 1024 * NW == A_STAGE && W_DMA * 1024 * NW == W_STAGE,
                   "tile does not split over the waves");
     static_assert(STAGES >= 2 && (STAGES - 1) * DMA < 64, "too many loads in flight for vmcnt");
@@ -138,13 +145,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     extern __shared__ __align__(16) uint8_t smem[];
     const uint32_t smem_base = lds_address(smem);
 
-    auto swz = [] __device__(int row) { return swz_bk<BK>(row); };
+    auto swz = [] __device__(int row) { return swz_bk<A_ROW>(row); };
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = (wave % WAVES_M) * WM, wn = (wave / WAVES_M) * WN;
     const int KT = K / BK;
     const int G = ((N + kNPad - 1) / kNPad) * (kNPad / kGroup);  // 32-row groups in the padded weight buffer
     const int64_t w_slice_stride = (int64_t)G * kGroupBytes;
+    const int code_row_bytes = A4 ? K / 2 : K;
 
     // Persistent workgroups.  Workgroup ids are dealt round-robin to the 8 XCDs; the j-th
     // tile of workgroup b is number j * grid + (b % 8) * (grid / 8) + b / 8, so the
@@ -182,12 +190,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
         if (issue_kt == 0 && issued < items) {
             int m0, n0;
             tile_origin(first_tile + issue_tile * grid, tiles_m, tiles_n, group_n, BM, BN, m0, n0);
-            a_base = uniform_ptr(codes + (int64_t)m0 * K);
+            a_base = uniform_ptr(codes + (int64_t)m0 * code_row_bytes);
             w_base = uniform_ptr(w + (int64_t)(n0 / kGroup) * kGroupBytes);
 #pragma unroll
             for (int i = 0; i < A_DMA; ++i) {
                 const int row = min(a_row[i], M - 1 - m0);   // rows past M re-read the last valid row
-                a_voff[i] = (uint32_t)row * K + (((lane % CHUNKS) ^ swz(a_row[i])) << 4);
+                a_voff[i] = (uint32_t)row * code_row_bytes + (((lane % CHUNKS) ^ swz(a_row[i])) << 4);
             }
             // The tile's scales go to LDS as well ([BM token scales][BN channel scales], two tiles
             // deep), so that the epilogue needs no vector-memory load: such a load would queue
@@ -203,6 +211,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
                 else
                     lds_direct_load4(w_scale, (uint32_t)min(n0 + (j - BM / 64) * 64 + lane, N - 1) * 4, sc + j * 256);
             }
+            // bias of a tile that lies fully inside N (the only case in which the epilogue reads it from LDS)
+            if (bias && n0 + BN <= N) {
+#pragma unroll
+                for (int j = 0; j < BN / 128; ++j)
+                    if (j % NW == wave)
+                        lds_direct_load4(bias + n0, (uint32_t)(j * 64 + lane) * 4, sc + (BM + BN) * 4 + j * 256);
+            }
         }
         issue_sa = smem_base + buf * STAGE;
     };
@@ -214,7 +229,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     };
     auto issue_advance = [&] __device__() {
         if (++issued < items) {
-            a_base += BK;
+            a_base += A_ROW;
             // items alternate between the halves of a 128-channel slice of the native layout when BK = 64
             w_base += (BK == 128 || (issue_kt & 1)) ? w_slice_stride - (kBK - BK) * (kGroup / 2) : (int64_t)W_GROUP;
             if (++issue_kt == KT) { issue_kt = 0; ++issue_tile; }
@@ -233,12 +248,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     const int frow = lane & 31, fhalf = lane >> 5;
     int a_row_off[TM];
 #pragma unroll
-    for (int j = 0; j < TM; ++j) a_row_off[j] = (wm + j * 32 + frow) * BK;
+    for (int j = 0; j < TM; ++j) a_row_off[j] = (wm + j * 32 + frow) * A_ROW;
     const int a_xor = swz(frow);  // == swz(row): wm and 32 j are multiples of 32
-    const int w_off = (wn / kGroup) * W_GROUP + fhalf * 256 + frow * 8;
+    // Weight fragment of MFMA t of step ks: the 16 channels at 32 (NT ks + t) + 16 fhalf of the slice
+    // with int8 codes; with packed codes lane half fhalf owns channels 64 ks + 32 fhalf + 16 t
+    // (what its 16-byte code fragment holds), i.e. k32 step 2 ks + fhalf, k16 half t of the layout.
+    const int w_off = (wn / kGroup) * W_GROUP + frow * 8 + fhalf * (A4 ? 512 : 256);
 
-    // fragments of one K=32 step: TM code fragments (16 B) and TN packed weight fragments (8 B)
-    struct Frags { v4i a[TM]; uint2 w[TN]; };
+    // fragments of one step: TM code fragments (16 B) and NT x TN packed weight fragments (8 B)
+    struct Frags { v4i a[TM]; uint2 w[NT][TN]; };
     auto load_frags = [&] __device__(Frags &f, int buf, int ks) {
         const uint8_t *sa = smem + buf * STAGE, *sw = sa + A_STAGE;
 #pragma unroll
@@ -246,23 +264,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
             f.a[j] = *reinterpret_cast<const v4i *>(sa + a_row_off[j] + (((ks * 2 + fhalf) ^ a_xor) << 4));
         }
 #pragma unroll
-        for (int i = 0; i < TN; ++i) {
-            f.w[i] = *reinterpret_cast<const uint2 *>(sw + w_off + i * W_GROUP + ks * 512);
-        }
-    };
-    auto mma_part = [&] __device__(const Frags &f, int i) {
-        v4i fw;   // int8 lanes of 16 * code, channel order
-        fw[0] = (int)((f.w[i].x << 4) & 0xF0F0F0F0u);
-        fw[1] = (int)(f.w[i].x & 0xF0F0F0F0u);
-        fw[2] = (int)((f.w[i].y << 4) & 0xF0F0F0F0u);
-        fw[3] = (int)(f.w[i].y & 0xF0F0F0F0u);
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int j = 0; j < TM; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw, f.a[j], acc[i][j], 0, 0, 0);
+            for (int i = 0; i < TN; ++i) {
+                f.w[t][i] = *reinterpret_cast<const uint2 *>(sw + w_off + i * W_GROUP +
+                                                             (A4 ? ks * 1024 + t * 256 : ks * 512));
+            }
     };
-    auto mma_step = [&] __device__(const Frags &f) {
-#pragma unroll
-        for (int i = 0; i < TN; ++i) mma_part(f, i);
+    // two packed dwords (16 codes) -> int8 lanes of 16 * code, channel order
+    auto widen = [] __device__(uint32_t lo, uint32_t hi) {
+        v4i f;
+        f[0] = (int)((lo << 4) & 0xF0F0F0F0u);
+        f[1] = (int)(lo & 0xF0F0F0F0u);
+        f[2] = (int)((hi << 4) & 0xF0F0F0F0u);
+        f[3] = (int)(hi & 0xF0F0F0F0u);
+        return f;
     };
 
     // ---- prologue: fill STAGES-1 buffers; with look-ahead also publish slice 0 and fetch its first fragments
@@ -314,11 +330,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
             else if (AHEAD) load_frags(nxt, (q + 1) % STAGES, 0);   // after the last item: stale but in-bounds, unused
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < TN; ++i) {
-                mma_part(cur, i);
+            for (int t = 0; t < NT; ++t) {
+                v4i fa[TM];
 #pragma unroll
-                for (int d = ks * TN + i; d < DMA; d += KS * TN) issue_one(d);
-                __builtin_amdgcn_sched_barrier(0);
+                for (int j = 0; j < TM; ++j)
+                    fa[j] = A4 ? widen((uint32_t)cur.a[j][2 * t], (uint32_t)cur.a[j][2 * t + 1]) : cur.a[j];
+#pragma unroll
+                for (int i = 0; i < TN; ++i) {
+                    const v4i fw = widen(cur.w[t][i].x, cur.w[t][i].y);
+#pragma unroll
+                    for (int j = 0; j < TM; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw, fa[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+                    for (int d = (ks * NT + t) * TN + i; d < DMA; d += KS * NT * TN) issue_one(d);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         }
         issue_advance();
@@ -333,14 +359,73 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
         const bool vec8 = (N & 7) == 0;
         const float *s_xs = reinterpret_cast<const float *>(smem + STAGES * STAGE + ((tile_j - 1) & 1) * SCALES);
         const float *s_ws = s_xs + BM;
-        // every lane of every wave stores all its values: the store count is exact (see the wait above)
-        if (vec8 && !acc_out && m0 + BM <= M && n0 + BN <= N && KT >= STAGES)
-            store_credit = STAGES - 1 - AHEAD;
+        constexpr float kUnwiden = A4 ? 0.00390625f : 0.0625f;  // the factor 16 of the widened weights (and codes)
+        if (vec8 && !acc_out && m0 + BM <= M && n0 + BN <= N) {
+            // ---- interior tile: no predicates, every vector the epilogue needs comes from LDS up front,
+            // one row pointer per lane.  Every lane of every wave stores all its values, so the number of
+            // stores is exact (see the store-aware wait above).
+            if (KT >= STAGES) store_credit = STAGES - 1 - AHEAD;
+            const float *ws_l = s_ws + wn + fhalf * 4;
+            const uint32_t *bias_l = reinterpret_cast<const uint32_t *>(s_ws + BN) + (wn + fhalf * 4) / 2;
+            float xs16[TM];
+#pragma unroll
+            for (int j = 0; j < TM; ++j) xs16[j] = s_xs[wm + j * 32 + frow] * kUnwiden;
+            uint16_t *yrow = y + (int64_t)(m0 + wm + frow) * N + (n0 + wn + fhalf * 8);
+#pragma unroll
+            for (int i = 0; i < TN; ++i) {
+                // two of the MFMA tile's four 8-channel groups at a time (bounds the live registers)
+#pragma unroll
+                for (int g = 0; g < 4; g += 2) {
+                    float4 wsv[2];
+                    uint2 bb[2];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        wsv[h] = *reinterpret_cast<const float4 *>(ws_l + i * 32 + (g + h) * 8);
+                        if (bias) bb[h] = *reinterpret_cast<const uint2 *>(bias_l + (i * 32 + (g + h) * 8) / 2);
+                    }
+#pragma unroll
+                    for (int j = 0; j < TM; ++j) {
+                        uint32_t pk[2][2];
+#pragma unroll
+                        for (int h = 0; h < 2; ++h) {
+                            const int r = (g + h) * 4;
+                            float o[4];
+                            o[0] = (float)acc[i][j][r + 0] * xs16[j] * wsv[h].x;
+                            o[1] = (float)acc[i][j][r + 1] * xs16[j] * wsv[h].y;
+                            o[2] = (float)acc[i][j][r + 2] * xs16[j] * wsv[h].z;
+                            o[3] = (float)acc[i][j][r + 3] * xs16[j] * wsv[h].w;
+                            if (bias) {
+                                o[0] += __uint_as_float(bb[h].x << 16);
+                                o[1] += __uint_as_float(bb[h].x & 0xFFFF0000u);
+                                o[2] += __uint_as_float(bb[h].y << 16);
+                                o[3] += __uint_as_float(bb[h].y & 0xFFFF0000u);
+                            }
+                            pk[h][0] = pack_bf16x2(o[0], o[1]);
+                            pk[h][1] = pack_bf16x2(o[2], o[3]);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) acc[i][j][r + e] = 0;
+                        }
+                        // lanes l and l+32 hold channels (8g .. 8g+3) and (8g+4 .. 8g+7): swap the upper half
+                        // of group g with the lower half of group g+1 so each lane owns 8 consecutive channels
+#pragma unroll
+                        for (int d = 0; d < 2; ++d) {
+                            auto sw = __builtin_amdgcn_permlane32_swap(pk[0][d], pk[1][d], false, false);
+                            pk[0][d] = sw[0];
+                            pk[1][d] = sw[1];
+                        }
+                        *reinterpret_cast<uint4 *>(yrow + (int64_t)j * 32 * N + i * 32 + g * 8) =
+                            make_uint4(pk[0][0], pk[0][1], pk[1][0], pk[1][1]);
+                    }
+                }
+            }
+            continue;
+        }
+        // ---- edge tiles, N not a multiple of 8, or the accumulator hook: predicated per element
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
             const int m = m0 + wm + j * 32 + frow;
             const bool m_ok = m < M;
-            const float xs16 = s_xs[wm + j * 32 + frow] * 0.0625f;   // folds the factor 16 of the widened weights
+            const float xs16 = s_xs[wm + j * 32 + frow] * kUnwiden;
 #pragma unroll
             for (int i = 0; i < TN; ++i) {
                 const int nb = n0 + wn + i * 32;   // this MFMA tile's first output channel
@@ -350,7 +435,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
                         const int n = nb + g * 8 + fhalf * 4;
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            if (n + e < N) acc_out[(int64_t)m * N + n + e] = acc[i][j][g * 4 + e] >> 4;
+                            if (n + e < N) acc_out[(int64_t)m * N + n + e] = acc[i][j][g * 4 + e] >> (A4 ? 8 : 4);
                     }
                 }
                 if (vec8) {
@@ -446,7 +531,7 @@ __global__ __launch_bounds__(256) void w4_prepack_kernel(const uint8_t *__restri
 
 int g_variant = -1;  // -1: pick by shape; set by the benchmark's sweep hook
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int OCC>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int OCC, bool A4 = false>
 int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                   const uint16_t *bias, int M, int N, int K, uint16_t *y, int32_t *acc_out, hipStream_t stream) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
@@ -457,8 +542,8 @@ int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, c
     // persistent: OCC workgroups per compute unit (256 CUs), grid a multiple of the 8 XCDs
     int grid = 256 * OCC;
     if (total < grid) grid = (total + 7) / 8 * 8;
-    const size_t smem = (size_t)STAGES * (BM * BK + BN * BK / 2) + 2 * (BM + BN) * 4;
-    auto k = w4ax_gemm_native_kernel<BM, BN, BK, WAVES_M, WAVES_N, STAGES, OCC>;
+    const size_t smem = (size_t)STAGES * (BM * (A4 ? BK / 2 : BK) + BN * BK / 2) + 2 * ((BM + BN) * 4 + BN * 2);
+    auto k = w4ax_gemm_native_kernel<BM, BN, BK, WAVES_M, WAVES_N, STAGES, OCC, A4>;
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), smem, stream, codes, x_scale, w,
                        w_scale, bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n);
@@ -470,21 +555,36 @@ int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, c
 void set_gemm_variant(int v) { g_variant = v; }
 
 int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
-                     const uint16_t *bias, int64_t M, int64_t N, int64_t K, int w_layout, uint16_t *y,
-                     int32_t *acc_out, hipStream_t stream) {
-    if (w_layout == DVDQ_W_CANONICAL)
+                     const uint16_t *bias, int64_t M, int64_t N, int64_t K, int codes_format, int w_layout,
+                     uint16_t *y, int32_t *acc_out, hipStream_t stream) {
+    if (w_layout == DVDQ_W_CANONICAL) {
+        if (codes_format != DVDQ_CODES_INT8) return DVDQ_ERR_UNSUPPORTED;
         return launch_w4ax_gemm_canonical(codes, x_scale, w, w_scale, bias, M, N, K, y, acc_out, stream);
+    }
     const int m = (int)M, n = (int)N, k = (int)K;
 #define DVDQ_GEMM_ARGS codes, x_scale, w, w_scale, bias, m, n, k, y, acc_out, stream
     // Tile variants: {tile M, tile N, K slice, waves M x N, ring depth, workgroups per compute unit}.
-    // Picked from sweeps over the DiT shapes (K = 1536 ... 13824): variant 3, a 256 x 256 tile owned
-    // by one 8-wave workgroup per compute unit with 128 x 64 wave tiles (fewest weight-unpack
-    // operations per MFMA), K slices of 128 through a 3-deep ring.  The others remain for sweeps.
-    int v = g_variant < 0 ? 3 : g_variant;
-    // the two-deep scale buffers of a workgroup need (K slices per tile) >= ring depth - 1 (see the
-    // kernel); shallow K falls back to the two-buffer variant, which always qualifies
-    const int bk = v == 4 ? 64 : 128, stages = v == 2 ? 2 : (v == 4 ? 4 : 3);
-    if (k / bk < stages - 1) v = 2;
+    // Variant 2 is the default for every shape: two independent 4-wave workgroups per compute unit,
+    // each owning a 128 x 256 tile (64 x 128 per wave) with K slices of 128 through two buffers.  In
+    // interleaved sweeps over the DiT shapes (K = 1536 ... 13824) it was fastest or within 1 % of the
+    // fastest: while one workgroup converts and stores its tile the other keeps the matrix cores busy,
+    // which the one-workgroup 256 x 256 variants cannot do.  The others remain for sweeps; a shape with
+    // fewer K slices than a variant's ring needs falls back to variant 2, which always qualifies.
+    int v = g_variant < 0 ? 2 : g_variant;
+    if (codes_format == DVDQ_CODES_PACKED4) {
+        if ((v == 1 && k / 128 < 2) || (v > 2 && k / 128 < 3)) v = 2;
+        switch (v) {
+            case 1: return launch_native<256, 256, 128, 2, 4, 3, 1, true>(DVDQ_GEMM_ARGS);
+            case 2: return launch_native<128, 256, 128, 2, 2, 2, 2, true>(DVDQ_GEMM_ARGS);
+            case 3: return launch_native<256, 256, 128, 2, 4, 4, 1, true>(DVDQ_GEMM_ARGS);
+            case 4: return launch_native<256, 256, 128, 4, 2, 4, 1, true>(DVDQ_GEMM_ARGS);
+            default: return DVDQ_ERR_UNSUPPORTED;
+        }
+    }
+    {
+        const int bk = v == 4 ? 64 : 128, stages = v == 2 ? 2 : (v == 4 ? 4 : 3);
+        if (k / bk < stages - 1) v = 2;
+    }
     switch (v) {
         case 1: return launch_native<256, 256, 128, 4, 2, 3, 1>(DVDQ_GEMM_ARGS);
         case 2: return launch_native<128, 256, 128, 2, 2, 2, 2>(DVDQ_GEMM_ARGS);

@@ -47,7 +47,7 @@ def test_full_size_workload(idx):
     print(f"[{wl.name}] dvdq_qlinear M={M} K={K} N={N}", flush=True)
     y, wsp = dvdq.qlinear(x_dev, w_native, ws_dev, B, bits, dvdq.W_NATIVE)
     torch.cuda.synchronize()
-    codes_dev, scale_dev = dvdq.workspace_views(wsp, M, K, bits)
+    codes_dev, scale_dev = dvdq.workspace_views(wsp, M, K)
 
     # ---- properties on every row (GPU side, cheap)
     row_max = codes_dev.abs().amax(dim=1)

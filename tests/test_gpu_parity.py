@@ -192,7 +192,7 @@ def test_qlinear_tiny_config_compositional(idx):
         wd = dvdq.w4_prepack(w_dev) if lay == dvdq.W_NATIVE else w_dev
         y, wsp = dvdq.qlinear(x_dev, wd, ws_dev, wl.had_block, wl.act_bits, lay)
         torch.cuda.synchronize()
-        codes_g, scale_g = dvdq.workspace_views(wsp, wl.M, wl.K, wl.act_bits)
+        codes_g, scale_g = dvdq.workspace_views(wsp, wl.M, wl.K)
         codes_g, scale_g = codes_g.cpu().numpy(), scale_g.cpu().numpy()
         ref = oracle.qlinear(xb, wp, ws, wl.had_block, wl.act_bits)
         xr = oracle.rotate(xb, wl.had_block)
