@@ -58,6 +58,12 @@ def _load():
         lib.dvdq_oracle_rel_l1.restype = C.c_double
         lib.dvdq_oracle_gbs_update.argtypes = [C.c_double, C.c_double, i32, i32, C.POINTER(C.c_double)]
         lib.dvdq_oracle_gbs_update.restype = i32
+        lib.dvdq_oracle_bgr_refine_step.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, vp]
+        lib.dvdq_oracle_minmax_quant.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp]
+        lib.dvdq_oracle_bgr.argtypes = [vp, i64, i64, i32, i32, i32, C.c_double, vp, vp, vp, vp]
+        lib.dvdq_oracle_w4ax_gemm_zp.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp]
+        for f in ("bgr_refine_step", "minmax_quant", "bgr", "w4ax_gemm_zp"):
+            getattr(lib, "dvdq_oracle_" + f).restype = i32
         for f in ("hadamard", "rotate", "quantize", "rotate_quant", "w4ax_gemm", "qlinear"):
             getattr(lib, "dvdq_oracle_" + f).restype = i32
         for f in ("unpack_w4", "pack_w4", "unpack_a4", "pack_a4", "int_gemm", "epilogue", "f64_to_bf16"):
@@ -237,3 +243,68 @@ def gbs_update(l1: float, delta: float, b_low: int, b_high: int, acc: float):
     c_acc = C.c_double(acc)
     bits = _load().dvdq_oracle_gbs_update(float(l1), float(delta), b_low, b_high, C.byref(c_acc))
     return bits, c_acc.value
+
+
+# ------------------------------------------------------------------ offline weight quantizer (Sec. 3.1)
+def minmax_quant(w: np.ndarray, bits: int = 4):
+    """Plain per-row MinMax: returns (codes uint8 [N, K] in [0, 2^b-1], delta f64 [N], zero int32 [N], err f64 [N])."""
+    a = _arr(w, np.float32, 2)
+    N, K = a.shape
+    q = np.empty((N, K), dtype=np.uint8)
+    d = np.empty(N, dtype=np.float64)
+    z = np.empty(N, dtype=np.int32)
+    e = np.empty(N, dtype=np.float64)
+    _check(_load().dvdq_oracle_minmax_quant(_p(a), N, K, bits, _p(q), _p(d), _p(z), _p(e)), "minmax_quant")
+    return q, d, z, e
+
+
+def bgr_refine_step(w_row: np.ndarray, q: np.ndarray, z: int, bits: int = 4):
+    """One refinement round on one row.  Returns (delta', z', q', err') or None when undefined."""
+    a = _arr(w_row, np.float32, 1)
+    qq = _arr(q, np.uint8, 1)
+    if a.size != qq.size:
+        raise ValueError("length mismatch")
+    d = C.c_double(0.0)
+    zn = C.c_int(0)
+    e = C.c_double(0.0)
+    qn = np.empty_like(qq)
+    rc = _load().dvdq_oracle_bgr_refine_step(_p(a), a.size, bits, _p(qq), int(z), C.byref(d), C.byref(zn), _p(qn),
+                                             C.byref(e))
+    return None if rc != 0 else (d.value, zn.value, qn, e.value)
+
+
+def bgr(w: np.ndarray, bits: int = 4, n_steps: int = 100, max_refine: int = 10, eps: float = 0.0):
+    """Bounded-init Grid Refinement per row.  Returns (codes uint8 [N, K], delta f64 [N], zero int32 [N], err f64 [N])."""
+    a = _arr(w, np.float32, 2)
+    N, K = a.shape
+    q = np.empty((N, K), dtype=np.uint8)
+    d = np.empty(N, dtype=np.float64)
+    z = np.empty(N, dtype=np.int32)
+    e = np.empty(N, dtype=np.float64)
+    _check(_load().dvdq_oracle_bgr(_p(a), N, K, bits, n_steps, max_refine, float(eps), _p(q), _p(d), _p(z), _p(e)), "bgr")
+    return q, d, z, e
+
+
+def w4ax_gemm_zp(codes, x_scale, w_packed, w_scale, w_zero, bias_bf16=None, return_acc: bool = False,
+                 return_rowsum: bool = False):
+    """GEMM + epilogue with signed per-channel weight zero-points (int8 [N])."""
+    q = _arr(codes, np.int8, 2)
+    w = _arr(w_packed, np.uint8, 2)
+    (M, K), N = q.shape, w.shape[0]
+    if w.shape[1] * 2 != K:
+        raise ValueError("K mismatch")
+    xs, ws, wz = _arr(x_scale, np.float32, 1), _arr(w_scale, np.float32, 1), _arr(w_zero, np.int8, 1)
+    if xs.size != M or ws.size != N or wz.size != N:
+        raise ValueError("scale / zero length mismatch")
+    b = None if bias_bf16 is None else _arr(bias_bf16, np.uint16, 1)
+    y = np.empty((M, N), dtype=np.uint16)
+    acc = np.empty((M, N), dtype=np.int64) if return_acc else None
+    rs = np.empty(M, dtype=np.int64) if return_rowsum else None
+    _check(_load().dvdq_oracle_w4ax_gemm_zp(_p(q), _p(xs), _p(w), _p(ws), _p(wz), _p(b), M, N, K, _p(y), _p(acc), _p(rs)),
+           "w4ax_gemm_zp")
+    out = (y,)
+    if return_acc:
+        out += (acc,)
+    if return_rowsum:
+        out += (rs,)
+    return out if len(out) > 1 else y

@@ -21,9 +21,14 @@
  * order) are listed in the repository's design notes; each function below says
  * which one it relies on.
  *
+ * Further down: the delta-guided bit switching controller (Sec. 3.3), the offline
+ * weight quantizer (Sec. 3.1: MinMax start, grid refinement, Alg. 1) and the GEMM
+ * with weight zero-points.
+ *
  * Parity status: every function here is pinned by CPU tests against closed
- * forms, hand-derived examples, a library Hadamard matrix, and brute force on
- * tiny shapes.  Nothing about video quality is pinned (it needs the real model).
+ * forms, hand-derived examples, a library Hadamard matrix, a library least-squares
+ * solver, and brute force on tiny shapes.  Nothing about video quality is pinned
+ * (it needs the real model).
  */
 #include <math.h>
 #include <stdint.h>
@@ -316,4 +321,186 @@ int dvdq_oracle_gbs_update(double l1, double delta, int b_low, int b_high, doubl
         return b_high;
     }
     return b_low;
+}
+
+/* ---------------------------------------------------------------- offline weight quantizer (Sec. 3.1)
+ *
+ * Asymmetric b-bit quantization of one weight row (one output channel):
+ *     Quant    q = clamp(rint(w / Delta) + z, 0, 2^b - 1)
+ *     DeQuant  w^ = Delta * (q - z)
+ * rint = round half to even; z an integer in [0, 2^b - 1].
+ */
+
+static double rint_clamp(double v, double lo, double hi)
+{
+    double r = nearbyint(v);     /* default rounding mode: ties to even */
+    return r < lo ? lo : (r > hi ? hi : r);
+}
+
+/* q_k and the row error ||w - Delta (q - z)||_2 for a given grid. */
+static double quant_row(const float *w, int64_t K, double delta, double z, double qmax, uint8_t *q)
+{
+    double e2 = 0.0;
+    for (int64_t k = 0; k < K; ++k) {
+        double c = nearbyint((double)w[k] / delta) + z;   /* round (ties to even), then shift by z */
+        c = c < 0.0 ? 0.0 : (c > qmax ? qmax : c);
+        q[k] = (uint8_t)c;
+        double r = (double)w[k] - delta * (c - z);
+        e2 += r * r;
+    }
+    return sqrt(e2);
+}
+
+/* The MinMax start (Sec. 3.1, the text under the Quant/DeQuant equations), with the range
+ * [lo, hi] given: Delta = (hi - lo) / (2^b - 1), z = clamp(-rint(lo / Delta), 0, 2^b - 1). */
+static void minmax_grid(double lo, double hi, double qmax, double *delta, double *z)
+{
+    *delta = (hi - lo) / qmax;
+    *z = rint_clamp(-(lo / *delta), 0.0, qmax);
+}
+
+/* One round of grid refinement (Sec. 3.1, the three primed equations): with the codes q and
+ * zero-point z fixed, Delta' is the least-squares step size <q - z, w> / <q - z, q - z>; with
+ * Delta' and q fixed, z' = clamp(rint(mean(q) - mean(w) / Delta'), 0, 2^b - 1); then the codes
+ * are re-quantized on the new grid.  Returns 0, or -1 when the step is undefined (all codes
+ * equal the zero-point, or a non-positive step size), leaving the outputs untouched. */
+int dvdq_oracle_bgr_refine_step(const float *w, int64_t K, int bits, const uint8_t *q, int z,
+                                double *delta_out, int *z_out, uint8_t *q_out, double *err_out)
+{
+    const double qmax = (double)((1 << bits) - 1);
+    double num = 0.0, den = 0.0, sq = 0.0, sw = 0.0;
+    for (int64_t k = 0; k < K; ++k) {
+        double d = (double)q[k] - (double)z;
+        num += d * (double)w[k];
+        den += d * d;
+        sq += (double)q[k];
+        sw += (double)w[k];
+    }
+    if (den == 0.0) return -1;
+    double delta = num / den;
+    if (!(delta > 0.0)) return -1;
+    double zn = rint_clamp(sq / (double)K - (sw / (double)K) / delta, 0.0, qmax);
+    *err_out = quant_row(w, K, delta, zn, qmax, q_out);
+    *delta_out = delta;
+    *z_out = (int)zn;
+    return 0;
+}
+
+/* Plain MinMax quantization of every row (the baseline the method improves on). */
+int dvdq_oracle_minmax_quant(const float *w, int64_t N, int64_t K, int bits, uint8_t *q, double *delta, int *zero,
+                             double *err)
+{
+    const double qmax = (double)((1 << bits) - 1);
+    for (int64_t n = 0; n < N; ++n) {
+        const float *row = w + n * K;
+        double lo = row[0], hi = row[0];
+        for (int64_t k = 1; k < K; ++k) { if (row[k] < lo) lo = row[k]; if (row[k] > hi) hi = row[k]; }
+        if (!(hi > lo)) return -2;
+        double d, z;
+        minmax_grid(lo, hi, qmax, &d, &z);
+        err[n] = quant_row(row, K, d, z, qmax, q + n * K);
+        delta[n] = d;
+        zero[n] = (int)z;
+    }
+    return 0;
+}
+
+/* Bounded-init Grid Refinement (Alg. 1), row by row.  For i = 0, 1, ... the clipping range
+ * [min + i * step, max - i * step], step = (max - min) / n_steps, gives a MinMax-style start
+ * (i = 0 is plain MinMax); each start is refined round after round until a round improves
+ * the row error by less than eps (or makes it worse), at most max_refine rounds; the best
+ * grid seen over all starts and rounds is returned, the earliest one on exact ties.
+ * Readings (the listing overloads n, and its stopping test as printed is always true):
+ * the number of shrink steps is a parameter; ranges that have collapsed (lo >= hi) end the
+ * search; every evaluated grid, including each start, competes for "best"; rows are
+ * independent; the zero-point is rounded and kept in [0, 2^b - 1] everywhere.
+ * A constant row c is represented exactly: Delta = |c| (1 if c = 0), z = (c < 0), q = (c > 0). */
+int dvdq_oracle_bgr(const float *w, int64_t N, int64_t K, int bits, int n_steps, int max_refine, double eps,
+                    uint8_t *q_out, double *delta_out, int *zero_out, double *err_out)
+{
+    if (bits < 2 || bits > 8 || n_steps < 1 || max_refine < 0 || K < 1) return -1;
+    const double qmax = (double)((1 << bits) - 1);
+    int rc = 0;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t n = 0; n < N; ++n) {
+        const float *row = w + n * K;
+        uint8_t *q = (uint8_t *)malloc((size_t)K), *qn = (uint8_t *)malloc((size_t)K);
+        if (!q || !qn) { rc = -3; free(q); free(qn); continue; }
+        double lo0 = row[0], hi0 = row[0];
+        for (int64_t k = 1; k < K; ++k) { if (row[k] < lo0) lo0 = row[k]; if (row[k] > hi0) hi0 = row[k]; }
+        if (!(hi0 > lo0)) {
+            const double c = lo0;
+            delta_out[n] = c == 0.0 ? 1.0 : fabs(c);
+            zero_out[n] = c < 0.0;
+            for (int64_t k = 0; k < K; ++k) q_out[n * K + k] = (uint8_t)(c > 0.0);
+            err_out[n] = 0.0;
+            free(q); free(qn);
+            continue;
+        }
+        const double step = (hi0 - lo0) / (double)n_steps;
+        double best = INFINITY;
+        for (int i = 0; i < n_steps; ++i) {
+            const double lo = lo0 + (double)i * step, hi = hi0 - (double)i * step;
+            if (!(lo < hi)) break;
+            double delta, z;
+            minmax_grid(lo, hi, qmax, &delta, &z);
+            double e = quant_row(row, K, delta, z, qmax, q);
+            if (e < best) {
+                best = e; delta_out[n] = delta; zero_out[n] = (int)z;
+                memcpy(q_out + n * K, q, (size_t)K);
+            }
+            double e_prev = e;
+            int zi = (int)z;
+            for (int j = 0; j < max_refine; ++j) {
+                double dn, en; int zn;
+                if (dvdq_oracle_bgr_refine_step(row, K, bits, q, zi, &dn, &zn, qn, &en) != 0) break;
+                if (en < best) {
+                    best = en; delta_out[n] = dn; zero_out[n] = zn;
+                    memcpy(q_out + n * K, qn, (size_t)K);
+                }
+                if (e_prev - en < eps) break;
+                e_prev = en; zi = zn;
+                memcpy(q, qn, (size_t)K);
+            }
+        }
+        err_out[n] = best;
+        free(q); free(qn);
+    }
+    return rc;
+}
+
+/* ---------------------------------------------------------------- GEMM with weight zero-points
+ *
+ * Steps 4-5 for asymmetric weights (DeQuant of Sec. 3.1 inside Y = X^ Lambda W^^T):
+ *     acc_mn = sum_k q_mk * (c_nk - z_n),    y_mn = bf16(acc_mn * s_m * ws_n [+ bias_n])
+ * with c the stored signed 4-bit codes and z the signed zero-point (both the unsigned
+ * quantities of the Quant equation minus 8).  Also returns, when asked, the per-token code
+ * sums sum_k q_mk that a kernel needs to apply z outside its integer GEMM. */
+int dvdq_oracle_w4ax_gemm_zp(const int8_t *codes, const float *x_scale, const uint8_t *w_packed,
+                             const float *w_scale, const int8_t *w_zero, const uint16_t *bias,
+                             int64_t M, int64_t N, int64_t K, uint16_t *y, int64_t *acc_out, int64_t *rowsum_out)
+{
+    if (K % 2) return -2;
+    int8_t *w = (int8_t *)malloc((size_t)N * K);
+    int64_t *acc = acc_out ? acc_out : (int64_t *)malloc(sizeof(int64_t) * (size_t)M * N);
+    if (!w || !acc) { free(w); if (!acc_out) free(acc); return -3; }
+    dvdq_oracle_unpack_w4(w_packed, N, K, w);
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t s = 0;
+            for (int64_t k = 0; k < K; ++k)
+                s += (int64_t)codes[m * K + k] * ((int64_t)w[n * K + k] - (int64_t)w_zero[n]);
+            acc[m * N + n] = s;
+        }
+        if (rowsum_out) {
+            int64_t s = 0;
+            for (int64_t k = 0; k < K; ++k) s += codes[m * K + k];
+            rowsum_out[m] = s;
+        }
+    }
+    dvdq_oracle_epilogue(acc, x_scale, w_scale, bias, M, N, y);
+    free(w);
+    if (!acc_out) free(acc);
+    return 0;
 }
