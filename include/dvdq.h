@@ -79,28 +79,37 @@ enum { DVDQ_CODES_INT8 = 0, DVDQ_CODES_PACKED4 = 1 };
  *                 DVDQ_ERR_UNSUPPORTED
  *   codes    out  int8 [M, K], or uint8 [M, K/2] when packed
  *   x_scale  out  fp32 [M]; 0 for an all-zero row (its codes are all 0)
+ *   code_rowsum out  int32 [M] or NULL; when given, receives sum_k codes[m,k], which the GEMM needs
+ *                 to apply weight zero-points (see dvdq_w4ax_gemm)
  *
  * K must be a multiple of 8 (DVDQ_ERR_SHAPE) and at most 65536 (DVDQ_ERR_UNSUPPORTED).
  */
 int dvdq_rotate_quant(const void *x_bf16, int64_t M, int64_t K, int had_block, int act_bits, int codes_format,
-                      int8_t *codes, float *x_scale, void *hip_stream);
+                      int8_t *codes, float *x_scale, int32_t *code_rowsum, void *hip_stream);
 
 /*
  * Low-bit GEMM with exact int32 accumulation and the dequantizing epilogue
- * (Sec. 3.2: Y = X^ Lambda W^^T; Sec. 3.1 DeQuant with zero-point 0):
+ * (Sec. 3.2: Y = X^ Lambda W^^T; Sec. 3.1 DeQuant, w^ = Delta (w_q - z)):
  *
- *     acc[m,n] = sum_k codes[m,k] * w[n,k]                       (exact, int32)
+ *     acc[m,n] = sum_k codes[m,k] * (w[n,k] - w_zero[n])         (exact, int32; w_zero = 0 when NULL)
  *     y[m,n]   = bf16( float(acc[m,n]) * x_scale[m] * w_scale[n] + bias[n] )
+ *
+ * The zero-point term is applied as acc - w_zero[n] * code_rowsum[m], so weights with
+ * zero-points need the per-token code sums that dvdq_rotate_quant can emit.
  *
  *   codes     in   int8 [M, K] or packed uint8 [M, K/2] per `codes_format`,
  *                  |code| <= 2^(act_bits-1) - 1 (not checked)
  *   x_scale   in   fp32 [M]
  *   w         in   packed INT4 weights, layout per `w_layout`
  *   w_scale   in   fp32 [N]
+ *   w_zero    in   int8 [N] or NULL: signed zero-points (the unsigned zero-point of the Quant
+ *                  equation minus 8, matching the signed weight codes); native layout only
+ *   code_rowsum in int32 [M]: sum_k codes[m,k]; required when w_zero is given (DVDQ_ERR_NULL
+ *                  otherwise), ignored when it is NULL
  *   bias_bf16 in   bf16 [N] or NULL
- *   act_bits       4, 6 or 8 (bounds the accumulator: qmax * 8 * K must stay below 2^27, or
- *                  2^23 with packed codes, DVDQ_ERR_UNSUPPORTED otherwise: the kernels
- *                  accumulate 16 * acc, resp. 256 * acc)
+ *   act_bits       4, 6 or 8 (bounds the accumulator: qmax * 8 * K, or qmax * 16 * K with
+ *                  zero-points, must stay below 2^27, or 2^23 with packed codes,
+ *                  DVDQ_ERR_UNSUPPORTED otherwise: the kernels accumulate 16 * acc, resp. 256 * acc)
  *   codes_format   DVDQ_CODES_PACKED4 needs act_bits = 4 and the native weight layout
  *                  (DVDQ_ERR_UNSUPPORTED otherwise)
  *   y_bf16    out  bf16 [M, N]
@@ -111,23 +120,28 @@ int dvdq_rotate_quant(const void *x_bf16, int64_t M, int64_t K, int had_block, i
  * (DVDQ_ERR_UNSUPPORTED otherwise).  Any M >= 1, N >= 1; ragged tiles are handled inside.
  */
 int dvdq_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
-                   const void *bias_bf16, int64_t M, int64_t N, int64_t K, int act_bits, int codes_format,
-                   int w_layout, void *y_bf16, int32_t *acc_out, void *hip_stream);
+                   const int8_t *w_zero, const int32_t *code_rowsum, const void *bias_bf16, int64_t M, int64_t N,
+                   int64_t K, int act_bits, int codes_format, int w_layout, void *y_bf16, int32_t *acc_out,
+                   void *hip_stream);
 
 /*
  * The whole layer in one call: dvdq_rotate_quant followed by dvdq_w4ax_gemm on
  * the same stream.  `workspace` (device, 256-byte aligned) must hold at least
  * dvdq_qlinear_workspace_bytes(M, K, codes_format) bytes; after the call completes it
- * contains the activation codes (in the container `codes_format` names) at offset 0
- * and the token scales (fp32 [M]) at offset dvdq_qlinear_scale_offset(M, K,
- * codes_format), so callers and tests can inspect them.  `codes_format` is the
- * container used between the two kernels; arguments as in the two calls above.
+ * contains the activation codes (in the container `codes_format` names) at offset 0,
+ * the token scales (fp32 [M]) at offset dvdq_qlinear_scale_offset(M, K, codes_format)
+ * and, when w_zero is given, the token code sums (int32 [M]) at offset
+ * dvdq_qlinear_rowsum_offset(M, K, codes_format), so callers and tests can inspect
+ * them.  `codes_format` is the container used between the two kernels; arguments
+ * as in the two calls above.
  */
-int dvdq_qlinear(const void *x_bf16, const uint8_t *w, const float *w_scale, const void *bias_bf16,
-                 int64_t M, int64_t N, int64_t K, int had_block, int act_bits, int codes_format, int w_layout,
-                 void *y_bf16, void *workspace, size_t workspace_bytes, void *hip_stream);
+int dvdq_qlinear(const void *x_bf16, const uint8_t *w, const float *w_scale, const int8_t *w_zero,
+                 const void *bias_bf16, int64_t M, int64_t N, int64_t K, int had_block, int act_bits,
+                 int codes_format, int w_layout, void *y_bf16, void *workspace, size_t workspace_bytes,
+                 void *hip_stream);
 size_t dvdq_qlinear_workspace_bytes(int64_t M, int64_t K, int codes_format);
 size_t dvdq_qlinear_scale_offset(int64_t M, int64_t K, int codes_format);
+size_t dvdq_qlinear_rowsum_offset(int64_t M, int64_t K, int codes_format);
 
 /*
  * One-time, offline: reorder canonical packed weights into the GEMM kernel's

@@ -15,7 +15,7 @@ import torch
 
 __all__ = [
     "DvdqError", "DvdqLibraryMissing", "lib", "library_path", "version", "status_string",
-    "rotate_quant", "w4ax_gemm", "qlinear", "qlinear_workspace_bytes", "qlinear_scale_offset",
+    "rotate_quant", "w4ax_gemm", "qlinear", "qlinear_workspace_bytes", "qlinear_scale_offset", "qlinear_rowsum_offset", "workspace_rowsum",
     "w4_prepack", "w4_native_bytes", "GbsController", "bench_copy", "bench_mfma_i8", "bench_set_gemm_variant",
     "W_CANONICAL", "W_NATIVE", "CODES_INT8", "CODES_PACKED4", "EXPORTED_SYMBOLS",
 ]
@@ -25,7 +25,7 @@ CODES_INT8, CODES_PACKED4 = 0, 1
 
 EXPORTED_SYMBOLS = (
     "dvdq_rotate_quant", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_qlinear_workspace_bytes",
-    "dvdq_qlinear_scale_offset", "dvdq_w4_prepack", "dvdq_w4_native_bytes", "dvdq_status_string",
+    "dvdq_qlinear_scale_offset", "dvdq_qlinear_rowsum_offset", "dvdq_w4_prepack", "dvdq_w4_native_bytes", "dvdq_status_string",
     "dvdq_version", "dvdq_gbs_workspace_bytes", "dvdq_gbs_reset", "dvdq_gbs_step", "dvdq_bench_copy", "dvdq_bench_mfma_i8", "dvdq_bench_set_gemm_variant",
 )
 
@@ -59,9 +59,10 @@ def lib() -> C.CDLL:
             "(hipcc, gfx950).  There is no fallback path.")
     L = C.CDLL(_LIB_PATH)
     i64, i32, vp, sz = C.c_int64, C.c_int, C.c_void_p, C.c_size_t
-    L.dvdq_rotate_quant.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp]
-    L.dvdq_w4ax_gemm.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, vp, vp]
-    L.dvdq_qlinear.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, i32, vp, vp, sz, vp]
+    L.dvdq_rotate_quant.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp, vp]
+    L.dvdq_w4ax_gemm.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, vp, vp]
+    L.dvdq_qlinear.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, i32, vp, vp, sz, vp]
+    L.dvdq_qlinear_rowsum_offset.argtypes = [i64, i64, i32]
     L.dvdq_qlinear_workspace_bytes.argtypes = [i64, i64, i32]
     L.dvdq_qlinear_scale_offset.argtypes = [i64, i64, i32]
     L.dvdq_w4_prepack.argtypes = [vp, i64, i64, vp, vp]
@@ -81,7 +82,8 @@ def lib() -> C.CDLL:
     for f in ("dvdq_rotate_quant", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_w4_prepack", "dvdq_version",
               "dvdq_bench_copy", "dvdq_bench_mfma_i8"):
         getattr(L, f).restype = i32
-    for f in ("dvdq_qlinear_workspace_bytes", "dvdq_qlinear_scale_offset", "dvdq_w4_native_bytes"):
+    for f in ("dvdq_qlinear_workspace_bytes", "dvdq_qlinear_scale_offset", "dvdq_qlinear_rowsum_offset",
+              "dvdq_w4_native_bytes"):
         getattr(L, f).restype = sz
     L.dvdq_status_string.restype = C.c_char_p
     _lib = L
@@ -133,9 +135,9 @@ def _codes_spec(M: int, K: int, codes_format: int):
 
 
 def rotate_quant(x, had_block: int, act_bits: int, codes=None, x_scale=None, stream=None,
-                 codes_format: int = CODES_INT8):
-    """x: bf16 [M, K] -> (codes int8 [M, K] or packed uint8 [M, K/2], x_scale fp32 [M]).
-    See dvdq_rotate_quant."""
+                 codes_format: int = CODES_INT8, code_rowsum=None, want_rowsum: bool = False):
+    """x: bf16 [M, K] -> (codes int8 [M, K] or packed uint8 [M, K/2], x_scale fp32 [M]); with
+    want_rowsum (or code_rowsum given) also the per-token code sums int32 [M].  See dvdq_rotate_quant."""
     L = lib()
     _need(x, torch.bfloat16, None, "x")
     M, K = x.shape
@@ -146,13 +148,18 @@ def rotate_quant(x, had_block: int, act_bits: int, codes=None, x_scale=None, str
         x_scale = torch.empty((M,), dtype=torch.float32, device=x.device)
     _need(codes, cdtype, cshape, "codes")
     _need(x_scale, torch.float32, (M,), "x_scale")
+    if want_rowsum and code_rowsum is None:
+        code_rowsum = torch.empty((M,), dtype=torch.int32, device=x.device)
+    if code_rowsum is not None:
+        _need(code_rowsum, torch.int32, (M,), "code_rowsum")
     _check(L.dvdq_rotate_quant(_ptr(x), M, K, had_block, act_bits, codes_format, _ptr(codes), _ptr(x_scale),
-                               _stream(stream)), "dvdq_rotate_quant")
-    return codes, x_scale
+                               _ptr(code_rowsum), _stream(stream)), "dvdq_rotate_quant")
+    return (codes, x_scale) if code_rowsum is None else (codes, x_scale, code_rowsum)
 
 
 def w4ax_gemm(codes, x_scale, w, w_scale, act_bits: int, w_layout: int = W_CANONICAL, bias=None,
-              y=None, acc_out=None, want_acc: bool = False, stream=None, codes_format: int = CODES_INT8):
+              y=None, acc_out=None, want_acc: bool = False, stream=None, codes_format: int = CODES_INT8,
+              w_zero=None, code_rowsum=None):
     """codes int8 [M, K] (or packed uint8 [M, K/2]), w uint8 packed INT4 [N, K/2] (or native)
     -> y bf16 [M, N].  With want_acc (or acc_out given) also returns the int32 accumulators."""
     L = lib()
@@ -172,6 +179,9 @@ def w4ax_gemm(codes, x_scale, w, w_scale, act_bits: int, w_layout: int = W_CANON
         raise ValueError("w: native buffer too small")
     if bias is not None:
         _need(bias, torch.bfloat16, (N,), "bias")
+    if w_zero is not None:
+        _need(w_zero, torch.int8, (N,), "w_zero")
+        _need(code_rowsum, torch.int32, (M,), "code_rowsum")
     if y is None:
         y = torch.empty((M, N), dtype=torch.bfloat16, device=codes.device)
     _need(y, torch.bfloat16, (M, N), "y")
@@ -179,8 +189,9 @@ def w4ax_gemm(codes, x_scale, w, w_scale, act_bits: int, w_layout: int = W_CANON
         acc_out = torch.empty((M, N), dtype=torch.int32, device=codes.device)
     if acc_out is not None:
         _need(acc_out, torch.int32, (M, N), "acc_out")
-    _check(L.dvdq_w4ax_gemm(_ptr(codes), _ptr(x_scale), _ptr(w), _ptr(w_scale), _ptr(bias), M, N, K, act_bits,
-                            codes_format, w_layout, _ptr(y), _ptr(acc_out), _stream(stream)), "dvdq_w4ax_gemm")
+    _check(L.dvdq_w4ax_gemm(_ptr(codes), _ptr(x_scale), _ptr(w), _ptr(w_scale), _ptr(w_zero), _ptr(code_rowsum),
+                            _ptr(bias), M, N, K, act_bits, codes_format, w_layout, _ptr(y), _ptr(acc_out),
+                            _stream(stream)), "dvdq_w4ax_gemm")
     return (y, acc_out) if acc_out is not None else y
 
 
@@ -192,8 +203,12 @@ def qlinear_scale_offset(M: int, K: int, codes_format: int = CODES_INT8) -> int:
     return lib().dvdq_qlinear_scale_offset(M, K, codes_format)
 
 
+def qlinear_rowsum_offset(M: int, K: int, codes_format: int = CODES_INT8) -> int:
+    return lib().dvdq_qlinear_rowsum_offset(M, K, codes_format)
+
+
 def qlinear(x, w, w_scale, had_block: int, act_bits: int, w_layout: int = W_CANONICAL, bias=None,
-            y=None, workspace=None, stream=None, codes_format: int = CODES_INT8):
+            y=None, workspace=None, stream=None, codes_format: int = CODES_INT8, w_zero=None):
     """The whole layer.  Returns (y bf16 [M, N], workspace uint8); the workspace holds the
     codes at offset 0 and the token scales at qlinear_scale_offset(M, K, codes_format)."""
     L = lib()
@@ -206,6 +221,8 @@ def qlinear(x, w, w_scale, had_block: int, act_bits: int, w_layout: int = W_CANO
         raise ValueError(f"w: expected shape {(N, K // 2)}, got {tuple(w.shape)}")
     if bias is not None:
         _need(bias, torch.bfloat16, (N,), "bias")
+    if w_zero is not None:
+        _need(w_zero, torch.int8, (N,), "w_zero")
     if y is None:
         y = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
     _need(y, torch.bfloat16, (M, N), "y")
@@ -213,8 +230,9 @@ def qlinear(x, w, w_scale, had_block: int, act_bits: int, w_layout: int = W_CANO
     if workspace is None:
         workspace = torch.empty((need,), dtype=torch.uint8, device=x.device)
     _need(workspace, torch.uint8, None, "workspace")
-    _check(L.dvdq_qlinear(_ptr(x), _ptr(w), _ptr(w_scale), _ptr(bias), M, N, K, had_block, act_bits, codes_format,
-                          w_layout, _ptr(y), _ptr(workspace), workspace.numel(), _stream(stream)), "dvdq_qlinear")
+    _check(L.dvdq_qlinear(_ptr(x), _ptr(w), _ptr(w_scale), _ptr(w_zero), _ptr(bias), M, N, K, had_block, act_bits,
+                          codes_format, w_layout, _ptr(y), _ptr(workspace), workspace.numel(), _stream(stream)),
+           "dvdq_qlinear")
     return y, workspace
 
 
@@ -225,6 +243,12 @@ def workspace_views(workspace, M: int, K: int, codes_format: int = CODES_INT8):
     codes = workspace[:cshape[0] * cshape[1]].view(cdtype).view(cshape)
     scale = workspace[off:off + 4 * M].view(torch.float32)
     return codes, scale
+
+
+def workspace_rowsum(workspace, M: int, K: int, codes_format: int = CODES_INT8):
+    """int32 [M] view of the token code sums in a qlinear workspace (written when w_zero is given)."""
+    off = qlinear_rowsum_offset(M, K, codes_format)
+    return workspace[off:off + 4 * M].view(torch.int32)
 
 
 def w4_native_bytes(N: int, K: int) -> int:

@@ -26,33 +26,38 @@ inline int check_format(int codes_format, int act_bits) {
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 int check_rotate_quant(const void *x, int64_t M, int64_t K, int had_block, int act_bits, int codes_format,
-                       const void *codes, const void *x_scale, int *log2b) {
+                       const void *codes, const void *x_scale, const void *code_rowsum, int *log2b) {
     if (!x || !codes || !x_scale) return DVDQ_ERR_NULL;
     if (M < 1 || K < 1 || (K % 8) != 0) return DVDQ_ERR_SHAPE;
     *log2b = log2_exact(had_block);
     if (*log2b < 0 || (K % had_block) != 0) return DVDQ_ERR_SHAPE;
     if (!bits_ok(act_bits) || had_block > 512 || K > 65536 || M > 0x7FFFFFFF) return DVDQ_ERR_UNSUPPORTED;
     if (check_format(codes_format, act_bits) != DVDQ_OK) return DVDQ_ERR_UNSUPPORTED;
-    if (!aligned16(x) || !aligned16(codes) || !aligned16(x_scale)) return DVDQ_ERR_ALIGN;
+    if (!aligned16(x) || !aligned16(codes) || !aligned16(x_scale) || (code_rowsum && !aligned16(code_rowsum)))
+        return DVDQ_ERR_ALIGN;
     return DVDQ_OK;
 }
 
-int check_gemm(const void *codes, const void *x_scale, const void *w, const void *w_scale, const void *bias,
-               int64_t M, int64_t N, int64_t K, int act_bits, int codes_format, int w_layout, const void *y,
-               const void *acc_out) {
-    if (!codes || !x_scale || !w || !w_scale || !y) return DVDQ_ERR_NULL;
+int check_gemm(const void *codes, const void *x_scale, const void *w, const void *w_scale, const void *w_zero,
+               const void *code_rowsum, const void *bias, int64_t M, int64_t N, int64_t K, int act_bits,
+               int codes_format, int w_layout, const void *y, const void *acc_out) {
+    if (!codes || !x_scale || !w || !w_scale || !y || (w_zero && !code_rowsum)) return DVDQ_ERR_NULL;
     if (M < 1 || N < 1 || K < 1 || (K % 64) != 0) return DVDQ_ERR_SHAPE;
     if (!bits_ok(act_bits) || (w_layout != DVDQ_W_CANONICAL && w_layout != DVDQ_W_NATIVE)) return DVDQ_ERR_UNSUPPORTED;
     if (w_layout == DVDQ_W_NATIVE && (K % 128) != 0) return DVDQ_ERR_UNSUPPORTED;
     if (check_format(codes_format, act_bits) != DVDQ_OK) return DVDQ_ERR_UNSUPPORTED;
     if (codes_format == DVDQ_CODES_PACKED4 && w_layout != DVDQ_W_NATIVE) return DVDQ_ERR_UNSUPPORTED;
+    if (w_zero && w_layout != DVDQ_W_NATIVE) return DVDQ_ERR_UNSUPPORTED;
     if (M > 0x7FFFFFFF || N > 0x7FFFFFFF || K > 0x7FFFFFFF) return DVDQ_ERR_UNSUPPORTED;
-    // the kernel accumulates 16 * sum(code * w), or 256 * with packed codes: |code| <= qmax, |w| <= 8
+    // the kernel accumulates 16 * sum(code * w), or 256 * with packed codes: |code| <= qmax, |w| <= 8,
+    // and |w - zero| <= 16 once a zero-point is taken out; the code sums must fit 24 bits for its multiply
     const int64_t qmax = (1 << (act_bits - 1)) - 1;
     const int64_t widen = codes_format == DVDQ_CODES_PACKED4 ? 256 : 16;
-    if (widen * qmax * 8 * K >= (int64_t)1 << 31) return DVDQ_ERR_UNSUPPORTED;
+    if (widen * qmax * (w_zero ? 16 : 8) * K >= (int64_t)1 << 31) return DVDQ_ERR_UNSUPPORTED;
+    if (w_zero && qmax * K >= (int64_t)1 << 23) return DVDQ_ERR_UNSUPPORTED;
     if (!aligned16(codes) || !aligned16(x_scale) || !aligned16(w) || !aligned16(w_scale) || !aligned16(y) ||
-        (bias && !aligned16(bias)) || (acc_out && !aligned16(acc_out)))
+        (bias && !aligned16(bias)) || (acc_out && !aligned16(acc_out)) || (w_zero && !aligned16(w_zero)) ||
+        (w_zero && !aligned16(code_rowsum)))
         return DVDQ_ERR_ALIGN;
     return DVDQ_OK;
 }
@@ -62,23 +67,25 @@ int check_gemm(const void *codes, const void *x_scale, const void *w, const void
 extern "C" {
 
 int dvdq_rotate_quant(const void *x_bf16, int64_t M, int64_t K, int had_block, int act_bits, int codes_format,
-                      int8_t *codes, float *x_scale, void *hip_stream) {
+                      int8_t *codes, float *x_scale, int32_t *code_rowsum, void *hip_stream) {
     int log2b = 0;
-    const int rc = check_rotate_quant(x_bf16, M, K, had_block, act_bits, codes_format, codes, x_scale, &log2b);
+    const int rc = check_rotate_quant(x_bf16, M, K, had_block, act_bits, codes_format, codes, x_scale, code_rowsum,
+                                      &log2b);
     if (rc != DVDQ_OK) return rc;
     return dvdq::launch_rotate_quant(static_cast<const uint16_t *>(x_bf16), M, K, log2b, act_bits, codes_format,
-                                     codes, x_scale, static_cast<hipStream_t>(hip_stream));
+                                     codes, x_scale, code_rowsum, static_cast<hipStream_t>(hip_stream));
 }
 
 int dvdq_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
-                   const void *bias_bf16, int64_t M, int64_t N, int64_t K, int act_bits, int codes_format,
-                   int w_layout, void *y_bf16, int32_t *acc_out, void *hip_stream) {
-    const int rc = check_gemm(codes, x_scale, w, w_scale, bias_bf16, M, N, K, act_bits, codes_format, w_layout,
-                              y_bf16, acc_out);
+                   const int8_t *w_zero, const int32_t *code_rowsum, const void *bias_bf16, int64_t M, int64_t N,
+                   int64_t K, int act_bits, int codes_format, int w_layout, void *y_bf16, int32_t *acc_out,
+                   void *hip_stream) {
+    const int rc = check_gemm(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias_bf16, M, N, K, act_bits,
+                              codes_format, w_layout, y_bf16, acc_out);
     if (rc != DVDQ_OK) return rc;
-    return dvdq::launch_w4ax_gemm(codes, x_scale, w, w_scale, static_cast<const uint16_t *>(bias_bf16), M, N, K,
-                                  codes_format, w_layout, static_cast<uint16_t *>(y_bf16), acc_out,
-                                  static_cast<hipStream_t>(hip_stream));
+    return dvdq::launch_w4ax_gemm(codes, x_scale, w, w_scale, w_zero, code_rowsum,
+                                  static_cast<const uint16_t *>(bias_bf16), M, N, K, codes_format, w_layout,
+                                  static_cast<uint16_t *>(y_bf16), acc_out, static_cast<hipStream_t>(hip_stream));
 }
 
 size_t dvdq_qlinear_scale_offset(int64_t M, int64_t K, int codes_format) {
@@ -87,33 +94,43 @@ size_t dvdq_qlinear_scale_offset(int64_t M, int64_t K, int codes_format) {
     return round_up(codes_format == DVDQ_CODES_PACKED4 ? code_bytes / 2 : code_bytes, 256);
 }
 
-size_t dvdq_qlinear_workspace_bytes(int64_t M, int64_t K, int codes_format) {
+size_t dvdq_qlinear_rowsum_offset(int64_t M, int64_t K, int codes_format) {
     if (M < 1 || K < 1) return 0;
     return dvdq_qlinear_scale_offset(M, K, codes_format) + round_up(sizeof(float) * (size_t)M, 256);
 }
 
-int dvdq_qlinear(const void *x_bf16, const uint8_t *w, const float *w_scale, const void *bias_bf16, int64_t M,
-                 int64_t N, int64_t K, int had_block, int act_bits, int codes_format, int w_layout, void *y_bf16,
-                 void *workspace, size_t workspace_bytes, void *hip_stream) {
+size_t dvdq_qlinear_workspace_bytes(int64_t M, int64_t K, int codes_format) {
+    if (M < 1 || K < 1) return 0;
+    return dvdq_qlinear_rowsum_offset(M, K, codes_format) + round_up(sizeof(int32_t) * (size_t)M, 256);
+}
+
+int dvdq_qlinear(const void *x_bf16, const uint8_t *w, const float *w_scale, const int8_t *w_zero,
+                 const void *bias_bf16, int64_t M, int64_t N, int64_t K, int had_block, int act_bits,
+                 int codes_format, int w_layout, void *y_bf16, void *workspace, size_t workspace_bytes,
+                 void *hip_stream) {
     if (!workspace) return DVDQ_ERR_NULL;
     if (M < 1 || K < 1) return DVDQ_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return DVDQ_ERR_ALIGN;
     int8_t *codes = static_cast<int8_t *>(workspace);
     float *x_scale = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) +
                                                dvdq_qlinear_scale_offset(M, K, codes_format));
+    int32_t *rowsum = !w_zero ? nullptr
+                              : reinterpret_cast<int32_t *>(static_cast<uint8_t *>(workspace) +
+                                                            dvdq_qlinear_rowsum_offset(M, K, codes_format));
     int log2b = 0;
-    int rc = check_rotate_quant(x_bf16, M, K, had_block, act_bits, codes_format, codes, x_scale, &log2b);
+    int rc = check_rotate_quant(x_bf16, M, K, had_block, act_bits, codes_format, codes, x_scale, rowsum, &log2b);
     if (rc != DVDQ_OK) return rc;
-    rc = check_gemm(codes, x_scale, w, w_scale, bias_bf16, M, N, K, act_bits, codes_format, w_layout, y_bf16,
-                    nullptr);
+    rc = check_gemm(codes, x_scale, w, w_scale, w_zero, rowsum, bias_bf16, M, N, K, act_bits, codes_format, w_layout,
+                    y_bf16, nullptr);
     if (rc != DVDQ_OK) return rc;
     if (workspace_bytes < dvdq_qlinear_workspace_bytes(M, K, codes_format)) return DVDQ_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     rc = dvdq::launch_rotate_quant(static_cast<const uint16_t *>(x_bf16), M, K, log2b, act_bits, codes_format,
-                                   codes, x_scale, stream);
+                                   codes, x_scale, rowsum, stream);
     if (rc != DVDQ_OK) return rc;
-    return dvdq::launch_w4ax_gemm(codes, x_scale, w, w_scale, static_cast<const uint16_t *>(bias_bf16), M, N, K,
-                                  codes_format, w_layout, static_cast<uint16_t *>(y_bf16), nullptr, stream);
+    return dvdq::launch_w4ax_gemm(codes, x_scale, w, w_scale, w_zero, rowsum,
+                                  static_cast<const uint16_t *>(bias_bf16), M, N, K, codes_format, w_layout,
+                                  static_cast<uint16_t *>(y_bf16), nullptr, stream);
 }
 
 size_t dvdq_w4_native_bytes(int64_t N, int64_t K) {

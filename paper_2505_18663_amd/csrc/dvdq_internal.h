@@ -11,11 +11,11 @@ namespace dvdq {
 // Launchers: arguments are already validated by the C-ABI layer in api.hip.
 // Each returns DVDQ_OK or DVDQ_ERR_HIP.
 int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block, int act_bits, int codes_format,
-                        int8_t *codes, float *x_scale, hipStream_t stream);
+                        int8_t *codes, float *x_scale, int32_t *code_rowsum, hipStream_t stream);
 
 int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
-                     const uint16_t *bias, int64_t M, int64_t N, int64_t K, int codes_format, int w_layout,
-                     uint16_t *y, int32_t *acc_out, hipStream_t stream);
+                     const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,
+                     int64_t K, int codes_format, int w_layout, uint16_t *y, int32_t *acc_out, hipStream_t stream);
 
 int launch_w4ax_gemm_canonical(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                                const uint16_t *bias, int64_t M, int64_t N, int64_t K, uint16_t *y, int32_t *acc_out,

@@ -92,10 +92,13 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
     double scale_mul,  // 1 / (sqrt(B) * qmax); fp64 so the fp32 scale is rounded once
     float recip_num,   // 1 / sqrt(B)
     int via_lds,       // PACK4 only: gather the packed codes through LDS into 16-byte stores (K % 32 == 0)
-    int8_t *__restrict__ codes, float *__restrict__ x_scale) {
+    int8_t *__restrict__ codes, float *__restrict__ x_scale,
+    int32_t *__restrict__ code_rowsum) {  // NULL, or [M]: sum of the row's codes (for weight zero-points)
     extern __shared__ float s_amax[];  // [2][rows_per_wg * waves_per_row], slots alternate per iteration
-    // then, 16-byte aligned, [waves][CPW][64] dwords for gathering packed codes (via_lds)
-    uint32_t *s_pack = reinterpret_cast<uint32_t *>(s_amax) + (2 * rows_per_wg * waves_per_row + 3) / 4 * 4;
+    // then [2][rows_per_wg * waves_per_row] per-wave code sums, then, 16-byte aligned,
+    // [waves][CPW][64] dwords for gathering packed codes (via_lds)
+    int32_t *s_sum = reinterpret_cast<int32_t *>(s_amax) + 2 * rows_per_wg * waves_per_row;
+    uint32_t *s_pack = reinterpret_cast<uint32_t *>(s_amax) + (4 * rows_per_wg * waves_per_row + 3) / 4 * 4;
     constexpr int MASK5 = LOG2B >= 5 ? 31 : ((1 << LOG2B) - 1);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
@@ -201,6 +204,7 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
         if (row_ok && wsub == 0 && lane == 0) x_scale[row] = scale;
 
         const float magic = 12582912.f;  // 1.5 * 2^23: adding it rounds to integer, ties to even
+        int csum = 0;                    // this lane's share of the row's code sum (padding chunks hold zeros)
         if (PACK4) {
             // two codes per byte, in the nibble order the GEMM widens with two masks: byte b of a
             // chunk's dword = code[b] (bits 0-3) | code[b + 4] (bits 4-7), two's complement
@@ -214,6 +218,7 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
                 for (int i = 0; i < 4; ++i) u[i] = (b[i] & 0xFu) | (b[i + 4] << 4);
                 p[c] = __builtin_amdgcn_perm(__builtin_amdgcn_perm(u[3], u[2], 0x0c0c0400u),
                                              __builtin_amdgcn_perm(u[1], u[0], 0x0c0c0400u), 0x05040100u);
+                if (code_rowsum) csum = __builtin_amdgcn_sdot8((int)p[c], 0x11111111, csum, false);  // 8 signed nibbles
             }
             if (via_lds) {
                 // K % 32 == 0: a unit's 64 dwords (one per lane, in chunk order) are gathered through
@@ -251,7 +256,23 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
                 out.y = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[7], b[6], 0x0c0c0400u),
                                               __builtin_amdgcn_perm(b[5], b[4], 0x0c0c0400u), 0x05040100u);
                 if (row_ok && k0[c] < K) *reinterpret_cast<uint2 *>(codes + row * K + k0[c]) = out;
+                if (code_rowsum) {
+                    csum = __builtin_amdgcn_sdot4((int)out.x, 0x01010101, csum, false);  // 4 signed bytes
+                    csum = __builtin_amdgcn_sdot4((int)out.y, 0x01010101, csum, false);
+                }
             }
+        }
+        if (code_rowsum) {   // (kernel argument: the whole workgroup takes the same path)
+#pragma unroll
+            for (int m = 1; m < kWave; m <<= 1) csum += __shfl_xor(csum, m, kWave);
+            if (waves_per_row > 1) {
+                int32_t *slots = s_sum + slot * (rows_per_wg * waves_per_row);
+                if (lane == 0) slots[wave] = csum;
+                __syncthreads();
+                csum = 0;
+                for (int i = 0; i < waves_per_row; ++i) csum += slots[row_in_wg * waves_per_row + i];
+            }
+            if (row_ok && wsub == 0 && lane == 0) code_rowsum[row] = csum;
         }
 #pragma unroll
         for (int c = 0; c < CPW; ++c) raw[c] = nxt[c];
@@ -261,15 +282,15 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
 template <int LOG2B>
 int launch_cpw(int cpw, dim3 grid, dim3 block, size_t smem, hipStream_t stream, const uint16_t *x, int64_t M,
                int K, int W, int rpw, double scale_mul, float recip_num, int pack4, int8_t *codes,
-               float *x_scale) {
+               float *x_scale, int32_t *code_rowsum) {
 #define DVDQ_RQ_CASE(C)                                                                                   \
     case C:                                                                                               \
         if (pack4)                                                                                        \
             hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C, true>), grid, block, smem, stream, x, M, K, \
-                               W, rpw, scale_mul, recip_num, pack4 == 2, codes, x_scale);                 \
+                               W, rpw, scale_mul, recip_num, pack4 == 2, codes, x_scale, code_rowsum);    \
         else                                                                                              \
             hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C, false>), grid, block, smem, stream, x, M,   \
-                               K, W, rpw, scale_mul, recip_num, 0, codes, x_scale);                       \
+                               K, W, rpw, scale_mul, recip_num, 0, codes, x_scale, code_rowsum);          \
         break;
     switch (cpw) {
         DVDQ_RQ_CASE(1) DVDQ_RQ_CASE(2) DVDQ_RQ_CASE(3) DVDQ_RQ_CASE(4)
@@ -283,7 +304,7 @@ int launch_cpw(int cpw, dim3 grid, dim3 block, size_t smem, hipStream_t stream, 
 }  // namespace
 
 int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block, int act_bits, int codes_format,
-                        int8_t *codes, float *x_scale, hipStream_t stream) {
+                        int8_t *codes, float *x_scale, int32_t *code_rowsum, hipStream_t stream) {
     const int pack4 = codes_format != DVDQ_CODES_PACKED4 ? 0 : ((K % 32) == 0 ? 2 : 1);
     const int units = (int)((K + kUnit - 1) / kUnit);
     // waves per row: at most 4 units (32 fp32 values per lane) in registers per wave, at most 16 waves
@@ -300,7 +321,7 @@ int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block,
     if (wgs_per_cu < 1) wgs_per_cu = 1;
     const int64_t wgs_resident = 256 * (int64_t)wgs_per_cu;
     const dim3 grid((unsigned)(wgs_needed < wgs_resident ? wgs_needed : wgs_resident));
-    size_t smem = 2 * sizeof(float) * W * rows_per_wg;
+    size_t smem = 4 * sizeof(float) * W * rows_per_wg;   // abs-max slots, then code-sum slots
     if (pack4 == 2) smem = (smem + 15) / 16 * 16 + (size_t)W * rows_per_wg * cpw * 256;
     const double qmax = (double)((1 << (act_bits - 1)) - 1);
     const double norm = 1.0 / sqrt((double)(1 << log2_block));
@@ -309,7 +330,7 @@ int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block,
 #define DVDQ_RQ_B(L)                                                                                        \
     case L:                                                                                                 \
         return launch_cpw<L>(cpw, grid, block, smem, stream, x, M, (int)K, W, rows_per_wg, scale_mul,       \
-                             recip_num, pack4, codes, x_scale);
+                             recip_num, pack4, codes, x_scale, code_rowsum);
     switch (log2_block) {
         DVDQ_RQ_B(0) DVDQ_RQ_B(1) DVDQ_RQ_B(2) DVDQ_RQ_B(3) DVDQ_RQ_B(4)
         DVDQ_RQ_B(5) DVDQ_RQ_B(6) DVDQ_RQ_B(7) DVDQ_RQ_B(8) DVDQ_RQ_B(9)

@@ -111,8 +111,9 @@ __device__ __forceinline__ void tile_origin(int t, int tiles_m, int tiles_n, int
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int OCC, bool A4>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_kernel(
     const int8_t *__restrict__ codes, const float *__restrict__ x_scale, const uint8_t *__restrict__ w,
-    const float *__restrict__ w_scale, const uint16_t *__restrict__ bias, int M, int N, int K,
-    uint16_t *__restrict__ y, int32_t *__restrict__ acc_out, int tiles_m, int tiles_n, int group_n) {
+    const float *__restrict__ w_scale, const int8_t *__restrict__ w_zero, const int32_t *__restrict__ code_rowsum,
+    const uint16_t *__restrict__ bias, int M, int N, int K, uint16_t *__restrict__ y, int32_t *__restrict__ acc_out,
+    int tiles_m, int tiles_n, int group_n) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave sub-tile
     constexpr int TM = WM / 32, TN = WN / 32;            // MFMA tiles per wave
@@ -132,8 +133,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     // With 3 or more buffers the item after the current one is already published, so the
     // first fragments of item q+1 are fetched while the last MFMAs of item q run.
     constexpr int AHEAD = STAGES >= 3 ? 1 : 0;
-    // bytes of one tile's epilogue vectors in LDS: token scales, channel scales (fp32), bias (bf16)
-    constexpr int SCALES = (BM + BN) * 4 + BN * 2;
+    // one tile's epilogue vectors in LDS: token scales, channel scales (fp32), bias (bf16), and for
+    // weights with zero-points the tokens' code sums (int32) and the channels' zero-points (int8)
+    constexpr int OFF_BIAS = (BM + BN) * 4, OFF_RSUM = OFF_BIAS + BN * 2, OFF_ZERO = OFF_RSUM + BM * 4;
+    constexpr int SCALES = OFF_ZERO + BN;
+    constexpr int SHIFT = A4 ? 8 : 4;                    // log2 of the factor the widened operands carry
     constexpr int STORES = TM * TN * 2;                  // 16-byte store instructions per wave per full tile
     static_assert((STAGES - 2 - AHEAD) * DMA + STORES < 64, "store-aware wait exceeds vmcnt");
     static_assert(BK == 64 || BK == 128, "K slice per item");
@@ -216,7 +220,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
 #pragma unroll
                 for (int j = 0; j < BN / 128; ++j)
                     if (j % NW == wave)
-                        lds_direct_load4(bias + n0, (uint32_t)(j * 64 + lane) * 4, sc + (BM + BN) * 4 + j * 256);
+                        lds_direct_load4(bias + n0, (uint32_t)(j * 64 + lane) * 4, sc + OFF_BIAS + j * 256);
+            }
+            if (w_zero) {
+#pragma unroll
+                for (int j = 0; j < BM / 64; ++j)
+                    if (j % NW == wave)
+                        lds_direct_load4(code_rowsum, (uint32_t)min(m0 + j * 64 + lane, M - 1) * 4, sc + OFF_RSUM + j * 256);
+                if (n0 + BN <= N) {
+#pragma unroll
+                    for (int j = 0; j < BN / 256; ++j)
+                        if (j % NW == wave)
+                            lds_direct_load4(w_zero + n0, (uint32_t)(j * 64 + lane) * 4, sc + OFF_ZERO + j * 256);
+                }
             }
         }
         issue_sa = smem_base + buf * STAGE;
@@ -359,14 +375,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
         const bool vec8 = (N & 7) == 0;
         const float *s_xs = reinterpret_cast<const float *>(smem + STAGES * STAGE + ((tile_j - 1) & 1) * SCALES);
         const float *s_ws = s_xs + BM;
-        constexpr float kUnwiden = A4 ? 0.00390625f : 0.0625f;  // the factor 16 of the widened weights (and codes)
+        constexpr float kUnwiden = 1.f / (float)(1 << SHIFT);  // the factor 16 of the widened weights (and codes)
+        const uint8_t *s_tile = smem + STAGES * STAGE + ((tile_j - 1) & 1) * SCALES;
+        const int32_t *s_rsum = reinterpret_cast<const int32_t *>(s_tile + OFF_RSUM);
+        // accumulator of channel zero-point z and token code sum rs: sum q (c - z) = acc - z * rs (times 2^SHIFT)
+        auto unzero = [] __device__(int a, int z, int rs) { return a - __mul24(z, rs) * (1 << SHIFT); };
         if (vec8 && !acc_out && m0 + BM <= M && n0 + BN <= N) {
             // ---- interior tile: no predicates, every vector the epilogue needs comes from LDS up front,
             // one row pointer per lane.  Every lane of every wave stores all its values, so the number of
             // stores is exact (see the store-aware wait above).
             if (KT >= STAGES) store_credit = STAGES - 1 - AHEAD;
             const float *ws_l = s_ws + wn + fhalf * 4;
-            const uint32_t *bias_l = reinterpret_cast<const uint32_t *>(s_ws + BN) + (wn + fhalf * 4) / 2;
+            const uint32_t *bias_l = reinterpret_cast<const uint32_t *>(s_tile + OFF_BIAS) + (wn + fhalf * 4) / 2;
+            const uint32_t *zero_l = reinterpret_cast<const uint32_t *>(s_tile + OFF_ZERO) + (wn + fhalf * 4) / 4;
             float xs16[TM];
 #pragma unroll
             for (int j = 0; j < TM; ++j) xs16[j] = s_xs[wm + j * 32 + frow] * kUnwiden;
@@ -378,22 +399,31 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
                 for (int g = 0; g < 4; g += 2) {
                     float4 wsv[2];
                     uint2 bb[2];
+                    uint32_t zq[2];
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
                         wsv[h] = *reinterpret_cast<const float4 *>(ws_l + i * 32 + (g + h) * 8);
                         if (bias) bb[h] = *reinterpret_cast<const uint2 *>(bias_l + (i * 32 + (g + h) * 8) / 2);
+                        if (w_zero) zq[h] = zero_l[(i * 32 + (g + h) * 8) / 4];
                     }
 #pragma unroll
                     for (int j = 0; j < TM; ++j) {
                         uint32_t pk[2][2];
+                        const int rsum = w_zero ? s_rsum[wm + j * 32 + frow] : 0;
 #pragma unroll
                         for (int h = 0; h < 2; ++h) {
                             const int r = (g + h) * 4;
+                            int a[4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                a[e] = acc[i][j][r + e];
+                                if (w_zero) a[e] = unzero(a[e], (int)(int8_t)(zq[h] >> (8 * e)), rsum);
+                            }
                             float o[4];
-                            o[0] = (float)acc[i][j][r + 0] * xs16[j] * wsv[h].x;
-                            o[1] = (float)acc[i][j][r + 1] * xs16[j] * wsv[h].y;
-                            o[2] = (float)acc[i][j][r + 2] * xs16[j] * wsv[h].z;
-                            o[3] = (float)acc[i][j][r + 3] * xs16[j] * wsv[h].w;
+                            o[0] = (float)a[0] * xs16[j] * wsv[h].x;
+                            o[1] = (float)a[1] * xs16[j] * wsv[h].y;
+                            o[2] = (float)a[2] * xs16[j] * wsv[h].z;
+                            o[3] = (float)a[3] * xs16[j] * wsv[h].w;
                             if (bias) {
                                 o[0] += __uint_as_float(bb[h].x << 16);
                                 o[1] += __uint_as_float(bb[h].x & 0xFFFF0000u);
@@ -429,13 +459,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
 #pragma unroll
             for (int i = 0; i < TN; ++i) {
                 const int nb = n0 + wn + i * 32;   // this MFMA tile's first output channel
+                if (w_zero) {   // remove the zero-point term from the accumulators in place
+                    const int rs = s_rsum[wm + j * 32 + frow];
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int n = nb + g * 8 + fhalf * 4 + e;
+                            if (n < N) acc[i][j][g * 4 + e] = unzero(acc[i][j][g * 4 + e], (int)w_zero[n], rs);
+                        }
+                }
                 if (acc_out && m_ok) {
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         const int n = nb + g * 8 + fhalf * 4;
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            if (n + e < N) acc_out[(int64_t)m * N + n + e] = acc[i][j][g * 4 + e] >> (A4 ? 8 : 4);
+                            if (n + e < N) acc_out[(int64_t)m * N + n + e] = acc[i][j][g * 4 + e] >> SHIFT;
                     }
                 }
                 if (vec8) {
@@ -533,7 +573,8 @@ int g_variant = -1;  // -1: pick by shape; set by the benchmark's sweep hook
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int OCC, bool A4 = false>
 int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
-                  const uint16_t *bias, int M, int N, int K, uint16_t *y, int32_t *acc_out, hipStream_t stream) {
+                  const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int M, int N, int K,
+                  uint16_t *y, int32_t *acc_out, hipStream_t stream) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     // column tiles per L2 sharing group: balanced groups of at most 16
     const int n_groups = (tiles_n + 15) / 16;
@@ -542,11 +583,13 @@ int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, c
     // persistent: OCC workgroups per compute unit (256 CUs), grid a multiple of the 8 XCDs
     int grid = 256 * OCC;
     if (total < grid) grid = (total + 7) / 8 * 8;
-    const size_t smem = (size_t)STAGES * (BM * (A4 ? BK / 2 : BK) + BN * BK / 2) + 2 * ((BM + BN) * 4 + BN * 2);
+    // the ring, then two tiles' epilogue vectors (scales, bias, code sums, zero-points; see the kernel)
+    const size_t smem = (size_t)STAGES * (BM * (A4 ? BK / 2 : BK) + BN * BK / 2) +
+                        2 * ((BM + BN) * 4 + BN * 2 + BM * 4 + BN);
     auto k = w4ax_gemm_native_kernel<BM, BN, BK, WAVES_M, WAVES_N, STAGES, OCC, A4>;
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), smem, stream, codes, x_scale, w,
-                       w_scale, bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n);
+                       w_scale, w_zero, code_rowsum, bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n);
     return check_launch();
 }
 
@@ -555,14 +598,14 @@ int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, c
 void set_gemm_variant(int v) { g_variant = v; }
 
 int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
-                     const uint16_t *bias, int64_t M, int64_t N, int64_t K, int codes_format, int w_layout,
-                     uint16_t *y, int32_t *acc_out, hipStream_t stream) {
+                     const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,
+                     int64_t K, int codes_format, int w_layout, uint16_t *y, int32_t *acc_out, hipStream_t stream) {
     if (w_layout == DVDQ_W_CANONICAL) {
-        if (codes_format != DVDQ_CODES_INT8) return DVDQ_ERR_UNSUPPORTED;
+        if (codes_format != DVDQ_CODES_INT8 || w_zero) return DVDQ_ERR_UNSUPPORTED;
         return launch_w4ax_gemm_canonical(codes, x_scale, w, w_scale, bias, M, N, K, y, acc_out, stream);
     }
     const int m = (int)M, n = (int)N, k = (int)K;
-#define DVDQ_GEMM_ARGS codes, x_scale, w, w_scale, bias, m, n, k, y, acc_out, stream
+#define DVDQ_GEMM_ARGS codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, m, n, k, y, acc_out, stream
     // Tile variants: {tile M, tile N, K slice, waves M x N, ring depth, workgroups per compute unit}.
     // Variant 2 is the default for every shape: two independent 4-wave workgroups per compute unit,
     // each owning a 128 x 256 tile (64 x 128 per wave) with K slices of 128 through two buffers.  In

@@ -38,36 +38,40 @@ ODD = C.c_void_p(0x1008)
 
 def test_rotate_quant_argument_errors():
     f = dvdq.lib().dvdq_rotate_quant
-    assert f(None, 4, 256, 256, 4, 0, FAKE, FAKE, None) == 1
-    assert f(FAKE, 4, 256, 256, 4, 0, None, FAKE, None) == 1
-    assert f(FAKE, 0, 256, 256, 4, 0, FAKE, FAKE, None) == 2          # M < 1
-    assert f(FAKE, 4, 252, 4, 4, 0, FAKE, FAKE, None) == 2            # K not a multiple of 8
-    assert f(FAKE, 4, 768, 512, 4, 0, FAKE, FAKE, None) == 2          # block does not divide K
-    assert f(FAKE, 4, 768, 96, 4, 0, FAKE, FAKE, None) == 2           # block not a power of two
-    assert f(FAKE, 4, 2048, 1024, 4, 0, FAKE, FAKE, None) == 3        # block > 512
-    assert f(FAKE, 4, 256, 256, 5, 0, FAKE, FAKE, None) == 3          # bits
-    assert f(FAKE, 4, 131072, 256, 4, 0, FAKE, FAKE, None) == 3       # K too large
-    assert f(ODD, 4, 256, 256, 4, 0, FAKE, FAKE, None) == 5
-    assert f(FAKE, 4, 256, 256, 6, 1, FAKE, FAKE, None) == 3       # packed container holds 4-bit codes only
-    assert f(FAKE, 4, 256, 256, 4, 2, FAKE, FAKE, None) == 3       # unknown container
+    assert f(None, 4, 256, 256, 4, 0, FAKE, FAKE, None, None) == 1
+    assert f(FAKE, 4, 256, 256, 4, 0, None, FAKE, None, None) == 1
+    assert f(FAKE, 0, 256, 256, 4, 0, FAKE, FAKE, None, None) == 2          # M < 1
+    assert f(FAKE, 4, 252, 4, 4, 0, FAKE, FAKE, None, None) == 2            # K not a multiple of 8
+    assert f(FAKE, 4, 768, 512, 4, 0, FAKE, FAKE, None, None) == 2          # block does not divide K
+    assert f(FAKE, 4, 768, 96, 4, 0, FAKE, FAKE, None, None) == 2           # block not a power of two
+    assert f(FAKE, 4, 2048, 1024, 4, 0, FAKE, FAKE, None, None) == 3        # block > 512
+    assert f(FAKE, 4, 256, 256, 5, 0, FAKE, FAKE, None, None) == 3          # bits
+    assert f(FAKE, 4, 131072, 256, 4, 0, FAKE, FAKE, None, None) == 3       # K too large
+    assert f(ODD, 4, 256, 256, 4, 0, FAKE, FAKE, None, None) == 5
+    assert f(FAKE, 4, 256, 256, 6, 1, FAKE, FAKE, None, None) == 3       # packed container holds 4-bit codes only
+    assert f(FAKE, 4, 256, 256, 4, 2, FAKE, FAKE, None, None) == 3       # unknown container
 
 
 def test_gemm_argument_errors():
     f = dvdq.lib().dvdq_w4ax_gemm
     ok = dict(M=4, N=8, K=64)
-    assert f(None, FAKE, FAKE, FAKE, None, 4, 8, 64, 4, 0, 0, FAKE, None, None) == 1
-    assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 8, 64, 4, 0, 0, None, None, None) == 1
-    assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 0, 64, 4, 0, 0, FAKE, None, None) == 2
-    assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 8, 96, 4, 0, 0, FAKE, None, None) == 2     # K % 64
-    assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 8, 64, 3, 0, 0, FAKE, None, None) == 3
-    assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 8, 64, 4, 0, 7, FAKE, None, None) == 3     # layout
-    assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 8, 64 * 4096, 8, 0, 0, FAKE, None, None) == 3   # accumulator bound
-    assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 8, 192, 4, 0, 1, FAKE, None, None) == 3    # native layout needs K % 128 == 0
-    assert f(FAKE, FAKE, ODD, FAKE, None, 4, 8, 64, 4, 0, 0, FAKE, None, None) == 5
-    assert f(FAKE, FAKE, FAKE, FAKE, ODD, 4, 8, 64, 4, 0, 0, FAKE, None, None) == 5
-    assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 8, 128, 4, 1, 0, FAKE, None, None) == 3   # packed codes need the native layout
-    assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 8, 128, 8, 1, 1, FAKE, None, None) == 3   # packed codes are 4-bit
-    assert f(FAKE, FAKE, FAKE, FAKE, None, 4, 8, 128 * 2048, 4, 1, 1, FAKE, None, None) == 3   # accumulator bound, 256 * acc
+    assert f(None, FAKE, FAKE, FAKE, None, None, None, 4, 8, 64, 4, 0, 0, FAKE, None, None) == 1
+    assert f(FAKE, FAKE, FAKE, FAKE, None, None, None, 4, 8, 64, 4, 0, 0, None, None, None) == 1
+    assert f(FAKE, FAKE, FAKE, FAKE, None, None, None, 4, 0, 64, 4, 0, 0, FAKE, None, None) == 2
+    assert f(FAKE, FAKE, FAKE, FAKE, None, None, None, 4, 8, 96, 4, 0, 0, FAKE, None, None) == 2     # K % 64
+    assert f(FAKE, FAKE, FAKE, FAKE, None, None, None, 4, 8, 64, 3, 0, 0, FAKE, None, None) == 3
+    assert f(FAKE, FAKE, FAKE, FAKE, None, None, None, 4, 8, 64, 4, 0, 7, FAKE, None, None) == 3     # layout
+    assert f(FAKE, FAKE, FAKE, FAKE, None, None, None, 4, 8, 64 * 4096, 8, 0, 0, FAKE, None, None) == 3   # accumulator bound
+    assert f(FAKE, FAKE, FAKE, FAKE, None, None, None, 4, 8, 192, 4, 0, 1, FAKE, None, None) == 3    # native layout needs K % 128 == 0
+    assert f(FAKE, FAKE, ODD, FAKE, None, None, None, 4, 8, 64, 4, 0, 0, FAKE, None, None) == 5
+    assert f(FAKE, FAKE, FAKE, FAKE, None, None, ODD, 4, 8, 64, 4, 0, 0, FAKE, None, None) == 5
+    assert f(FAKE, FAKE, FAKE, FAKE, None, None, None, 4, 8, 128, 4, 1, 0, FAKE, None, None) == 3   # packed codes need the native layout
+    assert f(FAKE, FAKE, FAKE, FAKE, None, None, None, 4, 8, 128, 8, 1, 1, FAKE, None, None) == 3   # packed codes are 4-bit
+    assert f(FAKE, FAKE, FAKE, FAKE, None, None, None, 4, 8, 128 * 2048, 4, 1, 1, FAKE, None, None) == 3   # accumulator bound, 256 * acc
+    assert f(FAKE, FAKE, FAKE, FAKE, FAKE, None, None, 4, 8, 128, 4, 0, 1, FAKE, None, None) == 1   # zero-points need the code sums
+    assert f(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 4, 8, 64, 4, 0, 0, FAKE, None, None) == 3    # zero-points: native layout only
+    assert f(FAKE, FAKE, FAKE, FAKE, ODD, FAKE, None, 4, 8, 128, 4, 0, 1, FAKE, None, None) == 5
+    assert f(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 4, 8, 128 * 600, 8, 0, 1, FAKE, None, None) == 3   # bound with |w - z| <= 16
     assert ok
 
 
@@ -80,14 +84,16 @@ def test_qlinear_workspace_and_argument_errors():
     off4 = dvdq.qlinear_scale_offset(M, K, dvdq.CODES_PACKED4)
     assert M * K // 2 <= off4 < M * K // 2 + 256 and off4 % 256 == 0
     assert dvdq.qlinear_workspace_bytes(M, K, dvdq.CODES_PACKED4) >= off4 + 4 * M
+    rs_off = dvdq.qlinear_rowsum_offset(M, K, dvdq.CODES_INT8)
+    assert rs_off >= off + 4 * M and rs_off % 256 == 0 and need >= rs_off + 4 * M
     assert dvdq.qlinear_workspace_bytes(0, K, 0) == 0
     f = L.dvdq_qlinear
-    assert f(FAKE, FAKE, FAKE, None, M, 64, K, 256, 4, 0, 0, FAKE, None, need, None) == 1
-    assert f(FAKE, FAKE, FAKE, None, M, 64, K, 256, 4, 0, 0, FAKE, C.c_void_p(0x1010), need, None) == 5
-    assert f(FAKE, FAKE, FAKE, None, M, 64, K, 256, 4, 0, 0, FAKE, C.c_void_p(0x1100), need - 1, None) == 4
-    assert f(FAKE, FAKE, FAKE, None, M, 64, K, 1024, 4, 0, 0, FAKE, C.c_void_p(0x1100), need, None) == 2   # 1024 does not divide 1536
-    assert f(FAKE, FAKE, FAKE, None, 8, 64, 2048, 1024, 4, 0, 0, FAKE, C.c_void_p(0x1100), 1 << 20, None) == 3
-    assert f(None, FAKE, FAKE, None, M, 64, K, 256, 4, 0, 0, FAKE, C.c_void_p(0x1100), need, None) == 1
+    assert f(FAKE, FAKE, FAKE, None, None, M, 64, K, 256, 4, 0, 0, FAKE, None, need, None) == 1
+    assert f(FAKE, FAKE, FAKE, None, None, M, 64, K, 256, 4, 0, 0, FAKE, C.c_void_p(0x1010), need, None) == 5
+    assert f(FAKE, FAKE, FAKE, None, None, M, 64, K, 256, 4, 0, 0, FAKE, C.c_void_p(0x1100), need - 1, None) == 4
+    assert f(FAKE, FAKE, FAKE, None, None, M, 64, K, 1024, 4, 0, 0, FAKE, C.c_void_p(0x1100), need, None) == 2   # 1024 does not divide 1536
+    assert f(FAKE, FAKE, FAKE, None, None, 8, 64, 2048, 1024, 4, 0, 0, FAKE, C.c_void_p(0x1100), 1 << 20, None) == 3
+    assert f(None, FAKE, FAKE, None, None, M, 64, K, 256, 4, 0, 0, FAKE, C.c_void_p(0x1100), need, None) == 1
 
 
 def test_prepack_argument_errors_and_size():
