@@ -186,6 +186,11 @@ def main():
     ctl = dvdq.GbsController(delta=0.1)
     gbs_avg, _ = time_launches(lambda i: ctl.step(f_cur, f_prev), 20, group=10)
 
+    # ---- the offline weight quantizer on this layer's weight shape (runs once per layer, fp64)
+    w_f32 = (torch.randn((N, K), device=dev) * 0.02).contiguous()
+    bgr_ms, _ = time_launches(lambda i: dvdq.bgr_quantize(w_f32), 2, group=1)
+    del w_f32
+
     out = {
         "metric": "fused W4A4 qlinear TOPS & % INT8-MFMA peak; rotate+quant HBM GB/s",
         "value": round(tops, 2), "unit": "TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -216,6 +221,9 @@ def main():
 
     out["gbs_controller"] = {"elements": n_lat, "us_per_step": round(gbs_avg * 1e3, 2),
                              "achieved_gbps": round(4.0 * n_lat / (gbs_avg * 1e-3) / 1e9, 1), "bound": "hbm (launch-bound at this size)"}
+
+    out["bgr_quantizer"] = {"rows": N, "K": K, "n_steps": 100, "max_refine": 10, "ms": round(bgr_ms, 2),
+                            "note": "offline, once per layer; fp64"}
 
     # ---- CPU baseline: the oracle as it stands, on a bounded token sample (about 10-30 s of CPU work)
     if not args.no_cpu_baseline:

@@ -154,6 +154,31 @@ int dvdq_w4_prepack(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w
 size_t dvdq_w4_native_bytes(int64_t N, int64_t K);
 
 /*
+ * One-time, offline: Bounded-init Grid Refinement (Sec. 3.1, Alg. 1), the INT4 weight
+ * quantizer.  For every row n of w (an output channel, already expressed in the rotated
+ * basis W H of Sec. 3.2) it finds a step size Delta_n and an integer zero-point z_n for
+ *     Quant    q = clamp(rint(w / Delta) + z, 0, 15)        DeQuant  w^ = Delta (q - z)
+ * by searching n_steps progressively clipped MinMax ranges [min + i s, max - i s],
+ * s = (max - min) / n_steps, i = 0, 1, ... while the range is non-empty (i = 0 is plain MinMax),
+ * refining each start with at most max_refine rounds of {least-squares Delta, relaxed-then-
+ * rounded z, re-quantization}, a start's refinement ending once a round improves the row
+ * error ||w - w^||_2 by less than eps (or worsens it); the grid with the smallest row error
+ * over everything evaluated is kept.  Arithmetic is fp64; rint rounds half to even.
+ *
+ *   w          in   fp32 [N, K]
+ *   n_steps         >= 1 (100 is customary); max_refine >= 0; eps >= 0
+ *   w_packed   out  canonical packed codes uint8 [N, K/2]: signed nibbles q - 8
+ *   w_scale    out  fp32 [N]: Delta_n
+ *   w_zero     out  int8 [N]: z_n - 8, the signed zero-point dvdq_w4ax_gemm takes
+ *   row_error  out  fp64 [N] or NULL: ||w_n - w^_n||_2 of the returned grid
+ *
+ * K must be even (DVDQ_ERR_SHAPE) and at most 32768 (DVDQ_ERR_UNSUPPORTED).  A constant row
+ * is represented exactly.  Results do not depend on the launch (no atomics).
+ */
+int dvdq_bgr_quantize(const float *w, int64_t N, int64_t K, int n_steps, int max_refine, double eps,
+                      uint8_t *w_packed, float *w_scale, int8_t *w_zero, double *row_error, void *hip_stream);
+
+/*
  * delta-Guided Bit Switching (Sec. 3.3): choose the activation bit-width of the next
  * denoising step from how much the model output changed.
  *

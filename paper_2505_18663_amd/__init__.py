@@ -16,7 +16,7 @@ import torch
 __all__ = [
     "DvdqError", "DvdqLibraryMissing", "lib", "library_path", "version", "status_string",
     "rotate_quant", "w4ax_gemm", "qlinear", "qlinear_workspace_bytes", "qlinear_scale_offset", "qlinear_rowsum_offset", "workspace_rowsum",
-    "w4_prepack", "w4_native_bytes", "GbsController", "bench_copy", "bench_mfma_i8", "bench_set_gemm_variant",
+    "w4_prepack", "w4_native_bytes", "bgr_quantize", "GbsController", "bench_copy", "bench_mfma_i8", "bench_set_gemm_variant",
     "W_CANONICAL", "W_NATIVE", "CODES_INT8", "CODES_PACKED4", "EXPORTED_SYMBOLS",
 ]
 
@@ -26,7 +26,7 @@ CODES_INT8, CODES_PACKED4 = 0, 1
 EXPORTED_SYMBOLS = (
     "dvdq_rotate_quant", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_qlinear_workspace_bytes",
     "dvdq_qlinear_scale_offset", "dvdq_qlinear_rowsum_offset", "dvdq_w4_prepack", "dvdq_w4_native_bytes", "dvdq_status_string",
-    "dvdq_version", "dvdq_gbs_workspace_bytes", "dvdq_gbs_reset", "dvdq_gbs_step", "dvdq_bench_copy", "dvdq_bench_mfma_i8", "dvdq_bench_set_gemm_variant",
+    "dvdq_version", "dvdq_gbs_workspace_bytes", "dvdq_gbs_reset", "dvdq_gbs_step", "dvdq_bgr_quantize", "dvdq_bench_copy", "dvdq_bench_mfma_i8", "dvdq_bench_set_gemm_variant",
 )
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -75,6 +75,8 @@ def lib() -> C.CDLL:
     L.dvdq_gbs_reset.restype = i32
     L.dvdq_gbs_step.argtypes = [vp, vp, i64, C.c_float, i32, i32, vp, vp, sz, vp]
     L.dvdq_gbs_step.restype = i32
+    L.dvdq_bgr_quantize.argtypes = [vp, i64, i64, i32, i32, C.c_double, vp, vp, vp, vp, vp]
+    L.dvdq_bgr_quantize.restype = i32
     L.dvdq_bench_copy.argtypes = [vp, vp, sz, vp]
     L.dvdq_bench_mfma_i8.argtypes = [i32, vp, C.POINTER(C.c_double), vp]
     L.dvdq_bench_set_gemm_variant.argtypes = [i32]
@@ -269,6 +271,21 @@ def w4_prepack(w_canonical, w_native=None, stream=None):
         raise ValueError("w_native too small")
     _check(L.dvdq_w4_prepack(_ptr(w_canonical), N, K, _ptr(w_native), _stream(stream)), "dvdq_w4_prepack")
     return w_native
+
+
+def bgr_quantize(w, n_steps: int = 100, max_refine: int = 10, eps: float = 0.0, want_error: bool = False, stream=None):
+    """Offline INT4 weight quantizer (Bounded-init Grid Refinement).  w: fp32 [N, K] ->
+    (w_packed uint8 [N, K/2] canonical, w_scale fp32 [N], w_zero int8 [N][, row_error fp64 [N]])."""
+    L = lib()
+    _need(w, torch.float32, None, "w")
+    N, K = w.shape
+    w_packed = torch.empty((N, K // 2), dtype=torch.uint8, device=w.device)
+    w_scale = torch.empty((N,), dtype=torch.float32, device=w.device)
+    w_zero = torch.empty((N,), dtype=torch.int8, device=w.device)
+    err = torch.empty((N,), dtype=torch.float64, device=w.device) if want_error else None
+    _check(L.dvdq_bgr_quantize(_ptr(w), N, K, n_steps, max_refine, float(eps), _ptr(w_packed), _ptr(w_scale),
+                               _ptr(w_zero), _ptr(err), _stream(stream)), "dvdq_bgr_quantize")
+    return (w_packed, w_scale, w_zero, err) if want_error else (w_packed, w_scale, w_zero)
 
 
 # ------------------------------------------------------------------ delta-GBS controller

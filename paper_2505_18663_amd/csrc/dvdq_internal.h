@@ -31,6 +31,9 @@ int launch_gbs_reset(void *state, int bits, hipStream_t stream);
 int launch_gbs_step(const uint16_t *ft, const uint16_t *fp, int64_t n, double delta, int b_low, int b_high,
                     void *state, void *workspace, hipStream_t stream);
 
+int launch_bgr(const float *w, int64_t N, int64_t K, int n_steps, int max_refine, double eps, uint8_t *w_packed,
+               float *w_scale, int8_t *w_zero, double *row_error, hipStream_t stream);
+
 inline int check_launch() { return hipGetLastError() == hipSuccess ? DVDQ_OK : DVDQ_ERR_HIP; }
 
 }  // namespace dvdq

@@ -106,6 +106,20 @@ def test_prepack_argument_errors_and_size():
     assert L.dvdq_w4_prepack(FAKE, 8, 128, ODD, None) == 5
 
 
+def test_bgr_argument_errors():
+    f = dvdq.lib().dvdq_bgr_quantize
+    assert f(None, 8, 64, 100, 10, 0.0, FAKE, FAKE, FAKE, None, None) == 1
+    assert f(FAKE, 8, 64, 100, 10, 0.0, FAKE, FAKE, None, None, None) == 1
+    assert f(FAKE, 0, 64, 100, 10, 0.0, FAKE, FAKE, FAKE, None, None) == 2
+    assert f(FAKE, 8, 63, 100, 10, 0.0, FAKE, FAKE, FAKE, None, None) == 2        # K odd
+    assert f(FAKE, 8, 64, 0, 10, 0.0, FAKE, FAKE, FAKE, None, None) == 2          # no search steps
+    assert f(FAKE, 8, 64, 100, -1, 0.0, FAKE, FAKE, FAKE, None, None) == 2
+    assert f(FAKE, 8, 64, 100, 10, -1.0, FAKE, FAKE, FAKE, None, None) == 2
+    assert f(FAKE, 8, 65536, 100, 10, 0.0, FAKE, FAKE, FAKE, None, None) == 3     # row does not fit LDS
+    assert f(FAKE, 8, 64, 100, 10, 0.0, ODD, FAKE, FAKE, None, None) == 5
+    assert f(FAKE, 8, 64, 100, 10, 0.0, FAKE, FAKE, FAKE, ODD, None) == 5
+
+
 def test_gbs_argument_errors():
     L = dvdq.lib()
     ws = L.dvdq_gbs_workspace_bytes()
