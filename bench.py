@@ -29,7 +29,7 @@ HBM_PEAK_GBPS = 8000.0           # published HBM3E bandwidth, MI355X
 # very command, scaled by the same counters' reading for dvdq_bench_copy; the summaries with the
 # commands are profiles/bench_<workload>_hbm_counters.md.  None where no counter run exists.
 MEASURED_HBM_TRAFFIC = {
-    "small_dit_qkv_w4a4": {"w4ax_gemm": 551.0e6, "rotate_quant": 126.1e6},
+    "small_dit_qkv_w4a4": {"w4ax_gemm": 562.6e6, "rotate_quant": 126.2e6},
 }
 
 
