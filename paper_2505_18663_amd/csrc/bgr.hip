@@ -22,6 +22,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr double kQmax = 15.0;   // INT4
+constexpr size_t kMaxK = 32768;  // longest row (the row is kept in LDS); the C ABI checks it
 
 struct Sums { double e2, num, den, sq; };
 
@@ -152,8 +153,9 @@ __global__ __launch_bounds__(kThreads) void bgr_kernel(const float *__restrict__
 int launch_bgr(const float *w, int64_t N, int64_t K, int n_steps, int max_refine, double eps, uint8_t *w_packed,
                float *w_scale, int8_t *w_zero, double *row_error, hipStream_t stream) {
     const size_t smem = kWaves * sizeof(double) + (size_t)K * sizeof(float);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(bgr_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)smem);
+    static std::atomic<uint64_t> configured{0};
+    allow_dynamic_lds(reinterpret_cast<const void *>(bgr_kernel), kWaves * sizeof(double) + kMaxK * sizeof(float),
+                      configured);   // the limit for the longest row the API admits
     hipLaunchKernelGGL(bgr_kernel, dim3((unsigned)N), dim3(kThreads), smem, stream, w, (int)K, n_steps, max_refine, eps,
                        w_packed, w_scale, w_zero, row_error);
     return check_launch();

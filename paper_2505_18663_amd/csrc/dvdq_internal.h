@@ -1,6 +1,7 @@
 // Internal declarations shared by the translation units of libdvdq (not installed).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -33,6 +34,18 @@ int launch_gbs_step(const uint16_t *ft, const uint16_t *fp, int64_t n, double de
 
 int launch_bgr(const float *w, int64_t N, int64_t K, int n_steps, int max_refine, double eps, uint8_t *w_packed,
                float *w_scale, int8_t *w_zero, double *row_error, hipStream_t stream);
+
+// Raise a kernel's dynamic-LDS limit to `bytes` once per kernel and device (`done` is the call
+// site's own bit mask of devices already configured).  Not a stream operation: after the first
+// launch on a device nothing but the launch itself is issued, also under stream capture.
+inline void allow_dynamic_lds(const void *kernel, size_t bytes, std::atomic<uint64_t> &done) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return;
+    const uint64_t bit = dev >= 0 && dev < 64 ? (uint64_t)1 << dev : 0;
+    if (bit && (done.load(std::memory_order_acquire) & bit)) return;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess && bit)
+        done.fetch_or(bit, std::memory_order_release);
+}
 
 inline int check_launch() { return hipGetLastError() == hipSuccess ? DVDQ_OK : DVDQ_ERR_HIP; }
 

@@ -587,7 +587,8 @@ int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, c
     const size_t smem = (size_t)STAGES * (BM * (A4 ? BK / 2 : BK) + BN * BK / 2) +
                         2 * ((BM + BN) * 4 + BN * 2 + BM * 4 + BN);
     auto k = w4ax_gemm_native_kernel<BM, BN, BK, WAVES_M, WAVES_N, STAGES, OCC, A4>;
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    static std::atomic<uint64_t> configured{0};   // one per template instantiation
+    allow_dynamic_lds(reinterpret_cast<const void *>(k), smem, configured);
     hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), smem, stream, codes, x_scale, w,
                        w_scale, w_zero, code_rowsum, bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n);
     return check_launch();

@@ -205,7 +205,8 @@ int launch_tile(const int8_t *codes, const float *x_scale, const uint8_t *w, con
     const size_t smem = 2 * (size_t)(BM + BN) * kBK;
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
     auto k = w4ax_gemm_canonical_kernel<BM, BN>;
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    static std::atomic<uint64_t> configured{0};   // one per template instantiation
+    allow_dynamic_lds(reinterpret_cast<const void *>(k), smem, configured);
     hipLaunchKernelGGL(k, grid, block, smem, stream, codes, x_scale, w, w_scale, bias, M, N, K, y, acc_out, tiles_m,
                        tiles_n);
     return check_launch();
