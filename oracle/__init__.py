@@ -44,6 +44,8 @@ def _load():
         lib.dvdq_oracle_hadamard.argtypes = [i32, vp]
         lib.dvdq_oracle_rotate.argtypes = [vp, i64, i64, i32, vp]
         lib.dvdq_oracle_quantize.argtypes = [vp, i64, i64, i32, vp, vp]
+        lib.dvdq_oracle_quantize_blockwise.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
+        lib.dvdq_oracle_quantize_blockwise.restype = i32
         lib.dvdq_oracle_rotate_quant.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
         lib.dvdq_oracle_unpack_w4.argtypes = [vp, i64, i64, vp]
         lib.dvdq_oracle_pack_w4.argtypes = [vp, i64, i64, vp]
@@ -115,6 +117,19 @@ def quantize(xrot: np.ndarray, act_bits: int):
     scale = np.empty(M, dtype=np.float32)
     _check(_load().dvdq_oracle_quantize(_p(xr), M, K, act_bits, _p(codes), _p(scale)), "quantize")
     return codes, scale
+
+
+def quantize_blockwise(xrot: np.ndarray, act_bits: int, group: int):
+    """Block-wise scaled codes in the int8 container.  Returns (values int8 [M, K], x_scale f32 [M] (already
+    divided by 2^emax), exps uint8 [M, K/group])."""
+    xr = _arr(xrot, np.float64, 2)
+    M, K = xr.shape
+    v = np.empty((M, K), dtype=np.int8)
+    scale = np.empty(M, dtype=np.float32)
+    exps = np.empty((M, K // max(group, 1)), dtype=np.uint8)
+    _check(_load().dvdq_oracle_quantize_blockwise(_p(xr), M, K, act_bits, group, _p(v), _p(scale), _p(exps)),
+           "quantize_blockwise")
+    return v, scale, exps
 
 
 def rotate_quant(x_bf16: np.ndarray, had_block: int, act_bits: int, return_rotated: bool = False):

@@ -159,6 +159,52 @@ int dvdq_oracle_quantize(const double *xrot, int64_t M, int64_t K, int bits,
     return 0;
 }
 
+/* Block-wise variant of steps 2-3 (Sec. 3.2, last paragraph: the deployed kernels scale block-wise,
+ * the definition being in a supplement that is not available; this is a reading).  Every group of
+ * `group` consecutive channels of a token gets its own step size, a power-of-two fraction of the
+ * token's:
+ *     s_m     = max_k |x~_mk| / qmax                         (as in step 2, rounded once to fp32)
+ *     e_mg    = the largest e in [0, emax] with  a_mg * 2^e <= max_k |x~_mk|,  a_mg = max_{k in g} |x~_mk|
+ *     s_mg    = s_m * 2^-e_mg
+ *     q_mk    = clamp(rint(x~_mk / s_mg), -qmax, qmax)
+ * so a quiet group is quantized up to 2^emax times finer.  Because the ratios are powers of two the
+ * group scales fold into an int8 container: the stored value is v_mk = q_mk * 2^(emax - e_mg), the
+ * scale handed on is s'_m = s_m * 2^-emax, and s'_m * v_mk = s_mg * q_mk; the integer GEMM runs on v
+ * unchanged.  emax = 8 - bits (|v| <= qmax * 2^emax <= 127).  exps_out ([M, K/group]) may be NULL. */
+int dvdq_oracle_quantize_blockwise(const double *xrot, int64_t M, int64_t K, int bits, int group,
+                                   int8_t *values, float *x_scale, uint8_t *exps_out)
+{
+    if (bits < 2 || bits > 8 || group < 1 || K % group) return -1;
+    const double qmax = (double)((1 << (bits - 1)) - 1);
+    const int emax = 8 - bits;
+    const int64_t G = K / group;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        const double *r = xrot + m * K;
+        double amax = 0.0;
+        for (int64_t k = 0; k < K; ++k) if (fabs(r[k]) > amax) amax = fabs(r[k]);
+        const float s = (float)(amax / qmax);
+        x_scale[m] = (float)ldexp((double)s, -emax);
+        for (int64_t g = 0; g < G; ++g) {
+            double a = 0.0;
+            for (int64_t k = g * group; k < (g + 1) * group; ++k) if (fabs(r[k]) > a) a = fabs(r[k]);
+            int e = 0;
+            for (int t = 1; t <= emax; ++t) if (ldexp(a, t) <= amax) e = t;
+            if (exps_out) exps_out[m * G + g] = (uint8_t)e;
+            for (int64_t k = g * group; k < (g + 1) * group; ++k) {
+                double q = 0.0;
+                if (s > 0.0f) {
+                    q = nearbyint(r[k] / ldexp((double)s, -e));
+                    if (q > qmax) q = qmax;
+                    if (q < -qmax) q = -qmax;
+                }
+                values[m * K + k] = (int8_t)ldexp(q, emax - e);
+            }
+        }
+    }
+    return 0;
+}
+
 /* Steps 1-3 in one call.  xrot_out may be NULL. */
 int dvdq_oracle_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int B, int bits,
                              int8_t *codes, float *x_scale, double *xrot_out)
