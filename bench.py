@@ -186,6 +186,21 @@ def main():
     ctl = dvdq.GbsController(delta=0.1)
     gbs_avg, _ = time_launches(lambda i: ctl.step(f_cur, f_prev), 20, group=10)
 
+    # ---- the block-wise scaled variant of the same layer (4-bit codes with power-of-two group steps in
+    # the int8 container; the GEMM then runs its int8-code path), as two calls on separate buffers
+    blockwise = None
+    if bits in (4, 6):
+        vals = [torch.empty((M, K), dtype=torch.int8, device=dev) for _ in range(nb)]
+
+        def bw(i):
+            j = i % nb
+            dvdq.rotate_quant_blockwise(xs[j], B, bits, 128, values=vals[j], x_scale=views[j][1])
+            dvdq.w4ax_gemm(vals[j], views[j][1], w_native, ws_dev, 8, dvdq.W_NATIVE, y=ys[j])
+        bw_avg, _ = time_launches(bw, args.steps)
+        blockwise = {"group": 128, "ms_per_step": round(bw_avg, 4), "value": round(ops / (bw_avg * 1e-3) / 1e12, 2),
+                     "unit": "TOP/s", "codes_format": "int8"}
+        del vals
+
     # ---- the offline weight quantizer on this layer's weight shape (runs once per layer, fp64)
     w_f32 = (torch.randn((N, K), device=dev) * 0.02).contiguous()
     bgr_ms, _ = time_launches(lambda i: dvdq.bgr_quantize(w_f32), 2, group=1)
@@ -222,6 +237,8 @@ def main():
     out["gbs_controller"] = {"elements": n_lat, "us_per_step": round(gbs_avg * 1e3, 2),
                              "achieved_gbps": round(4.0 * n_lat / (gbs_avg * 1e-3) / 1e9, 1), "bound": "hbm (launch-bound at this size)"}
 
+    if blockwise:
+        out["blockwise_scaling"] = blockwise
     out["bgr_quantizer"] = {"rows": N, "K": K, "n_steps": 100, "max_refine": 10, "ms": round(bgr_ms, 2),
                             "note": "offline, once per layer; fp64"}
 

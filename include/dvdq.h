@@ -88,6 +88,29 @@ int dvdq_rotate_quant(const void *x_bf16, int64_t M, int64_t K, int had_block, i
                       int8_t *codes, float *x_scale, int32_t *code_rowsum, void *hip_stream);
 
 /*
+ * Block-wise scaled variant of dvdq_rotate_quant (Sec. 3.2 closes by saying the deployed kernels
+ * scale block-wise; its definition is in a supplement that is not available, so this is a
+ * reading).  Every group of `group` consecutive channels of a token is quantized with its own
+ * step, a power-of-two fraction of the token's step s_m = max|x~_m| / qmax:
+ *     e_mg = largest e in [0, emax] with  max_{k in g}|x~_mk| * 2^e <= max_k|x~_mk|,   emax = 8 - act_bits
+ *     q_mk = clamp(rint(x~_mk / (s_m 2^-e_mg)), -qmax, qmax)
+ * and stored in the int8 container as  values[m,k] = q_mk * 2^(emax - e_mg), with
+ * x_scale[m] = s_m * 2^-emax, so that x_scale[m] * values[m,k] dequantizes every group and
+ * dvdq_w4ax_gemm runs on `values` unchanged: call it with act_bits = 8 (|values| <= 127) and
+ * DVDQ_CODES_INT8.  Quiet groups of a token are quantized up to 2^emax times finer at no cost
+ * in the GEMM.
+ *
+ *   act_bits      4 or 6 (8 leaves no headroom: DVDQ_ERR_UNSUPPORTED)
+ *   group         128, 256 or 512 channels (DVDQ_ERR_UNSUPPORTED otherwise); must divide K (DVDQ_ERR_SHAPE)
+ *   values   out  int8 [M, K]
+ *   x_scale  out  fp32 [M]
+ *   value_rowsum out int32 [M] or NULL: sum_k values[m,k], for weights with zero-points
+ * Other arguments and limits as for dvdq_rotate_quant.
+ */
+int dvdq_rotate_quant_blockwise(const void *x_bf16, int64_t M, int64_t K, int had_block, int act_bits, int group,
+                                int8_t *values, float *x_scale, int32_t *value_rowsum, void *hip_stream);
+
+/*
  * Low-bit GEMM with exact int32 accumulation and the dequantizing epilogue
  * (Sec. 3.2: Y = X^ Lambda W^^T; Sec. 3.1 DeQuant, w^ = Delta (w_q - z)):
  *

@@ -15,7 +15,7 @@ import torch
 
 __all__ = [
     "DvdqError", "DvdqLibraryMissing", "lib", "library_path", "version", "status_string",
-    "rotate_quant", "w4ax_gemm", "qlinear", "qlinear_workspace_bytes", "qlinear_scale_offset", "qlinear_rowsum_offset", "workspace_rowsum",
+    "rotate_quant", "rotate_quant_blockwise", "w4ax_gemm", "qlinear", "qlinear_workspace_bytes", "qlinear_scale_offset", "qlinear_rowsum_offset", "workspace_rowsum",
     "w4_prepack", "w4_native_bytes", "bgr_quantize", "GbsController", "bench_copy", "bench_mfma_i8", "bench_set_gemm_variant",
     "W_CANONICAL", "W_NATIVE", "CODES_INT8", "CODES_PACKED4", "EXPORTED_SYMBOLS",
 ]
@@ -24,7 +24,7 @@ W_CANONICAL, W_NATIVE = 0, 1
 CODES_INT8, CODES_PACKED4 = 0, 1
 
 EXPORTED_SYMBOLS = (
-    "dvdq_rotate_quant", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_qlinear_workspace_bytes",
+    "dvdq_rotate_quant", "dvdq_rotate_quant_blockwise", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_qlinear_workspace_bytes",
     "dvdq_qlinear_scale_offset", "dvdq_qlinear_rowsum_offset", "dvdq_w4_prepack", "dvdq_w4_native_bytes", "dvdq_status_string",
     "dvdq_version", "dvdq_gbs_workspace_bytes", "dvdq_gbs_reset", "dvdq_gbs_step", "dvdq_bgr_quantize", "dvdq_bench_copy", "dvdq_bench_mfma_i8", "dvdq_bench_set_gemm_variant",
 )
@@ -60,6 +60,8 @@ def lib() -> C.CDLL:
     L = C.CDLL(_LIB_PATH)
     i64, i32, vp, sz = C.c_int64, C.c_int, C.c_void_p, C.c_size_t
     L.dvdq_rotate_quant.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp, vp]
+    L.dvdq_rotate_quant_blockwise.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp, vp]
+    L.dvdq_rotate_quant_blockwise.restype = i32
     L.dvdq_w4ax_gemm.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, vp, vp]
     L.dvdq_qlinear.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, i32, vp, vp, sz, vp]
     L.dvdq_qlinear_rowsum_offset.argtypes = [i64, i64, i32]
@@ -81,7 +83,7 @@ def lib() -> C.CDLL:
     L.dvdq_bench_mfma_i8.argtypes = [i32, vp, C.POINTER(C.c_double), vp]
     L.dvdq_bench_set_gemm_variant.argtypes = [i32]
     L.dvdq_bench_set_gemm_variant.restype = i32
-    for f in ("dvdq_rotate_quant", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_w4_prepack", "dvdq_version",
+    for f in ("dvdq_rotate_quant", "dvdq_rotate_quant_blockwise", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_w4_prepack", "dvdq_version",
               "dvdq_bench_copy", "dvdq_bench_mfma_i8"):
         getattr(L, f).restype = i32
     for f in ("dvdq_qlinear_workspace_bytes", "dvdq_qlinear_scale_offset", "dvdq_qlinear_rowsum_offset",
@@ -157,6 +159,25 @@ def rotate_quant(x, had_block: int, act_bits: int, codes=None, x_scale=None, str
     _check(L.dvdq_rotate_quant(_ptr(x), M, K, had_block, act_bits, codes_format, _ptr(codes), _ptr(x_scale),
                                _ptr(code_rowsum), _stream(stream)), "dvdq_rotate_quant")
     return (codes, x_scale) if code_rowsum is None else (codes, x_scale, code_rowsum)
+
+
+def rotate_quant_blockwise(x, had_block: int, act_bits: int, group: int, values=None, x_scale=None,
+                           want_rowsum: bool = False, stream=None):
+    """Block-wise scaled quantizer: x bf16 [M, K] -> (values int8 [M, K], x_scale fp32 [M][, rowsum int32 [M]]).
+    Feed the result to w4ax_gemm with act_bits=8.  See dvdq_rotate_quant_blockwise."""
+    L = lib()
+    _need(x, torch.bfloat16, None, "x")
+    M, K = x.shape
+    if values is None:
+        values = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    if x_scale is None:
+        x_scale = torch.empty((M,), dtype=torch.float32, device=x.device)
+    _need(values, torch.int8, (M, K), "values")
+    _need(x_scale, torch.float32, (M,), "x_scale")
+    rs = torch.empty((M,), dtype=torch.int32, device=x.device) if want_rowsum else None
+    _check(L.dvdq_rotate_quant_blockwise(_ptr(x), M, K, had_block, act_bits, group, _ptr(values), _ptr(x_scale),
+                                         _ptr(rs), _stream(stream)), "dvdq_rotate_quant_blockwise")
+    return (values, x_scale, rs) if want_rowsum else (values, x_scale)
 
 
 def w4ax_gemm(codes, x_scale, w, w_scale, act_bits: int, w_layout: int = W_CANONICAL, bias=None,

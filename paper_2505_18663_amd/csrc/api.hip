@@ -72,8 +72,22 @@ int dvdq_rotate_quant(const void *x_bf16, int64_t M, int64_t K, int had_block, i
     const int rc = check_rotate_quant(x_bf16, M, K, had_block, act_bits, codes_format, codes, x_scale, code_rowsum,
                                       &log2b);
     if (rc != DVDQ_OK) return rc;
-    return dvdq::launch_rotate_quant(static_cast<const uint16_t *>(x_bf16), M, K, log2b, act_bits, codes_format,
+    return dvdq::launch_rotate_quant(static_cast<const uint16_t *>(x_bf16), M, K, log2b, act_bits, codes_format, 0,
                                      codes, x_scale, code_rowsum, static_cast<hipStream_t>(hip_stream));
+}
+
+int dvdq_rotate_quant_blockwise(const void *x_bf16, int64_t M, int64_t K, int had_block, int act_bits, int group,
+                                int8_t *values, float *x_scale, int32_t *value_rowsum, void *hip_stream) {
+    int log2b = 0;
+    const int rc = check_rotate_quant(x_bf16, M, K, had_block, act_bits, DVDQ_CODES_INT8, values, x_scale,
+                                      value_rowsum, &log2b);
+    if (rc != DVDQ_OK) return rc;
+    if (group < 1 || (K % group) != 0) return DVDQ_ERR_SHAPE;
+    if (group != 128 && group != 256 && group != 512) return DVDQ_ERR_UNSUPPORTED;
+    if (act_bits == 8) return DVDQ_ERR_UNSUPPORTED;   // 8-bit codes leave no room in the int8 container
+    return dvdq::launch_rotate_quant(static_cast<const uint16_t *>(x_bf16), M, K, log2b, act_bits, DVDQ_CODES_INT8,
+                                     log2_exact(group), values, x_scale, value_rowsum,
+                                     static_cast<hipStream_t>(hip_stream));
 }
 
 int dvdq_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
@@ -125,7 +139,7 @@ int dvdq_qlinear(const void *x_bf16, const uint8_t *w, const float *w_scale, con
     if (rc != DVDQ_OK) return rc;
     if (workspace_bytes < dvdq_qlinear_workspace_bytes(M, K, codes_format)) return DVDQ_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    rc = dvdq::launch_rotate_quant(static_cast<const uint16_t *>(x_bf16), M, K, log2b, act_bits, codes_format,
+    rc = dvdq::launch_rotate_quant(static_cast<const uint16_t *>(x_bf16), M, K, log2b, act_bits, codes_format, 0,
                                    codes, x_scale, rowsum, stream);
     if (rc != DVDQ_OK) return rc;
     return dvdq::launch_w4ax_gemm(codes, x_scale, w, w_scale, w_zero, rowsum,

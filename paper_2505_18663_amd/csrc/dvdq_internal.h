@@ -12,7 +12,7 @@ namespace dvdq {
 // Launchers: arguments are already validated by the C-ABI layer in api.hip.
 // Each returns DVDQ_OK or DVDQ_ERR_HIP.
 int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block, int act_bits, int codes_format,
-                        int8_t *codes, float *x_scale, int32_t *code_rowsum, hipStream_t stream);
+                        int group_log2, int8_t *codes, float *x_scale, int32_t *code_rowsum, hipStream_t stream);
 
 int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                      const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,

@@ -92,6 +92,8 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
     double scale_mul,  // 1 / (sqrt(B) * qmax); fp64 so the fp32 scale is rounded once
     float recip_num,   // 1 / sqrt(B)
     int via_lds,       // PACK4 only: gather the packed codes through LDS into 16-byte stores (K % 32 == 0)
+    int group_log2,    // int8 container only: 0, or log2 of the channel group (7, 8, 9) of block-wise scaling
+    int emax,          // block-wise scaling: largest power-of-two refinement of a group's step (8 - act_bits)
     int8_t *__restrict__ codes, float *__restrict__ x_scale,
     int32_t *__restrict__ code_rowsum) {  // NULL, or [M]: sum of the row's codes (for weight zero-points)
     extern __shared__ float s_amax[];  // [2][rows_per_wg * waves_per_row], slots alternate per iteration
@@ -201,7 +203,8 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
         // scale handed on = amax / (sqrt(B) * qmax); codes = rne(v * (1/sqrt(B)) / scale)
         const float scale = (float)((double)amax * scale_mul);
         const float r = scale > 0.f ? flip * (recip_num / scale) : 0.f;
-        if (row_ok && wsub == 0 && lane == 0) x_scale[row] = scale;
+        // (block-wise scaling stores values that carry a factor 2^emax, see below)
+        if (row_ok && wsub == 0 && lane == 0) x_scale[row] = group_log2 ? ldexpf(scale, -emax) : scale;
 
         const float magic = 12582912.f;  // 1.5 * 2^23: adding it rounds to integer, ties to even
         int csum = 0;                    // this lane's share of the row's code sum (padding chunks hold zeros)
@@ -247,8 +250,32 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
 #pragma unroll
             for (int c = 0; c < CPW; ++c) {
                 uint32_t b[8];
+                if (group_log2) {
+                    // Block-wise scaling (a reading of the block-wise variant of Sec. 3.2): a channel group
+                    // whose maximum a satisfies a * 2^e <= row maximum is quantized with the step scale / 2^e
+                    // (e <= emax, the largest such e) and stored as code * 2^(emax - e), so that one token
+                    // scale, scale / 2^emax, dequantizes every group and the GEMM is unchanged.  The lanes of
+                    // a group are those that agree in lane bits 2, 3 (128 channels), bit 2 (256), none (512).
+                    float a = 0.f;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) b[i] = __float_as_uint(fmaf(v[c][i], r, magic));
+                    for (int i = 0; i < 8; ++i) a = fmaxf(a, fabsf(v[c][i]));
+                    a = fmaxf(a, __shfl_xor(a, 1, kWave));
+                    a = fmaxf(a, __shfl_xor(a, 2, kWave));
+                    a = fmaxf(a, __shfl_xor(a, 16, kWave));
+                    a = fmaxf(a, __shfl_xor(a, 32, kWave));
+                    if (group_log2 >= 8) a = fmaxf(a, __shfl_xor(a, 8, kWave));
+                    if (group_log2 >= 9) a = fmaxf(a, __shfl_xor(a, 4, kWave));
+                    int e = 0;
+                    for (int t = 1; t <= emax; ++t)
+                        if (ldexpf(a, t) <= amax) e = t;
+                    const float rg = ldexpf(r, e);
+                    const int sh = emax - e;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) b[i] = __float_as_uint(fmaf(v[c][i], rg, magic)) << sh;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) b[i] = __float_as_uint(fmaf(v[c][i], r, magic));
+                }
                 // low bytes of b[0..3] / b[4..7] -> one dword each
                 uint2 out;
                 out.x = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u),
@@ -281,16 +308,18 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
 
 template <int LOG2B>
 int launch_cpw(int cpw, dim3 grid, dim3 block, size_t smem, hipStream_t stream, const uint16_t *x, int64_t M,
-               int K, int W, int rpw, double scale_mul, float recip_num, int pack4, int8_t *codes,
-               float *x_scale, int32_t *code_rowsum) {
+               int K, int W, int rpw, double scale_mul, float recip_num, int pack4, int group_log2, int emax,
+               int8_t *codes, float *x_scale, int32_t *code_rowsum) {
 #define DVDQ_RQ_CASE(C)                                                                                   \
     case C:                                                                                               \
         if (pack4)                                                                                        \
             hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C, true>), grid, block, smem, stream, x, M, K, \
-                               W, rpw, scale_mul, recip_num, pack4 == 2, codes, x_scale, code_rowsum);    \
+                               W, rpw, scale_mul, recip_num, pack4 == 2, 0, 0, codes, x_scale,            \
+                               code_rowsum);                                                              \
         else                                                                                              \
             hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C, false>), grid, block, smem, stream, x, M,   \
-                               K, W, rpw, scale_mul, recip_num, 0, codes, x_scale, code_rowsum);          \
+                               K, W, rpw, scale_mul, recip_num, 0, group_log2, emax, codes, x_scale,      \
+                               code_rowsum);                                                              \
         break;
     switch (cpw) {
         DVDQ_RQ_CASE(1) DVDQ_RQ_CASE(2) DVDQ_RQ_CASE(3) DVDQ_RQ_CASE(4)
@@ -304,7 +333,8 @@ int launch_cpw(int cpw, dim3 grid, dim3 block, size_t smem, hipStream_t stream, 
 }  // namespace
 
 int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block, int act_bits, int codes_format,
-                        int8_t *codes, float *x_scale, int32_t *code_rowsum, hipStream_t stream) {
+                        int group_log2, int8_t *codes, float *x_scale, int32_t *code_rowsum, hipStream_t stream) {
+    const int emax = group_log2 ? 8 - act_bits : 0;
     const int pack4 = codes_format != DVDQ_CODES_PACKED4 ? 0 : ((K % 32) == 0 ? 2 : 1);
     const int units = (int)((K + kUnit - 1) / kUnit);
     // waves per row: at most 4 units (32 fp32 values per lane) in registers per wave, at most 16 waves
@@ -330,7 +360,7 @@ int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block,
 #define DVDQ_RQ_B(L)                                                                                        \
     case L:                                                                                                 \
         return launch_cpw<L>(cpw, grid, block, smem, stream, x, M, (int)K, W, rows_per_wg, scale_mul,       \
-                             recip_num, pack4, codes, x_scale, code_rowsum);
+                             recip_num, pack4, group_log2, emax, codes, x_scale, code_rowsum);
     switch (log2_block) {
         DVDQ_RQ_B(0) DVDQ_RQ_B(1) DVDQ_RQ_B(2) DVDQ_RQ_B(3) DVDQ_RQ_B(4)
         DVDQ_RQ_B(5) DVDQ_RQ_B(6) DVDQ_RQ_B(7) DVDQ_RQ_B(8) DVDQ_RQ_B(9)

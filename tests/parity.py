@@ -75,3 +75,58 @@ def check_y(y_gpu_bits, y_ref_bits, label=""):
     assert rel.max(initial=0) <= 1e-2, f"{label}: max relative error {rel.max():.3e} > 1e-2"
     assert rel.mean() <= 1e-3, f"{label}: mean relative error {rel.mean():.3e} > 1e-3"
     return dict(max_rel=float(rel.max(initial=0)), mean_rel=float(rel.mean()), ulp1=int((d == 1).sum()))
+
+
+def check_blockwise(values_gpu, scale_gpu, values_ref, scale_ref, exps_ref, xrot_ref, act_bits, group, label=""):
+    """Block-wise scaled quantizer: stored int8 values against the oracle's.
+
+    Bars: handed-on token scales within 2 fp32 ulps.  A group whose stored values differ from the
+    oracle's is either (a) on the oracle's exponent, with code flips judged as in
+    check_codes_and_scales -- the tolerance, one fp32 ulp of the ROW maximum, is 2^e times larger in
+    the code units of a group that is quantized 2^e times finer -- or (b) one exponent off, which is
+    only accepted when the group maximum times a power of two is within 2^-20 of the row maximum
+    (the comparison that chooses the exponent is taken on fp32 butterfly sums by the kernel and on
+    exact values by the oracle); such a group must still be a valid quantization on its own step.
+    Budgets: ceil(1e-5 * elements) code flips, ceil(1e-4 * groups) exponent flips."""
+    qmax = 2 ** (act_bits - 1) - 1
+    emax = 8 - act_bits
+    M, K = values_ref.shape
+    G = K // group
+    d_ulp = ulp_diff_f32(scale_gpu, scale_ref)
+    assert d_ulp.max(initial=0) <= 2, f"{label}: token scale off by {d_ulp.max()} fp32 ulps (bar: 2)"
+    vg = values_gpu.astype(np.int64).reshape(M, G, group)
+    vr = values_ref.astype(np.int64).reshape(M, G, group)
+    xr = xrot_ref.reshape(M, G, group)
+    e = exps_ref.astype(np.int64)
+    s_tok = scale_ref.astype(np.float64) * 2.0 ** emax                  # s_m
+    out = dict(elements=int(values_ref.size), groups=int(M * G), code_flips=0, exp_flips=0, max_boundary_dist_ulps=0.0)
+    differing = np.argwhere(np.any(vg != vr, axis=2))
+    amax_row = np.abs(xrot_ref).max(axis=1)
+    for m, g in differing:
+        sh = emax - e[m, g]
+        same_exp = np.all(vg[m, g] % (1 << sh) == 0) and np.abs(vg[m, g] >> sh).max() <= qmax
+        if same_exp:
+            qg, qr = vg[m, g] >> sh, vr[m, g] >> sh
+            idx = np.nonzero(qg != qr)[0]
+            assert np.all(np.abs(qg[idx] - qr[idx]) == 1), f"{label}: a code differs by more than 1"
+            t = xr[m, g, idx] / (s_tok[m] * 2.0 ** -e[m, g])
+            dist = np.abs(t - (np.minimum(qg[idx], qr[idx]) + 0.5))
+            unit = qmax * 2.0 ** -23 * 2.0 ** e[m, g]
+            assert np.all(dist <= unit * (1.0 + d_ulp[m])), f"{label}: code flip {dist.max() / unit:.3f} ulps from its boundary"
+            out["code_flips"] += int(idx.size)
+            out["max_boundary_dist_ulps"] = max(out["max_boundary_dist_ulps"], float(dist.max() / unit))
+        else:
+            a = np.abs(xr[m, g]).max()
+            near = min(abs(a * 2.0 ** t / amax_row[m] - 1.0) for t in (e[m, g], e[m, g] + 1))
+            assert near <= 2.0 ** -20, f"{label}: group ({m},{g}) is on another exponent away from a boundary ({near:.3e})"
+            ok = False
+            for e_alt in (e[m, g] - 1, e[m, g] + 1):
+                if 0 <= e_alt <= emax and np.all(vg[m, g] % (1 << (emax - e_alt)) == 0):
+                    step = s_tok[m] * 2.0 ** -e_alt
+                    q = vg[m, g] >> (emax - e_alt)
+                    ok = ok or (np.abs(q).max() <= qmax and np.all(np.abs(xr[m, g] - q * step) <= step / 2 * (1 + 1e-5)))
+            assert ok, f"{label}: group ({m},{g}) is not a valid quantization on a neighbouring exponent"
+            out["exp_flips"] += 1
+    assert out["code_flips"] <= math.ceil(1e-5 * values_ref.size), f"{label}: {out['code_flips']} code flips"
+    assert out["exp_flips"] <= math.ceil(1e-4 * M * G), f"{label}: {out['exp_flips']} exponent flips"
+    return out

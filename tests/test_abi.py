@@ -52,6 +52,15 @@ def test_rotate_quant_argument_errors():
     assert f(FAKE, 4, 256, 256, 4, 2, FAKE, FAKE, None, None) == 3       # unknown container
 
 
+def test_rotate_quant_blockwise_argument_errors():
+    f = dvdq.lib().dvdq_rotate_quant_blockwise
+    assert f(None, 4, 1536, 256, 4, 128, FAKE, FAKE, None, None) == 1
+    assert f(FAKE, 4, 1536, 256, 4, 1024, FAKE, FAKE, None, None) == 2     # group does not divide K
+    assert f(FAKE, 4, 1536, 256, 4, 64, FAKE, FAKE, None, None) == 3       # group size not built
+    assert f(FAKE, 4, 1536, 256, 8, 128, FAKE, FAKE, None, None) == 3      # no headroom for 8-bit codes
+    assert f(FAKE, 4, 1536, 256, 4, 128, ODD, FAKE, None, None) == 5
+
+
 def test_gemm_argument_errors():
     f = dvdq.lib().dvdq_w4ax_gemm
     ok = dict(M=4, N=8, K=64)
