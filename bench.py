@@ -30,6 +30,9 @@ HBM_PEAK_GBPS = 8000.0           # published HBM3E bandwidth, MI355X
 # commands are profiles/bench_<workload>_hbm_counters.md.  None where no counter run exists.
 MEASURED_HBM_TRAFFIC = {
     "small_dit_qkv_w4a4": {"w4ax_gemm": 562.6e6, "rotate_quant": 126.2e6},
+    "small_dit_ffn_up_w4a6": {"w4ax_gemm": 1293.6e6, "rotate_quant": 151.3e6},
+    "large_dit_proj_w4a4": {"w4ax_gemm": 2273.9e6, "rotate_quant": 914.5e6},
+    "large_dit_ffn_down_w4a4": {"w4ax_gemm": 3590.6e6, "rotate_quant": 1133.4e6},
 }
 
 
