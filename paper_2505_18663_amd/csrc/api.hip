@@ -207,6 +207,6 @@ const char *dvdq_status_string(int status) {
     }
 }
 
-int dvdq_version(void) { return 100; }
+int dvdq_version(void) { return 200; }
 
 }  // extern "C"

@@ -2,9 +2,12 @@
 // transform; s = ||x~||_inf / qmax per token row; codes = round-half-even(x~ / s)).
 //
 // One pass over HBM: a token row is read once (bf16), kept in registers while the
-// transform, the row abs-max and the quantizer run, and written once (int8 codes +
-// one fp32 scale).  The kernel is bound by HBM only if the transform is cheap in
-// VALU instructions, so the 9 butterfly stages of a 512-channel unit are split:
+// transform, the row abs-max and the quantizer run, and written once (int8 codes, or
+// 4-bit codes packed two per byte, one fp32 scale, optionally the row's code sum for
+// weights with zero-points).  A block-wise scaled mode gives every channel group its own
+// power-of-two fraction of the token's step and folds it into the int8 value (see the
+// quantizer section of the kernel).  The kernel is bound by HBM only if the transform is
+// cheap in VALU instructions, so the 9 butterfly stages of a 512-channel unit are split:
 //
 //   * channel-index bits 0..4 (strides 1..16) go through the matrix cores: the lane's
 //     8 raw bf16 values are the B operand of two 16x16x32 bf16 MFMAs whose A operand
@@ -12,9 +15,10 @@
 //     products are exact and the sums are accumulated in fp32.  No bf16 -> fp32
 //     unpacking is needed and the result lands in the same lane, same order.
 //   * bits 5..8 (strides 32..256) are butterflies between lanes, on fp32 values, with
-//     DPP row operations (one fused multiply-add with a DPP operand per value).  The 16-byte chunks of a unit are dealt to lanes so that
-//     bits 5, 6, 7 pair lanes l ^ 1, l ^ 2, l ^ 8 (single DPP operations) and bit 8,
-//     which only 512-blocks transform, pairs l ^ 4 (two masked row shifts).
+//     DPP row operations (one fused multiply-add with a DPP operand per value).  The
+//     16-byte chunks of a unit are dealt to lanes so that bits 5, 6, 7 pair lanes l ^ 1,
+//     l ^ 2, l ^ 8 (single DPP operations) and bit 8, which only 512-blocks transform,
+//     pairs l ^ 4 (two masked row shifts).
 //
 // Chunk c (16 bytes = 8 channels) of a unit belongs to lane
 //   l = (c & 3) << 4 | (c >> 2 & 1) | (c >> 3 & 1) << 1 | (c >> 5 & 1) << 2 | (c >> 4 & 1) << 3,

@@ -108,7 +108,7 @@ def test_gemm_packed_codes_int32_exact(M, N, K, use_bias, variant):
     assert torch.equal(y8, y), "the container must not change the outputs"
 
 
-@pytest.mark.parametrize("idx", [0, 1, 4])
+@pytest.mark.parametrize("idx", [0, 1, 3, 4])
 def test_qlinear_with_packed_codes_matches_the_int8_container(idx):
     wl = di.WORKLOADS[idx]
     M, K, N, B = wl.M, wl.K, wl.N, wl.had_block
