@@ -24,6 +24,8 @@
 // the MFMA's row operand and the code fragment its column operand, so a lane holds
 // 4 consecutive output channels of one token; lane halves are exchanged
 // (v_permlane32_swap) so that every lane stores 16 contiguous bytes of bf16.
+#include <type_traits>
+
 #include "dvdq_internal.h"
 
 namespace dvdq {
@@ -378,76 +380,91 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
         constexpr float kUnwiden = 1.f / (float)(1 << SHIFT);  // the factor 16 of the widened weights (and codes)
         const uint8_t *s_tile = smem + STAGES * STAGE + ((tile_j - 1) & 1) * SCALES;
         const int32_t *s_rsum = reinterpret_cast<const int32_t *>(s_tile + OFF_RSUM);
-        // accumulator of channel zero-point z and token code sum rs: sum q (c - z) = acc - z * rs (times 2^SHIFT)
-        auto unzero = [] __device__(int a, int z, int rs) { return a - __mul24(z, rs) * (1 << SHIFT); };
+        // accumulator of channel zero-point z and token code sum rs: sum q (c - z) = acc - z * rs, all times
+        // 2^SHIFT.  zs = z << SHIFT and rs fit 24 bits and the product fits 32 (checked by the C ABI), so the
+        // 24-bit multiply is exact.
+        auto unzero = [] __device__(int a, int zs, int rs) { return a - __mul24(zs, rs); };
         if (vec8 && !acc_out && m0 + BM <= M && n0 + BN <= N) {
             // ---- interior tile: no predicates, every vector the epilogue needs comes from LDS up front,
             // one row pointer per lane.  Every lane of every wave stores all its values, so the number of
             // stores is exact (see the store-aware wait above).
             if (KT >= STAGES) store_credit = STAGES - 1 - AHEAD;
-            const float *ws_l = s_ws + wn + fhalf * 4;
-            const uint32_t *bias_l = reinterpret_cast<const uint32_t *>(s_tile + OFF_BIAS) + (wn + fhalf * 4) / 2;
-            const uint32_t *zero_l = reinterpret_cast<const uint32_t *>(s_tile + OFF_ZERO) + (wn + fhalf * 4) / 4;
-            float xs16[TM];
+            // Two specializations, with and without weight zero-points, chosen once per tile: inside the
+            // unrolled loops a run-time test of the pointer would cost a branch per element.
+            auto interior = [&] __device__(auto has_zero) __attribute__((always_inline)) {
+                constexpr bool ZP = decltype(has_zero)::value;
+                const float *ws_l = s_ws + wn + fhalf * 4;
+                const uint32_t *bias_l = reinterpret_cast<const uint32_t *>(s_tile + OFF_BIAS) + (wn + fhalf * 4) / 2;
+                const uint32_t *zero_l = reinterpret_cast<const uint32_t *>(s_tile + OFF_ZERO) + (wn + fhalf * 4) / 4;
+                float xs16[TM];
+                int rsum[TM];
 #pragma unroll
-            for (int j = 0; j < TM; ++j) xs16[j] = s_xs[wm + j * 32 + frow] * kUnwiden;
-            uint16_t *yrow = y + (int64_t)(m0 + wm + frow) * N + (n0 + wn + fhalf * 8);
+                for (int j = 0; j < TM; ++j) {
+                    xs16[j] = s_xs[wm + j * 32 + frow] * kUnwiden;
+                    rsum[j] = ZP ? s_rsum[wm + j * 32 + frow] : 0;
+                }
+                uint16_t *yrow = y + (int64_t)(m0 + wm + frow) * N + (n0 + wn + fhalf * 8);
 #pragma unroll
-            for (int i = 0; i < TN; ++i) {
-                // two of the MFMA tile's four 8-channel groups at a time (bounds the live registers)
+                for (int i = 0; i < TN; ++i) {
+                    // two of the MFMA tile's four 8-channel groups at a time (bounds the live registers)
 #pragma unroll
-                for (int g = 0; g < 4; g += 2) {
-                    float4 wsv[2];
-                    uint2 bb[2];
-                    uint32_t zq[2];
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        wsv[h] = *reinterpret_cast<const float4 *>(ws_l + i * 32 + (g + h) * 8);
-                        if (bias) bb[h] = *reinterpret_cast<const uint2 *>(bias_l + (i * 32 + (g + h) * 8) / 2);
-                        if (w_zero) zq[h] = zero_l[(i * 32 + (g + h) * 8) / 4];
-                    }
-#pragma unroll
-                    for (int j = 0; j < TM; ++j) {
-                        uint32_t pk[2][2];
-                        const int rsum = w_zero ? s_rsum[wm + j * 32 + frow] : 0;
+                    for (int g = 0; g < 4; g += 2) {
+                        float4 wsv[2];
+                        uint2 bb[2];
+                        int zv[2][4];
 #pragma unroll
                         for (int h = 0; h < 2; ++h) {
-                            const int r = (g + h) * 4;
-                            int a[4];
+                            wsv[h] = *reinterpret_cast<const float4 *>(ws_l + i * 32 + (g + h) * 8);
+                            if (bias) bb[h] = *reinterpret_cast<const uint2 *>(bias_l + (i * 32 + (g + h) * 8) / 2);
+                            if constexpr (ZP) {
+                                const uint32_t zq = zero_l[(i * 32 + (g + h) * 8) / 4];
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                a[e] = acc[i][j][r + e];
-                                if (w_zero) a[e] = unzero(a[e], (int)(int8_t)(zq[h] >> (8 * e)), rsum);
+                                for (int e = 0; e < 4; ++e) zv[h][e] = (int)(int8_t)(zq >> (8 * e)) * (1 << SHIFT);
                             }
-                            float o[4];
-                            o[0] = (float)a[0] * xs16[j] * wsv[h].x;
-                            o[1] = (float)a[1] * xs16[j] * wsv[h].y;
-                            o[2] = (float)a[2] * xs16[j] * wsv[h].z;
-                            o[3] = (float)a[3] * xs16[j] * wsv[h].w;
-                            if (bias) {
-                                o[0] += __uint_as_float(bb[h].x << 16);
-                                o[1] += __uint_as_float(bb[h].x & 0xFFFF0000u);
-                                o[2] += __uint_as_float(bb[h].y << 16);
-                                o[3] += __uint_as_float(bb[h].y & 0xFFFF0000u);
+                        }
+#pragma unroll
+                        for (int j = 0; j < TM; ++j) {
+                            uint32_t pk[2][2];
+#pragma unroll
+                            for (int h = 0; h < 2; ++h) {
+                                const int r = (g + h) * 4;
+                                float o[4];
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) {
+                                    int a = acc[i][j][r + e];
+                                    if constexpr (ZP) a = unzero(a, zv[h][e], rsum[j]);
+                                    o[e] = (float)a * xs16[j];
+                                    acc[i][j][r + e] = 0;
+                                }
+                                o[0] *= wsv[h].x;
+                                o[1] *= wsv[h].y;
+                                o[2] *= wsv[h].z;
+                                o[3] *= wsv[h].w;
+                                if (bias) {
+                                    o[0] += __uint_as_float(bb[h].x << 16);
+                                    o[1] += __uint_as_float(bb[h].x & 0xFFFF0000u);
+                                    o[2] += __uint_as_float(bb[h].y << 16);
+                                    o[3] += __uint_as_float(bb[h].y & 0xFFFF0000u);
+                                }
+                                pk[h][0] = pack_bf16x2(o[0], o[1]);
+                                pk[h][1] = pack_bf16x2(o[2], o[3]);
                             }
-                            pk[h][0] = pack_bf16x2(o[0], o[1]);
-                            pk[h][1] = pack_bf16x2(o[2], o[3]);
+                            // lanes l and l+32 hold channels (8g .. 8g+3) and (8g+4 .. 8g+7): swap the upper half
+                            // of group g with the lower half of group g+1 so each lane owns 8 consecutive channels
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) acc[i][j][r + e] = 0;
+                            for (int d = 0; d < 2; ++d) {
+                                auto sw = __builtin_amdgcn_permlane32_swap(pk[0][d], pk[1][d], false, false);
+                                pk[0][d] = sw[0];
+                                pk[1][d] = sw[1];
+                            }
+                            *reinterpret_cast<uint4 *>(yrow + (int64_t)j * 32 * N + i * 32 + g * 8) =
+                                make_uint4(pk[0][0], pk[0][1], pk[1][0], pk[1][1]);
                         }
-                        // lanes l and l+32 hold channels (8g .. 8g+3) and (8g+4 .. 8g+7): swap the upper half
-                        // of group g with the lower half of group g+1 so each lane owns 8 consecutive channels
-#pragma unroll
-                        for (int d = 0; d < 2; ++d) {
-                            auto sw = __builtin_amdgcn_permlane32_swap(pk[0][d], pk[1][d], false, false);
-                            pk[0][d] = sw[0];
-                            pk[1][d] = sw[1];
-                        }
-                        *reinterpret_cast<uint4 *>(yrow + (int64_t)j * 32 * N + i * 32 + g * 8) =
-                            make_uint4(pk[0][0], pk[0][1], pk[1][0], pk[1][1]);
                     }
                 }
-            }
+            };
+            if (w_zero) interior(std::true_type{});
+            else interior(std::false_type{});
             continue;
         }
         // ---- edge tiles, N not a multiple of 8, or the accumulator hook: predicated per element
@@ -466,7 +483,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             const int n = nb + g * 8 + fhalf * 4 + e;
-                            if (n < N) acc[i][j][g * 4 + e] = unzero(acc[i][j][g * 4 + e], (int)w_zero[n], rs);
+                            if (n < N) acc[i][j][g * 4 + e] = unzero(acc[i][j][g * 4 + e], (int)w_zero[n] * (1 << SHIFT), rs);
                         }
                 }
                 if (acc_out && m_ok) {
