@@ -162,6 +162,17 @@ def test_gemm_extreme_codes_and_one_hot_weights():
         _, acc = dvdq.w4ax_gemm(dev(codes), dev(ones_m), w_dev, dev(ones_n), 8, lay, want_acc=True)
         acc = acc.cpu().numpy()
         assert np.all(acc[:, 0::2] == -8 * 127 * K) and np.all(acc[:, 1::2] == 7 * 127 * K)
+    # the longest contraction the accumulator bound admits for 8-bit codes (16 * 127 * 8 * K < 2^31)
+    M, N, K = 40, 72, 131072
+    codes = np.full((M, K), 127, dtype=np.int8)
+    codes[1::2] = -127
+    wc = np.full((N, K), -8, dtype=np.int8)
+    wc[1::2] = 7
+    w_dev = dvdq.w4_prepack(dev(di.pack_w4(wc)))
+    _, acc = dvdq.w4ax_gemm(dev(codes), dev(np.ones(M, np.float32)), w_dev, dev(np.ones(N, np.float32)), 8, dvdq.W_NATIVE,
+                            want_acc=True)
+    expect = np.outer(np.where(np.arange(M) % 2 == 0, 127, -127), np.where(np.arange(N) % 2 == 0, -8, 7)).astype(np.int64) * K
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64), expect)
     rng = np.random.default_rng(3)
     K = 256
     q = rng.integers(-31, 32, size=(40, K)).astype(np.int8)
