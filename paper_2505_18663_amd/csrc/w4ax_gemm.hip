@@ -333,6 +333,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
             __builtin_amdgcn_s_barrier();
         }
         issue_prepare((q + STAGES - 1) % STAGES);
+        // A wave feeding the matrix cores outranks one that converts and stores a finished tile (the
+        // two workgroups of a compute unit are in different phases most of the time).
+        if (kt == 0) __builtin_amdgcn_s_setprio(2);
 
         // Software pipeline over the K=32 steps of the item: the fragments of step s+1 (or of
         // step 0 of the next item) are requested before the MFMAs of step s are issued, and the
@@ -367,6 +370,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
         }
         issue_advance();
         if (++kt < KT) continue;
+        __builtin_amdgcn_s_setprio(0);   // the epilogue yields issue slots to the other workgroup's K loop
 
         // ---- epilogue of tile tile_j.  Accumulator register r = 4 g + e of MFMA tile (i, j) in lane l is
         //   n = n0 + wn + 32 i + 8 g + 4 (l / 32) + e,   m = m0 + wm + 32 j + (l % 32),  value 16 * acc.
