@@ -47,6 +47,16 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
     return __builtin_bit_cast(uint32_t, p);
 }
 
+// 16-byte store of output the kernel never reads again.  Non-temporal: with whole 128-byte lines
+// per instruction (the staged epilogue) the output stream then bypasses the L2 instead of evicting
+// code and weight panels and leaving dirty lines to flush at the kernel's end.  (For partial-line
+// stores the same hint is much slower than write-back caching.)
+__device__ __forceinline__ void store_streaming16(uint16_t *p, uint4 v) {
+    typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+    const v4u vv = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(vv, reinterpret_cast<v4u *>(p));
+}
+
 // vmcnt-only wait (leave expcnt / lgkmcnt alone): gfx9 encoding, vmcnt = {imm[15:14], imm[3:0]}
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -147,6 +157,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     static_assert(A_DMA >= 1 && W_DMA >= 1 && A_DMA * 1024 * NW == A_STAGE && W_DMA * 1024 * NW == W_STAGE,
                   "tile does not split over the waves");
     static_assert(STAGES >= 2 && (STAGES - 1) * DMA < 64, "too many loads in flight for vmcnt");
+    static_assert(NW * 4096 <= STAGE && TN % 2 == 0, "the epilogue stages 4 KB per wave in one ring buffer");
 
     extern __shared__ __align__(16) uint8_t smem[];
     const uint32_t smem_base = lds_address(smem);
@@ -407,66 +418,90 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
                     xs16[j] = s_xs[wm + j * 32 + frow] * kUnwiden;
                     rsum[j] = ZP ? s_rsum[wm + j * 32 + frow] : 0;
                 }
-                uint16_t *yrow = y + (int64_t)(m0 + wm + frow) * N + (n0 + wn + fhalf * 8);
+                // The bf16 tile goes through LDS so that every store instruction writes whole 128-byte lines:
+                // in the accumulator layout a lane owns one token and 8 consecutive channels per register
+                // group, so a direct store touches 32 token rows with 32 bytes each.  32 tokens x 64 channels
+                // at a time are staged (16-byte pieces, piece index xor-ed with the row against bank
+                // conflicts) and read back with 8 lanes per token row.  The space is this wave's 4 KB of the
+                // ring buffer whose slice was consumed last: after the barrier no wave reads it any more, and
+                // the next loads into it are only issued after the next K loop's first barrier.
+                uint8_t *stg = smem + (q % STAGES) * STAGE + wave * 4096;
+                const int rd_row = lane >> 3, rd_piece = lane & 7;
 #pragma unroll
-                for (int i = 0; i < TN; ++i) {
-                    // two of the MFMA tile's four 8-channel groups at a time (bounds the live registers)
+                for (int j = 0; j < TM; ++j) {
 #pragma unroll
-                    for (int g = 0; g < 4; g += 2) {
-                        float4 wsv[2];
-                        uint2 bb[2];
-                        int zv[2][4];
+                    for (int ip = 0; ip < TN / 2; ++ip) {
 #pragma unroll
-                        for (int h = 0; h < 2; ++h) {
-                            wsv[h] = *reinterpret_cast<const float4 *>(ws_l + i * 32 + (g + h) * 8);
-                            if (bias) bb[h] = *reinterpret_cast<const uint2 *>(bias_l + (i * 32 + (g + h) * 8) / 2);
-                            if constexpr (ZP) {
-                                const uint32_t zq = zero_l[(i * 32 + (g + h) * 8) / 4];
+                        for (int ii = 0; ii < 2; ++ii) {
+                            const int i = 2 * ip + ii;
 #pragma unroll
-                                for (int e = 0; e < 4; ++e) zv[h][e] = (int)(int8_t)(zq >> (8 * e)) * (1 << SHIFT);
+                            for (int g = 0; g < 4; g += 2) {
+                                float4 wsv[2];
+                                uint2 bb[2];
+                                int zv[2][4];
+#pragma unroll
+                                for (int h = 0; h < 2; ++h) {
+                                    wsv[h] = *reinterpret_cast<const float4 *>(ws_l + i * 32 + (g + h) * 8);
+                                    if (bias) bb[h] = *reinterpret_cast<const uint2 *>(bias_l + (i * 32 + (g + h) * 8) / 2);
+                                    if constexpr (ZP) {
+                                        const uint32_t zq = zero_l[(i * 32 + (g + h) * 8) / 4];
+#pragma unroll
+                                        for (int e = 0; e < 4; ++e) zv[h][e] = (int)(int8_t)(zq >> (8 * e)) * (1 << SHIFT);
+                                    }
+                                }
+                                uint32_t pk[2][2];
+#pragma unroll
+                                for (int h = 0; h < 2; ++h) {
+                                    const int r = (g + h) * 4;
+                                    float o[4];
+#pragma unroll
+                                    for (int e = 0; e < 4; ++e) {
+                                        int a = acc[i][j][r + e];
+                                        if constexpr (ZP) a = unzero(a, zv[h][e], rsum[j]);
+                                        o[e] = (float)a * xs16[j];
+                                        acc[i][j][r + e] = 0;
+                                    }
+                                    o[0] *= wsv[h].x;
+                                    o[1] *= wsv[h].y;
+                                    o[2] *= wsv[h].z;
+                                    o[3] *= wsv[h].w;
+                                    if (bias) {
+                                        o[0] += __uint_as_float(bb[h].x << 16);
+                                        o[1] += __uint_as_float(bb[h].x & 0xFFFF0000u);
+                                        o[2] += __uint_as_float(bb[h].y << 16);
+                                        o[3] += __uint_as_float(bb[h].y & 0xFFFF0000u);
+                                    }
+                                    pk[h][0] = pack_bf16x2(o[0], o[1]);
+                                    pk[h][1] = pack_bf16x2(o[2], o[3]);
+                                }
+                                // lanes l and l+32 hold channels (8g .. 8g+3) and (8g+4 .. 8g+7): swap the upper half
+                                // of group g with the lower half of group g+1 so each lane owns 8 consecutive channels
+#pragma unroll
+                                for (int d = 0; d < 2; ++d) {
+                                    auto sw = __builtin_amdgcn_permlane32_swap(pk[0][d], pk[1][d], false, false);
+                                    pk[0][d] = sw[0];
+                                    pk[1][d] = sw[1];
+                                }
+                                const int piece = ii * 4 + g + fhalf;   // 16-byte piece of the 64-channel row
+                                *reinterpret_cast<uint4 *>(stg + frow * 128 + ((piece ^ (frow & 7)) << 4)) =
+                                    make_uint4(pk[0][0], pk[0][1], pk[1][0], pk[1][1]);
                             }
                         }
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                        uint16_t *yb = y + (int64_t)(m0 + wm + j * 32 + rd_row) * N + (n0 + wn + ip * 64 + rd_piece * 8);
 #pragma unroll
-                        for (int j = 0; j < TM; ++j) {
-                            uint32_t pk[2][2];
-#pragma unroll
-                            for (int h = 0; h < 2; ++h) {
-                                const int r = (g + h) * 4;
-                                float o[4];
-#pragma unroll
-                                for (int e = 0; e < 4; ++e) {
-                                    int a = acc[i][j][r + e];
-                                    if constexpr (ZP) a = unzero(a, zv[h][e], rsum[j]);
-                                    o[e] = (float)a * xs16[j];
-                                    acc[i][j][r + e] = 0;
-                                }
-                                o[0] *= wsv[h].x;
-                                o[1] *= wsv[h].y;
-                                o[2] *= wsv[h].z;
-                                o[3] *= wsv[h].w;
-                                if (bias) {
-                                    o[0] += __uint_as_float(bb[h].x << 16);
-                                    o[1] += __uint_as_float(bb[h].x & 0xFFFF0000u);
-                                    o[2] += __uint_as_float(bb[h].y << 16);
-                                    o[3] += __uint_as_float(bb[h].y & 0xFFFF0000u);
-                                }
-                                pk[h][0] = pack_bf16x2(o[0], o[1]);
-                                pk[h][1] = pack_bf16x2(o[2], o[3]);
-                            }
-                            // lanes l and l+32 hold channels (8g .. 8g+3) and (8g+4 .. 8g+7): swap the upper half
-                            // of group g with the lower half of group g+1 so each lane owns 8 consecutive channels
-#pragma unroll
-                            for (int d = 0; d < 2; ++d) {
-                                auto sw = __builtin_amdgcn_permlane32_swap(pk[0][d], pk[1][d], false, false);
-                                pk[0][d] = sw[0];
-                                pk[1][d] = sw[1];
-                            }
-                            *reinterpret_cast<uint4 *>(yrow + (int64_t)j * 32 * N + i * 32 + g * 8) =
-                                make_uint4(pk[0][0], pk[0][1], pk[1][0], pk[1][1]);
+                        for (int pass = 0; pass < 4; ++pass) {
+                            const int row = pass * 8 + rd_row;
+                            const uint4 v = *reinterpret_cast<const uint4 *>(stg + row * 128 + ((rd_piece ^ (row & 7)) << 4));
+                            store_streaming16(yb + (int64_t)pass * 8 * N, v);
                         }
+                        __builtin_amdgcn_wave_barrier();   // the next chunk's LDS writes stay behind these reads
                     }
                 }
             };
+            __builtin_amdgcn_s_barrier();   // every wave is done reading the last slice: its buffer stages the tile
             if (w_zero) interior(std::true_type{});
             else interior(std::false_type{});
             continue;
