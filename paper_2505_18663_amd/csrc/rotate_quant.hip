@@ -142,7 +142,13 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
             raw[c] = make_uint4(0, 0, 0, 0);
-            if (row < M && k0[c] < K) raw[c] = *reinterpret_cast<const uint4 *>(x + row * K + k0[c]);
+            if (row < M && k0[c] < K) {
+                // X is read exactly once: a streaming load keeps it from displacing the codes this kernel
+                // writes (and the weights) from the caches the GEMM is about to read them from
+                typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+                const v4u t = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(x + row * K + k0[c]));
+                raw[c] = make_uint4(t[0], t[1], t[2], t[3]);
+            }
         }
     };
 
