@@ -10,7 +10,11 @@ Bars (stated in the tests that call these):
     ceil(1e-5 * elements) of them.
   * token scales: within 2 fp32 ulps.
   * bf16 outputs on identical accumulators and scales: within 1 bf16 ulp
-    everywhere, max relative error <= 1e-2, mean relative error <= 1e-3.
+    everywhere, max relative error <= 1e-2, mean relative error <= 1e-3.  With a
+    bias the kernel's fp32 product (three roundings, relative 2^-22 at most) is
+    added to a number of similar size; where the two nearly cancel the result's
+    own ulp shrinks below that error, so there the bar is absolute:
+    |y - y_ref| <= 2^-21 * |bias|.
 """
 import math
 
@@ -64,12 +68,18 @@ def bf16_ulp_distance(a_bits, b_bits):
     return np.abs(key(a_bits) - key(b_bits))
 
 
-def check_y(y_gpu_bits, y_ref_bits, label=""):
-    """bf16 outputs computed from identical accumulators and scales."""
+def check_y(y_gpu_bits, y_ref_bits, label="", bias_bits=None):
+    """bf16 outputs computed from identical accumulators and scales (bias_bits: the layer's bias, if any)."""
     d = bf16_ulp_distance(y_gpu_bits, y_ref_bits)
-    assert d.max(initial=0) <= 1, f"{label}: output differs by {d.max()} bf16 ulps (bar: 1)"
     yg = di.bf16_bits_to_f32(y_gpu_bits).astype(np.float64)
     yr = di.bf16_bits_to_f32(y_ref_bits).astype(np.float64)
+    far = d > 1
+    if bias_bits is not None and far.any():
+        b = np.abs(di.bf16_bits_to_f32(bias_bits).astype(np.float64))[None, :]
+        cancel = np.abs(yg - yr) <= 2.0 ** -21 * np.broadcast_to(b, yr.shape)
+        assert int((far & cancel).sum()) <= max(4, int(1e-4 * d.size)), f"{label}: too many cancellation cases"
+        far = far & ~cancel
+    assert not far.any(), f"{label}: output differs by {d[far].max()} bf16 ulps (bar: 1)"
     rho = np.sqrt((yr ** 2).mean(axis=1, keepdims=True))              # floor for outputs near zero
     rel = np.abs(yg - yr) / np.maximum(np.abs(yr), np.maximum(rho, 1e-30))
     assert rel.max(initial=0) <= 1e-2, f"{label}: max relative error {rel.max():.3e} > 1e-2"

@@ -102,7 +102,7 @@ def test_gemm_packed_codes_int32_exact(M, N, K, use_bias, variant):
         dvdq.bench_set_gemm_variant(-1)
     y_ref, acc_ref = oracle.w4ax_gemm(codes, xs, wp, ws, bias, return_acc=True)
     assert np.array_equal(acc.cpu().numpy().astype(np.int64), acc_ref), "int32 accumulators must be bit-exact"
-    check_y(bits_of(y), y_ref, f"packed gemm M{M} N{N} K{K} v{variant}")
+    check_y(bits_of(y), y_ref, f"packed gemm M{M} N{N} K{K} v{variant}", bias)
     assert torch.equal(y2, y)
     y8 = dvdq.w4ax_gemm(dev(codes), dev(xs), w_native, dev(ws), 4, dvdq.W_NATIVE, bias=bias_dev)
     assert torch.equal(y8, y), "the container must not change the outputs"

@@ -140,7 +140,7 @@ def test_gemm_int32_exact_and_bf16_epilogue(M, N, K, bits, layout, use_bias):
     torch.cuda.synchronize()
     y_ref, acc_ref = oracle.w4ax_gemm(codes, xs, wp, ws, bias, return_acc=True)
     assert np.array_equal(acc.cpu().numpy().astype(np.int64), acc_ref), "int32 accumulators must be bit-exact"
-    stats = check_y(bits_of(y), y_ref, f"gemm M{M} N{N} K{K}")
+    stats = check_y(bits_of(y), y_ref, f"gemm M{M} N{N} K{K}", bias)
     # without the parity hook the outputs are the same
     y2 = dvdq.w4ax_gemm(dev(codes), dev(xs), w_dev, dev(ws), bits, lay, bias=None if bias is None else to_bf16(bias))
     assert torch.equal(y2, y)

@@ -84,7 +84,7 @@ def test_gemm_with_weight_zero_points(M, N, K, bits, packed, use_bias):
     torch.cuda.synchronize()
     y_ref, acc_ref = oracle.w4ax_gemm_zp(codes, xs, wp, ws, wz, bias, return_acc=True)
     assert np.array_equal(acc.cpu().numpy().astype(np.int64), acc_ref), "zero-point-corrected accumulators must be exact"
-    check_y(bits_of(y), y_ref, f"zp gemm M{M} N{N} K{K}")
+    check_y(bits_of(y), y_ref, f"zp gemm M{M} N{N} K{K}", bias)
     assert torch.equal(y2, y)
     # zero zero-points reproduce the symmetric path bit for bit
     y0 = dvdq.w4ax_gemm(codes_dev, dev(xs), w_native, dev(ws), bits, dvdq.W_NATIVE, bias=bias_dev, codes_format=fmt,
