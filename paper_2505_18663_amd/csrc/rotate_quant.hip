@@ -107,7 +107,8 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
     uint32_t *s_pack = reinterpret_cast<uint32_t *>(s_amax) + (4 * rows_per_wg * waves_per_row + 3) / 4 * 4;
     constexpr int MASK5 = LOG2B >= 5 ? 31 : ((1 << LOG2B) - 1);
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
+    // (provably wave-uniform, so that row numbers and row base addresses live in scalar registers)
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int row_in_wg = wave / waves_per_row;
     const int wsub = wave - row_in_wg * waves_per_row;
     // this lane's 16-byte chunk within a unit
