@@ -29,10 +29,10 @@ HBM_PEAK_GBPS = 8000.0           # published HBM3E bandwidth, MI355X
 # very command, scaled by the same counters' reading for dvdq_bench_copy; the summaries with the
 # commands are profiles/bench_<workload>_hbm_counters.md.  None where no counter run exists.
 MEASURED_HBM_TRAFFIC = {
-    "small_dit_qkv_w4a4": {"w4ax_gemm": 391.4e6, "rotate_quant": 126.1e6},
-    "small_dit_ffn_up_w4a6": {"w4ax_gemm": 949.8e6, "rotate_quant": 151.3e6},
-    "large_dit_proj_w4a4": {"w4ax_gemm": 2055.3e6, "rotate_quant": 914.5e6},
-    "large_dit_ffn_down_w4a4": {"w4ax_gemm": 3552.0e6, "rotate_quant": 1133.4e6},
+    "small_dit_qkv_w4a4": {"w4ax_gemm": 391.6e6, "rotate_quant": 126.2e6},
+    "small_dit_ffn_up_w4a6": {"w4ax_gemm": 950.6e6, "rotate_quant": 151.3e6},
+    "large_dit_proj_w4a4": {"w4ax_gemm": 2060.0e6, "rotate_quant": 914.4e6},
+    "large_dit_ffn_down_w4a4": {"w4ax_gemm": 3546.7e6, "rotate_quant": 1133.3e6},
 }
 
 
