@@ -34,6 +34,12 @@ int dvdq_bench_mfma_i8(int iters, int32_t *sink, double *ops_out, void *hip_stre
  * not thread-safe, meant for benchmarking only. */
 int dvdq_bench_set_gemm_variant(int variant);
 
+/* How the native-layout GEMM's persistent workgroups get their tiles: 0 = fixed equal shares,
+ * -1 = the library's own choice (tiles drawn from per-stream counters, fixed shares while a
+ * stream is being captured).  Results are identical either way.  Process-wide, not
+ * thread-safe, meant for benchmarking only. */
+int dvdq_bench_set_gemm_schedule(int schedule);
+
 #ifdef __cplusplus
 }
 #endif

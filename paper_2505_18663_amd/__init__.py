@@ -16,7 +16,7 @@ import torch
 __all__ = [
     "DvdqError", "DvdqLibraryMissing", "lib", "library_path", "version", "status_string",
     "rotate_quant", "rotate_quant_blockwise", "w4ax_gemm", "qlinear", "qlinear_workspace_bytes", "qlinear_scale_offset", "qlinear_rowsum_offset", "workspace_rowsum",
-    "w4_prepack", "w4_native_bytes", "bgr_quantize", "GbsController", "bench_copy", "bench_mfma_i8", "bench_set_gemm_variant",
+    "w4_prepack", "w4_native_bytes", "bgr_quantize", "GbsController", "bench_copy", "bench_mfma_i8", "bench_set_gemm_variant", "bench_set_gemm_schedule",
     "W_CANONICAL", "W_NATIVE", "CODES_INT8", "CODES_PACKED4", "EXPORTED_SYMBOLS",
 ]
 
@@ -26,7 +26,7 @@ CODES_INT8, CODES_PACKED4 = 0, 1
 EXPORTED_SYMBOLS = (
     "dvdq_rotate_quant", "dvdq_rotate_quant_blockwise", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_qlinear_workspace_bytes",
     "dvdq_qlinear_scale_offset", "dvdq_qlinear_rowsum_offset", "dvdq_w4_prepack", "dvdq_w4_native_bytes", "dvdq_status_string",
-    "dvdq_version", "dvdq_gbs_workspace_bytes", "dvdq_gbs_reset", "dvdq_gbs_step", "dvdq_bgr_quantize", "dvdq_bench_copy", "dvdq_bench_mfma_i8", "dvdq_bench_set_gemm_variant",
+    "dvdq_version", "dvdq_gbs_workspace_bytes", "dvdq_gbs_reset", "dvdq_gbs_step", "dvdq_bgr_quantize", "dvdq_bench_copy", "dvdq_bench_mfma_i8", "dvdq_bench_set_gemm_variant", "dvdq_bench_set_gemm_schedule",
 )
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -83,6 +83,8 @@ def lib() -> C.CDLL:
     L.dvdq_bench_mfma_i8.argtypes = [i32, vp, C.POINTER(C.c_double), vp]
     L.dvdq_bench_set_gemm_variant.argtypes = [i32]
     L.dvdq_bench_set_gemm_variant.restype = i32
+    L.dvdq_bench_set_gemm_schedule.argtypes = [i32]
+    L.dvdq_bench_set_gemm_schedule.restype = i32
     for f in ("dvdq_rotate_quant", "dvdq_rotate_quant_blockwise", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_w4_prepack", "dvdq_version",
               "dvdq_bench_copy", "dvdq_bench_mfma_i8"):
         getattr(L, f).restype = i32
@@ -353,3 +355,8 @@ def bench_mfma_i8(iters: int, sink, stream=None) -> float:
 
 def bench_set_gemm_variant(variant: int) -> None:
     _check(lib().dvdq_bench_set_gemm_variant(int(variant)), "dvdq_bench_set_gemm_variant")
+
+
+def bench_set_gemm_schedule(schedule: int) -> None:
+    """0: fixed tile shares; -1: the library's own choice (tiles drawn from counters)."""
+    _check(lib().dvdq_bench_set_gemm_schedule(int(schedule)), "dvdq_bench_set_gemm_schedule")

@@ -17,6 +17,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
     # keep the compiler from forming packed fp32 VALU ops
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # keep atomics as written: the wave-aggregating rewrite waits for the reply right behind the
+    # atomic (vmcnt 0), which would stall the GEMM's load pipeline at every tile draw
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
 ]
 
 

@@ -65,4 +65,10 @@ int dvdq_bench_set_gemm_variant(int variant) {
     return DVDQ_OK;
 }
 
+int dvdq_bench_set_gemm_schedule(int schedule) {
+    if (schedule < -1 || schedule > 0) return DVDQ_ERR_UNSUPPORTED;
+    dvdq::set_gemm_schedule(schedule);
+    return DVDQ_OK;
+}
+
 }  // extern "C"

@@ -24,6 +24,7 @@ int launch_w4ax_gemm_canonical(const int8_t *codes, const float *x_scale, const 
 
 size_t w4_native_bytes(int64_t N, int64_t K);
 void set_gemm_variant(int v);  // benchmark sweeps only; -1 = choose by shape
+void set_gemm_schedule(int v); // benchmark only; 0 = fixed tile shares, -1 = drawn from counters where possible
 
 int launch_w4_prepack(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, hipStream_t stream);
 

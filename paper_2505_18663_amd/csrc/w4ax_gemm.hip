@@ -24,7 +24,9 @@
 // the MFMA's row operand and the code fragment its column operand, so a lane holds
 // 4 consecutive output channels of one token; lane halves are exchanged
 // (v_permlane32_swap) so that every lane stores 16 contiguous bytes of bf16.
+#include <mutex>
 #include <type_traits>
+#include <unordered_map>
 
 #include "dvdq_internal.h"
 
@@ -125,7 +127,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     const int8_t *__restrict__ codes, const float *__restrict__ x_scale, const uint8_t *__restrict__ w,
     const float *__restrict__ w_scale, const int8_t *__restrict__ w_zero, const int32_t *__restrict__ code_rowsum,
     const uint16_t *__restrict__ bias, int M, int N, int K, uint16_t *__restrict__ y, int32_t *__restrict__ acc_out,
-    int tiles_m, int tiles_n, int group_n) {
+    int tiles_m, int tiles_n, int group_n, unsigned *__restrict__ sched) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave sub-tile
     constexpr int TM = WM / 32, TN = WN / 32;            // MFMA tiles per wave
@@ -171,15 +173,70 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     const int64_t w_slice_stride = (int64_t)G * kGroupBytes;
     const int code_row_bytes = A4 ? K / 2 : K;
 
-    // Persistent workgroups.  Workgroup ids are dealt round-robin to the 8 XCDs; the j-th
-    // tile of workgroup b is number j * grid + (b % 8) * (grid / 8) + b / 8, so the
-    // workgroups of one XCD work on one contiguous run of tile numbers at a time.
+    // Persistent workgroups take tiles until none is left.  Workgroup ids are dealt round-robin to
+    // the 8 XCDs, and the workgroups of one XCD work on one contiguous run of tile numbers at a time.
+    //   sched != nullptr: XCD x owns tile numbers [x total / 8, (x + 1) total / 8) and its workgroups
+    //     draw from them in order through the counter sched[x] (an atomic add).  The two workgroups
+    //     of a compute unit do not run at the same speed (the older one wins the issue arbitration),
+    //     so equal shares would leave the faster ones idle for the last tenth of the kernel.
+    //     sched[8] counts the workgroups that are done; the last one puts all nine words back to zero.
+    //   sched == nullptr: the j-th tile of workgroup b is number j * grid + (b % 8) * (grid / 8) + b / 8.
+    // The tile numbers a workgroup has drawn go through an 8-entry ring in LDS (s_tiles; -1 = no
+    // tile left).  Wave 0 draws tile n + 2 while the loads of tile n are being enqueued and writes the
+    // number into the ring one item later, before that item's barrier: the atomic's reply is then
+    // older than loads the wave has already awaited, so the draw never stalls anything.
     const int total = tiles_m * tiles_n;
     const int grid = gridDim.x;  // multiple of 8
-    const int first_tile = (blockIdx.x % 8) * (grid / 8) + blockIdx.x / 8;
-    const int my_tiles = first_tile < total ? (total - 1 - first_tile) / grid + 1 : 0;
-    const int items = my_tiles * KT;  // one item = one K slice of one tile
-    if (items == 0) return;           // (whole workgroup: nothing below is reached, no barrier is missed)
+    const int xcd = blockIdx.x % 8;
+    const int first_tile = xcd * (grid / 8) + blockIdx.x / 8;
+    const int run_lo = (int)((int64_t)xcd * total / 8);
+    const unsigned run_len = (unsigned)((int64_t)(xcd + 1) * total / 8) - (unsigned)run_lo;
+    typedef volatile __attribute__((address_space(3))) int lds_int;   // (explicitly LDS: a generic volatile access would be a flat one)
+    lds_int *s_tiles = (lds_int *)DVDQ_LDS(smem + STAGES * STAGE + 2 * SCALES);
+    int draws = 0;           // tiles drawn so far (the same in every wave)
+    unsigned drawn = 0;      // wave 0, lane 0: reply of the draw not yet written into the ring
+    bool draw_pending = false;
+    auto tile_of_draw = [&] __device__(unsigned i, int ordinal) {
+        if (sched) return i < run_len ? run_lo + (int)i : -1;
+        const int t = first_tile + ordinal * grid;
+        return t < total ? t : -1;
+    };
+    auto draw = [&] __device__() {
+        if (wave == 0 && sched && lane == 0) drawn = atomicAdd(sched + xcd, 1u);
+        ++draws;
+        draw_pending = true;
+    };
+    auto publish_draw = [&] __device__() {   // before a workgroup barrier
+        if (wave == 0) {
+            if (lane == 0) s_tiles[(draws - 1) & 7] = tile_of_draw(drawn, draws - 1);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+        draw_pending = false;
+    };
+    auto leave = [&] __device__() {          // every wave is past its last draw and its last load
+        if (sched && tid == 0) {
+            if (atomicAdd(sched + 8, 1u) == (unsigned)grid - 1) {
+#pragma unroll
+                for (int i = 0; i < 9; ++i) __hip_atomic_store(sched + i, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    };
+    // the first two tiles are drawn together
+    if (wave == 0) {
+        unsigned i = 0;
+        if (sched && lane == 0) i = atomicAdd(sched + xcd, 2u);
+        if (lane == 0) {
+            s_tiles[0] = tile_of_draw(i, 0);
+            s_tiles[1] = tile_of_draw(i + 1, 1);
+        }
+    }
+    draws = 2;
+    __syncthreads();
+    int comp_tile = __builtin_amdgcn_readfirstlane(s_tiles[0]);   // tile being multiplied
+    if (comp_tile < 0) {   // (whole workgroup: nothing below is reached, no barrier is missed)
+        leave();
+        return;
+    }
 
     // ---- LDS-direct load addressing: wave-uniform base pointer + per-lane 32-bit offset.
     // codes: load slot i of this wave fills ROWS_PER_DMA consecutive LDS rows of the stage;
@@ -189,24 +246,31 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     uint32_t a_voff[A_DMA];
 #pragma unroll
     for (int i = 0; i < A_DMA; ++i) a_row[i] = (wave * A_DMA + i) * ROWS_PER_DMA + lane / CHUNKS;
-    // weights: per item and 32-row group a contiguous run of W_GROUP bytes in the native buffer
-    uint32_t w_voff[W_DMA];
-#pragma unroll
-    for (int i = 0; i < W_DMA; ++i) {
-        const int byte = (wave * W_DMA + i) * 1024 + lane * 16;     // offset in the stage's weight image
-        w_voff[i] = (byte / W_GROUP) * kGroupBytes + (byte % W_GROUP);
-    }
+    // weights: per item and 32-row group a contiguous run of W_GROUP bytes in the native buffer, so the
+    // 1 KB piece p of the stage's weight image starts at byte p * W_PIECE of the item's slice: a
+    // wave-uniform term (added to the scalar base) plus 16 bytes per lane
+    constexpr int W_PIECE = 1024 / W_GROUP * kGroupBytes + 1024 % W_GROUP;
+    static_assert(W_GROUP == kGroupBytes || W_GROUP == 1024, "piece offsets are linear for whole slices or one group per piece");
+    const uint32_t lane16 = lane * 16;
     const int8_t *a_base = codes;   // start of the tile's first code row, advanced by BK per item
     const uint8_t *w_base = w;      // start of the tile's weight image for the item
-    int issue_tile = 0, issue_kt = 0, issued = 0;   // next item to enqueue
+    int issue_tile = 0, issue_kt = 0;   // next item to enqueue: K slice issue_kt of this workgroup's tile issue_tile
+    bool issue_live = true;             // false once the ring says there is no further tile
+    const int draw_kt = KT > 1 ? 1 : 0; // slice at whose enqueueing the tile after next is drawn
     uint32_t issue_sa = 0;                          // LDS address of the buffer being filled
     // The loads of one item are enqueued one at a time (issue_one) so they can be spread
     // between the MFMAs of the slice being multiplied.  Past the last item the same slice
     // is enqueued again (harmless, keeps the load count per item uniform for vmcnt).
     auto issue_prepare = [&] __device__(int buf) {
-        if (issue_kt == 0 && issued < items) {
+        int issue_no = -1;
+        if (issue_live && issue_kt == 0) {
+            issue_no = __builtin_amdgcn_readfirstlane(s_tiles[issue_tile & 7]);
+            issue_live = issue_no >= 0;
+        }
+        if (issue_live && issue_kt == draw_kt) draw();
+        if (issue_no >= 0) {
             int m0, n0;
-            tile_origin(first_tile + issue_tile * grid, tiles_m, tiles_n, group_n, BM, BN, m0, n0);
+            tile_origin(issue_no, tiles_m, tiles_n, group_n, BM, BN, m0, n0);
             a_base = uniform_ptr(codes + (int64_t)m0 * code_row_bytes);
             w_base = uniform_ptr(w + (int64_t)(n0 / kGroup) * kGroupBytes);
 #pragma unroll
@@ -254,14 +318,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
         if (idx < A_DMA)
             lds_direct_load16(a_base, a_voff[idx], issue_sa + (wave * A_DMA + idx) * 1024);
         else
-            lds_direct_load16(w_base, w_voff[idx - A_DMA], issue_sa + A_STAGE + (wave * W_DMA + idx - A_DMA) * 1024);
+            lds_direct_load16(w_base + (wave * W_DMA + idx - A_DMA) * W_PIECE, lane16,
+                              issue_sa + A_STAGE + (wave * W_DMA + idx - A_DMA) * 1024);
     };
     auto issue_advance = [&] __device__() {
-        if (++issued < items) {
+        if (!issue_live) return;
+        if (issue_kt + 1 < KT) {
             a_base += A_ROW;
             // items alternate between the halves of a 128-channel slice of the native layout when BK = 64
             w_base += (BK == 128 || (issue_kt & 1)) ? w_slice_stride - (kBK - BK) * (kGroup / 2) : (int64_t)W_GROUP;
-            if (++issue_kt == KT) { issue_kt = 0; ++issue_tile; }
+            ++issue_kt;
+        } else {   // next: slice 0 of the next tile, whose addresses issue_prepare sets (or none: stay on this slice)
+            issue_kt = 0;
+            ++issue_tile;
         }
     };
 
@@ -326,7 +395,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     }
 
     int kt = 0, tile_j = 0, store_credit = 0;
-    for (int q = 0; q < items; ++q) {
+    for (int q = 0;; ++q) {
         // Publish slice q + AHEAD: it has landed once at most the loads of the
         // (STAGES - 2 - AHEAD) younger slices are outstanding (a wave's vector memory
         // operations complete in issue order).  The barrier also means that everyone is
@@ -341,6 +410,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
             } else {
                 wait_vmcnt<(STAGES - 2 - AHEAD) * DMA>();
             }
+            if (draw_pending) publish_draw();
             __builtin_amdgcn_s_barrier();
         }
         issue_prepare((q + STAGES - 1) % STAGES);
@@ -386,9 +456,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
         // ---- epilogue of tile tile_j.  Accumulator register r = 4 g + e of MFMA tile (i, j) in lane l is
         //   n = n0 + wn + 32 i + 8 g + 4 (l / 32) + e,   m = m0 + wm + 32 j + (l % 32),  value 16 * acc.
         int m0, n0;
-        tile_origin(first_tile + tile_j * grid, tiles_m, tiles_n, group_n, BM, BN, m0, n0);
+        tile_origin(comp_tile, tiles_m, tiles_n, group_n, BM, BN, m0, n0);
         kt = 0;
         ++tile_j;
+        comp_tile = __builtin_amdgcn_readfirstlane(s_tiles[tile_j & 7]);   // the next one (its loads are under way)
         const bool vec8 = (N & 7) == 0;
         const float *s_xs = reinterpret_cast<const float *>(smem + STAGES * STAGE + ((tile_j - 1) & 1) * SCALES);
         const float *s_ws = s_xs + BM;
@@ -427,49 +498,55 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
                 // the next loads into it are only issued after the next K loop's first barrier.
                 uint8_t *stg = smem + (q % STAGES) * STAGE + wave * 4096;
                 const int rd_row = lane >> 3, rd_piece = lane & 7;
+                // A lane's channel vectors (4 channel scales, bias, zero-points) for register group g of MFMA
+                // tile column i are fetched one group ahead of their use: a read issued where its value is
+                // needed would expose the LDS latency once per group, 32 times per tile.
+                struct ChannelVec { float4 ws; uint2 bb; uint32_t zq; };
+                auto fetch = [&] __device__(ChannelVec &cv, int i, int g) {
+                    const int c = i * 32 + g * 8;
+                    cv.ws = *reinterpret_cast<const float4 *>(ws_l + c);
+                    if (bias) cv.bb = *reinterpret_cast<const uint2 *>(bias_l + c / 2);
+                    if constexpr (ZP) cv.zq = zero_l[c / 4];
+                };
+                ChannelVec cv[2];   // group k of the tile's 8 TM TN / 2 ... groups lives in cv[k & 1]
+                fetch(cv[0], 0, 0);
+                int k = 0;
 #pragma unroll
-                for (int j = 0; j < TM; ++j) {
+                for (int ip = 0; ip < TN / 2; ++ip) {
 #pragma unroll
-                    for (int ip = 0; ip < TN / 2; ++ip) {
+                    for (int j = 0; j < TM; ++j) {
 #pragma unroll
                         for (int ii = 0; ii < 2; ++ii) {
                             const int i = 2 * ip + ii;
 #pragma unroll
                             for (int g = 0; g < 4; g += 2) {
-                                float4 wsv[2];
-                                uint2 bb[2];
-                                int zv[2][4];
-#pragma unroll
-                                for (int h = 0; h < 2; ++h) {
-                                    wsv[h] = *reinterpret_cast<const float4 *>(ws_l + i * 32 + (g + h) * 8);
-                                    if (bias) bb[h] = *reinterpret_cast<const uint2 *>(bias_l + (i * 32 + (g + h) * 8) / 2);
-                                    if constexpr (ZP) {
-                                        const uint32_t zq = zero_l[(i * 32 + (g + h) * 8) / 4];
-#pragma unroll
-                                        for (int e = 0; e < 4; ++e) zv[h][e] = (int)(int8_t)(zq >> (8 * e)) * (1 << SHIFT);
-                                    }
-                                }
                                 uint32_t pk[2][2];
 #pragma unroll
-                                for (int h = 0; h < 2; ++h) {
+                                for (int h = 0; h < 2; ++h, ++k) {
+                                    {   // the group after this one, in this loop nest's order
+                                        int gn = g + h + 1, iin = ii, jn = j, ipn = ip;
+                                        if (gn == 4) { gn = 0; if (++iin == 2) { iin = 0; if (++jn == TM) { jn = 0; ++ipn; } } }
+                                        if (ipn < TN / 2) fetch(cv[(k + 1) & 1], 2 * ipn + iin, gn);
+                                    }
+                                    const ChannelVec &c = cv[k & 1];
                                     const int r = (g + h) * 4;
                                     float o[4];
 #pragma unroll
                                     for (int e = 0; e < 4; ++e) {
                                         int a = acc[i][j][r + e];
-                                        if constexpr (ZP) a = unzero(a, zv[h][e], rsum[j]);
+                                        if constexpr (ZP) a = unzero(a, (int)(int8_t)(c.zq >> (8 * e)) * (1 << SHIFT), rsum[j]);
                                         o[e] = (float)a * xs16[j];
                                         acc[i][j][r + e] = 0;
                                     }
-                                    o[0] *= wsv[h].x;
-                                    o[1] *= wsv[h].y;
-                                    o[2] *= wsv[h].z;
-                                    o[3] *= wsv[h].w;
+                                    o[0] *= c.ws.x;
+                                    o[1] *= c.ws.y;
+                                    o[2] *= c.ws.z;
+                                    o[3] *= c.ws.w;
                                     if (bias) {
-                                        o[0] += __uint_as_float(bb[h].x << 16);
-                                        o[1] += __uint_as_float(bb[h].x & 0xFFFF0000u);
-                                        o[2] += __uint_as_float(bb[h].y << 16);
-                                        o[3] += __uint_as_float(bb[h].y & 0xFFFF0000u);
+                                        o[0] += __uint_as_float(c.bb.x << 16);
+                                        o[1] += __uint_as_float(c.bb.x & 0xFFFF0000u);
+                                        o[2] += __uint_as_float(c.bb.y << 16);
+                                        o[3] += __uint_as_float(c.bb.y & 0xFFFF0000u);
                                     }
                                     pk[h][0] = pack_bf16x2(o[0], o[1]);
                                     pk[h][1] = pack_bf16x2(o[2], o[3]);
@@ -491,12 +568,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
                         __builtin_amdgcn_wave_barrier();
                         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                         uint16_t *yb = y + (int64_t)(m0 + wm + j * 32 + rd_row) * N + (n0 + wn + ip * 64 + rd_piece * 8);
+                        uint4 v[4];
 #pragma unroll
                         for (int pass = 0; pass < 4; ++pass) {
                             const int row = pass * 8 + rd_row;
-                            const uint4 v = *reinterpret_cast<const uint4 *>(stg + row * 128 + ((rd_piece ^ (row & 7)) << 4));
-                            store_streaming16(yb + (int64_t)pass * 8 * N, v);
+                            v[pass] = *reinterpret_cast<const uint4 *>(stg + row * 128 + ((rd_piece ^ (row & 7)) << 4));
                         }
+#pragma unroll
+                        for (int pass = 0; pass < 4; ++pass) store_streaming16(yb + (int64_t)pass * 8 * N, v[pass]);
                         __builtin_amdgcn_wave_barrier();   // the next chunk's LDS writes stay behind these reads
                     }
                 }
@@ -504,6 +583,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
             __builtin_amdgcn_s_barrier();   // every wave is done reading the last slice: its buffer stages the tile
             if (w_zero) interior(std::true_type{});
             else interior(std::false_type{});
+            if (comp_tile < 0) break;
             continue;
         }
         // ---- edge tiles, N not a multiple of 8, or the accumulator hook: predicated per element
@@ -591,8 +671,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
             }
         }
+        if (comp_tile < 0) break;
     }
     wait_vmcnt<0>();   // no LDS-direct load may still be in flight when the workgroup's LDS is released
+    leave();
 }
 
 namespace {
@@ -626,6 +708,46 @@ __global__ __launch_bounds__(256) void w4_prepack_kernel(const uint8_t *__restri
 }
 
 int g_variant = -1;  // -1: pick by shape; set by the benchmark's sweep hook
+int g_schedule = -1; // -1: tiles drawn from counters where possible; 0: fixed shares (benchmark hook)
+
+// Tile counters of the persistent kernel: one slot of 16 words per stream (kernels of one stream run
+// one after the other, and every kernel leaves its slot zero, as the module load did).
+constexpr int kSchedSlots = 512;
+__device__ unsigned g_sched[kSchedSlots][16];
+
+// The counter slot for a launch on `stream`, or nullptr (fixed shares) when the launch is being
+// captured into a graph -- the same node may later run in several graph instances at once, which
+// must not share counters -- or when all slots are taken.
+unsigned *sched_slot(hipStream_t stream) {
+    if (g_schedule == 0) return nullptr;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &cap) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    if (cap != hipStreamCaptureStatusNone) return nullptr;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    static std::mutex mu;
+    static unsigned *base[64] = {};
+    static std::unordered_map<uint64_t, int> slots[64];
+    std::lock_guard<std::mutex> lock(mu);
+    if (!base[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_sched)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        base[dev] = static_cast<unsigned *>(p);
+    }
+    auto &m = slots[dev];
+    auto it = m.find(reinterpret_cast<uint64_t>(stream));
+    if (it == m.end()) {
+        if ((int)m.size() >= kSchedSlots) return nullptr;
+        it = m.emplace(reinterpret_cast<uint64_t>(stream), (int)m.size()).first;
+    }
+    return base[dev] + it->second * 16;
+}
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int OCC, bool A4 = false>
 int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
@@ -641,18 +763,20 @@ int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, c
     if (total < grid) grid = (total + 7) / 8 * 8;
     // the ring, then two tiles' epilogue vectors (scales, bias, code sums, zero-points; see the kernel)
     const size_t smem = (size_t)STAGES * (BM * (A4 ? BK / 2 : BK) + BN * BK / 2) +
-                        2 * ((BM + BN) * 4 + BN * 2 + BM * 4 + BN);
+                        2 * ((BM + BN) * 4 + BN * 2 + BM * 4 + BN) + 8 * sizeof(int);   // + the ring of tile numbers
     auto k = w4ax_gemm_native_kernel<BM, BN, BK, WAVES_M, WAVES_N, STAGES, OCC, A4>;
     static std::atomic<uint64_t> configured{0};   // one per template instantiation
     allow_dynamic_lds(reinterpret_cast<const void *>(k), smem, configured);
     hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), smem, stream, codes, x_scale, w,
-                       w_scale, w_zero, code_rowsum, bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n);
+                       w_scale, w_zero, code_rowsum, bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n,
+                       sched_slot(stream));
     return check_launch();
 }
 
 }  // namespace
 
 void set_gemm_variant(int v) { g_variant = v; }
+void set_gemm_schedule(int v) { g_schedule = v; }
 
 int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                      const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,

@@ -1,0 +1,118 @@
+"""Tile scheduling of the native-layout GEMM.  The persistent workgroups either draw their tiles from
+per-stream counters in device memory (default) or take fixed equal shares (while a stream is being
+captured, or forced through the benchmark hook).  Which workgroup computes a tile must not show in
+the result: outputs are compared bit for bit between the two modes, over shapes with fewer tiles than
+workgroups, edge tiles, every tile variant, many launches in a row (the counters must be back at zero
+after every kernel) and launches on several streams at once (one counter slot per stream)."""
+import pytest
+import torch
+
+import paper_2505_18663_amd as dvdq
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(autouse=True)
+def _library_defaults():
+    yield
+    dvdq.bench_set_gemm_schedule(-1)
+    dvdq.bench_set_gemm_variant(-1)
+
+
+def _operands(M, K, N, bits, packed, seed):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    qmax = 2 ** (bits - 1) - 1
+    codes = torch.randint(-qmax, qmax + 1, (M, K), device=DEV, dtype=torch.int8, generator=g)
+    if packed:   # byte b of a group of 8 channels = code[8g+b] | code[8g+b+4] << 4
+        c = codes.view(M, K // 8, 2, 4).to(torch.int16) & 0xF
+        codes = (c[:, :, 0, :] | (c[:, :, 1, :] << 4)).to(torch.uint8).view(M, K // 2).contiguous()
+    xs = torch.rand((M,), device=DEV, generator=g) + 0.01
+    w = dvdq.w4_prepack(torch.randint(0, 256, (N, K // 2), device=DEV, dtype=torch.uint8, generator=g))
+    ws = torch.rand((N,), device=DEV, generator=g) * 0.01 + 1e-3
+    return codes, xs, w, ws
+
+
+def _gemm(ops, bits, packed, y=None, stream=None, want_acc=False):
+    codes, xs, w, ws = ops
+    fmt = dvdq.CODES_PACKED4 if packed else dvdq.CODES_INT8
+    return dvdq.w4ax_gemm(codes, xs, w, ws, bits, dvdq.W_NATIVE, y=y, codes_format=fmt, stream=stream, want_acc=want_acc)
+
+
+SHAPES = [
+    # M, K, N, bits, packed
+    (128, 128, 256, 4, True),        # one tile, one K slice
+    (100, 256, 200, 8, False),       # one edge tile
+    (1000, 384, 776, 6, False),      # 8 x 4 tiles: fewer than workgroups, ragged in M and N
+    (3000, 512, 1030, 4, True),      # N not a multiple of 8: per-element path on every tile
+    (8192, 1024, 4096, 4, True),     # 1024 tiles: two per workgroup
+    (20000, 640, 2304, 4, False),    # 157 x 9 tiles, uneven shares, ragged M
+]
+
+
+@pytest.mark.parametrize("M,K,N,bits,packed", SHAPES)
+def test_drawn_and_fixed_shares_give_identical_outputs(M, K, N, bits, packed):
+    ops = _operands(M, K, N, bits, packed, seed=M + N)
+    dvdq.bench_set_gemm_schedule(0)
+    y_fixed = _gemm(ops, bits, packed)                            # interior tiles take the staged epilogue
+    y2_fixed, acc_fixed = _gemm(ops, bits, packed, want_acc=True)  # the accumulator hook: per-element epilogue
+    dvdq.bench_set_gemm_schedule(-1)
+    y_drawn = _gemm(ops, bits, packed)
+    y2_drawn, acc_drawn = _gemm(ops, bits, packed, want_acc=True)
+    torch.cuda.synchronize()
+    assert torch.equal(acc_fixed, acc_drawn)
+    assert torch.equal(y_fixed.view(torch.int16), y_drawn.view(torch.int16))
+    assert torch.equal(y2_fixed.view(torch.int16), y2_drawn.view(torch.int16))
+    assert torch.equal(y_fixed.view(torch.int16), y2_fixed.view(torch.int16))
+
+
+@pytest.mark.parametrize("variant", [1, 2, 3, 4])
+@pytest.mark.parametrize("packed", [False, True])
+def test_every_tile_variant_agrees_between_the_two_modes(variant, packed):
+    M, K, N, bits = 5000, 768, 1536, 4
+    ops = _operands(M, K, N, bits, packed, seed=variant)
+    dvdq.bench_set_gemm_variant(variant)
+    dvdq.bench_set_gemm_schedule(0)
+    y_fixed = _gemm(ops, bits, packed)
+    dvdq.bench_set_gemm_schedule(-1)
+    y_drawn = _gemm(ops, bits, packed)
+    torch.cuda.synchronize()
+    assert torch.equal(y_fixed.view(torch.int16), y_drawn.view(torch.int16))
+
+
+def test_counters_are_back_at_zero_after_every_kernel():
+    """200 launches in a row on one stream, alternating between two shapes: a counter left dirty by one
+    kernel would make the next one skip or repeat tiles."""
+    a = _operands(4096, 512, 2048, 4, True, seed=1)
+    b = _operands(700, 256, 520, 6, False, seed=2)
+    dvdq.bench_set_gemm_schedule(0)
+    ya_ref, yb_ref = _gemm(a, 4, True), _gemm(b, 6, False)
+    dvdq.bench_set_gemm_schedule(-1)
+    ya, yb = torch.empty_like(ya_ref), torch.empty_like(yb_ref)
+    for it in range(100):
+        ya.zero_()
+        yb.zero_()
+        _gemm(a, 4, True, y=ya)
+        _gemm(b, 6, False, y=yb)
+        if it % 10 == 9:
+            torch.cuda.synchronize()
+            assert torch.equal(ya.view(torch.int16), ya_ref.view(torch.int16)), f"iteration {it}"
+            assert torch.equal(yb.view(torch.int16), yb_ref.view(torch.int16)), f"iteration {it}"
+
+
+def test_launches_on_several_streams_do_not_share_counters():
+    ops = [_operands(6000 + 512 * i, 512, 1536, 4, True, seed=10 + i) for i in range(4)]
+    dvdq.bench_set_gemm_schedule(0)
+    refs = [_gemm(o, 4, True) for o in ops]
+    dvdq.bench_set_gemm_schedule(-1)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in ops]
+    outs = [torch.zeros_like(r) for r in refs]
+    for rep in range(20):
+        for s, o, y in zip(streams, ops, outs):
+            with torch.cuda.stream(s):
+                _gemm(o, 4, True, y=y, stream=s)
+    torch.cuda.synchronize()
+    for i, (y, r) in enumerate(zip(outs, refs)):
+        assert torch.equal(y.view(torch.int16), r.view(torch.int16)), f"stream {i}"
