@@ -27,20 +27,33 @@
  *   - Tensors are dense row-major.  bf16 is passed as `void*` to 16-bit patterns.
  *
  * Activation codes, values in [-qmax, qmax], qmax = 2^(act_bits-1) - 1 (7, 31 or 127
- * for 4, 6, 8 bits), in one of two containers (`codes_format`):
+ * for 4, 6, 8 bits), in one of three containers (`codes_format`):
  *   DVDQ_CODES_INT8     int8 [M, K], one code per byte.  Every bit-width.
  *   DVDQ_CODES_PACKED4  uint8 [M, K/2], two 4-bit two's-complement codes per byte, act_bits = 4
  *                       only.  Channels are interleaved within groups of 8: byte b (0..3) of
  *                       group g of a row holds channel 8g+b in bits 0-3 and channel 8g+b+4 in
  *                       bits 4-7.  This is the order in which one shift and two masks turn a
  *                       32-bit word into int8 lanes in channel order; it halves the bytes the
- *                       quantizer writes and the GEMM reads.  Both are passed as `int8_t *`.
+ *                       quantizer writes and the GEMM reads.
+ *   DVDQ_CODES_FP6      6 bits per code, act_bits = 4 only, for the FP6 matrix path (twice the INT8
+ *                       rate on gfx950): a code c is the E2M3 bit pattern (c < 0) << 5 | |c|, whose
+ *                       value is c / 8 exactly.  dvdq_codes_bytes(M, K, DVDQ_CODES_FP6) bytes, K a
+ *                       multiple of 128, rows padded to a multiple of 32: blocks of 32 rows outermost,
+ *                       then slices of 128 channels; one block-slice is 3072 bytes,
+ *                       [16-byte chunk c = 0..5][row 0..31][16 B], where the 96 bytes c = 0..5 of a row
+ *                       are four 24-byte fragments f = 0..3 and field e (bits 6e .. 6e+5, little
+ *                       endian) of fragment f is channel 64 (f / 2) + 32 (f % 2) + e of the slice.
+ *                       Goes with DVDQ_W_NATIVE_FP6 weights only.
+ *                       All are passed as `int8_t *`.
  *
  * Weight codes, canonical layout (DVDQ_W_CANONICAL): uint8 [N, K/2]; byte j of
  * row n holds channel 2j in bits 0-3 and channel 2j+1 in bits 4-7, each a 4-bit
  * two's-complement number (offline quantizers produce [-7, 7]; -8 is accepted).
  * Native layout (DVDQ_W_NATIVE): the opaque buffer written by dvdq_w4_prepack,
  * dvdq_w4_native_bytes(N, K) bytes; same information, ordered for the GEMM kernel.
+ * FP6 native layout (DVDQ_W_NATIVE_FP6): the buffer written by dvdq_w4_prepack_fp6,
+ * dvdq_w4_native_fp6_bytes(N, K) bytes: the same codes as E2M3 patterns in the block-slice
+ * order described above (slices outermost, N padded to 256 rows); W4A4 only.
  */
 #ifndef DVDQ_H
 #define DVDQ_H
@@ -62,8 +75,12 @@ typedef enum {
     DVDQ_ERR_HIP = 6          /* a kernel launch failed (hipGetLastError) */
 } dvdq_status;
 
-enum { DVDQ_W_CANONICAL = 0, DVDQ_W_NATIVE = 1 };
-enum { DVDQ_CODES_INT8 = 0, DVDQ_CODES_PACKED4 = 1 };
+enum { DVDQ_W_CANONICAL = 0, DVDQ_W_NATIVE = 1, DVDQ_W_NATIVE_FP6 = 2 };
+enum { DVDQ_CODES_INT8 = 0, DVDQ_CODES_PACKED4 = 1, DVDQ_CODES_FP6 = 2 };
+
+/* Bytes of the activation-code buffer for M x K codes in the given container (0 for arguments
+ * the container does not admit). */
+size_t dvdq_codes_bytes(int64_t M, int64_t K, int codes_format);
 
 /*
  * Rotate + auto-scale + quantize (Sec. 3.2: X~ = XH by fast Hadamard transform,
@@ -133,8 +150,10 @@ int dvdq_rotate_quant_blockwise(const void *x_bf16, int64_t M, int64_t K, int ha
  *   act_bits       4, 6 or 8 (bounds the accumulator: qmax * 8 * K, or qmax * 16 * K with
  *                  zero-points, must stay below 2^27, or 2^23 with packed codes,
  *                  DVDQ_ERR_UNSUPPORTED otherwise: the kernels accumulate 16 * acc, resp. 256 * acc)
- *   codes_format   DVDQ_CODES_PACKED4 needs act_bits = 4 and the native weight layout
- *                  (DVDQ_ERR_UNSUPPORTED otherwise)
+ *   codes_format   DVDQ_CODES_PACKED4 needs act_bits = 4 and the native weight layout;
+ *                  DVDQ_CODES_FP6 and DVDQ_W_NATIVE_FP6 need each other, act_bits = 4 and
+ *                  7 * 8 * K < 2^24 (the fp32 accumulators then hold the integer sums exactly;
+ *                  results are bit-identical to the INT8 path) (DVDQ_ERR_UNSUPPORTED otherwise)
  *   y_bf16    out  bf16 [M, N]
  *   acc_out   out  int32 [M, N] or NULL; when given, receives the raw accumulators
  *                  (parity hook; costs extra bandwidth)
@@ -175,6 +194,9 @@ size_t dvdq_qlinear_rowsum_offset(int64_t M, int64_t K, int codes_format);
  */
 int dvdq_w4_prepack(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, void *hip_stream);
 size_t dvdq_w4_native_bytes(int64_t N, int64_t K);
+/* The same for the FP6 native layout (DVDQ_W_NATIVE_FP6; 6 bits per weight). */
+int dvdq_w4_prepack_fp6(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, void *hip_stream);
+size_t dvdq_w4_native_fp6_bytes(int64_t N, int64_t K);
 
 /*
  * One-time, offline: Bounded-init Grid Refinement (Sec. 3.1, Alg. 1), the INT4 weight

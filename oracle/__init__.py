@@ -183,6 +183,47 @@ def pack_a4(codes: np.ndarray) -> np.ndarray:
     return out
 
 
+def pack_fp6(codes: np.ndarray) -> np.ndarray:
+    """int8 [M, K] codes in [-15, 15] -> the FP6 container of the library's C header (uint8, flat).
+
+    A code c becomes the E2M3 bit pattern (c < 0) << 5 | |c| (value c / 8).  Rows are padded with zero
+    codes to a multiple of 32.  Order: [32-row block][128-channel slice][16-byte chunk 0..5][row 0..31][16 B];
+    a row's 96 bytes of a slice are four 24-byte fragments, field e (bits 6e..6e+5, little endian) of
+    fragment f being channel 64 (f // 2) + 32 (f % 2) + e of the slice."""
+    c = _arr(codes, np.int8, 2).astype(np.int16)
+    M, K = c.shape
+    if K % 128:
+        raise ValueError("K must be a multiple of 128")
+    if np.abs(c).max(initial=0) > 15:
+        raise ValueError("codes out of the E2M3 integer range")
+    Mp = (M + 31) // 32 * 32
+    full = np.zeros((Mp, K), dtype=np.int16)
+    full[:M] = c
+    field = (np.where(full < 0, 32, 0) | np.abs(full)).astype(np.uint8)            # [Mp, K]
+    KT = K // 128
+    # channel 64 h + 32 s + e of a slice is field e of fragment f = 2 h + s: plain channel order already
+    frag = field.reshape(Mp, KT, 4, 32)
+    bits = ((frag[..., None] >> np.arange(6, dtype=np.uint8)) & 1).astype(np.uint8)  # [Mp, KT, 4, 32, 6] LSB first
+    row_bytes = np.packbits(bits.reshape(Mp, KT, 4, 192), axis=-1, bitorder="little").reshape(Mp, KT, 96)
+    chunks = row_bytes.reshape(Mp // 32, 32, KT, 6, 16).transpose(0, 2, 3, 1, 4)     # [block, slice, chunk, row, 16]
+    return np.ascontiguousarray(chunks).reshape(-1)
+
+
+def unpack_fp6(buf: np.ndarray, M: int, K: int) -> np.ndarray:
+    """Inverse of pack_fp6: the first M rows as int8 [M, K]."""
+    if K % 128:
+        raise ValueError("K must be a multiple of 128")
+    Mp, KT = (M + 31) // 32 * 32, K // 128
+    b = _arr(buf, np.uint8, 1)
+    if b.size < Mp * KT * 96:
+        raise ValueError("buffer too small")
+    row_bytes = b[:Mp * KT * 96].reshape(Mp // 32, KT, 6, 32, 16).transpose(0, 3, 1, 2, 4).reshape(Mp, KT, 4, 24)
+    bits = np.unpackbits(row_bytes, axis=-1, bitorder="little").reshape(Mp, KT, 4, 32, 6)
+    field = (bits.astype(np.int16) << np.arange(6, dtype=np.int16)).sum(axis=-1)    # [Mp, KT, 4, 32]
+    mag, neg = field & 31, (field >> 5) & 1
+    return np.where(neg == 1, -mag, mag).astype(np.int8).reshape(Mp, K)[:M]
+
+
 def int_gemm(codes: np.ndarray, w_codes: np.ndarray) -> np.ndarray:
     q, w = _arr(codes, np.int8, 2), _arr(w_codes, np.int8, 2)
     (M, K), (N, K2) = q.shape, w.shape

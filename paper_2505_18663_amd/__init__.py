@@ -16,16 +16,17 @@ import torch
 __all__ = [
     "DvdqError", "DvdqLibraryMissing", "lib", "library_path", "version", "status_string",
     "rotate_quant", "rotate_quant_blockwise", "w4ax_gemm", "qlinear", "qlinear_workspace_bytes", "qlinear_scale_offset", "qlinear_rowsum_offset", "workspace_rowsum",
-    "w4_prepack", "w4_native_bytes", "bgr_quantize", "GbsController", "bench_copy", "bench_mfma_i8", "bench_set_gemm_variant", "bench_set_gemm_schedule",
-    "W_CANONICAL", "W_NATIVE", "CODES_INT8", "CODES_PACKED4", "EXPORTED_SYMBOLS",
+    "w4_prepack", "w4_native_bytes", "w4_prepack_fp6", "w4_native_fp6_bytes", "codes_bytes", "bgr_quantize", "GbsController", "bench_copy", "bench_mfma_i8", "bench_set_gemm_variant", "bench_set_gemm_schedule",
+    "W_CANONICAL", "W_NATIVE", "W_NATIVE_FP6", "CODES_INT8", "CODES_PACKED4", "CODES_FP6", "EXPORTED_SYMBOLS",
 ]
 
-W_CANONICAL, W_NATIVE = 0, 1
-CODES_INT8, CODES_PACKED4 = 0, 1
+W_CANONICAL, W_NATIVE, W_NATIVE_FP6 = 0, 1, 2
+CODES_INT8, CODES_PACKED4, CODES_FP6 = 0, 1, 2
 
 EXPORTED_SYMBOLS = (
     "dvdq_rotate_quant", "dvdq_rotate_quant_blockwise", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_qlinear_workspace_bytes",
-    "dvdq_qlinear_scale_offset", "dvdq_qlinear_rowsum_offset", "dvdq_w4_prepack", "dvdq_w4_native_bytes", "dvdq_status_string",
+    "dvdq_qlinear_scale_offset", "dvdq_qlinear_rowsum_offset", "dvdq_w4_prepack", "dvdq_w4_native_bytes", "dvdq_w4_prepack_fp6",
+    "dvdq_w4_native_fp6_bytes", "dvdq_codes_bytes", "dvdq_status_string",
     "dvdq_version", "dvdq_gbs_workspace_bytes", "dvdq_gbs_reset", "dvdq_gbs_step", "dvdq_bgr_quantize", "dvdq_bench_copy", "dvdq_bench_mfma_i8", "dvdq_bench_set_gemm_variant", "dvdq_bench_set_gemm_schedule",
 )
 
@@ -69,6 +70,12 @@ def lib() -> C.CDLL:
     L.dvdq_qlinear_scale_offset.argtypes = [i64, i64, i32]
     L.dvdq_w4_prepack.argtypes = [vp, i64, i64, vp, vp]
     L.dvdq_w4_native_bytes.argtypes = [i64, i64]
+    L.dvdq_w4_prepack_fp6.argtypes = [vp, i64, i64, vp, vp]
+    L.dvdq_w4_prepack_fp6.restype = i32
+    L.dvdq_w4_native_fp6_bytes.argtypes = [i64, i64]
+    L.dvdq_w4_native_fp6_bytes.restype = sz
+    L.dvdq_codes_bytes.argtypes = [i64, i64, i32]
+    L.dvdq_codes_bytes.restype = sz
     L.dvdq_status_string.argtypes = [i32]
     L.dvdq_version.argtypes = []
     L.dvdq_gbs_workspace_bytes.argtypes = []
@@ -137,7 +144,13 @@ def _codes_spec(M: int, K: int, codes_format: int):
     """(dtype, shape) of the tensor that carries the activation codes."""
     if codes_format == CODES_PACKED4:
         return torch.uint8, (M, K // 2)
+    if codes_format == CODES_FP6:   # opaque block layout, see include/dvdq.h
+        return torch.uint8, (lib().dvdq_codes_bytes(M, K, CODES_FP6),)
     return torch.int8, (M, K)
+
+
+def codes_bytes(M: int, K: int, codes_format: int) -> int:
+    return lib().dvdq_codes_bytes(M, K, codes_format)
 
 
 def rotate_quant(x, had_block: int, act_bits: int, codes=None, x_scale=None, stream=None,
@@ -184,11 +197,19 @@ def rotate_quant_blockwise(x, had_block: int, act_bits: int, group: int, values=
 
 def w4ax_gemm(codes, x_scale, w, w_scale, act_bits: int, w_layout: int = W_CANONICAL, bias=None,
               y=None, acc_out=None, want_acc: bool = False, stream=None, codes_format: int = CODES_INT8,
-              w_zero=None, code_rowsum=None):
-    """codes int8 [M, K] (or packed uint8 [M, K/2]), w uint8 packed INT4 [N, K/2] (or native)
-    -> y bf16 [M, N].  With want_acc (or acc_out given) also returns the int32 accumulators."""
+              w_zero=None, code_rowsum=None, K=None):
+    """codes int8 [M, K] (or packed uint8 [M, K/2], or the opaque FP6 buffer: then pass K), w uint8 packed
+    INT4 [N, K/2] (or native) -> y bf16 [M, N].  With want_acc (or acc_out given) also returns the int32
+    accumulators."""
     L = lib()
-    if codes_format == CODES_PACKED4:
+    if codes_format == CODES_FP6:
+        _need(codes, torch.uint8, None, "codes")
+        if K is None:
+            raise ValueError("K is required with FP6 codes")
+        M = x_scale.shape[0]
+        if codes.numel() < L.dvdq_codes_bytes(M, K, CODES_FP6):
+            raise ValueError("codes: FP6 buffer too small")
+    elif codes_format == CODES_PACKED4:
         _need(codes, torch.uint8, None, "codes")
         M, K = codes.shape[0], 2 * codes.shape[1]
     else:
@@ -202,6 +223,8 @@ def w4ax_gemm(codes, x_scale, w, w_scale, act_bits: int, w_layout: int = W_CANON
         raise ValueError(f"w: expected shape {(N, K // 2)}, got {tuple(w.shape)}")
     if w_layout == W_NATIVE and w.numel() < L.dvdq_w4_native_bytes(N, K):
         raise ValueError("w: native buffer too small")
+    if w_layout == W_NATIVE_FP6 and w.numel() < L.dvdq_w4_native_fp6_bytes(N, K):
+        raise ValueError("w: FP6 native buffer too small")
     if bias is not None:
         _need(bias, torch.bfloat16, (N,), "bias")
     if w_zero is not None:
@@ -265,7 +288,10 @@ def workspace_views(workspace, M: int, K: int, codes_format: int = CODES_INT8):
     """(codes int8 [M, K] or packed uint8 [M, K/2], x_scale fp32 [M]) views into a qlinear workspace."""
     off = qlinear_scale_offset(M, K, codes_format)
     cdtype, cshape = _codes_spec(M, K, codes_format)
-    codes = workspace[:cshape[0] * cshape[1]].view(cdtype).view(cshape)
+    n_el = 1
+    for d in cshape:
+        n_el *= d
+    codes = workspace[:n_el].view(cdtype).view(cshape)
     scale = workspace[off:off + 4 * M].view(torch.float32)
     return codes, scale
 
@@ -293,6 +319,26 @@ def w4_prepack(w_canonical, w_native=None, stream=None):
     if w_native.numel() < need:
         raise ValueError("w_native too small")
     _check(L.dvdq_w4_prepack(_ptr(w_canonical), N, K, _ptr(w_native), _stream(stream)), "dvdq_w4_prepack")
+    return w_native
+
+
+def w4_native_fp6_bytes(N: int, K: int) -> int:
+    return lib().dvdq_w4_native_fp6_bytes(N, K)
+
+
+def w4_prepack_fp6(w_canonical, w_native=None, stream=None):
+    """uint8 [N, K/2] canonical -> opaque FP6 native buffer for the W4A4 GEMM on the FP6 matrix path."""
+    L = lib()
+    _need(w_canonical, torch.uint8, None, "w_canonical")
+    N, K2 = w_canonical.shape
+    K = 2 * K2
+    need = L.dvdq_w4_native_fp6_bytes(N, K)
+    if w_native is None:
+        w_native = torch.empty((max(need, 1),), dtype=torch.uint8, device=w_canonical.device)
+    _need(w_native, torch.uint8, None, "w_native")
+    if w_native.numel() < need:
+        raise ValueError("w_native too small")
+    _check(L.dvdq_w4_prepack_fp6(_ptr(w_canonical), N, K, _ptr(w_native), _stream(stream)), "dvdq_w4_prepack_fp6")
     return w_native
 
 

@@ -16,10 +16,10 @@ inline int log2_exact(int v) {
 
 inline bool bits_ok(int b) { return b == 4 || b == 6 || b == 8; }
 
-// container of the activation codes: packed nibbles only hold 4-bit codes
+// container of the activation codes: packed nibbles and FP6 fields only hold 4-bit codes
 inline int check_format(int codes_format, int act_bits) {
     if (codes_format == DVDQ_CODES_INT8) return DVDQ_OK;
-    if (codes_format == DVDQ_CODES_PACKED4 && act_bits == 4) return DVDQ_OK;
+    if ((codes_format == DVDQ_CODES_PACKED4 || codes_format == DVDQ_CODES_FP6) && act_bits == 4) return DVDQ_OK;
     return DVDQ_ERR_UNSUPPORTED;
 }
 
@@ -33,6 +33,7 @@ int check_rotate_quant(const void *x, int64_t M, int64_t K, int had_block, int a
     if (*log2b < 0 || (K % had_block) != 0) return DVDQ_ERR_SHAPE;
     if (!bits_ok(act_bits) || had_block > 512 || K > 65536 || M > 0x7FFFFFFF) return DVDQ_ERR_UNSUPPORTED;
     if (check_format(codes_format, act_bits) != DVDQ_OK) return DVDQ_ERR_UNSUPPORTED;
+    if (codes_format == DVDQ_CODES_FP6 && (K % 128) != 0) return DVDQ_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(codes) || !aligned16(x_scale) || (code_rowsum && !aligned16(code_rowsum)))
         return DVDQ_ERR_ALIGN;
     return DVDQ_OK;
@@ -43,16 +44,21 @@ int check_gemm(const void *codes, const void *x_scale, const void *w, const void
                int codes_format, int w_layout, const void *y, const void *acc_out) {
     if (!codes || !x_scale || !w || !w_scale || !y || (w_zero && !code_rowsum)) return DVDQ_ERR_NULL;
     if (M < 1 || N < 1 || K < 1 || (K % 64) != 0) return DVDQ_ERR_SHAPE;
-    if (!bits_ok(act_bits) || (w_layout != DVDQ_W_CANONICAL && w_layout != DVDQ_W_NATIVE)) return DVDQ_ERR_UNSUPPORTED;
-    if (w_layout == DVDQ_W_NATIVE && (K % 128) != 0) return DVDQ_ERR_UNSUPPORTED;
+    if (!bits_ok(act_bits) ||
+        (w_layout != DVDQ_W_CANONICAL && w_layout != DVDQ_W_NATIVE && w_layout != DVDQ_W_NATIVE_FP6))
+        return DVDQ_ERR_UNSUPPORTED;
+    if (w_layout != DVDQ_W_CANONICAL && (K % 128) != 0) return DVDQ_ERR_UNSUPPORTED;
     if (check_format(codes_format, act_bits) != DVDQ_OK) return DVDQ_ERR_UNSUPPORTED;
     if (codes_format == DVDQ_CODES_PACKED4 && w_layout != DVDQ_W_NATIVE) return DVDQ_ERR_UNSUPPORTED;
-    if (w_zero && w_layout != DVDQ_W_NATIVE) return DVDQ_ERR_UNSUPPORTED;
+    if ((codes_format == DVDQ_CODES_FP6) != (w_layout == DVDQ_W_NATIVE_FP6)) return DVDQ_ERR_UNSUPPORTED;
+    if (w_zero && w_layout == DVDQ_W_CANONICAL) return DVDQ_ERR_UNSUPPORTED;
     if (M > 0x7FFFFFFF || N > 0x7FFFFFFF || K > 0x7FFFFFFF) return DVDQ_ERR_UNSUPPORTED;
+    // FP6 matrix path: sums of code products, |code| <= 7, |w| <= 8, must be exact in fp32
+    if (codes_format == DVDQ_CODES_FP6 && 7 * 8 * K >= (int64_t)1 << 24) return DVDQ_ERR_UNSUPPORTED;
     // the kernel accumulates 16 * sum(code * w), or 256 * with packed codes: |code| <= qmax, |w| <= 8,
     // and |w - zero| <= 16 once a zero-point is taken out; the code sums must fit 24 bits for its multiply
     const int64_t qmax = (1 << (act_bits - 1)) - 1;
-    const int64_t widen = codes_format == DVDQ_CODES_PACKED4 ? 256 : 16;
+    const int64_t widen = codes_format == DVDQ_CODES_PACKED4 ? 256 : (codes_format == DVDQ_CODES_FP6 ? 1 : 16);
     if (widen * qmax * (w_zero ? 16 : 8) * K >= (int64_t)1 << 31) return DVDQ_ERR_UNSUPPORTED;
     if (w_zero && qmax * K >= (int64_t)1 << 23) return DVDQ_ERR_UNSUPPORTED;
     if (!aligned16(codes) || !aligned16(x_scale) || !aligned16(w) || !aligned16(w_scale) || !aligned16(y) ||
@@ -97,13 +103,26 @@ int dvdq_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, 
     const int rc = check_gemm(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias_bf16, M, N, K, act_bits,
                               codes_format, w_layout, y_bf16, acc_out);
     if (rc != DVDQ_OK) return rc;
+    if (w_layout == DVDQ_W_NATIVE_FP6)
+        return dvdq::launch_w4a4_fp6_gemm(reinterpret_cast<const uint8_t *>(codes), x_scale, w, w_scale, w_zero,
+                                          code_rowsum, static_cast<const uint16_t *>(bias_bf16), M, N, K,
+                                          static_cast<uint16_t *>(y_bf16), acc_out, static_cast<hipStream_t>(hip_stream));
     return dvdq::launch_w4ax_gemm(codes, x_scale, w, w_scale, w_zero, code_rowsum,
                                   static_cast<const uint16_t *>(bias_bf16), M, N, K, codes_format, w_layout,
                                   static_cast<uint16_t *>(y_bf16), acc_out, static_cast<hipStream_t>(hip_stream));
 }
 
+size_t dvdq_codes_bytes(int64_t M, int64_t K, int codes_format) {
+    if (M < 1 || K < 1) return 0;
+    if (codes_format == DVDQ_CODES_INT8) return (size_t)M * (size_t)K;
+    if (codes_format == DVDQ_CODES_PACKED4) return (K % 2) ? 0 : (size_t)M * (size_t)K / 2;
+    if (codes_format == DVDQ_CODES_FP6) return (K % 128) ? 0 : dvdq::codes_fp6_bytes(M, K);
+    return 0;
+}
+
 size_t dvdq_qlinear_scale_offset(int64_t M, int64_t K, int codes_format) {
     if (M < 1 || K < 1) return 0;
+    if (codes_format == DVDQ_CODES_FP6) return round_up(dvdq::codes_fp6_bytes(M, K), 256);
     const size_t code_bytes = (size_t)M * (size_t)K;
     return round_up(codes_format == DVDQ_CODES_PACKED4 ? code_bytes / 2 : code_bytes, 256);
 }
@@ -142,6 +161,10 @@ int dvdq_qlinear(const void *x_bf16, const uint8_t *w, const float *w_scale, con
     rc = dvdq::launch_rotate_quant(static_cast<const uint16_t *>(x_bf16), M, K, log2b, act_bits, codes_format, 0,
                                    codes, x_scale, rowsum, stream);
     if (rc != DVDQ_OK) return rc;
+    if (w_layout == DVDQ_W_NATIVE_FP6)
+        return dvdq::launch_w4a4_fp6_gemm(reinterpret_cast<const uint8_t *>(codes), x_scale, w, w_scale, w_zero, rowsum,
+                                          static_cast<const uint16_t *>(bias_bf16), M, N, K,
+                                          static_cast<uint16_t *>(y_bf16), nullptr, stream);
     return dvdq::launch_w4ax_gemm(codes, x_scale, w, w_scale, w_zero, rowsum,
                                   static_cast<const uint16_t *>(bias_bf16), M, N, K, codes_format, w_layout,
                                   static_cast<uint16_t *>(y_bf16), nullptr, stream);
@@ -159,6 +182,20 @@ int dvdq_w4_prepack(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w
     if (N > 0x7FFFFFFF || K > 0x7FFFFFFF) return DVDQ_ERR_UNSUPPORTED;
     if (!aligned16(w_canonical) || !aligned16(w_native)) return DVDQ_ERR_ALIGN;
     return dvdq::launch_w4_prepack(w_canonical, N, K, w_native, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t dvdq_w4_native_fp6_bytes(int64_t N, int64_t K) {
+    if (N < 1 || K < 1 || (K % 128) != 0) return 0;
+    return dvdq::w4_native_fp6_bytes(N, K);
+}
+
+int dvdq_w4_prepack_fp6(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, void *hip_stream) {
+    if (!w_canonical || !w_native) return DVDQ_ERR_NULL;
+    if (N < 1 || K < 1 || (K % 2) != 0) return DVDQ_ERR_SHAPE;
+    if ((K % 128) != 0) return DVDQ_ERR_UNSUPPORTED;
+    if (N > 0x7FFFFFFF || K > 0x7FFFFFFF) return DVDQ_ERR_UNSUPPORTED;
+    if (!aligned16(w_canonical) || !aligned16(w_native)) return DVDQ_ERR_ALIGN;
+    return dvdq::launch_w4_prepack_fp6(w_canonical, N, K, w_native, static_cast<hipStream_t>(hip_stream));
 }
 
 int dvdq_bgr_quantize(const float *w, int64_t N, int64_t K, int n_steps, int max_refine, double eps,

@@ -22,6 +22,14 @@ int launch_w4ax_gemm_canonical(const int8_t *codes, const float *x_scale, const 
                                const uint16_t *bias, int64_t M, int64_t N, int64_t K, uint16_t *y, int32_t *acc_out,
                                hipStream_t stream);
 
+// W4A4 on the FP6 matrix path (w4a4_fp6_gemm.hip): codes and weights in the FP6 block-slice layouts
+int launch_w4a4_fp6_gemm(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
+                         const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,
+                         int64_t K, uint16_t *y, int32_t *acc_out, hipStream_t stream);
+size_t w4_native_fp6_bytes(int64_t N, int64_t K);
+size_t codes_fp6_bytes(int64_t M, int64_t K);
+int launch_w4_prepack_fp6(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, hipStream_t stream);
+
 size_t w4_native_bytes(int64_t N, int64_t K);
 void set_gemm_variant(int v);  // benchmark sweeps only; -1 = choose by shape
 void set_gemm_schedule(int v); // benchmark only; 0 = fixed tile shares, -1 = drawn from counters where possible

@@ -2,9 +2,9 @@
 // transform; s = ||x~||_inf / qmax per token row; codes = round-half-even(x~ / s)).
 //
 // One pass over HBM: a token row is read once (bf16), kept in registers while the
-// transform, the row abs-max and the quantizer run, and written once (int8 codes, or
-// 4-bit codes packed two per byte, one fp32 scale, optionally the row's code sum for
-// weights with zero-points).  A block-wise scaled mode gives every channel group its own
+// transform, the row abs-max and the quantizer run, and written once (int8 codes,
+// 4-bit codes packed two per byte, or 4-bit codes as 6-bit E2M3 patterns for the FP6 matrix
+// path; one fp32 scale; optionally the row's code sum for weights with zero-points).  A block-wise scaled mode gives every channel group its own
 // power-of-two fraction of the token's step and folds it into the int8 value (see the
 // quantizer section of the kernel).  The kernel is bound by HBM only if the transform is
 // cheap in VALU instructions, so the 9 butterfly stages of a 512-channel unit are split:
@@ -90,21 +90,23 @@ __device__ __forceinline__ uint32_t had5_bf16(int r, int k, int mask) {
 
 // CPW = units per wave.  waves_per_row (W) waves share a row; unit u of the row
 // belongs to wave (u % W) as its (u / W)-th unit.
-template <int LOG2B, int CPW, bool PACK4>
+// FMT: container of the codes: 0 int8, 1 two 4-bit codes per byte, 2 FP6 (E2M3 patterns, block layout).
+template <int LOG2B, int CPW, int FMT>
 __global__ __launch_bounds__(1024) void rotate_quant_kernel(
     const uint16_t *__restrict__ x, int64_t M, int K, int waves_per_row, int rows_per_wg,
     double scale_mul,  // 1 / (sqrt(B) * qmax); fp64 so the fp32 scale is rounded once
     float recip_num,   // 1 / sqrt(B)
-    int via_lds,       // PACK4 only: gather the packed codes through LDS into 16-byte stores (K % 32 == 0)
+    int via_lds,       // FMT 1 only: gather the packed codes through LDS into 16-byte stores (K % 32 == 0)
     int group_log2,    // int8 container only: 0, or log2 of the channel group (7, 8, 9) of block-wise scaling
     int emax,          // block-wise scaling: largest power-of-two refinement of a group's step (8 - act_bits)
     int8_t *__restrict__ codes, float *__restrict__ x_scale,
     int32_t *__restrict__ code_rowsum) {  // NULL, or [M]: sum of the row's codes (for weight zero-points)
     extern __shared__ float s_amax[];  // [2][rows_per_wg * waves_per_row], slots alternate per iteration
     // then [2][rows_per_wg * waves_per_row] per-wave code sums, then, 16-byte aligned,
-    // [waves][CPW][64] dwords for gathering packed codes (via_lds)
+    // [waves][CPW][64] dwords for gathering packed codes (via_lds), or [waves][CPW][96] dwords for FP6
     int32_t *s_sum = reinterpret_cast<int32_t *>(s_amax) + 2 * rows_per_wg * waves_per_row;
     uint32_t *s_pack = reinterpret_cast<uint32_t *>(s_amax) + (4 * rows_per_wg * waves_per_row + 3) / 4 * 4;
+    constexpr bool PACK4 = FMT == 1;
     constexpr int MASK5 = LOG2B >= 5 ? 31 : ((1 << LOG2B) - 1);
     const int lane = threadIdx.x & (kWave - 1);
     // (provably wave-uniform, so that row numbers and row base addresses live in scalar registers)
@@ -219,7 +221,63 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
 
         const float magic = 12582912.f;  // 1.5 * 2^23: adding it rounds to integer, ties to even
         int csum = 0;                    // this lane's share of the row's code sum (padding chunks hold zeros)
-        if (PACK4) {
+        if (FMT == 2) {
+            // FP6 container: code c as the E2M3 pattern (c < 0) << 5 | |c|.  The magnitude comes from the
+            // same fused multiply-add on absolute values (round-half-even is symmetric), the sign from
+            // the sign bits of value and reciprocal.  A lane's 8 fields are 48 bits; summing
+            // (magic + |c|) << 6 i and taking the magic's known contribution off once leaves the fields
+            // packed.  A unit's 384 bytes are put together in wave-private LDS in channel order and leave
+            // as 16-byte chunks: chunk j of a row's 128-channel slice goes to
+            // [row / 32][slice][j][row % 32][16 B].
+            uint8_t *sp = reinterpret_cast<uint8_t *>(s_pack) + wave * (CPW * 384);
+            const uint32_t rsign = __float_as_uint(r) & 0x80000000u;
+            constexpr uint32_t MB = 0x4B400000u;   // bit pattern of the magic number
+            constexpr uint32_t LO_C = MB + (MB << 6) + (MB << 12) + (MB << 18) + (MB << 24) + (MB << 30);
+            constexpr uint32_t HI_C = (MB >> 2) + (MB << 4) + (MB << 10);
+#pragma unroll
+            for (int c = 0; c < CPW; ++c) {
+                uint32_t t[8], sg[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    t[i] = __float_as_uint(fmaf(fabsf(v[c][i]), fabsf(r), magic));
+                    sg[i] = (__float_as_uint(v[c][i]) ^ rsign) >> 31;
+                }
+                uint32_t lo = t[0] + (t[1] << 6) + (t[2] << 12) + (t[3] << 18) + (t[4] << 24) + (t[5] << 30) - LO_C;
+                uint32_t hi = ((t[5] >> 2) + (t[6] << 4) + (t[7] << 10) - HI_C) & 0xFFFFu;
+                lo |= (sg[0] << 5) | (sg[1] << 11) | (sg[2] << 17) | (sg[3] << 23) | (sg[4] << 29);
+                hi |= (sg[5] << 3) | (sg[6] << 9) | (sg[7] << 15);
+                if (code_rowsum) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const int mag = (int)(t[i] & 0xFu);
+                        csum += sg[i] ? -mag : mag;
+                    }
+                }
+                uint8_t *d = sp + c * 384 + chunk * 6;   // 4-byte aligned for even chunks, 2-byte for odd ones
+                if (chunk & 1) {
+                    *reinterpret_cast<uint16_t *>(d) = (uint16_t)lo;
+                    *reinterpret_cast<uint32_t *>(d + 2) = (lo >> 16) | (hi << 16);
+                } else {
+                    *reinterpret_cast<uint32_t *>(d) = lo;
+                    *reinterpret_cast<uint16_t *>(d + 4) = (uint16_t)hi;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int slices = K >> 7;
+            uint8_t *out = reinterpret_cast<uint8_t *>(codes) + ((row >> 5) * slices) * 3072 + (row & 31) * 16;
+#pragma unroll
+            for (int idx0 = 0; idx0 < CPW * 24; idx0 += kWave) {
+                const int idx = idx0 + lane, c = idx / 24, part = idx - c * 24;
+                const int g = (wsub + c * waves_per_row) * 24 + part;   // 16-byte chunk of the row
+                const int slice = g / 6, j = g - slice * 6;
+                if (idx < CPW * 24 && row_ok && slice < slices)
+                    *reinterpret_cast<uint4 *>(out + (int64_t)slice * 3072 + j * 512) =
+                        *reinterpret_cast<const uint4 *>(sp + c * 384 + part * 16);
+            }
+            __builtin_amdgcn_wave_barrier();   // the next row's LDS writes stay behind these reads
+        } else if (PACK4) {
             // two codes per byte, in the nibble order the GEMM widens with two masks: byte b of a
             // chunk's dword = code[b] (bits 0-3) | code[b + 4] (bits 4-7), two's complement
             uint32_t p[CPW];
@@ -323,13 +381,15 @@ int launch_cpw(int cpw, dim3 grid, dim3 block, size_t smem, hipStream_t stream, 
                int8_t *codes, float *x_scale, int32_t *code_rowsum) {
 #define DVDQ_RQ_CASE(C)                                                                                   \
     case C:                                                                                               \
-        if (pack4)                                                                                        \
-            hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C, true>), grid, block, smem, stream, x, M, K, \
-                               W, rpw, scale_mul, recip_num, pack4 == 2, 0, 0, codes, x_scale,            \
-                               code_rowsum);                                                              \
+        if (pack4 == 3)                                                                                   \
+            hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C, 2>), grid, block, smem, stream, x, M, K, W, \
+                               rpw, scale_mul, recip_num, 0, 0, 0, codes, x_scale, code_rowsum);          \
+        else if (pack4)                                                                                   \
+            hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C, 1>), grid, block, smem, stream, x, M, K, W, \
+                               rpw, scale_mul, recip_num, pack4 == 2, 0, 0, codes, x_scale, code_rowsum); \
         else                                                                                              \
-            hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C, false>), grid, block, smem, stream, x, M,   \
-                               K, W, rpw, scale_mul, recip_num, 0, group_log2, emax, codes, x_scale,      \
+            hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C, 0>), grid, block, smem, stream, x, M, K, W, \
+                               rpw, scale_mul, recip_num, 0, group_log2, emax, codes, x_scale,            \
                                code_rowsum);                                                              \
         break;
     switch (cpw) {
@@ -346,7 +406,8 @@ int launch_cpw(int cpw, dim3 grid, dim3 block, size_t smem, hipStream_t stream, 
 int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block, int act_bits, int codes_format,
                         int group_log2, int8_t *codes, float *x_scale, int32_t *code_rowsum, hipStream_t stream) {
     const int emax = group_log2 ? 8 - act_bits : 0;
-    const int pack4 = codes_format != DVDQ_CODES_PACKED4 ? 0 : ((K % 32) == 0 ? 2 : 1);
+    // 0: int8; 1 / 2: packed nibbles stored per lane / gathered through LDS; 3: FP6 container
+    const int pack4 = codes_format == DVDQ_CODES_FP6 ? 3 : (codes_format != DVDQ_CODES_PACKED4 ? 0 : ((K % 32) == 0 ? 2 : 1));
     const int units = (int)((K + kUnit - 1) / kUnit);
     // waves per row: at most 4 units (32 fp32 values per lane) in registers per wave, at most 16 waves
     int W = (units + 3) / 4;
@@ -364,6 +425,7 @@ int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block,
     const dim3 grid((unsigned)(wgs_needed < wgs_resident ? wgs_needed : wgs_resident));
     size_t smem = 4 * sizeof(float) * W * rows_per_wg;   // abs-max slots, then code-sum slots
     if (pack4 == 2) smem = (smem + 15) / 16 * 16 + (size_t)W * rows_per_wg * cpw * 256;
+    if (pack4 == 3) smem = (smem + 15) / 16 * 16 + (size_t)W * rows_per_wg * cpw * 384;
     const double qmax = (double)((1 << (act_bits - 1)) - 1);
     const double norm = 1.0 / sqrt((double)(1 << log2_block));
     const double scale_mul = norm / qmax;

@@ -1,0 +1,577 @@
+// W4A4 GEMM on the FP6 matrix path of gfx950 (Sec. 3.2: Y = X^ Lambda W^^T with 4-bit codes on both
+// sides; Sec. 3.1 DeQuant, optional zero-points).
+//
+// Why FP6.  CDNA4 has no INT4 matrix instruction.  Its f8f6f4 MFMAs run 6-bit operands at twice the
+// INT8 rate, and the E2M3 format represents the integers a 4-bit code can take exactly: the value of
+// the bit pattern (sign << 5 | m), 0 <= m <= 15, is +-m / 8 (m < 8 are the format's subnormals, m >= 8
+// has exponent field 1 and mantissa m - 8).  Products of two such values are multiples of 1/64 and
+// their fp32 sum is exact while |sum of code products| < 2^24 (checked by the C ABI), so the fp32
+// accumulator times 64 IS the integer accumulator of the INT8 path, bit for bit.  There is no operand
+// widening in registers at all; the price is 6 instead of 4 bits per code in LDS and in HBM.
+//
+// Operand layout ("FP6 native", for the weights written by the prepack kernel below and for the
+// activation codes by the quantizer): K in slices of 128 channels, rows in blocks of 32.  One
+// block-slice is 3072 bytes: [16-byte chunk c = 0..5][row 0..31][16 B], where the 96 bytes
+// (c = 0..5) of a row hold its 128 codes of the slice as 6-bit fields, field e of 24-byte fragment
+// f = 2 h + s at bit 6 e, for channel 64 h + 32 s + e of the slice.  h is the MFMA's K half (lane / 32),
+// s the 64-channel step: a lane's two fragments of a slice are 48 contiguous bytes = three 16-byte
+// chunks, read from LDS as three conflict-free ds_read_b128 (8 lanes = 8 rows = 128 contiguous bytes)
+// straight into the 12 registers the two MFMAs take their operands from.  Weights: slices outermost,
+// then the 32-row groups of N (padded to 256).  Codes: row blocks outermost, then slices (rows padded
+// to 32).  Either way a tile's slice is a few linear runs, copied HBM/L2 -> LDS by LDS-direct loads.
+//
+// Everything else (ring of LDS buffers, hand-kept vmcnt, persistent workgroups drawing tiles, staged
+// whole-line epilogue) is the design of the INT8 kernel in w4ax_gemm.hip.
+#include <type_traits>
+
+#include "gemm_common.h"
+
+namespace dvdq {
+
+namespace {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int kFp6RowBytes = kBK * 6 / 8;              // 96: one row's codes of one K slice
+constexpr int kFp6Block = kGroup * kFp6RowBytes;       // 3072: 32 rows of one K slice
+constexpr float kFp6Unit = 64.f;                       // accumulator * 64 = integer sum of code products
+
+}  // namespace
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int OCC>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_kernel(
+    const uint8_t *__restrict__ codes, const float *__restrict__ x_scale, const uint8_t *__restrict__ w,
+    const float *__restrict__ w_scale, const int8_t *__restrict__ w_zero, const int32_t *__restrict__ code_rowsum,
+    const uint16_t *__restrict__ bias, int M, int N, int K, uint16_t *__restrict__ y, int32_t *__restrict__ acc_out,
+    int tiles_m, int tiles_n, int group_n, unsigned *__restrict__ sched) {
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave sub-tile
+    constexpr int TM = WM / 32, TN = WN / 32;            // MFMA tiles per wave
+    constexpr int A_STAGE = BM / 32 * kFp6Block, W_STAGE = BN / 32 * kFp6Block, STAGE = A_STAGE + W_STAGE;
+    constexpr int A_DMA = 3;                             // one 32-row block of codes (3 KB) per wave and item
+    constexpr int W_DMA = W_STAGE / 1024 / NW;
+    constexpr int DMA = A_DMA + W_DMA;
+    constexpr int GROUPS = 2 * TN;                       // MFMA groups (TM MFMAs each) per item
+    // one tile's epilogue vectors in LDS: token scales, channel scales (fp32), bias (bf16), and for
+    // weights with zero-points the tokens' code sums (int32) and the channels' zero-points (int8)
+    constexpr int OFF_BIAS = (BM + BN) * 4, OFF_RSUM = OFF_BIAS + BN * 2, OFF_ZERO = OFF_RSUM + BM * 4;
+    constexpr int SCALES = OFF_ZERO + BN;
+    constexpr int STORES = TM * TN * 2;                  // 16-byte store instructions per wave per full tile
+    static_assert(BM / 32 == NW, "one block of code rows per wave");
+    static_assert(W_DMA >= 1 && W_DMA * 1024 * NW == W_STAGE, "weight tile does not split over the waves");
+    static_assert(STAGES == 2, "two buffers: a slice is published at the barrier right before it is multiplied");
+    static_assert(DMA + STORES < 64, "store-aware wait exceeds vmcnt");
+    static_assert(NW * 4096 <= STAGE && TN % 2 == 0, "the epilogue stages 4 KB per wave in one ring buffer");
+
+    extern __shared__ __align__(16) uint8_t smem[];
+    const uint32_t smem_base = lds_address(smem);
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = (wave % WAVES_M) * WM, wn = (wave / WAVES_M) * WN;
+    const int KT = K / kBK;
+    const int G = ((N + kNPad - 1) / kNPad) * (kNPad / kGroup);  // 32-row groups in the padded weight buffer
+    const int64_t w_slice_stride = (int64_t)G * kFp6Block;
+    const int last_block = (M - 1) / 32;                         // code row blocks past it do not exist
+
+    // Persistent workgroups draw their tiles exactly as in the INT8 kernel (see there): per-XCD counters
+    // in sched[0..7], finished workgroups counted in sched[8], fixed shares when sched is null; tile
+    // numbers travel through an 8-entry ring in LDS.
+    const int total = tiles_m * tiles_n;
+    const int grid = gridDim.x;  // multiple of 8
+    const int xcd = blockIdx.x % 8;
+    const int first_tile = xcd * (grid / 8) + blockIdx.x / 8;
+    const int run_lo = (int)((int64_t)xcd * total / 8);
+    const unsigned run_len = (unsigned)((int64_t)(xcd + 1) * total / 8) - (unsigned)run_lo;
+    typedef volatile __attribute__((address_space(3))) int lds_int;
+    lds_int *s_tiles = (lds_int *)DVDQ_LDS(smem + STAGES * STAGE + 2 * SCALES);
+    int draws = 0;
+    unsigned drawn = 0;
+    bool draw_pending = false;
+    auto tile_of_draw = [&] __device__(unsigned i, int ordinal) {
+        if (sched) return i < run_len ? run_lo + (int)i : -1;
+        const int t = first_tile + ordinal * grid;
+        return t < total ? t : -1;
+    };
+    auto draw = [&] __device__() {
+        if (wave == 0 && sched && lane == 0) drawn = atomicAdd(sched + xcd, 1u);
+        ++draws;
+        draw_pending = true;
+    };
+    auto publish_draw = [&] __device__() {   // before a workgroup barrier
+        if (wave == 0) {
+            if (lane == 0) s_tiles[(draws - 1) & 7] = tile_of_draw(drawn, draws - 1);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+        draw_pending = false;
+    };
+    auto leave = [&] __device__() {
+        if (sched && tid == 0) {
+            if (atomicAdd(sched + 8, 1u) == (unsigned)grid - 1) {
+#pragma unroll
+                for (int i = 0; i < 9; ++i) __hip_atomic_store(sched + i, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    };
+    if (wave == 0) {
+        unsigned i = 0;
+        if (sched && lane == 0) i = atomicAdd(sched + xcd, 2u);
+        if (lane == 0) {
+            s_tiles[0] = tile_of_draw(i, 0);
+            s_tiles[1] = tile_of_draw(i + 1, 1);
+        }
+    }
+    draws = 2;
+    __syncthreads();
+    int comp_tile = __builtin_amdgcn_readfirstlane(s_tiles[0]);
+    if (comp_tile < 0) {   // (whole workgroup: nothing below is reached, no barrier is missed)
+        leave();
+        return;
+    }
+
+    // ---- LDS-direct loads: every piece is 1 KB that is contiguous in memory and in LDS, so a lane's
+    // offset is 16 * lane on both sides and the rest is wave-uniform.  Codes: this wave's row block of
+    // the tile (blocks past the last one repeat it; their rows are never stored).  Weights: the tile's
+    // 8 groups of a slice are one 24 KB run.
+    const uint32_t lane16 = lane * 16;
+    const uint8_t *a_base = codes;   // this wave's code block, slice issue_kt
+    const uint8_t *w_base = w;       // the tile's weight run, slice issue_kt
+    int issue_tile = 0, issue_kt = 0;
+    bool issue_live = true;
+    const int draw_kt = KT > 1 ? 1 : 0;
+    uint32_t issue_sa = 0;
+    auto issue_prepare = [&] __device__(int buf) {
+        int issue_no = -1;
+        if (issue_live && issue_kt == 0) {
+            issue_no = __builtin_amdgcn_readfirstlane(s_tiles[issue_tile & 7]);
+            issue_live = issue_no >= 0;
+        }
+        if (issue_live && issue_kt == draw_kt) draw();
+        if (issue_no >= 0) {
+            int m0, n0;
+            tile_origin(issue_no, tiles_m, tiles_n, group_n, BM, BN, m0, n0);
+            a_base = uniform_ptr(codes + (int64_t)min(m0 / 32 + wave, last_block) * KT * kFp6Block);
+            w_base = uniform_ptr(w + (int64_t)(n0 / kGroup) * kFp6Block);
+            const uint32_t sc = smem_base + STAGES * STAGE + (issue_tile & 1) * SCALES;
+#pragma unroll
+            for (int j = 0; j < (BM + BN) / 64; ++j) {
+                if (j % NW != wave) continue;
+                if (j < BM / 64)
+                    lds_direct_load4(x_scale, (uint32_t)min(m0 + j * 64 + lane, M - 1) * 4, sc + j * 256);
+                else
+                    lds_direct_load4(w_scale, (uint32_t)min(n0 + (j - BM / 64) * 64 + lane, N - 1) * 4, sc + j * 256);
+            }
+            if (bias && n0 + BN <= N) {
+#pragma unroll
+                for (int j = 0; j < BN / 128; ++j)
+                    if (j % NW == wave)
+                        lds_direct_load4(bias + n0, (uint32_t)(j * 64 + lane) * 4, sc + OFF_BIAS + j * 256);
+            }
+            if (w_zero) {
+#pragma unroll
+                for (int j = 0; j < BM / 64; ++j)
+                    if (j % NW == wave)
+                        lds_direct_load4(code_rowsum, (uint32_t)min(m0 + j * 64 + lane, M - 1) * 4, sc + OFF_RSUM + j * 256);
+                if (n0 + BN <= N) {
+#pragma unroll
+                    for (int j = 0; j < BN / 256; ++j)
+                        if (j % NW == wave)
+                            lds_direct_load4(w_zero + n0, (uint32_t)(j * 64 + lane) * 4, sc + OFF_ZERO + j * 256);
+                }
+            }
+        }
+        issue_sa = smem_base + buf * STAGE;
+    };
+    auto issue_one = [&] __device__(int idx) {
+        if (idx < A_DMA)
+            lds_direct_load16(a_base + idx * 1024, lane16, issue_sa + (wave * A_DMA + idx) * 1024);
+        else
+            lds_direct_load16(w_base + (wave * W_DMA + idx - A_DMA) * 1024, lane16,
+                              issue_sa + A_STAGE + (wave * W_DMA + idx - A_DMA) * 1024);
+    };
+    auto issue_advance = [&] __device__() {
+        if (!issue_live) return;
+        if (issue_kt + 1 < KT) {
+            a_base += kFp6Block;
+            w_base += w_slice_stride;
+            ++issue_kt;
+        } else {   // next: slice 0 of the next tile, whose addresses issue_prepare sets (or none: stay on this slice)
+            issue_kt = 0;
+            ++issue_tile;
+        }
+    };
+
+    v16f acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // ---- fragment addressing: MFMA operand row = lane % 32, K half = lane / 32
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int frag_off = fhalf * 1536 + frow * 16;   // chunks 3 h .. 3 h + 2 of the row, 512 bytes apart
+
+    // ---- prologue: fill the first buffer
+    issue_prepare(0);
+#pragma unroll
+    for (int d = 0; d < DMA; ++d) issue_one(d);
+    issue_advance();
+
+    int kt = 0, tile_j = 0, store_credit = 0;
+    for (int q = 0;; ++q) {
+        // Publish slice q (it has landed once nothing older is outstanding: a wave's vector memory
+        // operations complete in issue order); the barrier also means that everyone is done reading
+        // slice q-1, whose buffer the next loads overwrite.  Right after the epilogue of a full tile
+        // exactly STORES stores are this wave's youngest operations: their acknowledgement is not awaited.
+        if (store_credit > 0) {
+            wait_vmcnt<STORES>();
+            --store_credit;
+        } else {
+            wait_vmcnt<0>();
+        }
+        if (draw_pending) publish_draw();
+        __builtin_amdgcn_s_barrier();
+        issue_prepare((q + 1) % STAGES);
+        if (kt == 0) __builtin_amdgcn_s_setprio(2);
+
+        // The slice's fragments: per operand row three 16-byte chunks = the 12 registers of the two
+        // steps' operands.  All are requested up front (chunks 0 and 1, which step 0 needs, first); the
+        // LDS-direct loads of the next slice are dealt out between the MFMA groups.
+        const uint8_t *sa = smem + (q % STAGES) * STAGE + (wm / 32) * kFp6Block + frag_off;
+        const uint8_t *sw = smem + (q % STAGES) * STAGE + A_STAGE + (wn / 32) * kFp6Block + frag_off;
+        v4i ra[TM][3], rw[TN][3];
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+#pragma unroll
+            for (int j = 0; j < TM; ++j) ra[j][c] = *reinterpret_cast<const v4i *>(sa + j * kFp6Block + c * 512);
+#pragma unroll
+            for (int i = 0; i < TN; ++i) rw[i][c] = *reinterpret_cast<const v4i *>(sw + i * kFp6Block + c * 512);
+            if (c == 0) continue;   // (chunks 0 and 1 go out together)
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            v8i fa[TM];
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+                fa[j] = s == 0 ? v8i{ra[j][0][0], ra[j][0][1], ra[j][0][2], ra[j][0][3], ra[j][1][0], ra[j][1][1], 0, 0}
+                               : v8i{ra[j][1][2], ra[j][1][3], ra[j][2][0], ra[j][2][1], ra[j][2][2], ra[j][2][3], 0, 0};
+#pragma unroll
+            for (int i = 0; i < TN; ++i) {
+                const v8i fw = s == 0 ? v8i{rw[i][0][0], rw[i][0][1], rw[i][0][2], rw[i][0][3], rw[i][1][0], rw[i][1][1], 0, 0}
+                                      : v8i{rw[i][1][2], rw[i][1][3], rw[i][2][0], rw[i][2][1], rw[i][2][2], rw[i][2][3], 0, 0};
+#pragma unroll
+                for (int j = 0; j < TM; ++j)   // both operands FP6 E2M3 (format code 2), no block scales
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fw, fa[j], acc[i][j], 2, 2, 0, 0, 0, 0);
+#pragma unroll
+                for (int d = s * TN + i; d < DMA; d += GROUPS) issue_one(d);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        issue_advance();
+        if (++kt < KT) continue;
+        __builtin_amdgcn_s_setprio(0);
+
+        // ---- epilogue of tile comp_tile.  Accumulator register r = 4 g + e of MFMA tile (i, j) in lane l is
+        //   n = n0 + wn + 32 i + 8 g + 4 (l / 32) + e,   m = m0 + wm + 32 j + (l % 32),  value = integer sum / 64.
+        int m0, n0;
+        tile_origin(comp_tile, tiles_m, tiles_n, group_n, BM, BN, m0, n0);
+        kt = 0;
+        ++tile_j;
+        comp_tile = __builtin_amdgcn_readfirstlane(s_tiles[tile_j & 7]);   // the next one (its loads are under way)
+        const bool vec8 = (N & 7) == 0;
+        const uint8_t *s_tile = smem + STAGES * STAGE + ((tile_j - 1) & 1) * SCALES;
+        const float *s_xs = reinterpret_cast<const float *>(s_tile);
+        const float *s_ws = s_xs + BM;
+        const int32_t *s_rsum = reinterpret_cast<const int32_t *>(s_tile + OFF_RSUM);
+        // the integer accumulator (exact: see the top of this file), then sum q (c - z) = acc - z * rs with a
+        // 24-bit multiply (operands and product in range: checked by the C ABI)
+        auto acc_int = [] __device__(float a) { return (int)(a * kFp6Unit); };
+        auto unzero = [] __device__(int a, int z, int rs) { return a - __mul24(z, rs); };
+        if (vec8 && !acc_out && m0 + BM <= M && n0 + BN <= N) {
+            // ---- interior tile: no predicates, channel vectors fetched one register group ahead, bf16 tile
+            // transposed through this wave's 4 KB of the ring buffer that was consumed last, whole-line
+            // non-temporal stores (the INT8 kernel's epilogue; same arithmetic, same rounding order).
+            if (KT >= STAGES) store_credit = 1;
+            auto interior = [&] __device__(auto has_zero) __attribute__((always_inline)) {
+                constexpr bool ZP = decltype(has_zero)::value;
+                const float *ws_l = s_ws + wn + fhalf * 4;
+                const uint32_t *bias_l = reinterpret_cast<const uint32_t *>(s_tile + OFF_BIAS) + (wn + fhalf * 4) / 2;
+                const uint32_t *zero_l = reinterpret_cast<const uint32_t *>(s_tile + OFF_ZERO) + (wn + fhalf * 4) / 4;
+                float xs_l[TM];   // token scale; times 64 where it multiplies the fp32 accumulator directly
+                int rsum[TM];
+#pragma unroll
+                for (int j = 0; j < TM; ++j) {
+                    xs_l[j] = s_xs[wm + j * 32 + frow] * (ZP ? 1.f : kFp6Unit);
+                    rsum[j] = ZP ? s_rsum[wm + j * 32 + frow] : 0;
+                }
+                uint8_t *stg = smem + (q % STAGES) * STAGE + wave * 4096;
+                const int rd_row = lane >> 3, rd_piece = lane & 7;
+                struct ChannelVec { float4 ws; uint2 bb; uint32_t zq; };
+                auto fetch = [&] __device__(ChannelVec &cv, int i, int g) {
+                    const int c = i * 32 + g * 8;
+                    cv.ws = *reinterpret_cast<const float4 *>(ws_l + c);
+                    if (bias) cv.bb = *reinterpret_cast<const uint2 *>(bias_l + c / 2);
+                    if constexpr (ZP) cv.zq = zero_l[c / 4];
+                };
+                ChannelVec cv[2];
+                fetch(cv[0], 0, 0);
+                int k = 0;
+#pragma unroll
+                for (int ip = 0; ip < TN / 2; ++ip) {
+#pragma unroll
+                    for (int j = 0; j < TM; ++j) {
+#pragma unroll
+                        for (int ii = 0; ii < 2; ++ii) {
+                            const int i = 2 * ip + ii;
+#pragma unroll
+                            for (int g = 0; g < 4; g += 2) {
+                                uint32_t pk[2][2];
+#pragma unroll
+                                for (int h = 0; h < 2; ++h, ++k) {
+                                    {   // the group after this one, in this loop nest's order
+                                        int gn = g + h + 1, iin = ii, jn = j, ipn = ip;
+                                        if (gn == 4) { gn = 0; if (++iin == 2) { iin = 0; if (++jn == TM) { jn = 0; ++ipn; } } }
+                                        if (ipn < TN / 2) fetch(cv[(k + 1) & 1], 2 * ipn + iin, gn);
+                                    }
+                                    const ChannelVec &c = cv[k & 1];
+                                    const int r = (g + h) * 4;
+                                    float o[4];
+#pragma unroll
+                                    for (int e = 0; e < 4; ++e) {
+                                        if constexpr (ZP)
+                                            o[e] = (float)unzero(acc_int(acc[i][j][r + e]), (int)(int8_t)(c.zq >> (8 * e)), rsum[j]) * xs_l[j];
+                                        else
+                                            o[e] = acc[i][j][r + e] * xs_l[j];
+                                        acc[i][j][r + e] = 0.f;
+                                    }
+                                    o[0] *= c.ws.x;
+                                    o[1] *= c.ws.y;
+                                    o[2] *= c.ws.z;
+                                    o[3] *= c.ws.w;
+                                    if (bias) {
+                                        o[0] += __uint_as_float(c.bb.x << 16);
+                                        o[1] += __uint_as_float(c.bb.x & 0xFFFF0000u);
+                                        o[2] += __uint_as_float(c.bb.y << 16);
+                                        o[3] += __uint_as_float(c.bb.y & 0xFFFF0000u);
+                                    }
+                                    pk[h][0] = pack_bf16x2(o[0], o[1]);
+                                    pk[h][1] = pack_bf16x2(o[2], o[3]);
+                                }
+#pragma unroll
+                                for (int d = 0; d < 2; ++d) {
+                                    auto sw = __builtin_amdgcn_permlane32_swap(pk[0][d], pk[1][d], false, false);
+                                    pk[0][d] = sw[0];
+                                    pk[1][d] = sw[1];
+                                }
+                                const int piece = ii * 4 + g + fhalf;   // 16-byte piece of the 64-channel row
+                                *reinterpret_cast<uint4 *>(stg + frow * 128 + ((piece ^ (frow & 7)) << 4)) =
+                                    make_uint4(pk[0][0], pk[0][1], pk[1][0], pk[1][1]);
+                            }
+                        }
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                        uint16_t *yb = y + (int64_t)(m0 + wm + j * 32 + rd_row) * N + (n0 + wn + ip * 64 + rd_piece * 8);
+                        uint4 v[4];
+#pragma unroll
+                        for (int pass = 0; pass < 4; ++pass) {
+                            const int row = pass * 8 + rd_row;
+                            v[pass] = *reinterpret_cast<const uint4 *>(stg + row * 128 + ((rd_piece ^ (row & 7)) << 4));
+                        }
+#pragma unroll
+                        for (int pass = 0; pass < 4; ++pass) store_streaming16(yb + (int64_t)pass * 8 * N, v[pass]);
+                        __builtin_amdgcn_wave_barrier();   // the next chunk's LDS writes stay behind these reads
+                    }
+                }
+            };
+            __builtin_amdgcn_s_barrier();   // every wave is done reading the last slice: its buffer stages the tile
+            if (w_zero) interior(std::true_type{});
+            else interior(std::false_type{});
+            if (comp_tile < 0) break;
+            continue;
+        }
+        // ---- edge tiles, N not a multiple of 8, or the accumulator hook: predicated per element, through
+        // the integer accumulator (same values and rounding order as the interior path)
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int m = m0 + wm + j * 32 + frow;
+            const bool m_ok = m < M;
+            const float xs = s_xs[wm + j * 32 + frow];
+            const int rs = w_zero ? s_rsum[wm + j * 32 + frow] : 0;
+#pragma unroll
+            for (int i = 0; i < TN; ++i) {
+                const int nb = n0 + wn + i * 32;   // this MFMA tile's first output channel
+                int a[16];
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int n = nb + g * 8 + fhalf * 4 + e;
+                        a[g * 4 + e] = acc_int(acc[i][j][g * 4 + e]);
+                        if (w_zero && n < N) a[g * 4 + e] = unzero(a[g * 4 + e], (int)w_zero[n], rs);
+                        acc[i][j][g * 4 + e] = 0.f;
+                    }
+                if (acc_out && m_ok) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int n = nb + g * 8 + fhalf * 4;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (n + e < N) acc_out[(int64_t)m * N + n + e] = a[g * 4 + e];
+                    }
+                }
+                if (vec8) {
+                    uint32_t pk[4][2];
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int n = nb + g * 8 + fhalf * 4;
+                        float o[4];
+                        if (n < N) {  // N % 8 == 0 and n % 4 == 0: n + 3 < N as well
+                            const float4 ws = *reinterpret_cast<const float4 *>(s_ws + (n - n0));
+                            o[0] = (float)a[g * 4 + 0] * xs * ws.x;
+                            o[1] = (float)a[g * 4 + 1] * xs * ws.y;
+                            o[2] = (float)a[g * 4 + 2] * xs * ws.z;
+                            o[3] = (float)a[g * 4 + 3] * xs * ws.w;
+                            if (bias) {
+                                const uint2 bb = *reinterpret_cast<const uint2 *>(bias + n);
+                                o[0] += __uint_as_float(bb.x << 16);
+                                o[1] += __uint_as_float(bb.x & 0xFFFF0000u);
+                                o[2] += __uint_as_float(bb.y << 16);
+                                o[3] += __uint_as_float(bb.y & 0xFFFF0000u);
+                            }
+                        } else {
+                            o[0] = o[1] = o[2] = o[3] = 0.f;
+                        }
+                        pk[g][0] = pack_bf16x2(o[0], o[1]);
+                        pk[g][1] = pack_bf16x2(o[2], o[3]);
+                    }
+#pragma unroll
+                    for (int g = 0; g < 4; g += 2) {
+#pragma unroll
+                        for (int d = 0; d < 2; ++d) {
+                            auto r = __builtin_amdgcn_permlane32_swap(pk[g][d], pk[g + 1][d], false, false);
+                            pk[g][d] = r[0];
+                            pk[g + 1][d] = r[1];
+                        }
+                        const int n = nb + g * 8 + fhalf * 8;
+                        if (m_ok && n < N)
+                            *reinterpret_cast<uint4 *>(y + (int64_t)m * N + n) =
+                                make_uint4(pk[g][0], pk[g][1], pk[g + 1][0], pk[g + 1][1]);
+                    }
+                } else if (m_ok) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int n = nb + g * 8 + fhalf * 4;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            if (n + e >= N) break;
+                            float o = (float)a[g * 4 + e] * xs * s_ws[n + e - n0];
+                            if (bias) o += __uint_as_float((uint32_t)bias[n + e] << 16);
+                            y[(int64_t)m * N + n + e] = (uint16_t)(pack_bf16x2(o, 0.f) & 0xFFFFu);
+                        }
+                    }
+                }
+            }
+        }
+        if (comp_tile < 0) break;
+    }
+    wait_vmcnt<0>();   // no LDS-direct load may still be in flight when the workgroup's LDS is released
+    leave();
+}
+
+namespace {
+
+// canonical [N, K/2] (two signed 4-bit codes per byte, low nibble first) -> FP6 native layout (see the top
+// of this file).  One thread per 24-byte fragment (32 codes of one row).  Rows >= N are written as zero.
+__global__ __launch_bounds__(256) void w4_prepack_fp6_kernel(const uint8_t *__restrict__ src, uint32_t *__restrict__ dst,
+                                                             int N, int K, int G, int KT) {
+    const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t frags = (int64_t)KT * G * kGroup * 4;
+    if (o >= frags) return;
+    int64_t v = o;
+    const int f = (int)(v & 3); v >>= 2;       // fragment 2 h + s of the row's slice
+    const int r = (int)(v & 31); v >>= 5;
+    const int g = (int)(v % G);
+    const int kt = (int)(v / G);
+    const int n = g * kGroup + r;
+    const int k = kt * kBK + (f >> 1) * 64 + (f & 1) * 32;   // first channel of the fragment
+    uint32_t out[6] = {0, 0, 0, 0, 0, 0};
+    if (n < N) {
+        const uint4 p = *reinterpret_cast<const uint4 *>(src + (int64_t)n * (K / 2) + k / 2);
+        const uint32_t q[4] = {p.x, p.y, p.z, p.w};
+        uint64_t lo = 0, mid = 0, hi = 0;      // 192 bits, 64 each
+#pragma unroll
+        for (int e = 0; e < 32; ++e) {
+            const int c = (int)(q[e >> 3] << (28 - 4 * (e & 7))) >> 28;          // signed nibble e
+            const uint64_t field = (uint64_t)((c < 0 ? 32 : 0) | (c < 0 ? -c : c));
+            const int bit = 6 * e;
+            if (bit < 64) { lo |= field << bit; if (bit > 58) mid |= field >> (64 - bit); }
+            else if (bit < 128) { mid |= field << (bit - 64); if (bit > 122) hi |= field >> (128 - bit); }
+            else hi |= field << (bit - 128);
+        }
+        out[0] = (uint32_t)lo; out[1] = (uint32_t)(lo >> 32); out[2] = (uint32_t)mid;
+        out[3] = (uint32_t)(mid >> 32); out[4] = (uint32_t)hi; out[5] = (uint32_t)(hi >> 32);
+    }
+    // byte b of the row's 96 bytes lives in chunk b / 16 at [chunk][row][b % 16]
+    uint32_t *blk = dst + ((int64_t)kt * G + g) * (kFp6Block / 4);
+#pragma unroll
+    for (int d = 0; d < 6; ++d) {
+        const int b = f * 24 + d * 4;
+        blk[(b / 16) * (kGroup * 4) + r * 4 + (b % 16) / 4] = out[d];
+    }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int OCC>
+int launch_fp6(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale, const int8_t *w_zero,
+               const int32_t *code_rowsum, const uint16_t *bias, int M, int N, int K, uint16_t *y, int32_t *acc_out,
+               hipStream_t stream) {
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const int n_groups = (tiles_n + 15) / 16;
+    const int group_n = (tiles_n + n_groups - 1) / n_groups;
+    const int total = tiles_m * tiles_n;
+    int grid = 256 * OCC;
+    if (total < grid) grid = (total + 7) / 8 * 8;
+    const size_t smem = (size_t)STAGES * (BM / 32 + BN / 32) * kFp6Block + 2 * ((BM + BN) * 4 + BN * 2 + BM * 4 + BN) +
+                        8 * sizeof(int);
+    auto k = w4a4_fp6_gemm_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, OCC>;
+    static std::atomic<uint64_t> configured{0};
+    allow_dynamic_lds(reinterpret_cast<const void *>(k), smem, configured);
+    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), smem, stream, codes, x_scale, w, w_scale,
+                       w_zero, code_rowsum, bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n, sched_slot(stream));
+    return check_launch();
+}
+
+}  // namespace
+
+int launch_w4a4_fp6_gemm(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
+                         const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,
+                         int64_t K, uint16_t *y, int32_t *acc_out, hipStream_t stream) {
+    return launch_fp6<128, 256, 2, 2, 2, 2>(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K,
+                                            y, acc_out, stream);
+}
+
+size_t w4_native_fp6_bytes(int64_t N, int64_t K) {
+    const int64_t npad = (N + kNPad - 1) / kNPad * kNPad, kpad = (K + kBK - 1) / kBK * kBK;
+    return (size_t)(npad * kpad * 6 / 8);
+}
+
+size_t codes_fp6_bytes(int64_t M, int64_t K) {
+    const int64_t mpad = (M + 31) / 32 * 32, kpad = (K + kBK - 1) / kBK * kBK;
+    return (size_t)(mpad * kpad * 6 / 8);
+}
+
+int launch_w4_prepack_fp6(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, hipStream_t stream) {
+    const int G = (int)((N + kNPad - 1) / kNPad * (kNPad / kGroup));
+    const int KT = (int)(K / kBK);
+    const int64_t frags = (int64_t)KT * G * kGroup * 4;
+    const int64_t blocks = (frags + 255) / 256;
+    hipLaunchKernelGGL(w4_prepack_fp6_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, w_canonical,
+                       reinterpret_cast<uint32_t *>(w_native), (int)N, (int)K, G, KT);
+    return check_launch();
+}
+
+}  // namespace dvdq

@@ -28,99 +28,9 @@
 #include <type_traits>
 #include <unordered_map>
 
-#include "dvdq_internal.h"
+#include "gemm_common.h"
 
 namespace dvdq {
-namespace {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-
-constexpr int kBK = 128;      // K slice (bytes of int8 codes per row)
-constexpr int kGroup = 32;    // weight rows per native-layout group
-constexpr int kGroupBytes = kGroup * kBK / 2;  // 2048: one group, one K slice, packed
-constexpr int kNPad = 256;    // native layout pads N to a multiple of this
-
-#define DVDQ_LDS(p) ((__attribute__((address_space(3))) void *)(p))
-
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-    typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
-    v2bf p = {(__bf16)a, (__bf16)b};  // round-to-nearest-even conversions
-    return __builtin_bit_cast(uint32_t, p);
-}
-
-// 16-byte store of output the kernel never reads again.  Non-temporal: with whole 128-byte lines
-// per instruction (the staged epilogue) the output stream then bypasses the L2 instead of evicting
-// code and weight panels and leaving dirty lines to flush at the kernel's end.  (For partial-line
-// stores the same hint is much slower than write-back caching.)
-__device__ __forceinline__ void store_streaming16(uint16_t *p, uint4 v) {
-    typedef uint32_t v4u __attribute__((ext_vector_type(4)));
-    const v4u vv = {v.x, v.y, v.z, v.w};
-    __builtin_nontemporal_store(vv, reinterpret_cast<v4u *>(p));
-}
-
-// vmcnt-only wait (leave expcnt / lgkmcnt alone): gfx9 encoding, vmcnt = {imm[15:14], imm[3:0]}
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    static_assert(N >= 0 && N < 64, "vmcnt is 6 bits");
-    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
-}
-
-// One LDS-direct load: 16 bytes per lane from global address `sbase` + `voff` (sbase
-// wave-uniform, voff per lane) to LDS address `lds_base` + 16 * lane (lds_base
-// wave-uniform).  Written as inline assembly so that the compiler's waitcnt insertion
-// does not know about it: with the builtin it makes every later LDS read wait for ALL
-// outstanding LDS-direct loads (it cannot tell the ring buffers apart), which
-// serializes the pipeline.  Completion is awaited by hand (wait_vmcnt) before the
-// workgroup barrier that publishes a buffer.
-__device__ __forceinline__ void lds_direct_load16(const void *sbase, uint32_t voff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :
-                 : "v"(voff), "s"(sbase), "s"(lds_base)
-                 : "memory");
-}
-
-// chunk swizzle of a code row in LDS (see the kernel): 128-byte rows use row & 7, 64-byte rows
-// (two rows per 128-byte bank line) use (row >> 1) & 3
-template <int BK>
-__device__ __forceinline__ int swz_bk(int row) { return BK == 128 ? (row & 7) : ((row >> 1) & 3); }
-
-// Same, 4 bytes per lane (LDS address lds_base + 4 * lane): used for the per-tile scale vectors.
-__device__ __forceinline__ void lds_direct_load4(const void *sbase, uint32_t voff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
-                 :
-                 : "v"(voff), "s"(sbase), "s"(lds_base)
-                 : "memory");
-}
-
-__device__ __forceinline__ uint32_t lds_address(const void *p) {
-    return (uint32_t)(uintptr_t)DVDQ_LDS(p);
-}
-
-// make a 64-bit pointer provably wave-uniform (lives in SGPRs)
-template <typename T>
-__device__ __forceinline__ const T *uniform_ptr(const T *p) {
-    const uint64_t v = reinterpret_cast<uint64_t>(p);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return reinterpret_cast<const T *>(((uint64_t)hi << 32) | lo);
-}
-
-}  // namespace
-
-// Tile order.  Tiles are numbered so that `group_n` output-column tiles run fastest,
-// then token tiles, then column groups: tiles with neighbouring numbers share code
-// panels and a bounded set of weight panels, which is what stays in an XCD's L2.
-__device__ __forceinline__ void tile_origin(int t, int tiles_m, int tiles_n, int group_n, int BM, int BN, int &m0,
-                                            int &n0) {
-    const int per_group = tiles_m * group_n;
-    const int grp = t / per_group;
-    const int in_grp = t - grp * per_group;
-    const int gw = min(group_n, tiles_n - grp * group_n);  // columns in this (possibly last, narrower) group
-    const int tile_m = in_grp / gw;
-    m0 = tile_m * BM;
-    n0 = (grp * group_n + (in_grp - tile_m * gw)) * BN;
-}
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int OCC, bool A4>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_kernel(
@@ -715,6 +625,8 @@ int g_schedule = -1; // -1: tiles drawn from counters where possible; 0: fixed s
 constexpr int kSchedSlots = 512;
 __device__ unsigned g_sched[kSchedSlots][16];
 
+}  // namespace
+
 // The counter slot for a launch on `stream`, or nullptr (fixed shares) when the launch is being
 // captured into a graph -- the same node may later run in several graph instances at once, which
 // must not share counters -- or when all slots are taken.
@@ -748,6 +660,8 @@ unsigned *sched_slot(hipStream_t stream) {
     }
     return base[dev] + it->second * 16;
 }
+
+namespace {
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int OCC, bool A4 = false>
 int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,

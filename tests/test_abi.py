@@ -49,7 +49,9 @@ def test_rotate_quant_argument_errors():
     assert f(FAKE, 4, 131072, 256, 4, 0, FAKE, FAKE, None, None) == 3       # K too large
     assert f(ODD, 4, 256, 256, 4, 0, FAKE, FAKE, None, None) == 5
     assert f(FAKE, 4, 256, 256, 6, 1, FAKE, FAKE, None, None) == 3       # packed container holds 4-bit codes only
-    assert f(FAKE, 4, 256, 256, 4, 2, FAKE, FAKE, None, None) == 3       # unknown container
+    assert f(FAKE, 4, 256, 256, 4, 7, FAKE, FAKE, None, None) == 3       # unknown container
+    assert f(FAKE, 4, 256, 256, 6, 2, FAKE, FAKE, None, None) == 3       # the FP6 container holds 4-bit codes only
+    assert f(FAKE, 4, 192, 64, 4, 2, FAKE, FAKE, None, None) == 3        # and whole 128-channel slices
 
 
 def test_rotate_quant_blockwise_argument_errors():
