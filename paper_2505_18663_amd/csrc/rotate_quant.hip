@@ -96,14 +96,15 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
     const uint16_t *__restrict__ x, int64_t M, int K, int waves_per_row, int rows_per_wg,
     double scale_mul,  // 1 / (sqrt(B) * qmax); fp64 so the fp32 scale is rounded once
     float recip_num,   // 1 / sqrt(B)
-    int via_lds,       // FMT 1 only: gather the packed codes through LDS into 16-byte stores (K % 32 == 0)
+    int via_lds,       // FMT 1: gather the packed codes through LDS into 16-byte stores (K % 32 == 0);
+                       // FMT 2: consecutive rows a wave takes in turn before it strides on (8, 4, 2 or 1)
     int group_log2,    // int8 container only: 0, or log2 of the channel group (7, 8, 9) of block-wise scaling
     int emax,          // block-wise scaling: largest power-of-two refinement of a group's step (8 - act_bits)
     int8_t *__restrict__ codes, float *__restrict__ x_scale,
     int32_t *__restrict__ code_rowsum) {  // NULL, or [M]: sum of the row's codes (for weight zero-points)
     extern __shared__ float s_amax[];  // [2][rows_per_wg * waves_per_row], slots alternate per iteration
     // then [2][rows_per_wg * waves_per_row] per-wave code sums, then, 16-byte aligned,
-    // [waves][CPW][64] dwords for gathering packed codes (via_lds), or [waves][CPW][96] dwords for FP6
+    // [waves][CPW][64] dwords for gathering packed codes (via_lds), or [waves][rows in turn][CPW * 384 + 16] bytes for FP6
     int32_t *s_sum = reinterpret_cast<int32_t *>(s_amax) + 2 * rows_per_wg * waves_per_row;
     uint32_t *s_pack = reinterpret_cast<uint32_t *>(s_amax) + (4 * rows_per_wg * waves_per_row + 3) / 4 * 4;
     constexpr bool PACK4 = FMT == 1;
@@ -155,15 +156,27 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
         }
     };
 
-    // Workgroups stride over the rows; the next row's loads are in flight while this one is processed.
-    const int64_t row_step = (int64_t)gridDim.x * rows_per_wg;
-    int64_t row = (int64_t)blockIdx.x * rows_per_wg + row_in_wg;
+    // Workgroups stride over groups of rows; the next row's loads are in flight while this one is
+    // processed.  A group is rows_per_wg rows handled at once, except for the FP6 container: there the
+    // waves of a row take `run` consecutive rows in turn (a group is rows_per_wg runs), because the
+    // 16-byte chunks of 8 neighbouring rows make up one 128-byte line of that layout; a wave collects
+    // its chunks of a run in LDS and writes them as whole lines (16-byte stores scattered over 64 lines
+    // per instruction make the whole kernel take twice as long).
+    const int run = FMT == 2 ? via_lds : 1;
+    // row of wave row 0 in the workgroup's it-th iteration; wave row r is r * run rows further on
+    auto first_row_of = [&] __device__(int64_t it) {
+        const int64_t g = it / run;
+        return ((int64_t)blockIdx.x + g * gridDim.x) * (run * rows_per_wg) + (it - g * run);
+    };
+    int64_t it = 0;
+    int64_t row = first_row_of(0) + row_in_wg * run;
     uint4 raw[CPW];
     load_row(raw, row);
     int slot = 0;
-    for (int64_t base = (int64_t)blockIdx.x * rows_per_wg; base < M; base += row_step, row += row_step, slot ^= 1) {
+    for (int64_t base = first_row_of(0); base < M; slot ^= 1) {
+        const int64_t next_base = first_row_of(++it);
         uint4 nxt[CPW];
-        load_row(nxt, row + row_step);
+        load_row(nxt, next_base + row_in_wg * run);
         const bool row_ok = row < M;
 
         float v[CPW][8];
@@ -223,34 +236,36 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
         int csum = 0;                    // this lane's share of the row's code sum (padding chunks hold zeros)
         if (FMT == 2) {
             // FP6 container: code c as the E2M3 pattern (c < 0) << 5 | |c|.  The magnitude comes from the
-            // same fused multiply-add on absolute values (round-half-even is symmetric), the sign from
-            // the sign bits of value and reciprocal.  A lane's 8 fields are 48 bits; summing
-            // (magic + |c|) << 6 i and taking the magic's known contribution off once leaves the fields
-            // packed.  A unit's 384 bytes are put together in wave-private LDS in channel order and leave
-            // as 16-byte chunks: chunk j of a row's 128-channel slice goes to
-            // [row / 32][slice][j][row % 32][16 B].
-            uint8_t *sp = reinterpret_cast<uint8_t *>(s_pack) + wave * (CPW * 384);
+            // same fused multiply-add on absolute values (round-half-even is symmetric); the value's sign
+            // bit is or-ed in at bit 5, and the sign of the reciprocal (the same for all 8 values of a lane)
+            // flips the 8 sign positions at the end.  A lane's 8 fields are 48 bits; summing
+            // (magic + field) << 6 i and taking the magic's known contribution off once leaves the fields
+            // packed.  The bytes of the group's rows are put together in LDS in channel order.
+            constexpr int TURN_BYTES = CPW * 384 + 16;   // + 16: the 8 turns a quarter-wave reads back sit in different banks
+            const int turn = (int)((it - 1) % run);
+            uint8_t *stage = reinterpret_cast<uint8_t *>(s_pack) + wave * (run * TURN_BYTES);
+            uint8_t *sp = stage + turn * TURN_BYTES;
             const uint32_t rsign = __float_as_uint(r) & 0x80000000u;
+            const uint32_t rflip_lo = rsign ? 0x20820820u : 0u;   // bits 5, 11, 17, 23, 29: the signs of fields 0..4
+            const uint32_t rflip_hi = rsign ? 0x8208u : 0u;       // bits 3, 9, 15 of the upper 16: fields 5..7
             constexpr uint32_t MB = 0x4B400000u;   // bit pattern of the magic number
             constexpr uint32_t LO_C = MB + (MB << 6) + (MB << 12) + (MB << 18) + (MB << 24) + (MB << 30);
             constexpr uint32_t HI_C = (MB >> 2) + (MB << 4) + (MB << 10);
 #pragma unroll
             for (int c = 0; c < CPW; ++c) {
-                uint32_t t[8], sg[8];
+                uint32_t t[8];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    t[i] = __float_as_uint(fmaf(fabsf(v[c][i]), fabsf(r), magic));
-                    sg[i] = (__float_as_uint(v[c][i]) ^ rsign) >> 31;
-                }
+                for (int i = 0; i < 8; ++i)
+                    t[i] = __float_as_uint(fmaf(fabsf(v[c][i]), fabsf(r), magic)) | ((__float_as_uint(v[c][i]) >> 26) & 32u);
                 uint32_t lo = t[0] + (t[1] << 6) + (t[2] << 12) + (t[3] << 18) + (t[4] << 24) + (t[5] << 30) - LO_C;
                 uint32_t hi = ((t[5] >> 2) + (t[6] << 4) + (t[7] << 10) - HI_C) & 0xFFFFu;
-                lo |= (sg[0] << 5) | (sg[1] << 11) | (sg[2] << 17) | (sg[3] << 23) | (sg[4] << 29);
-                hi |= (sg[5] << 3) | (sg[6] << 9) | (sg[7] << 15);
+                lo ^= rflip_lo;
+                hi ^= rflip_hi;
                 if (code_rowsum) {
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
                         const int mag = (int)(t[i] & 0xFu);
-                        csum += sg[i] ? -mag : mag;
+                        csum += (((t[i] >> 5) & 1u) != (rsign >> 31)) ? -mag : mag;
                     }
                 }
                 uint8_t *d = sp + c * 384 + chunk * 6;   // 4-byte aligned for even chunks, 2-byte for odd ones
@@ -262,21 +277,29 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
                     *reinterpret_cast<uint16_t *>(d + 4) = (uint16_t)hi;
                 }
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            const int slices = K >> 7;
-            uint8_t *out = reinterpret_cast<uint8_t *>(codes) + ((row >> 5) * slices) * 3072 + (row & 31) * 16;
-#pragma unroll
-            for (int idx0 = 0; idx0 < CPW * 24; idx0 += kWave) {
-                const int idx = idx0 + lane, c = idx / 24, part = idx - c * 24;
-                const int g = (wsub + c * waves_per_row) * 24 + part;   // 16-byte chunk of the row
-                const int slice = g / 6, j = g - slice * 6;
-                if (idx < CPW * 24 && row_ok && slice < slices)
-                    *reinterpret_cast<uint4 *>(out + (int64_t)slice * 3072 + j * 512) =
-                        *reinterpret_cast<const uint4 *>(sp + c * 384 + part * 16);
+            if (turn == run - 1 || next_base >= M) {
+                // the run is complete (or the rows are): chunk j of slice s of rows row0 .. row0 + run - 1 is the
+                // line [row / 32][s][j][row % 32][16 B]; neighbouring lanes take neighbouring rows.  Wave-private
+                // LDS, in order: no workgroup barrier.
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                const int64_t row0 = row - turn;
+                const int slices = K >> 7;
+                for (int idx0 = 0; idx0 < CPW * 24 * run; idx0 += kWave) {
+                    const int idx = idx0 + lane;
+                    const int L = idx / run, rr = idx - L * run;          // chunk of the wave's units, turn
+                    const int c = L / 24, part = L - c * 24;
+                    const int g = (wsub + c * waves_per_row) * 24 + part;  // 16-byte chunk of the row
+                    const int slice = g / 6, j = g - slice * 6;
+                    const int64_t grow = row0 + rr;
+                    if (idx < CPW * 24 * run && rr <= turn && grow < M && slice < slices)
+                        *reinterpret_cast<uint4 *>(reinterpret_cast<uint8_t *>(codes) +
+                                                   ((grow >> 5) * slices + slice) * 3072 + j * 512 + (grow & 31) * 16) =
+                            *reinterpret_cast<const uint4 *>(stage + rr * TURN_BYTES + c * 384 + part * 16);
+                }
+                __builtin_amdgcn_wave_barrier();   // the next run's LDS writes stay behind these reads
             }
-            __builtin_amdgcn_wave_barrier();   // the next row's LDS writes stay behind these reads
         } else if (PACK4) {
             // two codes per byte, in the nibble order the GEMM widens with two masks: byte b of a
             // chunk's dword = code[b] (bits 0-3) | code[b + 4] (bits 4-7), two's complement
@@ -372,6 +395,8 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
         }
 #pragma unroll
         for (int c = 0; c < CPW; ++c) raw[c] = nxt[c];
+        base = next_base;
+        row = next_base + row_in_wg * run;
     }
 }
 
@@ -383,7 +408,7 @@ int launch_cpw(int cpw, dim3 grid, dim3 block, size_t smem, hipStream_t stream, 
     case C:                                                                                               \
         if (pack4 == 3)                                                                                   \
             hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C, 2>), grid, block, smem, stream, x, M, K, W, \
-                               rpw, scale_mul, recip_num, 0, 0, 0, codes, x_scale, code_rowsum);          \
+                               rpw, scale_mul, recip_num, group_log2, 0, 0, codes, x_scale, code_rowsum); \
         else if (pack4)                                                                                   \
             hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C, 1>), grid, block, smem, stream, x, M, K, W, \
                                rpw, scale_mul, recip_num, pack4 == 2, 0, 0, codes, x_scale, code_rowsum); \
@@ -418,14 +443,21 @@ int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block,
     const dim3 block(kWave * W * rows_per_wg);
     // resident workgroups: a whole number per compute unit (256 of them), about 16 waves each,
     // every workgroup striding over the rows
-    const int64_t wgs_needed = (M + rows_per_wg - 1) / rows_per_wg;
+    // FP6: consecutive rows a wave takes in turn (see the kernel): 8 if the LDS for collecting them allows
     int wgs_per_cu = 16 / (W * rows_per_wg);
     if (wgs_per_cu < 1) wgs_per_cu = 1;
+    int run = 1;
+    if (pack4 == 3) {
+        const size_t budget = wgs_per_cu <= 2 ? 65536 - 4096 : (size_t)150 * 1024 / wgs_per_cu;
+        for (run = 8; run > 1 && (size_t)W * rows_per_wg * run * (cpw * 384 + 16) > budget;) run /= 2;
+    }
+    const int group_rows = rows_per_wg * run;
+    const int64_t wgs_needed = (M + group_rows - 1) / group_rows;
     const int64_t wgs_resident = 256 * (int64_t)wgs_per_cu;
     const dim3 grid((unsigned)(wgs_needed < wgs_resident ? wgs_needed : wgs_resident));
     size_t smem = 4 * sizeof(float) * W * rows_per_wg;   // abs-max slots, then code-sum slots
     if (pack4 == 2) smem = (smem + 15) / 16 * 16 + (size_t)W * rows_per_wg * cpw * 256;
-    if (pack4 == 3) smem = (smem + 15) / 16 * 16 + (size_t)W * rows_per_wg * cpw * 384;
+    if (pack4 == 3) smem = (smem + 15) / 16 * 16 + (size_t)W * rows_per_wg * run * (cpw * 384 + 16);
     const double qmax = (double)((1 << (act_bits - 1)) - 1);
     const double norm = 1.0 / sqrt((double)(1 << log2_block));
     const double scale_mul = norm / qmax;
@@ -433,7 +465,7 @@ int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block,
 #define DVDQ_RQ_B(L)                                                                                        \
     case L:                                                                                                 \
         return launch_cpw<L>(cpw, grid, block, smem, stream, x, M, (int)K, W, rows_per_wg, scale_mul,       \
-                             recip_num, pack4, group_log2, emax, codes, x_scale, code_rowsum);
+                             recip_num, pack4, pack4 == 3 ? run : group_log2, emax, codes, x_scale, code_rowsum);
     switch (log2_block) {
         DVDQ_RQ_B(0) DVDQ_RQ_B(1) DVDQ_RQ_B(2) DVDQ_RQ_B(3) DVDQ_RQ_B(4)
         DVDQ_RQ_B(5) DVDQ_RQ_B(6) DVDQ_RQ_B(7) DVDQ_RQ_B(8) DVDQ_RQ_B(9)

@@ -53,6 +53,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_ker
     constexpr int W_DMA = W_STAGE / 1024 / NW;
     constexpr int DMA = A_DMA + W_DMA;
     constexpr int GROUPS = 2 * TN;                       // MFMA groups (TM MFMAs each) per item
+#ifndef DVDQ_FP6_DMA_PER_GROUP
+#define DVDQ_FP6_DMA_PER_GROUP 2
+#endif
+    constexpr int DMA_PER_GROUP = DVDQ_FP6_DMA_PER_GROUP;  // the next slice's loads go out with the first MFMA groups
+    static_assert(GROUPS * DMA_PER_GROUP >= DMA, "not every load of an item would be issued");
     // one tile's epilogue vectors in LDS: token scales, channel scales (fp32), bias (bf16), and for
     // weights with zero-points the tokens' code sums (int32) and the channels' zero-points (int8)
     constexpr int OFF_BIAS = (BM + BN) * 4, OFF_RSUM = OFF_BIAS + BN * 2, OFF_ZERO = OFF_RSUM + BM * 4;
@@ -267,7 +272,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_ker
                 for (int j = 0; j < TM; ++j)   // both operands FP6 E2M3 (format code 2), no block scales
                     acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fw, fa[j], acc[i][j], 2, 2, 0, 0, 0, 0);
 #pragma unroll
-                for (int d = s * TN + i; d < DMA; d += GROUPS) issue_one(d);
+                for (int d = (s * TN + i) * DMA_PER_GROUP; d < DMA && d < (s * TN + i + 1) * DMA_PER_GROUP; ++d) issue_one(d);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -298,6 +303,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_ker
             if (KT >= STAGES) store_credit = 1;
             auto interior = [&] __device__(auto has_zero) __attribute__((always_inline)) {
                 constexpr bool ZP = decltype(has_zero)::value;
+                // Lane-dependent addresses of the epilogue are derived from a lane number the compiler cannot
+                // trace back: computed here once per tile instead of being kept (and spilled) across the K loop.
+                int lane_e = lane;
+                asm volatile("" : "+v"(lane_e));
+                const int frow = lane_e & 31, fhalf = lane_e >> 5;
                 const float *ws_l = s_ws + wn + fhalf * 4;
                 const uint32_t *bias_l = reinterpret_cast<const uint32_t *>(s_tile + OFF_BIAS) + (wn + fhalf * 4) / 2;
                 const uint32_t *zero_l = reinterpret_cast<const uint32_t *>(s_tile + OFF_ZERO) + (wn + fhalf * 4) / 4;
@@ -309,7 +319,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_ker
                     rsum[j] = ZP ? s_rsum[wm + j * 32 + frow] : 0;
                 }
                 uint8_t *stg = smem + (q % STAGES) * STAGE + wave * 4096;
-                const int rd_row = lane >> 3, rd_piece = lane & 7;
+                const int rd_row = lane_e >> 3, rd_piece = lane_e & 7;
                 struct ChannelVec { float4 ws; uint2 bb; uint32_t zq; };
                 auto fetch = [&] __device__(ChannelVec &cv, int i, int g) {
                     const int c = i * 32 + g * 8;
@@ -396,6 +406,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_ker
         }
         // ---- edge tiles, N not a multiple of 8, or the accumulator hook: predicated per element, through
         // the integer accumulator (same values and rounding order as the interior path)
+        int lane_s = lane;   // (as in the interior path: keeps this path's addresses out of the K loop's registers)
+        asm volatile("" : "+v"(lane_s));
+        const int frow = lane_s & 31, fhalf = lane_s >> 5;
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
             const int m = m0 + wm + j * 32 + frow;
