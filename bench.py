@@ -5,12 +5,15 @@ A step is one pass of the whole path -- dvdq_qlinear: block-Hadamard rotation,
 per-token auto-scale, quantization, INT4 x INTb GEMM, dequantizing epilogue --
 over one batch of synthetic activations of the small-video-DiT QKV projection
 (M=32760 tokens, K=1536, N=4608, W4A4, Hadamard block 256).  Inputs are resident
-in HBM before the timed region; weights are pre-packed offline.  Between the two
-kernels 4-bit codes travel packed two per byte (the int8 container otherwise).
+in HBM before the timed region; weights are pre-packed offline.  W4A4 runs on the
+FP6 matrix path (4-bit codes carried as E2M3 patterns, integer-exact, twice the INT8
+matrix rate; --w4a4-path int8 selects the INT8 matrix path with codes packed two per
+byte); other bit-widths run on the INT8 matrix path with the int8 container.
 
 Prints ONE JSON line: whole-path throughput in TOP/s (2*M*N*K per step), the
-roofline of the dominant kernel (the INT8-MFMA GEMM) from per-launch HIP-event
-timings, the same for the HBM-bound rotate+quantize kernel, and the CPU oracle
+roofline of the dominant kernel (the GEMM, against the matrix peak of the operand
+type it runs on) from per-launch HIP-event timings, the same for the HBM-bound
+rotate+quantize kernel, the other W4A4 matrix path for reference, and the CPU oracle
 timed on this machine's host cores on a bounded token sample.
 """
 import argparse
@@ -23,16 +26,20 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 INT8_MFMA_PEAK_TOPS = 5000.0     # published dense INT8 matrix peak, MI355X
+FP6_MFMA_PEAK_TOPS = 10100.0     # published dense FP6 / FP4 matrix peak, MI355X
 HBM_PEAK_GBPS = 8000.0           # published HBM3E bandwidth, MI355X
 
 # HBM bytes per launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
 # very command, scaled by the same counters' reading for dvdq_bench_copy; the summaries with the
 # commands are profiles/bench_<workload>_hbm_counters.md.  None where no counter run exists.
-MEASURED_HBM_TRAFFIC = {
-    "small_dit_qkv_w4a4": {"w4ax_gemm": 391.6e6, "rotate_quant": 126.2e6},
-    "small_dit_ffn_up_w4a6": {"w4ax_gemm": 950.6e6, "rotate_quant": 151.3e6},
-    "large_dit_proj_w4a4": {"w4ax_gemm": 2060.0e6, "rotate_quant": 914.4e6},
-    "large_dit_ffn_down_w4a4": {"w4ax_gemm": 3546.7e6, "rotate_quant": 1133.3e6},
+MEASURED_HBM_TRAFFIC = {   # keyed by (workload, container of the codes between the two kernels)
+    ("small_dit_qkv_w4a4", "fp6"): {"gemm": 459.7e6, "rotate_quant": 138.6e6},
+    ("small_dit_qkv_w4a4", "packed4"): {"gemm": 368.0e6, "rotate_quant": 126.2e6},
+    ("small_dit_ffn_up_w4a6", "int8"): {"gemm": 795.6e6, "rotate_quant": 151.3e6},
+    ("large_dit_proj_w4a4", "fp6"): {"gemm": 2807.9e6, "rotate_quant": 1004.3e6},
+    ("large_dit_proj_w4a4", "packed4"): {"gemm": 2000.5e6, "rotate_quant": 914.3e6},
+    ("large_dit_ffn_down_w4a4", "fp6"): {"gemm": 5888.6e6, "rotate_quant": 1245.9e6},
+    ("large_dit_ffn_down_w4a4", "packed4"): {"gemm": 3445.9e6, "rotate_quant": 1133.3e6},
 }
 
 
@@ -43,6 +50,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", type=int, default=1, help="index into the five configs (default: the headline one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--w4a4-path", choices=("fp6", "int8"), default="fp6",
+                    help="matrix path of 4-bit activations: FP6 (E2M3 patterns, default) or INT8 (packed nibbles)")
     ap.add_argument("--bufs", type=int, default=3, help="input/output buffer sets rotated through (cache defeat)")
     return ap.parse_args()
 
@@ -73,9 +82,15 @@ def main():
     nb = max(1, args.bufs)
     x0 = torch.from_numpy(xb.view(np.int16)).view(torch.bfloat16).to(dev)
     xs = [x0] + [x0.clone() for _ in range(nb - 1)]
-    w_native = dvdq.w4_prepack(torch.from_numpy(wp).to(dev))
+    wp_dev = torch.from_numpy(wp).to(dev)
     ws_dev = torch.from_numpy(ws).to(dev)
-    fmt = dvdq.CODES_PACKED4 if bits == 4 else dvdq.CODES_INT8
+    use_fp6 = bits == 4 and args.w4a4_path == "fp6"
+    if use_fp6:
+        fmt, lay, w_native = dvdq.CODES_FP6, dvdq.W_NATIVE_FP6, dvdq.w4_prepack_fp6(wp_dev)
+    else:
+        fmt, lay, w_native = (dvdq.CODES_PACKED4 if bits == 4 else dvdq.CODES_INT8), dvdq.W_NATIVE, dvdq.w4_prepack(wp_dev)
+    fmt_name = {dvdq.CODES_INT8: "int8", dvdq.CODES_PACKED4: "packed4", dvdq.CODES_FP6: "fp6"}[fmt]
+    peak_tops = FP6_MFMA_PEAK_TOPS if use_fp6 else INT8_MFMA_PEAK_TOPS
     need = dvdq.qlinear_workspace_bytes(M, K, fmt)
     wsp = [torch.empty((need,), dtype=torch.uint8, device=dev) for _ in range(nb)]
     ys = [torch.empty((M, N), dtype=torch.bfloat16, device=dev) for _ in range(nb)]
@@ -83,7 +98,7 @@ def main():
 
     def step(i):
         j = i % nb
-        dvdq.qlinear(xs[j], w_native, ws_dev, B, bits, dvdq.W_NATIVE, y=ys[j], workspace=wsp[j], codes_format=fmt)
+        dvdq.qlinear(xs[j], w_native, ws_dev, B, bits, lay, y=ys[j], workspace=wsp[j], codes_format=fmt)
 
     # ---- timed region: whole path.  Before the W warm-up steps the same step runs for about half a
     # second: coming out of idle the chip needs tens of milliseconds to settle its clocks, and
@@ -129,13 +144,13 @@ def main():
 
     def gemm(i):
         j = i % nb
-        dvdq.w4ax_gemm(views[j][0], views[j][1], w_native, ws_dev, bits, dvdq.W_NATIVE, y=ys[j], codes_format=fmt)
+        dvdq.w4ax_gemm(views[j][0], views[j][1], w_native, ws_dev, bits, lay, y=ys[j], codes_format=fmt, K=K)
 
     # The two kernels of the path in the order the fused call runs them, one event after every
     # kernel: a kernel's duration is the time between the events around it.  Measured in this
     # context (the quantizer runs while the GEMM's output is still draining from the memory-side
     # cache; the GEMM finds the codes the quantizer just wrote) the two durations add up to the step.
-    def time_in_context(n):
+    def time_in_context(n, rq=rq, gemm=gemm):
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(2 * n + 1)]
         for i in range(min(args.warmup, 5)):
             rq(i)
@@ -156,7 +171,32 @@ def main():
     # the same kernels launched back to back on their own (no other kernel in between)
     rq_alone, _ = time_launches(rq, args.steps)
     gemm_alone, _ = time_launches(gemm, args.steps)
-    code_bytes = 0.5 if fmt == dvdq.CODES_PACKED4 else 1.0
+    # ---- W4A4 only: the other matrix path on the same inputs (separate workspaces), same in-context timing
+    other_path = None
+    if bits == 4:
+        if use_fp6:
+            o_fmt, o_lay, o_w, o_name, o_peak = dvdq.CODES_PACKED4, dvdq.W_NATIVE, dvdq.w4_prepack(wp_dev), "int8 matrix path, packed4 codes", INT8_MFMA_PEAK_TOPS
+        else:
+            o_fmt, o_lay, o_w, o_name, o_peak = dvdq.CODES_FP6, dvdq.W_NATIVE_FP6, dvdq.w4_prepack_fp6(wp_dev), "fp6 matrix path", FP6_MFMA_PEAK_TOPS
+        o_wsp = [torch.empty((dvdq.qlinear_workspace_bytes(M, K, o_fmt),), dtype=torch.uint8, device=dev) for _ in range(nb)]
+        o_views = [dvdq.workspace_views(w_, M, K, o_fmt) for w_ in o_wsp]
+
+        def o_rq(i):
+            j = i % nb
+            dvdq.rotate_quant(xs[j], B, bits, codes=o_views[j][0], x_scale=o_views[j][1], codes_format=o_fmt)
+
+        def o_gemm(i):
+            j = i % nb
+            dvdq.w4ax_gemm(o_views[j][0], o_views[j][1], o_w, ws_dev, bits, o_lay, y=ys[j], codes_format=o_fmt, K=K)
+        o_rq_avg, _, o_gemm_avg, _ = time_in_context(args.steps, o_rq, o_gemm)
+        o_step = o_rq_avg + o_gemm_avg
+        other_path = {"path": o_name, "ms_per_step": round(o_step, 4), "value": round(ops / (o_step * 1e-3) / 1e12, 2),
+                      "unit": "TOP/s", "gemm_avg_launch_ms": round(o_gemm_avg, 4),
+                      "gemm_frac_of_its_peak": round(ops / (o_gemm_avg * 1e-3) / 1e12 / o_peak, 4), "gemm_peak": o_peak,
+                      "rotate_quant_avg_launch_ms": round(o_rq_avg, 4)}
+        del o_wsp, o_views, o_w
+
+    code_bytes = {dvdq.CODES_INT8: 1.0, dvdq.CODES_PACKED4: 0.5, dvdq.CODES_FP6: 0.75}[fmt]
     rq_bytes = 2.0 * M * K + code_bytes * M * K + 4.0 * M      # bf16 in, codes out, fp32 scales out
     rq_gbps = rq_bytes / (rq_avg * 1e-3) / 1e9
     # the same kernel writing the int8 container (3 bytes per element), for reference
@@ -179,6 +219,11 @@ def main():
         mfma_ops[0] = dvdq.bench_mfma_i8(2000, sink)
     mfma_avg, _ = time_launches(mfma, 4, group=2)
     mfma_ceiling = mfma_ops[0] / (mfma_avg * 1e-3) / 1e12
+
+    def mfma6(i):
+        mfma_ops[0] = dvdq.bench_mfma_fp6(2000, sink)
+    mfma6_avg, _ = time_launches(mfma6, 4, group=2)
+    mfma6_ceiling = mfma_ops[0] / (mfma6_avg * 1e-3) / 1e12
     del src, dst
 
     # ---- the delta-GBS controller step on a 720p-class latent (16 x 33 x 90 x 160 bf16 values):
@@ -194,11 +239,12 @@ def main():
     blockwise = None
     if bits in (4, 6):
         vals = [torch.empty((M, K), dtype=torch.int8, device=dev) for _ in range(nb)]
+        w_int8_path = w_native if lay == dvdq.W_NATIVE else dvdq.w4_prepack(wp_dev)
 
         def bw(i):
             j = i % nb
             dvdq.rotate_quant_blockwise(xs[j], B, bits, 128, values=vals[j], x_scale=views[j][1])
-            dvdq.w4ax_gemm(vals[j], views[j][1], w_native, ws_dev, 8, dvdq.W_NATIVE, y=ys[j])
+            dvdq.w4ax_gemm(vals[j], views[j][1], w_int8_path, ws_dev, 8, dvdq.W_NATIVE, y=ys[j])
         bw_avg, _ = time_launches(bw, args.steps)
         blockwise = {"group": 128, "ms_per_step": round(bw_avg, 4), "value": round(ops / (bw_avg * 1e-3) / 1e12, 2),
                      "unit": "TOP/s", "codes_format": "int8"}
@@ -213,20 +259,25 @@ def main():
         "metric": "fused W4A4 qlinear TOPS & % INT8-MFMA peak; rotate+quant HBM GB/s",
         "value": round(tops, 2), "unit": "TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(t_step * 1e3, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "int8 x int4 -> int32 (bf16 in/out)", "data": "synthetic",
+        "vs_baseline": None,
+        "dtype": ("fp6 e2m3 x fp6 e2m3 -> fp32, integer-exact (int4 codes; bf16 in/out)" if use_fp6
+                  else "int8 x int4 -> int32 (bf16 in/out)"),
+        "data": "synthetic",
         "config": {"workload": wl.name, "M": M, "K": K, "N": N, "had_block": B, "act_bits": bits,
-                   "w_layout": "native", "codes_format": "packed4" if fmt == dvdq.CODES_PACKED4 else "int8",
-                   "buffers_rotated": nb},
+                   "w_layout": "native_fp6" if use_fp6 else "native", "codes_format": fmt_name,
+                   "matrix_path": "fp6" if use_fp6 else "int8", "buffers_rotated": nb},
         "frac_int8_mfma_peak": round(tops / INT8_MFMA_PEAK_TOPS, 4),
-        "roofline": {"kernel": "w4ax_gemm", "bound": "mfma", "achieved": round(gemm_tops, 2),
-                     "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(gemm_tops / INT8_MFMA_PEAK_TOPS, 4),
-                     "traffic": MEASURED_HBM_TRAFFIC.get(wl.name, {}).get("w4ax_gemm"),
+        "roofline": {"kernel": "w4a4_fp6_gemm" if use_fp6 else "w4ax_gemm", "bound": "mfma", "achieved": round(gemm_tops, 2),
+                     "peak": peak_tops, "unit": "TOP/s", "frac": round(gemm_tops / peak_tops, 4),
+                     "traffic": MEASURED_HBM_TRAFFIC.get((wl.name, fmt_name), {}).get("gemm"),
                      "avg_launch_ms": round(gemm_avg, 4), "median_launch_ms": round(gemm_med, 4),
                      "avg_launch_ms_alone": round(gemm_alone, 4),
-                     "measured_mfma_ceiling_tops": round(mfma_ceiling, 1)},
+                     "frac_of_int8_peak": round(gemm_tops / INT8_MFMA_PEAK_TOPS, 4),
+                     "measured_mfma_ceiling_tops": round(mfma6_ceiling if use_fp6 else mfma_ceiling, 1),
+                     "measured_int8_mfma_ceiling_tops": round(mfma_ceiling, 1)},
         "roofline_rotate_quant": {"kernel": "rotate_quant", "bound": "hbm", "achieved": round(rq_gbps, 1),
                                   "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(rq_gbps / HBM_PEAK_GBPS, 4),
-                                  "traffic": MEASURED_HBM_TRAFFIC.get(wl.name, {}).get("rotate_quant"),
+                                  "traffic": MEASURED_HBM_TRAFFIC.get((wl.name, fmt_name), {}).get("rotate_quant"),
                                   "avg_launch_ms": round(rq_avg, 4),
                                   "median_launch_ms": round(rq_med, 4), "avg_launch_ms_alone": round(rq_alone, 4),
                                   "algorithmic_bytes": rq_bytes,
@@ -240,6 +291,8 @@ def main():
     out["gbs_controller"] = {"elements": n_lat, "us_per_step": round(gbs_avg * 1e3, 2),
                              "achieved_gbps": round(4.0 * n_lat / (gbs_avg * 1e-3) / 1e9, 1), "bound": "hbm (launch-bound at this size)"}
 
+    if other_path:
+        out["other_w4a4_path"] = other_path
     if blockwise:
         out["blockwise_scaling"] = blockwise
     out["bgr_quantizer"] = {"rows": N, "K": K, "n_steps": 100, "max_refine": 10, "ms": round(bgr_ms, 2),

@@ -28,6 +28,10 @@ int dvdq_bench_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
  * number of integer operations (2 per multiply-add) the launch performs. */
 int dvdq_bench_mfma_i8(int iters, int32_t *sink, double *ops_out, void *hip_stream);
 
+/* The same with `iters` x 8 independent 32x32x64 MFMAs on FP6 (E2M3) operands, the instruction the
+ * W4A4 GEMM of the FP6 matrix path issues. */
+int dvdq_bench_mfma_fp6(int iters, int32_t *sink, double *ops_out, void *hip_stream);
+
 /* Tile-configuration sweeps: force the native-layout GEMM to use tile variant `variant`
  * (1..4, see the dispatch tables in w4ax_gemm.hip, one per code container; shapes too shallow
  * in K for a variant's ring fall back to variant 2); -1 restores the library's own choice.  Process-wide,

@@ -16,7 +16,7 @@ import torch
 __all__ = [
     "DvdqError", "DvdqLibraryMissing", "lib", "library_path", "version", "status_string",
     "rotate_quant", "rotate_quant_blockwise", "w4ax_gemm", "qlinear", "qlinear_workspace_bytes", "qlinear_scale_offset", "qlinear_rowsum_offset", "workspace_rowsum",
-    "w4_prepack", "w4_native_bytes", "w4_prepack_fp6", "w4_native_fp6_bytes", "codes_bytes", "bgr_quantize", "GbsController", "bench_copy", "bench_mfma_i8", "bench_set_gemm_variant", "bench_set_gemm_schedule",
+    "w4_prepack", "w4_native_bytes", "w4_prepack_fp6", "w4_native_fp6_bytes", "codes_bytes", "bgr_quantize", "GbsController", "bench_copy", "bench_mfma_i8", "bench_mfma_fp6", "bench_set_gemm_variant", "bench_set_gemm_schedule",
     "W_CANONICAL", "W_NATIVE", "W_NATIVE_FP6", "CODES_INT8", "CODES_PACKED4", "CODES_FP6", "EXPORTED_SYMBOLS",
 ]
 
@@ -27,7 +27,7 @@ EXPORTED_SYMBOLS = (
     "dvdq_rotate_quant", "dvdq_rotate_quant_blockwise", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_qlinear_workspace_bytes",
     "dvdq_qlinear_scale_offset", "dvdq_qlinear_rowsum_offset", "dvdq_w4_prepack", "dvdq_w4_native_bytes", "dvdq_w4_prepack_fp6",
     "dvdq_w4_native_fp6_bytes", "dvdq_codes_bytes", "dvdq_status_string",
-    "dvdq_version", "dvdq_gbs_workspace_bytes", "dvdq_gbs_reset", "dvdq_gbs_step", "dvdq_bgr_quantize", "dvdq_bench_copy", "dvdq_bench_mfma_i8", "dvdq_bench_set_gemm_variant", "dvdq_bench_set_gemm_schedule",
+    "dvdq_version", "dvdq_gbs_workspace_bytes", "dvdq_gbs_reset", "dvdq_gbs_step", "dvdq_bgr_quantize", "dvdq_bench_copy", "dvdq_bench_mfma_i8", "dvdq_bench_mfma_fp6", "dvdq_bench_set_gemm_variant", "dvdq_bench_set_gemm_schedule",
 )
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -88,6 +88,8 @@ def lib() -> C.CDLL:
     L.dvdq_bgr_quantize.restype = i32
     L.dvdq_bench_copy.argtypes = [vp, vp, sz, vp]
     L.dvdq_bench_mfma_i8.argtypes = [i32, vp, C.POINTER(C.c_double), vp]
+    L.dvdq_bench_mfma_fp6.argtypes = [i32, vp, C.POINTER(C.c_double), vp]
+    L.dvdq_bench_mfma_fp6.restype = i32
     L.dvdq_bench_set_gemm_variant.argtypes = [i32]
     L.dvdq_bench_set_gemm_variant.restype = i32
     L.dvdq_bench_set_gemm_schedule.argtypes = [i32]
@@ -396,6 +398,12 @@ def bench_copy(src, dst, stream=None):
 def bench_mfma_i8(iters: int, sink, stream=None) -> float:
     ops = C.c_double(0.0)
     _check(lib().dvdq_bench_mfma_i8(iters, _ptr(sink), C.byref(ops), _stream(stream)), "dvdq_bench_mfma_i8")
+    return ops.value
+
+
+def bench_mfma_fp6(iters: int, sink, stream=None) -> float:
+    ops = C.c_double(0.0)
+    _check(lib().dvdq_bench_mfma_fp6(iters, _ptr(sink), C.byref(ops), _stream(stream)), "dvdq_bench_mfma_fp6")
     return ops.value
 
 

@@ -1,5 +1,5 @@
-// Calibration kernels for the benchmark: a plain copy and a register-only INT8
-// MFMA loop.  Neither is part of the layer.
+// Calibration kernels for the benchmark: a plain copy and register-only MFMA loops (INT8 and
+// FP6).  None is part of the layer.
 #include "dvdq_internal.h"
 #include "../../include/dvdq_bench.h"
 
@@ -33,6 +33,32 @@ __global__ __launch_bounds__(256) void mfma_i8_kernel(int iters, int32_t *sink) 
     if (s == 0x7fffffff) sink[0] = s;  // practically never true; keeps the loop alive
 }
 
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(256) void mfma_fp6_kernel(int iters, int32_t *sink) {
+    // E2M3 patterns of small integers / 8 in every field (values stay finite: the sums are bounded by iters)
+    v8i a = {0x04104104, 0x41041041, 0x10410410, 0x04104104, 0x41041041, 0x10410410, 0, 0};
+    v8i b = {0x08208208, (int)0x82082082, 0x20820820, 0x08208208, (int)0x82082082, 0x20820820, 0, 0};
+    a[0] ^= (int)(threadIdx.x & 3);
+    v16f acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            acc[t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[t], 2, 2, 0, 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[t][r];
+    if (s == -1.f) sink[0] = 1;  // never true (the sums are positive); keeps the loop alive
+}
+
 constexpr int kMfmaBlocks = 256 * 2;  // two 4-wave workgroups per compute unit
 
 }  // namespace
@@ -57,6 +83,15 @@ int dvdq_bench_mfma_i8(int iters, int32_t *sink, double *ops_out, void *hip_stre
     hipLaunchKernelGGL(mfma_i8_kernel, dim3(kMfmaBlocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream), iters,
                        sink);
     if (ops_out) *ops_out = 2.0 * 32 * 32 * 32 * 16.0 * iters * 4.0 * kMfmaBlocks;
+    return dvdq::check_launch();
+}
+
+int dvdq_bench_mfma_fp6(int iters, int32_t *sink, double *ops_out, void *hip_stream) {
+    if (!sink) return DVDQ_ERR_NULL;
+    if (iters < 1) return DVDQ_ERR_SHAPE;
+    hipLaunchKernelGGL(mfma_fp6_kernel, dim3(kMfmaBlocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream), iters,
+                       sink);
+    if (ops_out) *ops_out = 2.0 * 32 * 32 * 64 * 8.0 * iters * 4.0 * kMfmaBlocks;
     return dvdq::check_launch();
 }
 

@@ -543,7 +543,10 @@ int launch_fp6(const uint8_t *codes, const float *x_scale, const uint8_t *w, con
                const int32_t *code_rowsum, const uint16_t *bias, int M, int N, int K, uint16_t *y, int32_t *acc_out,
                hipStream_t stream) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    const int n_groups = (tiles_n + 15) / 16;
+#ifndef DVDQ_FP6_GROUPN
+#define DVDQ_FP6_GROUPN 16
+#endif
+    const int n_groups = (tiles_n + DVDQ_FP6_GROUPN - 1) / DVDQ_FP6_GROUPN;
     const int group_n = (tiles_n + n_groups - 1) / n_groups;
     const int total = tiles_m * tiles_n;
     int grid = 256 * OCC;
@@ -563,6 +566,10 @@ int launch_fp6(const uint8_t *codes, const float *x_scale, const uint8_t *w, con
 int launch_w4a4_fp6_gemm(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                          const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,
                          int64_t K, uint16_t *y, int32_t *acc_out, hipStream_t stream) {
+#ifdef DVDQ_FP6_BIG
+    return launch_fp6<256, 256, 4, 2, 2, 1>(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K,
+                                            y, acc_out, stream);
+#endif
     return launch_fp6<128, 256, 2, 2, 2, 2>(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K,
                                             y, acc_out, stream);
 }

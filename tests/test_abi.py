@@ -153,6 +153,8 @@ def test_bench_helpers_argument_errors():
     assert L.dvdq_bench_copy(FAKE, FAKE, 24, None) == 2
     assert L.dvdq_bench_mfma_i8(0, FAKE, None, None) == 2
     assert L.dvdq_bench_mfma_i8(4, None, None, None) == 1
+    assert L.dvdq_bench_mfma_fp6(0, FAKE, None, None) == 2
+    assert L.dvdq_bench_mfma_fp6(4, None, None, None) == 1
 
 
 def test_binding_refuses_cpu_tensors():
