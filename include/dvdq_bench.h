@@ -32,10 +32,11 @@ int dvdq_bench_mfma_i8(int iters, int32_t *sink, double *ops_out, void *hip_stre
  * W4A4 GEMM of the FP6 matrix path issues. */
 int dvdq_bench_mfma_fp6(int iters, int32_t *sink, double *ops_out, void *hip_stream);
 
-/* Tile-configuration sweeps: force the native-layout GEMM to use tile variant `variant`
- * (1..4, see the dispatch tables in w4ax_gemm.hip, one per code container; shapes too shallow
- * in K for a variant's ring fall back to variant 2); -1 restores the library's own choice.  Process-wide,
- * not thread-safe, meant for benchmarking only. */
+/* Tile-configuration sweeps: force the native-layout GEMMs to use tile variant `variant`
+ * (INT8 matrix path: 1..4, see the dispatch tables in w4ax_gemm.hip, one per code container; shapes too
+ * shallow in K for a variant's ring fall back to variant 2.  FP6 matrix path: 1..2, see w4a4_fp6_gemm.hip,
+ * other values mean its own choice); -1 restores the library's own choice.  Process-wide, not
+ * thread-safe, meant for benchmarking only. */
 int dvdq_bench_set_gemm_variant(int variant);
 
 /* How the native-layout GEMM's persistent workgroups get their tiles: 0 = fixed equal shares,

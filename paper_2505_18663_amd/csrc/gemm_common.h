@@ -96,5 +96,6 @@ static __device__ __forceinline__ void tile_origin(int t, int tiles_m, int tiles
 // The per-stream tile counters of the persistent kernels (defined in w4ax_gemm.hip): 16 words, the first
 // eight the XCDs' draw counters, the ninth the count of finished workgroups; nullptr = fixed shares.
 unsigned *sched_slot(hipStream_t stream);
+int gemm_variant();   // the benchmark hook's tile variant (-1: the kernels' own choice)
 
 }  // namespace dvdq

@@ -65,8 +65,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_ker
     constexpr int STORES = TM * TN * 2;                  // 16-byte store instructions per wave per full tile
     static_assert(BM / 32 == NW, "one block of code rows per wave");
     static_assert(W_DMA >= 1 && W_DMA * 1024 * NW == W_STAGE, "weight tile does not split over the waves");
-    static_assert(STAGES == 2, "two buffers: a slice is published at the barrier right before it is multiplied");
-    static_assert(DMA + STORES < 64, "store-aware wait exceeds vmcnt");
+    static_assert(STAGES >= 2 && (STAGES - 1) * DMA < 64, "too many loads in flight for vmcnt");
+    static_assert((STAGES - 2) * DMA + STORES < 64, "store-aware wait exceeds vmcnt");
     static_assert(NW * 4096 <= STAGE && TN % 2 == 0, "the epilogue stages 4 KB per wave in one ring buffer");
 
     extern __shared__ __align__(16) uint8_t smem[];
@@ -94,6 +94,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_ker
     int draws = 0;
     unsigned drawn = 0;
     bool draw_pending = false;
+    int draw_wait = 0;   // loop tops until the pending draw's reply is older than loads already awaited
     auto tile_of_draw = [&] __device__(unsigned i, int ordinal) {
         if (sched) return i < run_len ? run_lo + (int)i : -1;
         const int t = first_tile + ordinal * grid;
@@ -103,6 +104,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_ker
         if (wave == 0 && sched && lane == 0) drawn = atomicAdd(sched + xcd, 1u);
         ++draws;
         draw_pending = true;
+        draw_wait = STAGES - 1;
     };
     auto publish_draw = [&] __device__() {   // before a workgroup barrier
         if (wave == 0) {
@@ -219,27 +221,31 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_ker
     const int frow = lane & 31, fhalf = lane >> 5;
     const int frag_off = fhalf * 1536 + frow * 16;   // chunks 3 h .. 3 h + 2 of the row, 512 bytes apart
 
-    // ---- prologue: fill the first buffer
-    issue_prepare(0);
+    // ---- prologue: fill STAGES - 1 buffers
 #pragma unroll
-    for (int d = 0; d < DMA; ++d) issue_one(d);
-    issue_advance();
+    for (int st = 0; st < STAGES - 1; ++st) {
+        issue_prepare(st);
+#pragma unroll
+        for (int d = 0; d < DMA; ++d) issue_one(d);
+        issue_advance();
+    }
 
     int kt = 0, tile_j = 0, store_credit = 0;
     for (int q = 0;; ++q) {
-        // Publish slice q (it has landed once nothing older is outstanding: a wave's vector memory
-        // operations complete in issue order); the barrier also means that everyone is done reading
-        // slice q-1, whose buffer the next loads overwrite.  Right after the epilogue of a full tile
-        // exactly STORES stores are this wave's youngest operations: their acknowledgement is not awaited.
+        // Publish slice q (it has landed once at most the loads of the STAGES - 2 younger slices are
+        // outstanding: a wave's vector memory operations complete in issue order); the barrier also means
+        // that everyone is done reading slice q-1, whose buffer the next loads overwrite.  Right after the
+        // epilogue of a full tile exactly STORES stores are this wave's youngest operations (for the next
+        // STAGES - 1 slices the awaited loads are older than them): their acknowledgement is not awaited.
         if (store_credit > 0) {
-            wait_vmcnt<STORES>();
+            wait_vmcnt<(STAGES - 2) * DMA + STORES>();
             --store_credit;
         } else {
-            wait_vmcnt<0>();
+            wait_vmcnt<(STAGES - 2) * DMA>();
         }
-        if (draw_pending) publish_draw();
+        if (draw_pending && --draw_wait == 0) publish_draw();
         __builtin_amdgcn_s_barrier();
-        issue_prepare((q + 1) % STAGES);
+        issue_prepare((q + STAGES - 1) % STAGES);
         if (kt == 0) __builtin_amdgcn_s_setprio(2);
 
         // The slice's fragments: per operand row three 16-byte chunks = the 12 registers of the two
@@ -300,7 +306,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_ker
             // ---- interior tile: no predicates, channel vectors fetched one register group ahead, bf16 tile
             // transposed through this wave's 4 KB of the ring buffer that was consumed last, whole-line
             // non-temporal stores (the INT8 kernel's epilogue; same arithmetic, same rounding order).
-            if (KT >= STAGES) store_credit = 1;
+            if (KT >= STAGES) store_credit = STAGES - 1;
             auto interior = [&] __device__(auto has_zero) __attribute__((always_inline)) {
                 constexpr bool ZP = decltype(has_zero)::value;
                 // Lane-dependent addresses of the epilogue are derived from a lane number the compiler cannot
@@ -566,12 +572,22 @@ int launch_fp6(const uint8_t *codes, const float *x_scale, const uint8_t *w, con
 int launch_w4a4_fp6_gemm(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                          const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,
                          int64_t K, uint16_t *y, int32_t *acc_out, hipStream_t stream) {
-#ifdef DVDQ_FP6_BIG
-    return launch_fp6<256, 256, 4, 2, 2, 1>(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K,
-                                            y, acc_out, stream);
-#endif
-    return launch_fp6<128, 256, 2, 2, 2, 2>(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K,
-                                            y, acc_out, stream);
+#define DVDQ_FP6_ARGS codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K, y, acc_out, stream
+    // Tile variants {tile M, tile N, waves M x N, ring depth, workgroups per compute unit}:
+    //   1: two independent 4-wave workgroups per compute unit, 128 x 256 tiles, two buffers: while one
+    //      converts and stores a tile the other multiplies;
+    //   2: one 8-wave workgroup, 256 x 256 tiles, three buffers: a third fewer LDS-direct bytes per MFMA and
+    //      one more slice of prefetch distance, which is what this kernel is short of (it is bound by the
+    //      path from L2 / HBM into LDS, not by the matrix cores); 3-11 % faster on the DiT shapes although
+    //      no second workgroup hides its epilogue.  Taken when there are at least two rounds of such tiles
+    //      and K is deep enough for the ring; the benchmark hook can force either.
+    int v = gemm_variant();
+    const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
+    if (v != 1 && v != 2) v = big_tiles >= 512 ? 2 : 1;
+    if (K / kBK < 2) v = 1;
+    if (v == 2) return launch_fp6<256, 256, 4, 2, 3, 1>(DVDQ_FP6_ARGS);
+    return launch_fp6<128, 256, 2, 2, 2, 2>(DVDQ_FP6_ARGS);
+#undef DVDQ_FP6_ARGS
 }
 
 size_t w4_native_fp6_bytes(int64_t N, int64_t K) {

@@ -690,6 +690,7 @@ int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, c
 }  // namespace
 
 void set_gemm_variant(int v) { g_variant = v; }
+int gemm_variant() { return g_variant; }
 void set_gemm_schedule(int v) { g_schedule = v; }
 
 int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,

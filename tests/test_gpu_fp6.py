@@ -49,7 +49,7 @@ def test_fp6_weight_prepack_holds_the_oracle_encoding():
     assert np.array_equal(native.reshape(K // 128, 512 // 32, 3072), ref)
 
 
-@pytest.mark.parametrize("schedule", [-1, 0])
+@pytest.mark.parametrize("schedule,variant", [(-1, -1), (0, -1), (-1, 1), (-1, 2), (0, 2)])
 @pytest.mark.parametrize("M,N,K,use_bias", [
     (1, 1, 128, False),          # one row, one channel, one K slice
     (128, 256, 256, True),       # exactly one interior tile
@@ -57,9 +57,10 @@ def test_fp6_weight_prepack_holds_the_oracle_encoding():
     (513, 260, 1536, True),
     (37, 50, 512, True),         # N % 8 != 0: scalar store path
     (1000, 1024, 640, False),    # 32 tiles
+    (4100, 2056, 384, True),     # 17 x 9 tiles of 256 x 256, ragged in M and N
     (256, 768, 13824, False),    # deepest K of the workloads
 ])
-def test_fp6_gemm_int32_exact(M, N, K, use_bias, schedule):
+def test_fp6_gemm_int32_exact(M, N, K, use_bias, schedule, variant):
     rng = np.random.default_rng(M + 7 * N + 13 * K)
     codes, wc, xs, ws = gemm_case(rng, M, N, K)
     wp = di.pack_w4(wc)
@@ -69,6 +70,7 @@ def test_fp6_gemm_int32_exact(M, N, K, use_bias, schedule):
     c6 = dev(oracle.pack_fp6(codes))
     assert c6.numel() == dvdq.codes_bytes(M, K, dvdq.CODES_FP6)
     dvdq.bench_set_gemm_schedule(schedule)
+    dvdq.bench_set_gemm_variant(variant)   # 1: 128 x 256 tiles, two workgroups per compute unit; 2: 256 x 256 tiles, one
     try:
         y, acc = dvdq.w4ax_gemm(c6, dev(xs), w6, dev(ws), 4, dvdq.W_NATIVE_FP6, bias=bias_dev, want_acc=True,
                                 codes_format=dvdq.CODES_FP6, K=K)
@@ -76,6 +78,7 @@ def test_fp6_gemm_int32_exact(M, N, K, use_bias, schedule):
         torch.cuda.synchronize()
     finally:
         dvdq.bench_set_gemm_schedule(-1)
+        dvdq.bench_set_gemm_variant(-1)
     y_ref, acc_ref = oracle.w4ax_gemm(codes, xs, wp, ws, bias, return_acc=True)
     assert np.array_equal(acc.cpu().numpy().astype(np.int64), acc_ref), "accumulators must be bit-exact"
     check_y(bits_of(y), y_ref, f"fp6 gemm M{M} N{N} K{K}", bias)
