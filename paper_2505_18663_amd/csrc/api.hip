@@ -244,6 +244,6 @@ const char *dvdq_status_string(int status) {
     }
 }
 
-int dvdq_version(void) { return 200; }
+int dvdq_version(void) { return 210; }
 
 }  // extern "C"
