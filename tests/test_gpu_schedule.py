@@ -116,3 +116,53 @@ def test_launches_on_several_streams_do_not_share_counters():
     torch.cuda.synchronize()
     for i, (y, r) in enumerate(zip(outs, refs)):
         assert torch.equal(y.view(torch.int16), r.view(torch.int16)), f"stream {i}"
+
+
+def _fp6_operands(M, K, N, seed):
+    import oracle
+    rng = __import__("numpy").random.default_rng(seed)
+    codes = rng.integers(-7, 8, (M, K)).astype("int8")
+    c6 = torch.from_numpy(oracle.pack_fp6(codes)).to(DEV)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    xs = torch.rand((M,), device=DEV, generator=g) + 0.01
+    w = dvdq.w4_prepack_fp6(torch.randint(0, 256, (N, K // 2), device=DEV, dtype=torch.uint8, generator=g))
+    ws = torch.rand((N,), device=DEV, generator=g) * 0.01 + 1e-3
+    return c6, xs, w, ws, K
+
+
+def _fp6_gemm(ops, y=None, stream=None):
+    c6, xs, w, ws, K = ops
+    return dvdq.w4ax_gemm(c6, xs, w, ws, 4, dvdq.W_NATIVE_FP6, y=y, codes_format=dvdq.CODES_FP6, K=K, stream=stream)
+
+
+@pytest.mark.parametrize("variant", [1, 2])
+def test_fp6_kernel_counters_and_streams(variant):
+    """the FP6 matrix path's kernel draws tiles the same way: both tile variants, many launches in a row on
+    one stream and launches on several streams at once, against fixed shares"""
+    a = _fp6_operands(4100, 512, 2056, seed=3)     # 17 x 9 tiles of 256 x 256 (33 x 9 of 128 x 256), ragged
+    b = _fp6_operands(700, 256, 520, seed=4)
+    dvdq.bench_set_gemm_variant(variant)
+    dvdq.bench_set_gemm_schedule(0)
+    ya_ref, yb_ref = _fp6_gemm(a), _fp6_gemm(b)
+    dvdq.bench_set_gemm_schedule(-1)
+    ya, yb = torch.empty_like(ya_ref), torch.empty_like(yb_ref)
+    for it in range(60):
+        ya.zero_()
+        yb.zero_()
+        _fp6_gemm(a, y=ya)
+        _fp6_gemm(b, y=yb)
+        if it % 10 == 9:
+            torch.cuda.synchronize()
+            assert torch.equal(ya.view(torch.int16), ya_ref.view(torch.int16)), f"iteration {it}"
+            assert torch.equal(yb.view(torch.int16), yb_ref.view(torch.int16)), f"iteration {it}"
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    outs = [torch.zeros_like(ya_ref) for _ in streams]
+    torch.cuda.synchronize()
+    for rep in range(10):
+        for s, y in zip(streams, outs):
+            with torch.cuda.stream(s):
+                _fp6_gemm(a, y=y, stream=s)
+    torch.cuda.synchronize()
+    for i, y in enumerate(outs):
+        assert torch.equal(y.view(torch.int16), ya_ref.view(torch.int16)), f"stream {i}"
