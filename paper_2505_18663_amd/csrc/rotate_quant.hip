@@ -444,7 +444,9 @@ int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block,
     // resident workgroups: a whole number per compute unit (256 of them), about 16 waves each,
     // every workgroup striding over the rows
     // FP6: consecutive rows a wave takes in turn (see the kernel): 8 if the LDS for collecting them allows
-    int wgs_per_cu = 16 / (W * rows_per_wg);
+    // resident waves per compute unit: 16; 20 with the FP6 container, whose extra vector work per element
+    // more waves hide (measured: -4 % on 1536- and 3072-channel rows; the other containers get slower)
+    int wgs_per_cu = (pack4 == 3 ? 20 : 16) / (W * rows_per_wg);
     if (wgs_per_cu < 1) wgs_per_cu = 1;
     int run = 1;
     if (pack4 == 3) {
