@@ -15,8 +15,14 @@
  *
  * Conventions shared by every entry point
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
- *     never allocates, frees or keeps device memory and holds no global state
- *     (the tile-variant switch of dvdq_bench.h, a measurement hook, aside).
+ *     never allocates or frees device memory.  Its only state: the measurement hooks
+ *     of dvdq_bench.h, and a fixed 32 KB array of device memory per GPU (part of the
+ *     loaded code object) that the GEMM kernels use as tile counters, 64 bytes per
+ *     stream: zero at load, and put back to zero by every kernel before it ends.
+ *     Kernels of one stream run one after the other and therefore share a slot; up to
+ *     512 streams per GPU get slots, further streams and launches under stream capture
+ *     use fixed tile shares instead (same results).  A stream must not be destroyed
+ *     while a GEMM it was given is still running and its handle be reused at once.
  *   - `hip_stream` is the caller's hipStream_t (NULL = the default stream).  All
  *     work is enqueued on it; calls return without synchronizing.
  *   - Inputs are read-only; outputs must not overlap inputs or each other.
