@@ -53,10 +53,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_ker
     constexpr int W_DMA = W_STAGE / 1024 / NW;
     constexpr int DMA = A_DMA + W_DMA;
     constexpr int GROUPS = 2 * TN;                       // MFMA groups (TM MFMAs each) per item
-#ifndef DVDQ_FP6_DMA_PER_GROUP
-#define DVDQ_FP6_DMA_PER_GROUP 2
-#endif
-    constexpr int DMA_PER_GROUP = DVDQ_FP6_DMA_PER_GROUP;  // the next slice's loads go out with the first MFMA groups
+    constexpr int DMA_PER_GROUP = 2;                     // the next slice's loads go out with the first MFMA groups
     static_assert(GROUPS * DMA_PER_GROUP >= DMA, "not every load of an item would be issued");
     // one tile's epilogue vectors in LDS: token scales, channel scales (fp32), bias (bf16), and for
     // weights with zero-points the tokens' code sums (int32) and the channels' zero-points (int8)
@@ -549,10 +546,10 @@ int launch_fp6(const uint8_t *codes, const float *x_scale, const uint8_t *w, con
                const int32_t *code_rowsum, const uint16_t *bias, int M, int N, int K, uint16_t *y, int32_t *acc_out,
                hipStream_t stream) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-#ifndef DVDQ_FP6_GROUPN
-#define DVDQ_FP6_GROUPN 16
-#endif
-    const int n_groups = (tiles_n + DVDQ_FP6_GROUPN - 1) / DVDQ_FP6_GROUPN;
+    // column tiles are walked in groups of at most 16, so that workgroups at work at the same time share
+    // weight panels in the L2s (2 to 16 measured within 3 % of each other)
+    constexpr int kMaxGroupN = 16;
+    const int n_groups = (tiles_n + kMaxGroupN - 1) / kMaxGroupN;
     const int group_n = (tiles_n + n_groups - 1) / n_groups;
     const int total = tiles_m * tiles_n;
     int grid = 256 * OCC;
