@@ -215,15 +215,18 @@ def main():
     sink = torch.zeros((4,), dtype=torch.int32, device=dev)
     mfma_ops = [0.0]
 
-    def mfma(i):
-        mfma_ops[0] = dvdq.bench_mfma_i8(2000, sink)
-    mfma_avg, _ = time_launches(mfma, 4, group=2)
-    mfma_ceiling = mfma_ops[0] / (mfma_avg * 1e-3) / 1e12
-
-    def mfma6(i):
-        mfma_ops[0] = dvdq.bench_mfma_fp6(2000, sink)
-    mfma6_avg, _ = time_launches(mfma6, 4, group=2)
-    mfma6_ceiling = mfma_ops[0] / (mfma6_avg * 1e-3) / 1e12
+    # register-only MFMA loops: on constant operands (only MFMA issue limits them) and on random 4-bit codes in
+    # every lane and register (the chip's power management then holds a lower clock: the rate the matrix cores
+    # sustain on the layer's kind of data, before any operand traffic)
+    def mfma_rate(fn, data):
+        def launch(i):
+            mfma_ops[0] = fn(8000, sink, data=data)
+        avg, _ = time_launches(launch, 4, group=2)
+        return mfma_ops[0] / (avg * 1e-3) / 1e12
+    mfma_ceiling = mfma_rate(dvdq.bench_mfma_i8, 0)
+    mfma_ceiling_codes = mfma_rate(dvdq.bench_mfma_i8, 1)
+    mfma6_ceiling = mfma_rate(dvdq.bench_mfma_fp6, 0)
+    mfma6_ceiling_codes = mfma_rate(dvdq.bench_mfma_fp6, 1)
     del src, dst
 
     # ---- the delta-GBS controller step on a 720p-class latent (16 x 33 x 90 x 160 bf16 values):
@@ -274,7 +277,9 @@ def main():
                      "avg_launch_ms_alone": round(gemm_alone, 4),
                      "frac_of_int8_peak": round(gemm_tops / INT8_MFMA_PEAK_TOPS, 4),
                      "measured_mfma_ceiling_tops": round(mfma6_ceiling if use_fp6 else mfma_ceiling, 1),
-                     "measured_int8_mfma_ceiling_tops": round(mfma_ceiling, 1)},
+                     "measured_mfma_ceiling_random_codes_tops": round(mfma6_ceiling_codes if use_fp6 else mfma_ceiling_codes, 1),
+                     "measured_int8_mfma_ceiling_tops": round(mfma_ceiling, 1),
+                     "measured_int8_mfma_ceiling_random_codes_tops": round(mfma_ceiling_codes, 1)},
         "roofline_rotate_quant": {"kernel": "rotate_quant", "bound": "hbm", "achieved": round(rq_gbps, 1),
                                   "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(rq_gbps / HBM_PEAK_GBPS, 4),
                                   "traffic": MEASURED_HBM_TRAFFIC.get((wl.name, fmt_name), {}).get("rotate_quant"),

@@ -4,8 +4,9 @@
  * its rooflines on the machine it runs on:
  *   - a plain copy kernel of known size (reference reading for the HBM traffic
  *     counters and for achievable copy bandwidth),
- *   - a register-only INT8 MFMA loop (the matrix-core rate the chip sustains when
- *     nothing but MFMA issue limits it).
+ *   - register-only MFMA loops, INT8 and FP6 (the matrix-core rate the chip sustains when
+ *     nothing but MFMA issue limits it, and the rate it sustains on random 4-bit codes, where
+ *     its power management lowers the clock).
  * Same conventions as dvdq.h: device pointers owned by the caller, work enqueued
  * on the caller's stream, DVDQ_OK or a dvdq_status code returned.
  */
@@ -25,12 +26,16 @@ int dvdq_bench_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
 /* Every wave of a full-chip launch issues `iters` x 16 independent 32x32x32 INT8 MFMAs on
  * registers; `sink` (device, >= 4 bytes) receives a value that depends on the
  * result so the loop is not removed.  *ops_out (host pointer, may be NULL) receives the
- * number of integer operations (2 per multiply-add) the launch performs. */
-int dvdq_bench_mfma_i8(int iters, int32_t *sink, double *ops_out, void *hip_stream);
+ * number of integer operations (2 per multiply-add) the launch performs.
+ * data: 0 = the same small constants in every lane and instruction; 1 = independent random codes in
+ * [-7, 7] in every lane and operand register (4 x 4 operand pairs), which is the kind of data the layer
+ * multiplies: how many operand bits change between instructions decides what the matrix cores draw and
+ * with it the clock the chip holds.  Other values: DVDQ_ERR_UNSUPPORTED. */
+int dvdq_bench_mfma_i8(int iters, int data, int32_t *sink, double *ops_out, void *hip_stream);
 
 /* The same with `iters` x 8 independent 32x32x64 MFMAs on FP6 (E2M3) operands, the instruction the
- * W4A4 GEMM of the FP6 matrix path issues. */
-int dvdq_bench_mfma_fp6(int iters, int32_t *sink, double *ops_out, void *hip_stream);
+ * W4A4 GEMM of the FP6 matrix path issues (data 1: 4 x 2 operand pairs of random codes as E2M3 patterns). */
+int dvdq_bench_mfma_fp6(int iters, int data, int32_t *sink, double *ops_out, void *hip_stream);
 
 /* Tile-configuration sweeps: force the native-layout GEMMs to use tile variant `variant`
  * (INT8 matrix path: 1..4, see the dispatch tables in w4ax_gemm.hip, one per code container; shapes too

@@ -87,8 +87,8 @@ def lib() -> C.CDLL:
     L.dvdq_bgr_quantize.argtypes = [vp, i64, i64, i32, i32, C.c_double, vp, vp, vp, vp, vp]
     L.dvdq_bgr_quantize.restype = i32
     L.dvdq_bench_copy.argtypes = [vp, vp, sz, vp]
-    L.dvdq_bench_mfma_i8.argtypes = [i32, vp, C.POINTER(C.c_double), vp]
-    L.dvdq_bench_mfma_fp6.argtypes = [i32, vp, C.POINTER(C.c_double), vp]
+    L.dvdq_bench_mfma_i8.argtypes = [i32, i32, vp, C.POINTER(C.c_double), vp]
+    L.dvdq_bench_mfma_fp6.argtypes = [i32, i32, vp, C.POINTER(C.c_double), vp]
     L.dvdq_bench_mfma_fp6.restype = i32
     L.dvdq_bench_set_gemm_variant.argtypes = [i32]
     L.dvdq_bench_set_gemm_variant.restype = i32
@@ -395,15 +395,16 @@ def bench_copy(src, dst, stream=None):
     _check(lib().dvdq_bench_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "dvdq_bench_copy")
 
 
-def bench_mfma_i8(iters: int, sink, stream=None) -> float:
+def bench_mfma_i8(iters: int, sink, stream=None, data: int = 0) -> float:
+    """data 0: constant operands (issue-limited rate); 1: random 4-bit codes (the rate under the layer's kind of data)"""
     ops = C.c_double(0.0)
-    _check(lib().dvdq_bench_mfma_i8(iters, _ptr(sink), C.byref(ops), _stream(stream)), "dvdq_bench_mfma_i8")
+    _check(lib().dvdq_bench_mfma_i8(iters, int(data), _ptr(sink), C.byref(ops), _stream(stream)), "dvdq_bench_mfma_i8")
     return ops.value
 
 
-def bench_mfma_fp6(iters: int, sink, stream=None) -> float:
+def bench_mfma_fp6(iters: int, sink, stream=None, data: int = 0) -> float:
     ops = C.c_double(0.0)
-    _check(lib().dvdq_bench_mfma_fp6(iters, _ptr(sink), C.byref(ops), _stream(stream)), "dvdq_bench_mfma_fp6")
+    _check(lib().dvdq_bench_mfma_fp6(iters, int(data), _ptr(sink), C.byref(ops), _stream(stream)), "dvdq_bench_mfma_fp6")
     return ops.value
 
 

@@ -244,6 +244,6 @@ const char *dvdq_status_string(int status) {
     }
 }
 
-int dvdq_version(void) { return 210; }
+int dvdq_version(void) { return 211; }
 
 }  // extern "C"

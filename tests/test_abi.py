@@ -151,10 +151,12 @@ def test_bench_helpers_argument_errors():
     L = dvdq.lib()
     assert L.dvdq_bench_copy(None, FAKE, 64, None) == 1
     assert L.dvdq_bench_copy(FAKE, FAKE, 24, None) == 2
-    assert L.dvdq_bench_mfma_i8(0, FAKE, None, None) == 2
-    assert L.dvdq_bench_mfma_i8(4, None, None, None) == 1
-    assert L.dvdq_bench_mfma_fp6(0, FAKE, None, None) == 2
-    assert L.dvdq_bench_mfma_fp6(4, None, None, None) == 1
+    assert L.dvdq_bench_mfma_i8(0, 0, FAKE, None, None) == 2
+    assert L.dvdq_bench_mfma_i8(4, 0, None, None, None) == 1
+    assert L.dvdq_bench_mfma_i8(4, 2, FAKE, None, None) == 3
+    assert L.dvdq_bench_mfma_fp6(0, 1, FAKE, None, None) == 2
+    assert L.dvdq_bench_mfma_fp6(4, 1, None, None, None) == 1
+    assert L.dvdq_bench_mfma_fp6(4, -1, FAKE, None, None) == 3
 
 
 def test_binding_refuses_cpu_tensors():
