@@ -33,13 +33,13 @@ HBM_PEAK_GBPS = 8000.0           # published HBM3E bandwidth, MI355X
 # very command, scaled by the same counters' reading for dvdq_bench_copy; the summaries with the
 # commands are profiles/bench_<workload>_hbm_counters.md.  None where no counter run exists.
 MEASURED_HBM_TRAFFIC = {   # keyed by (workload, container of the codes between the two kernels)
-    ("small_dit_qkv_w4a4", "fp6"): {"gemm": 496.8e6, "rotate_quant": 138.7e6},
+    ("small_dit_qkv_w4a4", "fp6"): {"gemm": 496.2e6, "rotate_quant": 138.7e6},
     ("small_dit_qkv_w4a4", "packed4"): {"gemm": 368.0e6, "rotate_quant": 126.2e6},
-    ("small_dit_ffn_up_w4a6", "int8"): {"gemm": 795.6e6, "rotate_quant": 151.3e6},
-    ("large_dit_proj_w4a4", "fp6"): {"gemm": 2556.4e6, "rotate_quant": 1004.3e6},
-    ("large_dit_proj_w4a4", "packed4"): {"gemm": 2000.5e6, "rotate_quant": 914.3e6},
-    ("large_dit_ffn_down_w4a4", "fp6"): {"gemm": 3613.7e6, "rotate_quant": 1245.9e6},
-    ("large_dit_ffn_down_w4a4", "packed4"): {"gemm": 3445.9e6, "rotate_quant": 1133.3e6},
+    ("small_dit_ffn_up_w4a6", "int8"): {"gemm": 795.7e6, "rotate_quant": 151.3e6},
+    ("large_dit_proj_w4a4", "fp6"): {"gemm": 2545.7e6, "rotate_quant": 1004.3e6},
+    ("large_dit_proj_w4a4", "packed4"): {"gemm": 2000.1e6, "rotate_quant": 914.3e6},
+    ("large_dit_ffn_down_w4a4", "fp6"): {"gemm": 3587.2e6, "rotate_quant": 1245.9e6},
+    ("large_dit_ffn_down_w4a4", "packed4"): {"gemm": 3446.7e6, "rotate_quant": 1133.3e6},
 }
 
 
