@@ -52,10 +52,12 @@ static __device__ __forceinline__ void lds_direct_load16(const void *sbase, uint
                  : "memory");
 }
 
-// chunk swizzle of a code row in LDS (see the kernel): 128-byte rows use row & 7, 64-byte rows
-// (two rows per 128-byte bank line) use (row >> 1) & 3
+// chunk swizzle of a code row in LDS (see the kernel).  A 16-byte read is served 16 lanes = 16 rows at a
+// time by the 64 banks (256 bytes), and rows 128 bytes apart alternate between the two halves of the
+// banks: the 8 rows of a half take 8 different chunk slots with (row >> 1) & 7.  With 64-byte rows four
+// rows share a quarter of the banks and take its 4 slots with (row >> 2) & 3.
 template <int BK>
-static __device__ __forceinline__ int swz_bk(int row) { return BK == 128 ? (row & 7) : ((row >> 1) & 3); }
+static __device__ __forceinline__ int swz_bk(int row) { return BK == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
 
 // Same, 4 bytes per lane (LDS address lds_base + 4 * lane): used for the per-tile scale vectors.
 static __device__ __forceinline__ void lds_direct_load4(const void *sbase, uint32_t voff, uint32_t lds_base) {

@@ -151,7 +151,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     // ---- LDS-direct load addressing: wave-uniform base pointer + per-lane 32-bit offset.
     // codes: load slot i of this wave fills ROWS_PER_DMA consecutive LDS rows of the stage;
     // LDS position p of a row holds the row's 16-byte chunk p ^ swz(row), where swz spreads
-    // the 8 rows that one quarter-wave reads over the 8 16-byte slots of a 128-byte bank line.
+    // the 16 rows that one quarter-wave reads over the 64 banks (see swz_bk).
     int a_row[A_DMA];
     uint32_t a_voff[A_DMA];
 #pragma unroll
