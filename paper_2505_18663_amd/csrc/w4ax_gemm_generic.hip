@@ -28,7 +28,8 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kBK = 64;  // K slice per main-loop step (bytes of int8 codes)
 
-__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 3); }
+// 64-byte rows: four rows share a quarter of the 64 LDS banks; a 16-byte read serves 16 rows at a time
+__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 2) & 3); }
 
 // 8 packed nibbles (nibble i = channel i) -> two dwords of int8 lanes (16*code),
 // channels in natural order: interleave the bytes of the even and odd nibbles.
