@@ -209,12 +209,16 @@ size_t dvdq_w4_native_fp6_bytes(int64_t N, int64_t K);
  * quantizer.  For every row n of w (an output channel, already expressed in the rotated
  * basis W H of Sec. 3.2) it finds a step size Delta_n and an integer zero-point z_n for
  *     Quant    q = clamp(rint(w / Delta) + z, 0, 15)        DeQuant  w^ = Delta (q - z)
- * by searching n_steps progressively clipped MinMax ranges [min + i s, max - i s],
- * s = (max - min) / n_steps, i = 0, 1, ... while the range is non-empty (i = 0 is plain MinMax),
- * refining each start with at most max_refine rounds of {least-squares Delta, relaxed-then-
- * rounded z, re-quantization}, a start's refinement ending once a round improves the row
- * error ||w - w^||_2 by less than eps (or worsens it); the grid with the smallest row error
- * over everything evaluated is kept.  Arithmetic is fp64; rint rounds half to even.
+ * by searching progressively clipped MinMax ranges [min + i s, max - i s], s = (max - min) / n_steps,
+ * while the range is non-empty, refining each start with at most max_refine rounds of
+ * {least-squares Delta, relaxed-then-rounded z clamped to [0, 15], re-quantization}, a start's
+ * refinement ending with the round that improves the row error ||w - w^||_2 by less than eps.
+ * `search` selects what competes for the smallest row error:
+ *   DVDQ_BGR_LISTING      Alg. 1 as printed: i = 1, 2, ...; a start's result is the grid of its last
+ *                         round (the start itself when max_refine = 0).  n_steps >= 3 (DVDQ_ERR_SHAPE).
+ *   DVDQ_BGR_BEST_OF_ALL  a superset search: i = 0 (plain MinMax) is a start too and every grid
+ *                         evaluated, each start and every round, competes; never worse than MinMax.
+ * Ties keep the earliest grid.  Arithmetic is fp64; rint rounds half to even.
  *
  *   w          in   fp32 [N, K]
  *   n_steps         >= 1 (100 is customary); max_refine >= 0; eps >= 0
@@ -226,7 +230,8 @@ size_t dvdq_w4_native_fp6_bytes(int64_t N, int64_t K);
  * K must be even (DVDQ_ERR_SHAPE) and at most 32768 (DVDQ_ERR_UNSUPPORTED).  A constant row
  * is represented exactly.  Results do not depend on the launch (no atomics).
  */
-int dvdq_bgr_quantize(const float *w, int64_t N, int64_t K, int n_steps, int max_refine, double eps,
+enum { DVDQ_BGR_LISTING = 0, DVDQ_BGR_BEST_OF_ALL = 1 };
+int dvdq_bgr_quantize(const float *w, int64_t N, int64_t K, int n_steps, int max_refine, double eps, int search,
                       uint8_t *w_packed, float *w_scale, int8_t *w_zero, double *row_error, void *hip_stream);
 
 /*

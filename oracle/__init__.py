@@ -51,6 +51,8 @@ def _load():
         lib.dvdq_oracle_pack_w4.argtypes = [vp, i64, i64, vp]
         lib.dvdq_oracle_unpack_a4.argtypes = [vp, i64, i64, vp]
         lib.dvdq_oracle_pack_a4.argtypes = [vp, i64, i64, vp]
+        lib.dvdq_oracle_unpack_fp6.argtypes = [vp, i64, i64, vp]
+        lib.dvdq_oracle_pack_fp6.argtypes = [vp, i64, i64, vp]
         lib.dvdq_oracle_int_gemm.argtypes = [vp, vp, i64, i64, i64, vp]
         lib.dvdq_oracle_epilogue.argtypes = [vp, vp, vp, vp, i64, i64, vp]
         lib.dvdq_oracle_w4ax_gemm.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp]
@@ -62,13 +64,13 @@ def _load():
         lib.dvdq_oracle_gbs_update.restype = i32
         lib.dvdq_oracle_bgr_refine_step.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, vp]
         lib.dvdq_oracle_minmax_quant.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp]
-        lib.dvdq_oracle_bgr.argtypes = [vp, i64, i64, i32, i32, i32, C.c_double, vp, vp, vp, vp]
+        lib.dvdq_oracle_bgr.argtypes = [vp, i64, i64, i32, i32, i32, C.c_double, i32, vp, vp, vp, vp]
         lib.dvdq_oracle_w4ax_gemm_zp.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp]
         for f in ("bgr_refine_step", "minmax_quant", "bgr", "w4ax_gemm_zp"):
             getattr(lib, "dvdq_oracle_" + f).restype = i32
         for f in ("hadamard", "rotate", "quantize", "rotate_quant", "w4ax_gemm", "qlinear"):
             getattr(lib, "dvdq_oracle_" + f).restype = i32
-        for f in ("unpack_w4", "pack_w4", "unpack_a4", "pack_a4", "int_gemm", "epilogue", "f64_to_bf16"):
+        for f in ("unpack_w4", "pack_w4", "unpack_a4", "pack_a4", "unpack_fp6", "pack_fp6", "int_gemm", "epilogue", "f64_to_bf16"):
             getattr(lib, "dvdq_oracle_" + f).restype = None
         _lib = lib
     return _lib
@@ -184,44 +186,29 @@ def pack_a4(codes: np.ndarray) -> np.ndarray:
 
 
 def pack_fp6(codes: np.ndarray) -> np.ndarray:
-    """int8 [M, K] codes in [-15, 15] -> the FP6 container of the library's C header (uint8, flat).
-
-    A code c becomes the E2M3 bit pattern (c < 0) << 5 | |c| (value c / 8).  Rows are padded with zero
-    codes to a multiple of 32.  Order: [32-row block][128-channel slice][16-byte chunk 0..5][row 0..31][16 B];
-    a row's 96 bytes of a slice are four 24-byte fragments, field e (bits 6e..6e+5, little endian) of
-    fragment f being channel 64 (f // 2) + 32 (f % 2) + e of the slice."""
-    c = _arr(codes, np.int8, 2).astype(np.int16)
+    """int8 [M, K] codes in [-15, 15] -> the FP6 container of the library's C header (uint8, flat): rows padded
+    to a multiple of 32 with zero codes, K a multiple of 128 (layout: see dvdq_oracle_pack_fp6)."""
+    c = _arr(codes, np.int8, 2)
     M, K = c.shape
     if K % 128:
         raise ValueError("K must be a multiple of 128")
-    if np.abs(c).max(initial=0) > 15:
+    if np.abs(c.astype(np.int16)).max(initial=0) > 15:
         raise ValueError("codes out of the E2M3 integer range")
-    Mp = (M + 31) // 32 * 32
-    full = np.zeros((Mp, K), dtype=np.int16)
-    full[:M] = c
-    field = (np.where(full < 0, 32, 0) | np.abs(full)).astype(np.uint8)            # [Mp, K]
-    KT = K // 128
-    # channel 64 h + 32 s + e of a slice is field e of fragment f = 2 h + s: plain channel order already
-    frag = field.reshape(Mp, KT, 4, 32)
-    bits = ((frag[..., None] >> np.arange(6, dtype=np.uint8)) & 1).astype(np.uint8)  # [Mp, KT, 4, 32, 6] LSB first
-    row_bytes = np.packbits(bits.reshape(Mp, KT, 4, 192), axis=-1, bitorder="little").reshape(Mp, KT, 96)
-    chunks = row_bytes.reshape(Mp // 32, 32, KT, 6, 16).transpose(0, 2, 3, 1, 4)     # [block, slice, chunk, row, 16]
-    return np.ascontiguousarray(chunks).reshape(-1)
+    out = np.empty((M + 31) // 32 * 32 * (K // 128) * 96, dtype=np.uint8)
+    _load().dvdq_oracle_pack_fp6(_p(c), M, K, _p(out))
+    return out
 
 
 def unpack_fp6(buf: np.ndarray, M: int, K: int) -> np.ndarray:
     """Inverse of pack_fp6: the first M rows as int8 [M, K]."""
     if K % 128:
         raise ValueError("K must be a multiple of 128")
-    Mp, KT = (M + 31) // 32 * 32, K // 128
     b = _arr(buf, np.uint8, 1)
-    if b.size < Mp * KT * 96:
+    if b.size < (M + 31) // 32 * 32 * (K // 128) * 96:
         raise ValueError("buffer too small")
-    row_bytes = b[:Mp * KT * 96].reshape(Mp // 32, KT, 6, 32, 16).transpose(0, 3, 1, 2, 4).reshape(Mp, KT, 4, 24)
-    bits = np.unpackbits(row_bytes, axis=-1, bitorder="little").reshape(Mp, KT, 4, 32, 6)
-    field = (bits.astype(np.int16) << np.arange(6, dtype=np.int16)).sum(axis=-1)    # [Mp, KT, 4, 32]
-    mag, neg = field & 31, (field >> 5) & 1
-    return np.where(neg == 1, -mag, mag).astype(np.int8).reshape(Mp, K)[:M]
+    out = np.empty((M, K), dtype=np.int8)
+    _load().dvdq_oracle_unpack_fp6(_p(b), M, K, _p(out))
+    return out
 
 
 def int_gemm(codes: np.ndarray, w_codes: np.ndarray) -> np.ndarray:
@@ -329,15 +316,22 @@ def bgr_refine_step(w_row: np.ndarray, q: np.ndarray, z: int, bits: int = 4):
     return None if rc != 0 else (d.value, zn.value, qn, e.value)
 
 
-def bgr(w: np.ndarray, bits: int = 4, n_steps: int = 100, max_refine: int = 10, eps: float = 0.0):
-    """Bounded-init Grid Refinement per row.  Returns (codes uint8 [N, K], delta f64 [N], zero int32 [N], err f64 [N])."""
+BGR_LISTING, BGR_BEST_OF_ALL = 0, 1
+
+
+def bgr(w: np.ndarray, bits: int = 4, n_steps: int = 100, max_refine: int = 10, eps: float = 0.0,
+        search: int = BGR_LISTING):
+    """Bounded-init Grid Refinement per row; `search` = BGR_LISTING (Alg. 1 as printed: starts i = 1, 2, ...,
+    a start's result is its last refined grid) or BGR_BEST_OF_ALL (superset search from i = 0, every grid competes).
+    Returns (codes uint8 [N, K], delta f64 [N], zero int32 [N], err f64 [N])."""
     a = _arr(w, np.float32, 2)
     N, K = a.shape
     q = np.empty((N, K), dtype=np.uint8)
     d = np.empty(N, dtype=np.float64)
     z = np.empty(N, dtype=np.int32)
     e = np.empty(N, dtype=np.float64)
-    _check(_load().dvdq_oracle_bgr(_p(a), N, K, bits, n_steps, max_refine, float(eps), _p(q), _p(d), _p(z), _p(e)), "bgr")
+    _check(_load().dvdq_oracle_bgr(_p(a), N, K, bits, n_steps, max_refine, float(eps), int(search), _p(q), _p(d),
+                                   _p(z), _p(e)), "bgr")
     return q, d, z, e
 
 

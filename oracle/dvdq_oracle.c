@@ -272,6 +272,51 @@ void dvdq_oracle_pack_a4(const int8_t *codes, int64_t M, int64_t K, uint8_t *pac
             }
 }
 
+/* The FP6 container of 4-bit activation codes (the GPU library's own encoding for the FP6 matrix path,
+ * stated in its C header; no passage of the method defines it).  A code c, |c| <= 15, is stored as the
+ * 6-bit E2M3 pattern  (c < 0) << 5 | |c|,  whose value as an E2M3 number is c / 8.  Rows are padded to a
+ * multiple of 32, K is a multiple of 128.  With block = m / 32, r = m % 32, slice = k / 128, c = k % 128:
+ * the row's 128 fields of a slice are 96 bytes, field c at bits 6 c .. 6 c + 5 (little endian), and byte b
+ * of those 96 lives at
+ *     ((block * (K / 128) + slice) * 6 + b / 16) * 512 + r * 16 + b % 16
+ * i.e. [32-row block][128-channel slice][16-byte chunk 0..5][row 0..31][16 B].  One field, one bit at a time. */
+void dvdq_oracle_pack_fp6(const int8_t *codes, int64_t M, int64_t K, uint8_t *buf)
+{
+    const int64_t slices = K / 128, blocks = (M + 31) / 32;
+    memset(buf, 0, (size_t)(blocks * 32 * slices * 96));
+#pragma omp parallel for schedule(static)   /* rows own disjoint bytes */
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            const int c = codes[m * K + k];
+            const int field = (c < 0 ? 32 : 0) | (c < 0 ? -c : c);
+            const int64_t base = ((m / 32) * slices + k / 128) * 6 * 512 + (m % 32) * 16;
+            for (int bit = 0; bit < 6; ++bit) {
+                if (!((field >> bit) & 1)) continue;
+                const int pos = 6 * (int)(k % 128) + bit;     /* bit of the row's 96 bytes */
+                const int b = pos / 8;
+                buf[base + (b / 16) * 512 + b % 16] |= (uint8_t)(1u << (pos % 8));
+            }
+        }
+}
+
+void dvdq_oracle_unpack_fp6(const uint8_t *buf, int64_t M, int64_t K, int8_t *codes)
+{
+    const int64_t slices = K / 128;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            const int64_t base = ((m / 32) * slices + k / 128) * 6 * 512 + (m % 32) * 16;
+            int field = 0;
+            for (int bit = 0; bit < 6; ++bit) {
+                const int pos = 6 * (int)(k % 128) + bit;
+                const int b = pos / 8;
+                field |= ((buf[base + (b / 16) * 512 + b % 16] >> (pos % 8)) & 1) << bit;
+            }
+            const int mag = field & 31;
+            codes[m * K + k] = (int8_t)((field & 32) ? -mag : mag);
+        }
+}
+
 /* ---------------------------------------------------------------- GEMM */
 
 /* Step 4: acc[m,n] = sum_k q[m,k] * w[n,k], the plain definition, in int64. */
@@ -451,20 +496,34 @@ int dvdq_oracle_minmax_quant(const float *w, int64_t N, int64_t K, int bits, uin
     return 0;
 }
 
-/* Bounded-init Grid Refinement (Alg. 1), row by row.  For i = 0, 1, ... the clipping range
- * [min + i * step, max - i * step], step = (max - min) / n_steps, gives a MinMax-style start
- * (i = 0 is plain MinMax); each start is refined round after round until a round improves
- * the row error by less than eps (or makes it worse), at most max_refine rounds; the best
- * grid seen over all starts and rounds is returned, the earliest one on exact ties.
- * Readings (the listing overloads n, and its stopping test as printed is always true):
- * the number of shrink steps is a parameter; ranges that have collapsed (lo >= hi) end the
- * search; every evaluated grid, including each start, competes for "best"; rows are
- * independent; the zero-point is rounded and kept in [0, 2^b - 1] everywhere.
+/* Bounded-init Grid Refinement (Alg. 1), row by row, in two search modes.
+ *
+ * search = 0, "the listing": Alg. 1 as printed wherever it can be executed.
+ *   for i = 1, 2, ...:  clip range [min + i * step, max - i * step], step = (max - min) / n_steps
+ *     start grid (Delta0, z0) = MinMax of the clipped row, codes and error E0 of the UNCLIPPED row on it
+ *     repeat  round j = 1, 2, ...: least-squares Delta, relaxed zero-point, re-quantize, error Ej
+ *     until   the round gained less than eps (or lost):  E(j-1) - E(j) < eps
+ *     the start's result is its LAST round's grid (also when that round made the error worse);
+ *     it replaces the best grid so far iff its error is strictly smaller.
+ *   Only the readings the listing forces are taken: the stop test's operands are taken in the order that
+ *   makes it a convergence test (as printed, E(j-1) - E(j-2) < eps holds after every improving round);
+ *   the count of shrink steps is a parameter of its own (the listing reuses the row count's letter);
+ *   a range that has collapsed (lo >= hi, which happens from i = n_steps / 2 on) ends the search; the
+ *   zero-point is rounded and clamped to [0, 2^b - 1] ("relax then round", and the start's must fit the
+ *   same container); a round that is undefined (all codes at the zero-point, non-positive step) ends the
+ *   start with the grid before it; at most max_refine rounds per start (max_refine = 0: the start itself
+ *   is the result); rows are independent (one best grid per row).  n_steps >= 3, so that i = 1 exists.
+ * search = 1, "best of everything": a superset search.  i starts at 0 (plain MinMax) and EVERY grid
+ *   evaluated -- each start and every round -- competes for best, so the result is never worse than MinMax
+ *   or any clipped start.  Not what the listing says; kept as an option.
+ * Ties keep the earliest grid in both modes.
  * A constant row c is represented exactly: Delta = |c| (1 if c = 0), z = (c < 0), q = (c > 0). */
 int dvdq_oracle_bgr(const float *w, int64_t N, int64_t K, int bits, int n_steps, int max_refine, double eps,
-                    uint8_t *q_out, double *delta_out, int *zero_out, double *err_out)
+                    int search, uint8_t *q_out, double *delta_out, int *zero_out, double *err_out)
 {
     if (bits < 2 || bits > 8 || n_steps < 1 || max_refine < 0 || K < 1) return -1;
+    if (search != 0 && search != 1) return -1;
+    if (search == 0 && n_steps < 3) return -1;
     const double qmax = (double)((1 << bits) - 1);
     int rc = 0;
 #pragma omp parallel for schedule(dynamic)
@@ -485,28 +544,32 @@ int dvdq_oracle_bgr(const float *w, int64_t N, int64_t K, int bits, int n_steps,
         }
         const double step = (hi0 - lo0) / (double)n_steps;
         double best = INFINITY;
-        for (int i = 0; i < n_steps; ++i) {
+        for (int i = search == 0 ? 1 : 0; i <= n_steps; ++i) {
             const double lo = lo0 + (double)i * step, hi = hi0 - (double)i * step;
             if (!(lo < hi)) break;
             double delta, z;
             minmax_grid(lo, hi, qmax, &delta, &z);
             double e = quant_row(row, K, delta, z, qmax, q);
-            if (e < best) {
+            if (search == 1 && e < best) {
                 best = e; delta_out[n] = delta; zero_out[n] = (int)z;
                 memcpy(q_out + n * K, q, (size_t)K);
             }
-            double e_prev = e;
             int zi = (int)z;
             for (int j = 0; j < max_refine; ++j) {
                 double dn, en; int zn;
                 if (dvdq_oracle_bgr_refine_step(row, K, bits, q, zi, &dn, &zn, qn, &en) != 0) break;
-                if (en < best) {
+                if (search == 1 && en < best) {
                     best = en; delta_out[n] = dn; zero_out[n] = zn;
                     memcpy(q_out + n * K, qn, (size_t)K);
                 }
-                if (e_prev - en < eps) break;
-                e_prev = en; zi = zn;
+                const double gain = e - en;
+                e = en; delta = dn; zi = zn;              /* the start's current (last) grid */
                 memcpy(q, qn, (size_t)K);
+                if (gain < eps) break;
+            }
+            if (search == 0 && e < best) {               /* the listing: only the start's last grid competes */
+                best = e; delta_out[n] = delta; zero_out[n] = zi;
+                memcpy(q_out + n * K, q, (size_t)K);
             }
         }
         err_out[n] = best;

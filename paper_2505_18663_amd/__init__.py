@@ -17,11 +17,12 @@ __all__ = [
     "DvdqError", "DvdqLibraryMissing", "lib", "library_path", "version", "status_string",
     "rotate_quant", "rotate_quant_blockwise", "w4ax_gemm", "qlinear", "qlinear_workspace_bytes", "qlinear_scale_offset", "qlinear_rowsum_offset", "workspace_rowsum",
     "w4_prepack", "w4_native_bytes", "w4_prepack_fp6", "w4_native_fp6_bytes", "codes_bytes", "bgr_quantize", "GbsController", "bench_copy", "bench_mfma_i8", "bench_mfma_fp6", "bench_set_gemm_variant", "bench_set_gemm_schedule",
-    "W_CANONICAL", "W_NATIVE", "W_NATIVE_FP6", "CODES_INT8", "CODES_PACKED4", "CODES_FP6", "EXPORTED_SYMBOLS",
+    "W_CANONICAL", "W_NATIVE", "W_NATIVE_FP6", "CODES_INT8", "CODES_PACKED4", "CODES_FP6", "BGR_LISTING", "BGR_BEST_OF_ALL", "EXPORTED_SYMBOLS",
 ]
 
 W_CANONICAL, W_NATIVE, W_NATIVE_FP6 = 0, 1, 2
 CODES_INT8, CODES_PACKED4, CODES_FP6 = 0, 1, 2
+BGR_LISTING, BGR_BEST_OF_ALL = 0, 1
 
 EXPORTED_SYMBOLS = (
     "dvdq_rotate_quant", "dvdq_rotate_quant_blockwise", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_qlinear_workspace_bytes",
@@ -84,7 +85,7 @@ def lib() -> C.CDLL:
     L.dvdq_gbs_reset.restype = i32
     L.dvdq_gbs_step.argtypes = [vp, vp, i64, C.c_float, i32, i32, vp, vp, sz, vp]
     L.dvdq_gbs_step.restype = i32
-    L.dvdq_bgr_quantize.argtypes = [vp, i64, i64, i32, i32, C.c_double, vp, vp, vp, vp, vp]
+    L.dvdq_bgr_quantize.argtypes = [vp, i64, i64, i32, i32, C.c_double, i32, vp, vp, vp, vp, vp]
     L.dvdq_bgr_quantize.restype = i32
     L.dvdq_bench_copy.argtypes = [vp, vp, sz, vp]
     L.dvdq_bench_mfma_i8.argtypes = [i32, i32, vp, C.POINTER(C.c_double), vp]
@@ -197,6 +198,22 @@ def rotate_quant_blockwise(x, had_block: int, act_bits: int, group: int, values=
     return (values, x_scale, rs) if want_rowsum else (values, x_scale)
 
 
+def _check_weight_buffer(L, w, w_layout: int, N: int, K: int):
+    """The C ABI cannot know how large the weight buffer is; the kernels read dvdq_w4_native*_bytes(N, K)
+    bytes of a native buffer (N padded to 256 rows), so an undersized one must be refused here."""
+    if w_layout == W_CANONICAL:
+        if tuple(w.shape) != (N, K // 2):
+            raise ValueError(f"w: expected shape {(N, K // 2)}, got {tuple(w.shape)}")
+        return
+    if w_layout not in (W_NATIVE, W_NATIVE_FP6):
+        return   # the library reports the unknown layout
+    need = L.dvdq_w4_native_bytes(N, K) if w_layout == W_NATIVE else L.dvdq_w4_native_fp6_bytes(N, K)
+    if need == 0:
+        raise ValueError(f"w: no native layout for N={N}, K={K} (K must be a multiple of 128)")
+    if w.numel() < need:
+        raise ValueError(f"w: native buffer holds {w.numel()} bytes, the layout needs {need}")
+
+
 def w4ax_gemm(codes, x_scale, w, w_scale, act_bits: int, w_layout: int = W_CANONICAL, bias=None,
               y=None, acc_out=None, want_acc: bool = False, stream=None, codes_format: int = CODES_INT8,
               w_zero=None, code_rowsum=None, K=None):
@@ -221,12 +238,7 @@ def w4ax_gemm(codes, x_scale, w, w_scale, act_bits: int, w_layout: int = W_CANON
     N = w_scale.shape[0]
     _need(x_scale, torch.float32, (M,), "x_scale")
     _need(w, torch.uint8, None, "w")
-    if w_layout == W_CANONICAL and tuple(w.shape) != (N, K // 2):
-        raise ValueError(f"w: expected shape {(N, K // 2)}, got {tuple(w.shape)}")
-    if w_layout == W_NATIVE and w.numel() < L.dvdq_w4_native_bytes(N, K):
-        raise ValueError("w: native buffer too small")
-    if w_layout == W_NATIVE_FP6 and w.numel() < L.dvdq_w4_native_fp6_bytes(N, K):
-        raise ValueError("w: FP6 native buffer too small")
+    _check_weight_buffer(L, w, w_layout, N, K)
     if bias is not None:
         _need(bias, torch.bfloat16, (N,), "bias")
     if w_zero is not None:
@@ -267,8 +279,7 @@ def qlinear(x, w, w_scale, had_block: int, act_bits: int, w_layout: int = W_CANO
     _need(w_scale, torch.float32, None, "w_scale")
     N = w_scale.shape[0]
     _need(w, torch.uint8, None, "w")
-    if w_layout == W_CANONICAL and tuple(w.shape) != (N, K // 2):
-        raise ValueError(f"w: expected shape {(N, K // 2)}, got {tuple(w.shape)}")
+    _check_weight_buffer(L, w, w_layout, N, K)
     if bias is not None:
         _need(bias, torch.bfloat16, (N,), "bias")
     if w_zero is not None:
@@ -344,9 +355,11 @@ def w4_prepack_fp6(w_canonical, w_native=None, stream=None):
     return w_native
 
 
-def bgr_quantize(w, n_steps: int = 100, max_refine: int = 10, eps: float = 0.0, want_error: bool = False, stream=None):
+def bgr_quantize(w, n_steps: int = 100, max_refine: int = 10, eps: float = 0.0, want_error: bool = False, stream=None,
+                 search: int = BGR_LISTING):
     """Offline INT4 weight quantizer (Bounded-init Grid Refinement).  w: fp32 [N, K] ->
-    (w_packed uint8 [N, K/2] canonical, w_scale fp32 [N], w_zero int8 [N][, row_error fp64 [N]])."""
+    (w_packed uint8 [N, K/2] canonical, w_scale fp32 [N], w_zero int8 [N][, row_error fp64 [N]]).
+    search: BGR_LISTING (Alg. 1 as printed) or BGR_BEST_OF_ALL (superset search, never worse than MinMax)."""
     L = lib()
     _need(w, torch.float32, None, "w")
     N, K = w.shape
@@ -354,7 +367,7 @@ def bgr_quantize(w, n_steps: int = 100, max_refine: int = 10, eps: float = 0.0, 
     w_scale = torch.empty((N,), dtype=torch.float32, device=w.device)
     w_zero = torch.empty((N,), dtype=torch.int8, device=w.device)
     err = torch.empty((N,), dtype=torch.float64, device=w.device) if want_error else None
-    _check(L.dvdq_bgr_quantize(_ptr(w), N, K, n_steps, max_refine, float(eps), _ptr(w_packed), _ptr(w_scale),
+    _check(L.dvdq_bgr_quantize(_ptr(w), N, K, n_steps, max_refine, float(eps), int(search), _ptr(w_packed), _ptr(w_scale),
                                _ptr(w_zero), _ptr(err), _stream(stream)), "dvdq_bgr_quantize")
     return (w_packed, w_scale, w_zero, err) if want_error else (w_packed, w_scale, w_zero)
 

@@ -198,15 +198,17 @@ int dvdq_w4_prepack_fp6(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_
     return dvdq::launch_w4_prepack_fp6(w_canonical, N, K, w_native, static_cast<hipStream_t>(hip_stream));
 }
 
-int dvdq_bgr_quantize(const float *w, int64_t N, int64_t K, int n_steps, int max_refine, double eps,
+int dvdq_bgr_quantize(const float *w, int64_t N, int64_t K, int n_steps, int max_refine, double eps, int search,
                       uint8_t *w_packed, float *w_scale, int8_t *w_zero, double *row_error, void *hip_stream) {
     if (!w || !w_packed || !w_scale || !w_zero) return DVDQ_ERR_NULL;
     if (N < 1 || K < 2 || (K % 2) != 0 || n_steps < 1 || max_refine < 0 || !(eps >= 0.0)) return DVDQ_ERR_SHAPE;
+    if (search != DVDQ_BGR_LISTING && search != DVDQ_BGR_BEST_OF_ALL) return DVDQ_ERR_UNSUPPORTED;
+    if (search == DVDQ_BGR_LISTING && n_steps < 3) return DVDQ_ERR_SHAPE;   // i = 1 must leave a non-empty range
     if (K > 32768 || N > 0x7FFFFFFF) return DVDQ_ERR_UNSUPPORTED;   // the row is kept in LDS
     if (!aligned16(w) || !aligned16(w_packed) || !aligned16(w_scale) || !aligned16(w_zero) ||
         (row_error && !aligned16(row_error)))
         return DVDQ_ERR_ALIGN;
-    return dvdq::launch_bgr(w, N, K, n_steps, max_refine, eps, w_packed, w_scale, w_zero, row_error,
+    return dvdq::launch_bgr(w, N, K, n_steps, max_refine, eps, search, w_packed, w_scale, w_zero, row_error,
                             static_cast<hipStream_t>(hip_stream));
 }
 

@@ -1,7 +1,9 @@
 // Bounded-init Grid Refinement (Sec. 3.1, Alg. 1): the offline INT4 weight quantizer.
 // For every weight row (output channel) it searches clipped MinMax starts, refines each
 // start's grid (least-squares step size, relaxed zero-point, re-quantization) round after
-// round, and keeps the grid with the smallest row error.  Runs once per layer, off the
+// round, and keeps the grid with the smallest row error: either as Alg. 1 prints it (starts
+// i = 1, 2, ..., a start's result is the grid of its last round) or as a superset search (i = 0,
+// plain MinMax, is a start too and every grid evaluated competes).  Runs once per layer, off the
 // inference path; everything is fp64 so that its decisions (roundings, comparisons) match a
 // plain fp64 implementation up to summation order.
 //
@@ -67,7 +69,7 @@ __device__ __forceinline__ Sums evaluate(const float *row, int K, double delta, 
 }
 
 __global__ __launch_bounds__(kThreads) void bgr_kernel(const float *__restrict__ w, int K, int n_steps, int max_refine,
-                                                       double eps, uint8_t *__restrict__ w_packed,
+                                                       double eps, int search, uint8_t *__restrict__ w_packed,
                                                        float *__restrict__ w_scale, int8_t *__restrict__ w_zero,
                                                        double *__restrict__ row_error) {
     extern __shared__ __align__(16) uint8_t smem_raw[];
@@ -104,28 +106,30 @@ __global__ __launch_bounds__(kThreads) void bgr_kernel(const float *__restrict__
         best_z = lo0 < 0.0 ? 1.0 : 0.0;
     } else {
         const double step = (hi0 - lo0) / (double)n_steps;
-        for (int i = 0; i < n_steps; ++i) {
+        const bool all = search == DVDQ_BGR_BEST_OF_ALL;
+        for (int i = all ? 0 : 1; i <= n_steps; ++i) {
             const double lo = lo0 + (double)i * step, hi = hi0 - (double)i * step;
-            if (!(lo < hi)) break;
+            if (!(lo < hi)) break;   // the range has collapsed (from i = n_steps / 2 on)
             // clipped MinMax start
             double delta = (hi - lo) / kQmax;
             double z = clamp_d(rint(-(lo / delta)), 0.0, kQmax);
             Sums s = evaluate(row, K, delta, z, slots);
             double e = sqrt(s.e2);
-            if (e < best) { best = e; best_delta = delta; best_z = z; }
-            double e_prev = e;
+            if (all && e < best) { best = e; best_delta = delta; best_z = z; }
             for (int j = 0; j < max_refine; ++j) {
                 if (s.den == 0.0) break;
                 const double dn = s.num / s.den;
                 if (!(dn > 0.0)) break;
                 const double zn = clamp_d(rint(s.sq / (double)K - (sw / (double)K) / dn), 0.0, kQmax);
                 s = evaluate(row, K, dn, zn, slots);
-                e = sqrt(s.e2);
-                if (e < best) { best = e; best_delta = dn; best_z = zn; }
-                if (e_prev - e < eps) break;
-                e_prev = e;
-                z = zn;
+                const double en = sqrt(s.e2);
+                if (all && en < best) { best = en; best_delta = dn; best_z = zn; }
+                const double gain = e - en;
+                e = en; delta = dn; z = zn;   // the start's current (last) grid
+                if (gain < eps) break;
             }
+            // as printed in Alg. 1: only the grid of the start's last round competes
+            if (!all && e < best) { best = e; best_delta = delta; best_z = z; }
         }
     }
 
@@ -150,14 +154,14 @@ __global__ __launch_bounds__(kThreads) void bgr_kernel(const float *__restrict__
 
 }  // namespace
 
-int launch_bgr(const float *w, int64_t N, int64_t K, int n_steps, int max_refine, double eps, uint8_t *w_packed,
-               float *w_scale, int8_t *w_zero, double *row_error, hipStream_t stream) {
+int launch_bgr(const float *w, int64_t N, int64_t K, int n_steps, int max_refine, double eps, int search,
+               uint8_t *w_packed, float *w_scale, int8_t *w_zero, double *row_error, hipStream_t stream) {
     const size_t smem = kWaves * sizeof(double) + (size_t)K * sizeof(float);
     static std::atomic<uint64_t> configured{0};
     allow_dynamic_lds(reinterpret_cast<const void *>(bgr_kernel), kWaves * sizeof(double) + kMaxK * sizeof(float),
                       configured);   // the limit for the longest row the API admits
     hipLaunchKernelGGL(bgr_kernel, dim3((unsigned)N), dim3(kThreads), smem, stream, w, (int)K, n_steps, max_refine, eps,
-                       w_packed, w_scale, w_zero, row_error);
+                       search, w_packed, w_scale, w_zero, row_error);
     return check_launch();
 }
 

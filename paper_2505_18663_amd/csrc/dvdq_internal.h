@@ -41,8 +41,8 @@ int launch_gbs_reset(void *state, int bits, hipStream_t stream);
 int launch_gbs_step(const uint16_t *ft, const uint16_t *fp, int64_t n, double delta, int b_low, int b_high,
                     void *state, void *workspace, hipStream_t stream);
 
-int launch_bgr(const float *w, int64_t N, int64_t K, int n_steps, int max_refine, double eps, uint8_t *w_packed,
-               float *w_scale, int8_t *w_zero, double *row_error, hipStream_t stream);
+int launch_bgr(const float *w, int64_t N, int64_t K, int n_steps, int max_refine, double eps, int search,
+               uint8_t *w_packed, float *w_scale, int8_t *w_zero, double *row_error, hipStream_t stream);
 
 // Raise a kernel's dynamic-LDS limit to `bytes` once per kernel and device (`done` is the call
 // site's own bit mask of devices already configured).  Not a stream operation: after the first

@@ -7,11 +7,13 @@ Bars (stated in the tests that call these):
     within one fp32 ulp of the row maximum (in code units: qmax * 2^-23) of a
     rounding boundary -- widened by the row's own scale difference, which is
     itself limited to 2 fp32 ulps -- each off by exactly 1, and at most
-    ceil(1e-5 * elements) of them.  Not counted against that budget: values that
-    sit within half an fp32 ulp OF THEMSELVES (2^-24 * max(1, |t|) in code units)
-    of the boundary, i.e. ties at the resolution of any fp32 evaluation; bf16
-    inputs rotated over tiny blocks produce such values in clusters (the same
-    few input values recur along a row).
+    ceil(1e-5 * elements) of them.  Only where a caller asks for it
+    (allow_fp32_ties=True: the sweeps over tiny rotation blocks and random shapes,
+    never a task workload) values that sit within half an fp32 ulp OF THEMSELVES
+    (2^-24 * max(1, |t|) in code units) of the boundary -- ties at the resolution
+    of any fp32 evaluation, which bf16 inputs rotated over blocks of 1 to 8
+    channels produce in clusters (the same few input values recur along a row)
+    -- are checked like every other flip but not counted against the budget.
   * token scales: within 2 fp32 ulps.
   * bf16 outputs on identical accumulators and scales: within 1 bf16 ulp
     everywhere, max relative error <= 1e-2, mean relative error <= 1e-3.  With a
@@ -33,7 +35,8 @@ def ulp_diff_f32(a, b):
     return np.abs(ia - ib)        # inputs here are non-negative scales: bit patterns are ordered
 
 
-def check_codes_and_scales(codes_gpu, scale_gpu, codes_ref, scale_ref, xrot_ref, act_bits, label=""):
+def check_codes_and_scales(codes_gpu, scale_gpu, codes_ref, scale_ref, xrot_ref, act_bits, label="",
+                           allow_fp32_ties=False):
     """Returns a dict of counters; raises AssertionError on any violation."""
     qmax = 2 ** (act_bits - 1) - 1
     d_ulp = ulp_diff_f32(scale_gpu, scale_ref)
@@ -62,7 +65,7 @@ def check_codes_and_scales(codes_gpu, scale_gpu, codes_ref, scale_ref, xrot_ref,
                            f"boundary (worst {float((dist / unit).max()):.3f} ulps)")
     fp32_ties = dist <= 2.0 ** -24 * np.maximum(1.0, np.abs(t))
     out["fp32_ties"] = int(fp32_ties.sum())
-    counted = n_mis - out["fp32_ties"]
+    counted = n_mis - (out["fp32_ties"] if allow_fp32_ties else 0)
     assert counted <= budget, f"{label}: {counted} boundary flips exceed the budget of {budget}"
     return out
 
@@ -94,7 +97,8 @@ def check_y(y_gpu_bits, y_ref_bits, label="", bias_bits=None):
     return dict(max_rel=float(rel.max(initial=0)), mean_rel=float(rel.mean()), ulp1=int((d == 1).sum()))
 
 
-def check_blockwise(values_gpu, scale_gpu, values_ref, scale_ref, exps_ref, xrot_ref, act_bits, group, label=""):
+def check_blockwise(values_gpu, scale_gpu, values_ref, scale_ref, exps_ref, xrot_ref, act_bits, group, label="",
+                    allow_fp32_ties=False):
     """Block-wise scaled quantizer: stored int8 values against the oracle's.
 
     Bars: handed-on token scales within 2 fp32 ulps.  A group whose stored values differ from the
@@ -104,9 +108,9 @@ def check_blockwise(values_gpu, scale_gpu, values_ref, scale_ref, exps_ref, xrot
     only accepted when the group maximum times a power of two is within 2^-20 of the row maximum
     (the comparison that chooses the exponent is taken on fp32 butterfly sums by the kernel and on
     exact values by the oracle); such a group must still be a valid quantization on its own step.
-    Budgets: ceil(1e-5 * elements) code flips (as in check_codes_and_scales, values within half an fp32 ulp
-    of themselves of a boundary are checked but not counted: unrotated bf16 inputs produce such exact
-    ties in clusters), ceil(1e-4 * groups) exponent flips."""
+    Budgets: ceil(1e-5 * elements) code flips (with allow_fp32_ties, as in check_codes_and_scales, values
+    within half an fp32 ulp of themselves of a boundary are checked but not counted: unrotated bf16 inputs
+    produce such exact ties in clusters), ceil(1e-4 * groups) exponent flips."""
     qmax = 2 ** (act_bits - 1) - 1
     emax = 8 - act_bits
     M, K = values_ref.shape
@@ -134,7 +138,7 @@ def check_blockwise(values_gpu, scale_gpu, values_ref, scale_ref, exps_ref, xrot
             assert np.all(dist <= unit * (1.0 + d_ulp[m])), f"{label}: code flip {dist.max() / unit:.3f} ulps from its boundary"
             ties = dist <= 2.0 ** -24 * np.maximum(1.0, np.abs(t))      # ties at fp32 resolution: checked, not counted
             out["fp32_ties"] = out.get("fp32_ties", 0) + int(ties.sum())
-            out["code_flips"] += int(idx.size - ties.sum())
+            out["code_flips"] += int(idx.size - (ties.sum() if allow_fp32_ties else 0))
             out["max_boundary_dist_ulps"] = max(out["max_boundary_dist_ulps"], float(dist.max() / unit))
         else:
             a = np.abs(xr[m, g]).max()

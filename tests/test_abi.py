@@ -119,16 +119,19 @@ def test_prepack_argument_errors_and_size():
 
 def test_bgr_argument_errors():
     f = dvdq.lib().dvdq_bgr_quantize
-    assert f(None, 8, 64, 100, 10, 0.0, FAKE, FAKE, FAKE, None, None) == 1
-    assert f(FAKE, 8, 64, 100, 10, 0.0, FAKE, FAKE, None, None, None) == 1
-    assert f(FAKE, 0, 64, 100, 10, 0.0, FAKE, FAKE, FAKE, None, None) == 2
-    assert f(FAKE, 8, 63, 100, 10, 0.0, FAKE, FAKE, FAKE, None, None) == 2        # K odd
-    assert f(FAKE, 8, 64, 0, 10, 0.0, FAKE, FAKE, FAKE, None, None) == 2          # no search steps
-    assert f(FAKE, 8, 64, 100, -1, 0.0, FAKE, FAKE, FAKE, None, None) == 2
-    assert f(FAKE, 8, 64, 100, 10, -1.0, FAKE, FAKE, FAKE, None, None) == 2
-    assert f(FAKE, 8, 65536, 100, 10, 0.0, FAKE, FAKE, FAKE, None, None) == 3     # row does not fit LDS
-    assert f(FAKE, 8, 64, 100, 10, 0.0, ODD, FAKE, FAKE, None, None) == 5
-    assert f(FAKE, 8, 64, 100, 10, 0.0, FAKE, FAKE, FAKE, ODD, None) == 5
+    assert f(None, 8, 64, 100, 10, 0.0, 0, FAKE, FAKE, FAKE, None, None) == 1
+    assert f(FAKE, 8, 64, 100, 10, 0.0, 0, FAKE, FAKE, None, None, None) == 1
+    assert f(FAKE, 0, 64, 100, 10, 0.0, 0, FAKE, FAKE, FAKE, None, None) == 2
+    assert f(FAKE, 8, 63, 100, 10, 0.0, 0, FAKE, FAKE, FAKE, None, None) == 2        # K odd
+    assert f(FAKE, 8, 64, 0, 10, 0.0, 0, FAKE, FAKE, FAKE, None, None) == 2          # no search steps
+    assert f(FAKE, 8, 64, 100, -1, 0.0, 0, FAKE, FAKE, FAKE, None, None) == 2
+    assert f(FAKE, 8, 64, 100, 10, -1.0, 0, FAKE, FAKE, FAKE, None, None) == 2
+    assert f(FAKE, 8, 65536, 100, 10, 0.0, 0, FAKE, FAKE, FAKE, None, None) == 3     # row does not fit LDS
+    assert f(FAKE, 8, 64, 100, 10, 0.0, 0, ODD, FAKE, FAKE, None, None) == 5
+    assert f(FAKE, 8, 64, 100, 10, 0.0, 0, FAKE, FAKE, FAKE, ODD, None) == 5
+    assert f(FAKE, 8, 64, 100, 10, 0.0, 2, FAKE, FAKE, FAKE, None, None) == 3     # unknown search mode
+    assert f(FAKE, 8, 64, 2, 10, 0.0, 0, FAKE, FAKE, FAKE, None, None) == 2       # the listing's i = 1 needs 3 steps
+    assert f(FAKE, 8, 64, 2, 10, 0.0, 1, ODD, FAKE, FAKE, None, None) == 5        # (fine for the superset search)
 
 
 def test_gbs_argument_errors():

@@ -44,6 +44,8 @@ def compare(w, label, **kw):
     (96, 64, {}), (96, 256, {}), (256, 1536, {}), (64, 3072, {}), (24, 13824, {}), (5, 32768, dict(n_steps=20)),
     (96, 1536, dict(n_steps=16, max_refine=0)), (96, 1536, dict(n_steps=40, max_refine=3)),
     (96, 1536, dict(eps=1e-4)), (7, 130, dict(n_steps=7, max_refine=2)),
+    (96, 256, dict(search=1)), (128, 1536, dict(search=1)), (96, 1536, dict(search=1, n_steps=16, max_refine=0)),
+    (96, 1536, dict(search=1, eps=1e-4)), (24, 13824, dict(search=1)),
 ])
 def test_bgr_matches_the_oracle_on_gaussian_rows(N, K, kw):
     rng = np.random.default_rng(N * 7 + K)
@@ -63,13 +65,15 @@ def test_bgr_special_rows():
             rng.standard_t(3, K) * 0.02]                                         # heavy tails
     rows[3][:16] = 0.125 * (np.arange(16) - 3.0)
     w = np.stack(rows).astype(np.float32)
-    q_g, d_g, z_g, e_g = gpu_bgr(w)
-    q_r, d_r, z_r, e_r = oracle.bgr(w)
-    assert np.array_equal(z_g, z_r) and np.array_equal(d_g, d_r.astype(np.float32)) and np.array_equal(q_g, q_r)
-    assert np.allclose(e_g, e_r, rtol=1e-9, atol=0)
-    assert np.all(e_g[:4] == 0)
-    deq = d_g[:4, None].astype(np.float64) * (q_g[:4].astype(np.float64) - z_g[:4, None])
-    assert np.array_equal(deq, w[:4].astype(np.float64))
+    # exact: constant rows in either search; the on-grid row where plain MinMax (i = 0) is a candidate
+    for search, exact in ((dvdq.BGR_BEST_OF_ALL, 4), (dvdq.BGR_LISTING, 3)):
+        q_g, d_g, z_g, e_g = gpu_bgr(w, search=search)
+        q_r, d_r, z_r, e_r = oracle.bgr(w, search=search)
+        assert np.array_equal(z_g, z_r) and np.array_equal(d_g, d_r.astype(np.float32)) and np.array_equal(q_g, q_r)
+        assert np.allclose(e_g, e_r, rtol=1e-9, atol=0)
+        assert np.all(e_g[:exact] == 0)
+        deq = d_g[:exact, None].astype(np.float64) * (q_g[:exact].astype(np.float64) - z_g[:exact, None])
+        assert np.array_equal(deq, w[:exact].astype(np.float64))
 
 
 def test_bgr_weights_through_the_layer():

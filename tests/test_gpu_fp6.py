@@ -144,7 +144,8 @@ def test_rotate_quant_fp6_decodes_to_the_int8_codes(M, K, B):
     assert np.array_equal(decoded, codes8.cpu().numpy()), "both containers must carry the same codes"
     assert torch.equal(scale6, scale8) and torch.equal(rs6, rs8)
     codes_r, scale_r, xr = oracle.rotate_quant(xb, B, 4, return_rotated=True)
-    check_codes_and_scales(decoded, scale6.cpu().numpy(), codes_r, scale_r, xr, 4, f"fp6 M{M} K{K} B{B}")
+    check_codes_and_scales(decoded, scale6.cpu().numpy(), codes_r, scale_r, xr, 4, f"fp6 M{M} K{K} B{B}",
+                           allow_fp32_ties=B <= 8)
 
 
 def test_rotate_quant_fp6_leaves_neighbouring_memory_alone():
@@ -178,7 +179,10 @@ def test_qlinear_on_the_fp6_path_matches_the_int8_path(idx):
     c6, scale = dvdq.workspace_views(wsp, M, K, dvdq.CODES_FP6)
     codes8, scale8 = dvdq.workspace_views(wsp8, M, K)
     assert torch.equal(scale, scale8)
-    rows = di.sample_rows(M, 128)
+    # first 256 + last 256 rows (the ragged last tile) + 64 from the middle, as in the INT8 full-size test
+    rows = di.sample_rows(M, 256)
+    if M > 512:
+        rows = np.unique(np.concatenate([rows, np.random.default_rng(M).choice(np.arange(256, M - 256), 64, replace=False)]))
     rows_t = torch.from_numpy(rows).to(DEV)
     decoded = oracle.unpack_fp6(c6.cpu().numpy(), M, K)[rows]
     assert np.array_equal(decoded, codes8[rows_t].cpu().numpy())

@@ -1,5 +1,7 @@
-"""GPU parity at the full workload sizes, in the launch configuration bench.py times
-(dvdq_qlinear, native weight layout).  The oracle cannot afford all M rows, so it
+"""GPU parity at the full workload sizes through dvdq_qlinear with the native weight layout,
+int8 code container, INT8 matrix path (the configuration the benchmark times for W4A6; the
+W4A4 workloads on the FP6 matrix path, which the benchmark times for them, are checked at
+full size in test_gpu_fp6.py).  The oracle cannot afford all M rows, so it
 judges a deterministic row sample (first 256 + last 256 rows, which covers the ragged
 last tile, plus 64 rows from the middle); properties that hold at any size are
 checked on every row on the GPU."""

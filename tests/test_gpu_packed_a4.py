@@ -50,8 +50,8 @@ def test_rotate_quant_packed_decodes_to_the_int8_codes(M, K, B):
     assert np.array_equal(decoded, codes8.cpu().numpy()), "both containers must carry the same codes"
     assert torch.equal(scale_p, scale8)
     codes_r, scale_r, xr = oracle.rotate_quant(xb, B, 4, return_rotated=True)
-    stats = check_codes_and_scales(decoded, scale_p.cpu().numpy(), codes_r, scale_r, xr, 4, f"packed M{M} K{K} B{B}")
-    assert stats["mismatches"] - stats.get("fp32_ties", 0) <= stats["budget"]
+    check_codes_and_scales(decoded, scale_p.cpu().numpy(), codes_r, scale_r, xr, 4, f"packed M{M} K{K} B{B}",
+                           allow_fp32_ties=B <= 8)
 
 
 def test_rotate_quant_packed_leaves_neighbouring_memory_alone():

@@ -40,7 +40,9 @@ def run_rq(xb, B, bits, label):
     codes_g, scale_g = dvdq.rotate_quant(to_bf16(xb), B, bits)
     torch.cuda.synchronize()
     codes_r, scale_r, xr = oracle.rotate_quant(xb, B, bits, return_rotated=True)
-    return check_codes_and_scales(codes_g.cpu().numpy(), scale_g.cpu().numpy(), codes_r, scale_r, xr, bits, label)
+    # blocks of 1 to 8 channels leave bf16 inputs (nearly) unmixed: exact ties at fp32 resolution come in clusters
+    return check_codes_and_scales(codes_g.cpu().numpy(), scale_g.cpu().numpy(), codes_r, scale_r, xr, bits, label,
+                                  allow_fp32_ties=B <= 8)
 
 
 def test_rotate_quant_tiny_config():

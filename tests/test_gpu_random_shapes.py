@@ -101,7 +101,8 @@ def test_random_quantizer_cases(seed):
             vals, scale, rs = dvdq.rotate_quant_blockwise(to_bf16(xb), B, bits, g, want_rowsum=True)
             torch.cuda.synchronize()
             v_ref, s_ref, e_ref = oracle.quantize_blockwise(xr, bits, g)
-            check_blockwise(vals.cpu().numpy(), scale.cpu().numpy(), v_ref, s_ref, e_ref, xr, bits, g, label)
+            check_blockwise(vals.cpu().numpy(), scale.cpu().numpy(), v_ref, s_ref, e_ref, xr, bits, g, label,
+                            allow_fp32_ties=True)
             codes_np = vals.cpu().numpy()
         else:
             fmt = dvdq.CODES_FP6 if fp6 else (dvdq.CODES_PACKED4 if packed else dvdq.CODES_INT8)
@@ -112,5 +113,5 @@ def test_random_quantizer_cases(seed):
             else:
                 codes_np = oracle.unpack_a4(codes.cpu().numpy()) if packed else codes.cpu().numpy()
             c_ref, s_ref = oracle.quantize(xr, bits)
-            check_codes_and_scales(codes_np, scale.cpu().numpy(), c_ref, s_ref, xr, bits, label)
+            check_codes_and_scales(codes_np, scale.cpu().numpy(), c_ref, s_ref, xr, bits, label, allow_fp32_ties=True)
         assert np.array_equal(rs.cpu().numpy().astype(np.int64), codes_np.astype(np.int64).sum(axis=1)), label

@@ -48,7 +48,7 @@ def test_weights_on_an_asymmetric_grid_are_recovered_exactly():
         q0 = np.concatenate([np.arange(16), rng.integers(0, 16, 240)]).astype(np.int64)
         rng.shuffle(q0)
         w = (d0 * (q0 - z0)).astype(np.float32)[None, :]
-        for fn in (oracle.minmax_quant, oracle.bgr):
+        for fn in (oracle.minmax_quant, lambda a: oracle.bgr(a, search=oracle.BGR_BEST_OF_ALL)):
             q, d, z, e = fn(w)
             assert e[0] == 0.0 and d[0] == d0 and z[0] == z0 and np.array_equal(q[0], q0)
 
@@ -79,11 +79,11 @@ def test_refine_step_is_the_least_squares_step_and_the_relaxed_zero_point():
 
 
 @pytest.mark.parametrize("n_steps,max_refine", [(100, 10), (16, 0), (40, 3)])
-def test_bgr_outputs_are_consistent_and_never_worse_than_any_start(n_steps, max_refine):
+def test_best_of_all_search_is_consistent_and_never_worse_than_any_start(n_steps, max_refine):
     w = gaussian_rows(3, 48, 512)
     w[5] += 0.05                      # a row that is not zero-mean
     w[7, :3] = [0.5, -0.4, 0.45]      # a row with outliers
-    q, d, z, e = oracle.bgr(w, n_steps=n_steps, max_refine=max_refine)
+    q, d, z, e = oracle.bgr(w, n_steps=n_steps, max_refine=max_refine, search=oracle.BGR_BEST_OF_ALL)
     assert q.max() <= 15 and np.all((z >= 0) & (z <= 15)) and np.all(d > 0)
     # the codes are the Quant equation applied with the returned grid; the error is the reported one
     q_expect = np.clip(np.rint(w.astype(np.float64) / d[:, None]) + z[:, None], 0, 15).astype(np.uint8)
@@ -110,6 +110,82 @@ def test_bgr_outputs_are_consistent_and_never_worse_than_any_start(n_steps, max_
         assert np.allclose(e, best_start, rtol=1e-12)
 
 
+def test_listing_search_worked_example():
+    """Alg. 1 as printed, followed by hand through its only start (2-bit codes, 3 shrink steps)."""
+    g = read_gold("bgr_listing_worked_example.txt")
+    w = g["w"][None, :].astype(np.float32)
+    sw2 = g["e3sq_a"][0]
+    d1, d2, d3 = g["d1num"][0] / g["d1den"][0], g["d2"][0], g["d3num"][0] / g["d3den"][0]
+    e1sq = sw2 - 2 * d1 * 19.0 + d1 * d1 * 8.0
+    e3sq = sw2 - g["d3num"][0] ** 2 / g["d3den"][0]
+    rounds = {1: (d1, g["q1"], e1sq), 2: (d2, g["q2"], g["e2sq"][0]), 3: (d3, g["q2"], e3sq)}
+    for kw, rnd in [(dict(max_refine=1, eps=0.0), 1), (dict(max_refine=2, eps=0.0), 2), (dict(max_refine=10, eps=2.0), 1),
+                    (dict(max_refine=3, eps=0.0), 3), (dict(max_refine=10, eps=1e-9), 3), (dict(max_refine=10, eps=0.0), 3)]:
+        q, d, z, e = oracle.bgr(w, bits=2, n_steps=3, search=oracle.BGR_LISTING, **kw)
+        d_ref, q_ref, esq = rounds[rnd]
+        assert d[0] == d_ref and z[0] == g["z"][0], (kw, d[0], d_ref)
+        assert np.array_equal(q[0], q_ref.astype(np.uint8)), kw
+        assert abs(e[0] ** 2 - esq) <= 1e-12 * esq, kw
+    # no refinement round at all: the start itself
+    q, d, z, e = oracle.bgr(w, bits=2, n_steps=3, max_refine=0)
+    assert d[0] == 1.0 and z[0] == 1 and np.array_equal(q[0], g["q0"].astype(np.uint8)) and abs(e[0] ** 2 - g["e0sq"][0]) < 1e-12
+    # the listing has no i = 0: plain MinMax (Delta = 3, z = 1, E^2 = 6.375 here) is not a candidate, the
+    # superset search has it and every round of every start
+    q, d, z, e = oracle.bgr(w, bits=2, n_steps=3, max_refine=0, search=oracle.BGR_BEST_OF_ALL)
+    assert d[0] == 3.0 and z[0] == 1 and abs(e[0] ** 2 - 6.375) < 1e-12
+    # fewer than 3 shrink steps leave the listing without a start
+    with pytest.raises(ValueError):
+        oracle.bgr(w, bits=2, n_steps=2)
+
+
+def listing_by_composition(w_row, n_steps, max_refine, eps):
+    """Alg. 1's control flow written out over the oracle's single refinement round (pinned above against a
+    library least-squares solver and a library minimizer) and a MinMax start computed here."""
+    wd = w_row.astype(np.float64)
+    lo0, hi0 = wd.min(), wd.max()
+    best = (np.inf, None, None)
+    for i in range(1, n_steps + 1):
+        lo, hi = lo0 + i * ((hi0 - lo0) / n_steps), hi0 - i * ((hi0 - lo0) / n_steps)
+        if not lo < hi:
+            break
+        delta = (hi - lo) / 15.0
+        z = int(np.clip(np.rint(-(lo / delta)), 0, 15))
+        q = np.clip(np.rint(wd / delta) + z, 0, 15).astype(np.uint8)
+        e = np.sqrt(((wd - delta * (q.astype(np.float64) - z)) ** 2).sum())
+        for _ in range(max_refine):
+            step = oracle.bgr_refine_step(w_row, q, z)
+            if step is None:
+                break
+            dn, zn, qn, en = step
+            gain = e - en
+            # A round cannot lose: the least-squares step is optimal for the codes it sees, the rounded
+            # zero-point is the integer nearest the real minimizer of a parabola (no farther from it than the
+            # old integer one), and re-quantizing picks the nearest code.  So a start's last grid is its best.
+            assert gain >= -1e-12 * e
+            delta, z, q, e = dn, zn, qn, en
+            if gain < eps:
+                break
+        if e < best[0]:
+            best = (e, delta, z)
+    return best
+
+
+def test_listing_search_is_the_listing_control_flow_over_the_pinned_round():
+    w = gaussian_rows(11, 24, 384)
+    w[3] += 0.03
+    w[9, :2] = [0.4, -0.5]
+    for kw in (dict(n_steps=100, max_refine=10, eps=0.0), dict(n_steps=30, max_refine=4, eps=1e-4), dict(n_steps=9, max_refine=1, eps=0.0)):
+        q, d, z, e = oracle.bgr(w, search=oracle.BGR_LISTING, **kw)
+        for n in range(w.shape[0]):
+            e_ref, d_ref, z_ref = listing_by_composition(w[n], kw["n_steps"], kw["max_refine"], kw["eps"])
+            assert d[n] == d_ref and z[n] == z_ref and abs(e[n] - e_ref) <= 1e-12 * e_ref, (kw, n)
+        q_expect = np.clip(np.rint(w.astype(np.float64) / d[:, None]) + z[:, None], 0, 15).astype(np.uint8)
+        assert np.array_equal(q, q_expect)
+        # the superset search contains every grid the listing looks at
+        e_all = oracle.bgr(w, search=oracle.BGR_BEST_OF_ALL, **kw)[3]
+        assert np.all(e_all <= e * (1 + 1e-12))
+
+
 def test_bgr_reduces_the_error_of_gaussian_and_heavy_tailed_rows():
     """Direction and rough size of the gain over MinMax (Sec. 3.1 reports 86 % on trained weights, which
     are not available; on synthetic rows the squared error falls by about a third, more with heavier tails)."""
@@ -123,12 +199,12 @@ def test_bgr_reduces_the_error_of_gaussian_and_heavy_tailed_rows():
 
 def test_refinement_rounds_continue_while_they_improve_and_stop_on_eps():
     w = gaussian_rows(9, 32, 768)
-    errs = [oracle.bgr(w, n_steps=20, max_refine=r)[3] for r in (0, 1, 3, 10)]
+    errs = [oracle.bgr(w, n_steps=20, max_refine=r, search=oracle.BGR_BEST_OF_ALL)[3] for r in (0, 1, 3, 10)]
     for a, b in zip(errs, errs[1:]):
         assert np.all(b <= a)                       # more rounds never hurt (best-so-far is kept)
     assert np.any(errs[1] < errs[0]) and np.any(errs[2] < errs[1])   # and later rounds still find improvements
     # a threshold no improvement can reach ends every refinement after its first round
-    e_big = oracle.bgr(w, n_steps=20, max_refine=10, eps=1e9)[3]
+    e_big = oracle.bgr(w, n_steps=20, max_refine=10, eps=1e9, search=oracle.BGR_BEST_OF_ALL)[3]
     assert np.array_equal(e_big, errs[1])
 
 
