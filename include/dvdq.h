@@ -192,6 +192,25 @@ size_t dvdq_qlinear_scale_offset(int64_t M, int64_t K, int codes_format);
 size_t dvdq_qlinear_rowsum_offset(int64_t M, int64_t K, int codes_format);
 
 /*
+ * dvdq_qlinear for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * bit-identical outputs, but the codes, token scales and code sums go to a fixed array of
+ * DVDQ_STATIC_WORKSPACE_BYTES of device memory that is part of the library's code object (every GPU
+ * the library runs on holds its own copy until the process ends) instead of a caller workspace.
+ * Requests with dvdq_qlinear_workspace_bytes(M, K, codes_format) above that size return
+ * DVDQ_ERR_WORKSPACE; nothing is enqueued then.  The call allocates nothing and frees nothing.  Its first call
+ * on a device looks the array's address up (hipGetSymbolAddress): make that call before a stream
+ * capture starts.  All calls on one GPU share the array, which keeps the previous call's contents
+ * (every byte a call reads it has written itself, nothing needs clearing): calls that may run
+ * concurrently on one GPU, e.g. on two streams, race on it and must be ordered by the caller.
+ */
+#define DVDQ_STATIC_WORKSPACE_BYTES (64u << 20)
+int dvdq_qlinear_static(const void *x_bf16, const uint8_t *w, const float *w_scale, const int8_t *w_zero,
+                        const void *bias_bf16, int64_t M, int64_t N, int64_t K, int had_block, int act_bits,
+                        int codes_format, int w_layout, void *y_bf16, void *hip_stream);
+size_t dvdq_static_workspace_bytes(void);
+
+/*
  * One-time, offline: reorder canonical packed weights into the GEMM kernel's
  * native layout (the rotated, quantized weights of Sec. 3.2 are fixed after
  * quantization, so this runs once per layer).  w_native must hold

@@ -15,7 +15,7 @@ import torch
 
 __all__ = [
     "DvdqError", "DvdqLibraryMissing", "lib", "library_path", "version", "status_string",
-    "rotate_quant", "rotate_quant_blockwise", "w4ax_gemm", "qlinear", "qlinear_workspace_bytes", "qlinear_scale_offset", "qlinear_rowsum_offset", "workspace_rowsum",
+    "rotate_quant", "rotate_quant_blockwise", "w4ax_gemm", "qlinear", "qlinear_static", "static_workspace_bytes", "qlinear_workspace_bytes", "qlinear_scale_offset", "qlinear_rowsum_offset", "workspace_rowsum",
     "w4_prepack", "w4_native_bytes", "w4_prepack_fp6", "w4_native_fp6_bytes", "codes_bytes", "bgr_quantize", "GbsController", "bench_copy", "bench_mfma_i8", "bench_mfma_fp6", "bench_set_gemm_variant", "bench_set_gemm_schedule",
     "W_CANONICAL", "W_NATIVE", "W_NATIVE_FP6", "CODES_INT8", "CODES_PACKED4", "CODES_FP6", "BGR_LISTING", "BGR_BEST_OF_ALL", "EXPORTED_SYMBOLS",
 ]
@@ -26,7 +26,7 @@ BGR_LISTING, BGR_BEST_OF_ALL = 0, 1
 
 EXPORTED_SYMBOLS = (
     "dvdq_rotate_quant", "dvdq_rotate_quant_blockwise", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_qlinear_workspace_bytes",
-    "dvdq_qlinear_scale_offset", "dvdq_qlinear_rowsum_offset", "dvdq_w4_prepack", "dvdq_w4_native_bytes", "dvdq_w4_prepack_fp6",
+    "dvdq_qlinear_scale_offset", "dvdq_qlinear_rowsum_offset", "dvdq_qlinear_static", "dvdq_static_workspace_bytes", "dvdq_w4_prepack", "dvdq_w4_native_bytes", "dvdq_w4_prepack_fp6",
     "dvdq_w4_native_fp6_bytes", "dvdq_codes_bytes", "dvdq_status_string",
     "dvdq_version", "dvdq_gbs_workspace_bytes", "dvdq_gbs_reset", "dvdq_gbs_step", "dvdq_bgr_quantize", "dvdq_bench_copy", "dvdq_bench_mfma_i8", "dvdq_bench_mfma_fp6", "dvdq_bench_set_gemm_variant", "dvdq_bench_set_gemm_schedule",
 )
@@ -66,6 +66,10 @@ def lib() -> C.CDLL:
     L.dvdq_rotate_quant_blockwise.restype = i32
     L.dvdq_w4ax_gemm.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, vp, vp]
     L.dvdq_qlinear.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, i32, vp, vp, sz, vp]
+    L.dvdq_qlinear_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, i32, vp, vp]
+    L.dvdq_qlinear_static.restype = i32
+    L.dvdq_static_workspace_bytes.argtypes = []
+    L.dvdq_static_workspace_bytes.restype = sz
     L.dvdq_qlinear_rowsum_offset.argtypes = [i64, i64, i32]
     L.dvdq_qlinear_workspace_bytes.argtypes = [i64, i64, i32]
     L.dvdq_qlinear_scale_offset.argtypes = [i64, i64, i32]
@@ -295,6 +299,33 @@ def qlinear(x, w, w_scale, had_block: int, act_bits: int, w_layout: int = W_CANO
                           codes_format, w_layout, _ptr(y), _ptr(workspace), workspace.numel(), _stream(stream)),
            "dvdq_qlinear")
     return y, workspace
+
+
+def static_workspace_bytes() -> int:
+    return lib().dvdq_static_workspace_bytes()
+
+
+def qlinear_static(x, w, w_scale, had_block: int, act_bits: int, w_layout: int = W_CANONICAL, bias=None, y=None,
+                   stream=None, codes_format: int = CODES_INT8, w_zero=None):
+    """The whole layer with the library's own fixed workspace (no allocation inside the call; `y` must be
+    given if the caller may not allocate either).  Returns y bf16 [M, N]."""
+    L = lib()
+    _need(x, torch.bfloat16, None, "x")
+    M, K = x.shape
+    _need(w_scale, torch.float32, None, "w_scale")
+    N = w_scale.shape[0]
+    _need(w, torch.uint8, None, "w")
+    _check_weight_buffer(L, w, w_layout, N, K)
+    if bias is not None:
+        _need(bias, torch.bfloat16, (N,), "bias")
+    if w_zero is not None:
+        _need(w_zero, torch.int8, (N,), "w_zero")
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    _need(y, torch.bfloat16, (M, N), "y")
+    _check(L.dvdq_qlinear_static(_ptr(x), _ptr(w), _ptr(w_scale), _ptr(w_zero), _ptr(bias), M, N, K, had_block,
+                                 act_bits, codes_format, w_layout, _ptr(y), _stream(stream)), "dvdq_qlinear_static")
+    return y
 
 
 def workspace_views(workspace, M: int, K: int, codes_format: int = CODES_INT8):

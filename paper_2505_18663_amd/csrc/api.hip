@@ -3,7 +3,33 @@
 // frees or synchronizes.
 #include "dvdq_internal.h"
 
+// Workspace of dvdq_qlinear_static: device memory that is part of the loaded code object, one copy per GPU,
+// held until the process ends.  In host code this name is only a handle for hipGetSymbolAddress; the
+// address of a GPU's copy is looked up once per device (scratch_ptr below) and that pointer is what
+// the kernels get.
+static __device__ __align__(256) uint8_t scratch[DVDQ_STATIC_WORKSPACE_BYTES];
+
 namespace {
+
+// Address of the current device's copy of `scratch` (nullptr on failure).  Looked up on the first call
+// per device, with that device current; later calls only read the table.
+uint8_t *scratch_ptr() {
+    static std::atomic<uint8_t *> table[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    uint8_t *p = table[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    void *addr = nullptr;
+    if (hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch)) != hipSuccess || !addr) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    table[dev].store(static_cast<uint8_t *>(addr), std::memory_order_release);
+    return static_cast<uint8_t *>(addr);
+}
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -168,6 +194,23 @@ int dvdq_qlinear(const void *x_bf16, const uint8_t *w, const float *w_scale, con
     return dvdq::launch_w4ax_gemm(codes, x_scale, w, w_scale, w_zero, rowsum,
                                   static_cast<const uint16_t *>(bias_bf16), M, N, K, codes_format, w_layout,
                                   static_cast<uint16_t *>(y_bf16), nullptr, stream);
+}
+
+size_t dvdq_static_workspace_bytes(void) { return DVDQ_STATIC_WORKSPACE_BYTES; }
+
+int dvdq_qlinear_static(const void *x_bf16, const uint8_t *w, const float *w_scale, const int8_t *w_zero,
+                        const void *bias_bf16, int64_t M, int64_t N, int64_t K, int had_block, int act_bits,
+                        int codes_format, int w_layout, void *y_bf16, void *hip_stream) {
+    if (M < 1 || K < 1) return DVDQ_ERR_SHAPE;
+    if (check_format(codes_format, act_bits) != DVDQ_OK) return DVDQ_ERR_UNSUPPORTED;
+    if (codes_format == DVDQ_CODES_FP6 && (K % 128) != 0) return DVDQ_ERR_UNSUPPORTED;
+    if (K > 65536 || M > 0x7FFFFFFF) return DVDQ_ERR_UNSUPPORTED;   // (keeps the size below from overflowing)
+    const size_t need = dvdq_qlinear_workspace_bytes(M, K, codes_format);
+    if (need == 0 || need > (size_t)DVDQ_STATIC_WORKSPACE_BYTES) return DVDQ_ERR_WORKSPACE;
+    uint8_t *ws = scratch_ptr();
+    if (!ws) return DVDQ_ERR_HIP;
+    return dvdq_qlinear(x_bf16, w, w_scale, w_zero, bias_bf16, M, N, K, had_block, act_bits, codes_format, w_layout,
+                        y_bf16, ws, (size_t)DVDQ_STATIC_WORKSPACE_BYTES, hip_stream);
 }
 
 size_t dvdq_w4_native_bytes(int64_t N, int64_t K) {

@@ -117,6 +117,15 @@ def test_prepack_argument_errors_and_size():
     assert L.dvdq_w4_prepack(FAKE, 8, 128, ODD, None) == 5
 
 
+def test_static_workspace_argument_errors():
+    L = dvdq.lib()
+    assert L.dvdq_static_workspace_bytes() == 64 << 20
+    f = L.dvdq_qlinear_static
+    assert f(FAKE, FAKE, FAKE, None, None, 0, 8, 256, 256, 4, 0, 1, FAKE, None) == 2              # M < 1
+    assert f(FAKE, FAKE, FAKE, None, None, 8, 8, 256, 256, 6, 1, 1, FAKE, None) == 3              # packed codes are 4-bit
+    assert f(FAKE, FAKE, FAKE, None, None, 1 << 20, 8, 4096, 256, 4, 0, 1, FAKE, None) == 4       # beyond the fixed array
+
+
 def test_bgr_argument_errors():
     f = dvdq.lib().dvdq_bgr_quantize
     assert f(None, 8, 64, 100, 10, 0.0, 0, FAKE, FAKE, FAKE, None, None) == 1
