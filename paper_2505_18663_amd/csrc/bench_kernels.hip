@@ -8,10 +8,23 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-__global__ __launch_bounds__(256) void copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n) {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (; i < n; i += stride) dst[i] = src[i];
+// Streaming copy used as the yardstick for HBM-bound kernels: every lane keeps four independent 16-byte
+// non-temporal loads in flight (a wave instruction covers one contiguous kilobyte), then stores them
+// non-temporally; workgroups stride over the buffer.
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+constexpr int kCopyUnroll = 4;
+__global__ __launch_bounds__(256) void copy_kernel(const v4u *__restrict__ src, v4u *__restrict__ dst, size_t n) {
+    const size_t stride = (size_t)gridDim.x * (256 * kCopyUnroll);
+    size_t i = (size_t)blockIdx.x * (256 * kCopyUnroll) + threadIdx.x;
+    for (; i + 256 * (kCopyUnroll - 1) < n; i += stride) {
+        v4u v[kCopyUnroll];
+#pragma unroll
+        for (int u = 0; u < kCopyUnroll; ++u) v[u] = __builtin_nontemporal_load(src + i + 256 * u);
+#pragma unroll
+        for (int u = 0; u < kCopyUnroll; ++u) __builtin_nontemporal_store(v[u], dst + i + 256 * u);
+    }
+    for (int u = 0; u < kCopyUnroll; ++u)   // the last, partial group of the buffer (at most one workgroup gets here with work)
+        if (i + 256 * u < n) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i + 256 * u), dst + i + 256 * u);
 }
 
 // Operand words of the MFMA loops.  data 0: the same small constants in every lane (nothing but MFMA issue
@@ -128,10 +141,10 @@ int dvdq_bench_copy(const void *src, void *dst, size_t bytes, void *hip_stream) 
     if (bytes == 0 || (bytes % 16) != 0) return DVDQ_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(src) & 15u) || (reinterpret_cast<uintptr_t>(dst) & 15u)) return DVDQ_ERR_ALIGN;
     const size_t n = bytes / 16;
-    size_t blocks = (n + 255) / 256;
-    if (blocks > 256 * 32) blocks = 256 * 32;
+    size_t blocks = (n + 256 * kCopyUnroll - 1) / (256 * kCopyUnroll);
+    if (blocks > 256 * 8) blocks = 256 * 8;   // 8 resident workgroups per compute unit stride over the buffer
     hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
-                       static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n);
+                       static_cast<const v4u *>(src), static_cast<v4u *>(dst), n);
     return dvdq::check_launch();
 }
 

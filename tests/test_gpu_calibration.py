@@ -10,14 +10,17 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def test_copy_kernel_copies():
+@pytest.mark.parametrize("nbytes", [16, 4096 - 16, 16384, (1 << 20) + 4096, (1 << 20) + 16 * 1021, 40 << 20])
+def test_copy_kernel_copies(nbytes):
     g = torch.Generator(device=DEV)
     g.manual_seed(5)
-    src = torch.randint(0, 256, ((1 << 20) + 4096,), device=DEV, dtype=torch.uint8, generator=g)
-    dst = torch.zeros_like(src)
+    buf = torch.randint(0, 256, (nbytes + 512,), device=DEV, dtype=torch.uint8, generator=g)
+    out = torch.full((nbytes + 512,), 0xA5, device=DEV, dtype=torch.uint8)
+    src, dst = buf[256:256 + nbytes], out[256:256 + nbytes]
     dvdq.bench_copy(src, dst)
     torch.cuda.synchronize()
     assert torch.equal(src, dst)
+    assert bool((out[:256] == 0xA5).all()) and bool((out[256 + nbytes:] == 0xA5).all())   # nothing written outside
 
 
 @pytest.mark.parametrize("data", [0, 1])
