@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdvdq.so")
 
-SOURCES = ["api.hip", "rotate_quant.hip", "w4ax_gemm.hip", "w4a4_fp6_gemm.hip", "w4ax_gemm_generic.hip", "gbs.hip", "bgr.hip", "bench_kernels.hip"]
+SOURCES = ["api.hip", "rotate_quant.hip", "w4ax_gemm.hip", "w4a4_fp6_gemm.hip", "w4ax_gemm_wide.hip", "w4ax_gemm_generic.hip", "gbs.hip", "bgr.hip", "bench_kernels.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

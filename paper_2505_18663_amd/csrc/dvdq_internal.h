@@ -26,6 +26,11 @@ int launch_w4ax_gemm_canonical(const int8_t *codes, const float *x_scale, const 
 int launch_w4a4_fp6_gemm(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                          const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,
                          int64_t K, uint16_t *y, int32_t *acc_out, hipStream_t stream);
+// One 4-wave workgroup per compute unit, 128 x 128 wave tiles, accumulators in AGPRs (w4ax_gemm_wide.hip):
+// int8 codes x native weights (fp6 = false) or FP6 codes x FP6 native weights (fp6 = true)
+int launch_w4ax_gemm_wide(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
+                          const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,
+                          int64_t K, bool fp6, uint16_t *y, int32_t *acc_out, hipStream_t stream);
 size_t w4_native_fp6_bytes(int64_t N, int64_t K);
 size_t codes_fp6_bytes(int64_t M, int64_t K);
 int launch_w4_prepack_fp6(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, hipStream_t stream);

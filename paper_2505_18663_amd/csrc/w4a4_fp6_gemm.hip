@@ -579,6 +579,7 @@ int launch_w4a4_fp6_gemm(const uint8_t *codes, const float *x_scale, const uint8
     //      no second workgroup hides its epilogue.  Taken when there are at least two rounds of such tiles
     //      and K is deep enough for the ring; the benchmark hook can force either.
     int v = gemm_variant();
+    if (v == 3) return launch_w4ax_gemm_wide(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, M, N, K, true, y, acc_out, stream);
     const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
     if (v != 1 && v != 2) v = big_tiles >= 512 ? 2 : 1;
     if (K / kBK < 2) v = 1;

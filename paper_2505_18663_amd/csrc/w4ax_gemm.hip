@@ -720,6 +720,9 @@ int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w
             default: return DVDQ_ERR_UNSUPPORTED;
         }
     }
+    if (v == 5)
+        return launch_w4ax_gemm_wide(reinterpret_cast<const uint8_t *>(codes), x_scale, w, w_scale, w_zero, code_rowsum, bias,
+                                     M, N, K, false, y, acc_out, stream);
     {
         const int bk = v == 4 ? 64 : 128, stages = v == 2 ? 2 : (v == 4 ? 4 : 3);
         if (k / bk < stages - 1) v = 2;
