@@ -35,27 +35,17 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kFp6Block = kGroup * kBK * 6 / 8;   // 3072: 32 rows of one K slice as E2M3 patterns
 
-// One group of four MFMAs that share the row operand `w` (output channels) against four column operands
-// (tokens).  Inline assembly with the accumulators constrained to AGPRs; the leading s_nop covers the two
-// wait states an MFMA needs after a VALU write of one of its operand registers (the widening), which the
-// compiler cannot insert for an instruction it does not see.
-__device__ __forceinline__ void mfma4_i8(v16i &c0, v16i &c1, v16i &c2, v16i &c3, v4i w, v4i a0, v4i a1, v4i a2, v4i a3) {
-    asm volatile("s_nop 1\n\t"
-                 "v_mfma_i32_32x32x32_i8 %0, %4, %5, %0\n\t"
-                 "v_mfma_i32_32x32x32_i8 %1, %4, %6, %1\n\t"
-                 "v_mfma_i32_32x32x32_i8 %2, %4, %7, %2\n\t"
-                 "v_mfma_i32_32x32x32_i8 %3, %4, %8, %3"
-                 : "+a"(c0), "+a"(c1), "+a"(c2), "+a"(c3)
-                 : "v"(w), "v"(a0), "v"(a1), "v"(a2), "v"(a3));
+// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
+template <int V> using I = std::integral_constant<int, V>;
+template <int N, int K0 = 0, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (K0 < N) {
+        f(I<K0>{});
+        static_for<N, K0 + 1>(f);
+    }
 }
-__device__ __forceinline__ void mfma4_fp6(v16f &c0, v16f &c1, v16f &c2, v16f &c3, v6i w, v6i a0, v6i a1, v6i a2, v6i a3) {
-    asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %4, %5, %0 cbsz:2 blgp:2\n\t"
-                 "v_mfma_f32_32x32x64_f8f6f4 %1, %4, %6, %1 cbsz:2 blgp:2\n\t"
-                 "v_mfma_f32_32x32x64_f8f6f4 %2, %4, %7, %2 cbsz:2 blgp:2\n\t"
-                 "v_mfma_f32_32x32x64_f8f6f4 %3, %4, %8, %3 cbsz:2 blgp:2"
-                 : "+a"(c0), "+a"(c1), "+a"(c2), "+a"(c3)
-                 : "v"(w), "v"(a0), "v"(a1), "v"(a2), "v"(a3));
-}
+
+#include "wide_acc.inc"
 
 }  // namespace
 
@@ -66,14 +56,12 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
     const uint16_t *__restrict__ bias, int M, int N, int K, uint16_t *__restrict__ y, int32_t *__restrict__ acc_out,
     int tiles_m, int tiles_n, int group_n, unsigned *__restrict__ sched) {
     constexpr int BM = 256, BN = 256, NW = 4, WM = 128, WN = 128, TM = 4, TN = 4, STAGES = 3;
-    constexpr int STEPS = FP6 ? 2 : 4;                       // pipeline steps per slice: 64 resp. 32 channels
+    // (pipeline steps per slice: FP6 path 2 of 64 channels, INT8 path 4 of 32)
     constexpr int A_ROW = kBK;                               // INT8 path: bytes of one code row per slice
     constexpr int A_STAGE = FP6 ? BM / 32 * kFp6Block : BM * A_ROW;
     constexpr int W_STAGE = FP6 ? BN / 32 * kFp6Block : BN * kBK / 2;
     constexpr int STAGE = A_STAGE + W_STAGE;                 // 48 KB on both paths
     constexpr int A_DMA = A_STAGE / 1024 / NW, W_DMA = W_STAGE / 1024 / NW, DMA = A_DMA + W_DMA;   // 12 per wave and slice
-    constexpr int GROUPS = (STEPS - 1) * TN;                 // MFMA groups of a slice's steps before its barrier
-    constexpr int DMA_PER_GROUP = (DMA + GROUPS - 1) / GROUPS;
     constexpr int OFF_BIAS = (BM + BN) * 4, OFF_RSUM = OFF_BIAS + BN * 2, OFF_ZERO = OFF_RSUM + BM * 4;
     constexpr int SCALES = OFF_ZERO + BN;
     constexpr int SHIFT = 4;                                 // INT8 path: the widened weights carry a factor 16
@@ -82,10 +70,10 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
     static_assert(STAGE == 48 * 1024 && DMA == 12, "ring geometry");
     static_assert(DMA + STORES < 64 && (STAGES - 1) * DMA + 8 < 64, "vmcnt is 6 bits");
     static_assert(NW * 4096 <= STAGE, "the epilogue stages 4 KB per wave in one ring buffer");
-    using Acc = std::conditional_t<FP6, v16f, v16i>;
 
     extern __shared__ __align__(16) uint8_t smem[];
     const uint32_t smem_base = lds_address(smem);
+    claim_all_agprs();
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -105,39 +93,32 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
     const unsigned run_len = (unsigned)((int64_t)(xcd + 1) * total / 8) - (unsigned)run_lo;
     typedef volatile __attribute__((address_space(3))) int lds_int;
     lds_int *s_tiles = (lds_int *)DVDQ_LDS(smem + STAGES * STAGE + 3 * SCALES);
-    // A tile number drawn while slice `draw_kt` of tile n is issued belongs to tile n + 2.  It is written into the
-    // ring before a later barrier: the barrier after next when it comes from an atomic (by then the loads issued
-    // around the atomic have been awaited, so its reply is there), the next barrier with fixed shares.  Draws follow
-    // each other by K / 128 issue steps, and the prologue issues two steps at once, so up to three can be pending.
-    int draws = 0, published = 2;          // tiles drawn / tile numbers written into the ring
-    unsigned pend_v0 = 0, pend_v1 = 0, pend_v2 = 0;   // wave 0, lane 0: replies not yet written, oldest first
-    int pend_a0 = 0, pend_a1 = 0, pend_a2 = 0, pend_n = 0;   // barriers they have seen
-    const int publish_age = sched ? 2 : 1;
-    auto tile_of_draw = [&] __device__(unsigned i, int ordinal) {
-        if (sched) return i < run_len ? run_lo + (int)i : -1;
+    // Fixed shares (sched == nullptr): the ordinal-th tile of this workgroup is first_tile + ordinal * grid, which
+    // every wave computes for itself.  Drawn tiles (K / 128 >= 2): the number drawn while slice `draw_kt` of tile n
+    // is issued belongs to tile n + 2; wave 0 writes it into the ring before the barrier after next (by then the
+    // loads issued around the atomic have been awaited, so its reply is there), two barriers before it is
+    // read.  Draws are at least two slices apart, so at most one is pending.
+    int published = 2;       // tile numbers written into the ring
+    unsigned drawn = 0;      // wave 0, lane 0: reply of the pending draw
+    int draw_wait = 0;       // barriers until the pending draw is written into the ring (0: none pending)
+    auto tile_of_ordinal = [&] __device__(int ordinal) {   // fixed shares
         const int t = first_tile + ordinal * grid;
         return t < total ? t : -1;
     };
+    auto tile_of_draw = [&] __device__(unsigned i) { return i < run_len ? run_lo + (int)i : -1; };
     auto draw = [&] __device__() {
-        unsigned v = 0;
-        if (wave == 0 && sched && lane == 0) v = atomicAdd(sched + xcd, 1u);
-        if (pend_n == 0) { pend_v0 = v; pend_a0 = 0; }
-        else if (pend_n == 1) { pend_v1 = v; pend_a1 = 0; }
-        else { pend_v2 = v; pend_a2 = 0; }
-        ++pend_n;
-        ++draws;
+        if (!sched) return;
+        if (wave == 0 && lane == 0) drawn = atomicAdd(sched + xcd, 1u);
+        draw_wait = 2;
     };
     auto before_barrier = [&] __device__() {   // every wave, before each workgroup barrier of the pipeline
-        ++pend_a0; ++pend_a1; ++pend_a2;
-        while (pend_n > 0 && pend_a0 >= publish_age) {
+        draw_wait = __builtin_amdgcn_readfirstlane(draw_wait);   // (wave-uniform: keep it in a scalar register)
+        if (draw_wait > 0 && --draw_wait == 0) {
             if (wave == 0) {
-                if (lane == 0) s_tiles[published & 7] = tile_of_draw(pend_v0, published);
+                if (lane == 0) s_tiles[published & 7] = tile_of_draw(drawn);
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             }
             ++published;
-            pend_v0 = pend_v1; pend_a0 = pend_a1;
-            pend_v1 = pend_v2; pend_a1 = pend_a2;
-            --pend_n;
         }
     };
     auto leave = [&] __device__() {
@@ -148,19 +129,21 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
             }
         }
     };
-    if (wave == 0) {
+    if (sched && wave == 0) {
         unsigned i = 0;
-        if (sched && lane == 0) i = atomicAdd(sched + xcd, 2u);
         if (lane == 0) {
-            s_tiles[0] = tile_of_draw(i, 0);
-            s_tiles[1] = tile_of_draw(i + 1, 1);
+            i = atomicAdd(sched + xcd, 2u);
+            s_tiles[0] = tile_of_draw(i);
+            s_tiles[1] = tile_of_draw(i + 1);
         } else if (lane >= 2 && lane < 8) {
             s_tiles[lane] = -1;   // a ring entry read before it was written would end the workgroup's work, not misdirect it
         }
     }
-    draws = 2;
     __syncthreads();
-    int comp_tile = __builtin_amdgcn_readfirstlane(s_tiles[0]);
+    auto tile_number = [&] __device__(int ordinal) {   // the ordinal-th tile of this workgroup (-1: none left)
+        return sched ? __builtin_amdgcn_readfirstlane(s_tiles[ordinal & 7]) : tile_of_ordinal(ordinal);
+    };
+    int comp_tile = tile_number(0);
     if (comp_tile < 0) {   // (whole workgroup: nothing below is reached, no barrier is missed)
         leave();
         return;
@@ -185,10 +168,10 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
     bool issue_live = true;
     const int draw_kt = KT > 1 ? 1 : 0;
     uint32_t issue_sa = 0;
-    auto issue_prepare = [&] __device__(int buf) {
+    auto issue_prepare = [&] __device__(uint32_t buf_off) {
         int issue_no = -1;
         if (issue_live && issue_kt == 0) {
-            issue_no = __builtin_amdgcn_readfirstlane(s_tiles[issue_tile & 7]);
+            issue_no = tile_number(issue_tile);
             issue_live = issue_no >= 0;
         }
         if (issue_live && issue_kt == draw_kt) draw();
@@ -239,9 +222,12 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                 }
             }
         }
-        issue_sa = smem_base + buf * STAGE;
+        issue_sa = smem_base + buf_off;
     };
     auto issue_one = [&] __device__(int idx) {
+#ifdef ABL_NO_DMA
+        if (issue_sa != 1) return;
+#endif
         if constexpr (FP6) {
             if (idx < 3)
                 lds_direct_load16(a_base + idx * 1024, lane16, issue_sa + (wave * A_DMA + idx) * 1024);
@@ -280,8 +266,16 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
     // INT8 path: a step is 32 channels.  Code fragment: 16-byte chunk 2 s + fhalf of the row (xor swizzle);
     // weight fragment: 8 bytes at [32-row group][k32 step s][k16 half fhalf][row], widened to int8 lanes of 16 * code.
     // FP6 path: a step is 64 channels.  The 24-byte fragment 2 fhalf + s of a row is bytes 24 f .. 24 f + 23 of its
-    // 96: step 0 takes chunk 3 fhalf whole and the lower half of chunk 3 fhalf + 1, step 1 the upper half of
-    // that chunk and chunk 3 fhalf + 2 whole (a 16-byte and an 8-byte read per fragment and step).
+    // 96: step 0 takes chunk 3 fhalf whole ("head") and the lower half of chunk 3 fhalf + 1 ("tail"), step 1 the
+    // upper half of that chunk (tail, the operand's first two registers) and chunk 3 fhalf + 2 whole (head).
+    // A fragment set is 8 fragments in 16 parts (FP6: head and tail; INT8: the 4 code fragments count as one part
+    // each, the 4 weight fragments as one part each, 8 parts); part p of the NEXT step is requested right behind
+    // MFMA p of the current step.  With one wave per SIMD nothing but this interleaving keeps the matrix cores
+    // fed: a wave issues about one instruction per 4 - 5 clocks, an MFMA occupies its pipe for 32, so every
+    // MFMA can carry about six other instructions in its shadow, but only if they stand between MFMAs.
+    // (FP6 operands are kept as whole 6-register vectors that the two reads of a fragment fill in halves: pieces
+    // put together from separate 4- and 2-register members make the compiler widen loads across the members,
+    // after which the set no longer lives in registers)
     struct FragsI8 { v4i a[TM]; v2i w[TN]; };
     struct FragsF6 { v6i a[TM]; v6i w[TN]; };
     using Frags = std::conditional_t<FP6, FragsF6, FragsI8>;
@@ -289,78 +283,79 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
     const int w_frag_off = FP6 ? A_STAGE + (wn / 32) * kFp6Block + fhalf * 1536 + frow * 16
                                : A_STAGE + (wn / kGroup) * kGroupBytes + frow * 8 + fhalf * 256;
     const int a_xor = swz_bk<A_ROW>(frow);
-    auto load_frags = [&] __device__(Frags &f, int buf, int s) {
-        const uint8_t *st = smem + buf * STAGE;
+    constexpr int PARTS = FP6 ? 16 : 8;
+    // request part P of the fragments of step S of the slice at LDS byte offset `off` (P, S compile-time: every
+    // register of a fragment set keeps a fixed place)
+    auto load_part = [&] __device__(Frags &f, uint32_t off, auto s_c, auto p_c) __attribute__((always_inline)) {
+        constexpr int S = decltype(s_c)::value, P = decltype(p_c)::value;
+        const uint8_t *st = smem + off;
         if constexpr (FP6) {
-#pragma unroll
-            for (int j = 0; j < TM; ++j) {
-                const uint8_t *p = st + a_frag_off + j * kFp6Block;
-                if (s == 0) {
-                    const v4i h = *reinterpret_cast<const v4i *>(p);
-                    const v2i t = *reinterpret_cast<const v2i *>(p + 512);
-                    f.a[j] = v6i{h[0], h[1], h[2], h[3], t[0], t[1]};
-                } else {
-                    const v2i t = *reinterpret_cast<const v2i *>(p + 512 + 8);
-                    const v4i h = *reinterpret_cast<const v4i *>(p + 1024);
-                    f.a[j] = v6i{t[0], t[1], h[0], h[1], h[2], h[3]};
-                }
+            // order: w0.h w0.t a0.h a0.t a1.h a1.t a2.h a2.t a3.h a3.t w1.h w1.t w2.h w2.t w3.h w3.t
+            constexpr bool is_w = P < 2 || P >= 10;
+            constexpr int idx = P < 2 ? 0 : (P < 10 ? (P - 2) / 2 : (P - 8) / 2);
+            constexpr bool tail = P & 1;
+            const uint8_t *q = st + (is_w ? w_frag_off : a_frag_off) + idx * kFp6Block;
+            v6i v = is_w ? f.w[idx] : f.a[idx];
+            if constexpr (!tail) {   // the whole chunk: registers 0-3 (step 0) or 2-5 (step 1) of the operand
+                const v4i h = *reinterpret_cast<const v4i *>(q + (S == 0 ? 0 : 1024));
+                constexpr int o = S == 0 ? 0 : 2;
+                v[o] = h[0]; v[o + 1] = h[1]; v[o + 2] = h[2]; v[o + 3] = h[3];
+            } else {                 // half of the middle chunk: registers 4-5 (step 0) or 0-1 (step 1)
+                const v2i t = *reinterpret_cast<const v2i *>(q + (S == 0 ? 512 : 512 + 8));
+                constexpr int o = S == 0 ? 4 : 0;
+                v[o] = t[0]; v[o + 1] = t[1];
             }
-#pragma unroll
-            for (int i = 0; i < TN; ++i) {
-                const uint8_t *p = st + w_frag_off + i * kFp6Block;
-                if (s == 0) {
-                    const v4i h = *reinterpret_cast<const v4i *>(p);
-                    const v2i t = *reinterpret_cast<const v2i *>(p + 512);
-                    f.w[i] = v6i{h[0], h[1], h[2], h[3], t[0], t[1]};
-                } else {
-                    const v2i t = *reinterpret_cast<const v2i *>(p + 512 + 8);
-                    const v4i h = *reinterpret_cast<const v4i *>(p + 1024);
-                    f.w[i] = v6i{t[0], t[1], h[0], h[1], h[2], h[3]};
-                }
-            }
+            if constexpr (is_w) f.w[idx] = v;
+            else f.a[idx] = v;
         } else {
-#pragma unroll
-            for (int j = 0; j < TM; ++j)
-                f.a[j] = *reinterpret_cast<const v4i *>(st + a_frag_off + j * 32 * A_ROW + (((s * 2 + fhalf) ^ a_xor) << 4));
-#pragma unroll
-            for (int i = 0; i < TN; ++i)
-                f.w[i] = *reinterpret_cast<const v2i *>(st + w_frag_off + i * kGroupBytes + s * 512);
+            // order: w0 a0 a1 a2 a3 w1 w2 w3
+            if constexpr (P >= 1 && P <= 4) {
+                f.a[P - 1] = *reinterpret_cast<const v4i *>(st + a_frag_off + (P - 1) * 32 * A_ROW + (((S * 2 + fhalf) ^ a_xor) << 4));
+            } else {
+                constexpr int i = P == 0 ? 0 : P - 4;
+                f.w[i] = *reinterpret_cast<const v2i *>(st + w_frag_off + i * kGroupBytes + S * 512);
+            }
+        }
+    };
+    auto widen = [] __device__(auto p) {   // INT8 path: two packed dwords (16 codes) -> int8 lanes of 16 * code, channel order
+        if constexpr (sizeof(p) == sizeof(v2i)) {
+            const uint32_t lo = (uint32_t)p[0], hi = (uint32_t)p[1];
+            return v4i{(int)((lo << 4) & 0xF0F0F0F0u), (int)(lo & 0xF0F0F0F0u), (int)((hi << 4) & 0xF0F0F0F0u), (int)(hi & 0xF0F0F0F0u)};
+        } else {
+            return v4i{0, 0, 0, 0};
         }
     };
 
-    Acc acc[TN][TM];
-    auto clear_acc = [&] __device__() {
-#pragma unroll
-        for (int i = 0; i < TN; ++i)
-#pragma unroll
-            for (int j = 0; j < TM; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-    };
-    // the MFMAs of one step; `first_load` .. : LDS-direct loads dealt out behind the groups (none when < 0)
-    auto mfma_step = [&] __device__(const Frags &f, int group0) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < TN; ++i) {
-            if constexpr (FP6) {
-                mfma4_fp6(acc[i][0], acc[i][1], acc[i][2], acc[i][3], f.w[i], f.a[0], f.a[1], f.a[2], f.a[3]);
-            } else {
-                const uint32_t lo = (uint32_t)f.w[i][0], hi = (uint32_t)f.w[i][1];
-                const v4i fw = {(int)((lo << 4) & 0xF0F0F0F0u), (int)(lo & 0xF0F0F0F0u), (int)((hi << 4) & 0xF0F0F0F0u),
-                                (int)(hi & 0xF0F0F0F0u)};
-                mfma4_i8(acc[i][0], acc[i][1], acc[i][2], acc[i][3], fw, f.a[0], f.a[1], f.a[2], f.a[3]);
-            }
-            if (group0 >= 0) {
-#pragma unroll
-                for (int d = (group0 + i) * DMA_PER_GROUP; d < DMA && d < (group0 + i + 1) * DMA_PER_GROUP; ++d) issue_one(d);
+    // One step: 16 MFMAs on the fragment set `cur`.  Behind MFMA p: the caller's hook for slot p, then part p of step S_NXT of the slice at `nxt_off` into `nxt`,
+    // and LDS-direct loads DMA0 .. DMA0 + DMA_N - 1 of the slice being issued, one every DMA_EVERY MFMAs from
+    // MFMA DMA_FROM on.  INT8 path: the widened weights of the next group are formed behind a group's second MFMA.
+    v4i fw_cur = {0, 0, 0, 0};   // INT8 path: widened weight fragment of the group being multiplied
+    auto mfma_step = [&] __device__(auto first_c, const Frags &cur, Frags &nxt, uint32_t nxt_off, auto s_nxt_c, auto dma0_c,
+                                    auto dma_n_c, auto dma_from_c, auto dma_every_c, auto &&hook) __attribute__((always_inline)) {
+        constexpr bool FIRST = decltype(first_c)::value != 0;   // the tile's first step: the accumulators start from zero
+        constexpr int DMA0 = decltype(dma0_c)::value, DMA_N = decltype(dma_n_c)::value;
+        constexpr int DMA_FROM = decltype(dma_from_c)::value, DMA_EVERY = decltype(dma_every_c)::value;
+        static_for<TN * TM>([&](auto p_c) __attribute__((always_inline)) {
+            constexpr int P = decltype(p_c)::value, i = P / TM, j = P % TM;
+            // (INT8 path: the s_nop variant covers the wait states between a VALU write of an operand -- the
+            // widening -- and the MFMA, which the compiler cannot insert for an instruction it does not see)
+            if constexpr (FP6) mfma_fp6_acc<P, FIRST, false>(cur.w[i], cur.a[j]);
+            else mfma_i8_acc<P, FIRST, j == 0>(fw_cur, cur.a[j]);
+            hook(p_c);   // the caller's bookkeeping for this slot (scalar work in the MFMA's shadow)
+            if constexpr (P < PARTS) load_part(nxt, nxt_off, s_nxt_c, p_c);
+            if constexpr (DMA_N > 0 && P >= DMA_FROM && (P - DMA_FROM) % DMA_EVERY == 0 && (P - DMA_FROM) / DMA_EVERY < DMA_N)
+                issue_one(DMA0 + (P - DMA_FROM) / DMA_EVERY);
+            if constexpr (!FP6 && j == TM - 1) {   // the next group's widened weights (the next step's first group after the last)
+                if constexpr (i + 1 < TN) fw_cur = widen(cur.w[i + 1]);
+                else fw_cur = widen(nxt.w[0]);
             }
             __builtin_amdgcn_sched_barrier(0);
-        }
+        });
     };
-
     // ---- prologue: slices 0 and 1 on their way, slice 0 published, its first fragments requested
 #pragma unroll
     for (int st = 0; st < STAGES - 1; ++st) {
-        issue_prepare(st);
+        issue_prepare(st * STAGE);
 #pragma unroll
         for (int d = 0; d < DMA; ++d) issue_one(d);
         issue_advance();
@@ -369,22 +364,38 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
     before_barrier();
     __builtin_amdgcn_s_barrier();
     Frags f0, f1;
-    load_frags(f0, 0, 0);
-    clear_acc();
+    static_for<PARTS>([&](auto p_c) __attribute__((always_inline)) { load_part(f0, 0u, I<0>{}, p_c); });
+    if constexpr (!FP6) fw_cur = widen(f0.w[0]);
 
+    // LDS byte offsets of the ring buffers holding slice q (being multiplied), q + 1 and q + 2 (being issued)
+    uint32_t cur_off = 0, nxt_off = STAGE, fill_off = 2 * STAGE;
     int store_credit = 0, tile_j = 0;
-    for (int q = 0;;) {
-        for (int kt = 0; kt < KT; ++kt, ++q) {
-            const int buf = q % STAGES;
-            issue_prepare((q + STAGES - 1) % STAGES);   // slice q + 2 goes where slice q - 1 was
-            // steps 0 .. STEPS - 2 of slice q; step s + 1's fragments are requested before step s multiplies
-#pragma unroll
-            for (int s = 0; s < STEPS - 1; ++s) {
-                load_frags((s & 1) ? f0 : f1, buf, s + 1);
-                __builtin_amdgcn_sched_barrier(0);
-                mfma_step((s & 1) ? f1 : f0, s * TN);
+    for (;;) {
+        for (int kt = 0; kt < KT; ++kt) {
+            // Steps 0 .. last - 1 of slice q, the loads of slice q + 2 dealt out between their MFMAs.  The scalar
+            // bookkeeping of the load pipeline stands behind MFMAs as well: the addresses of slice q + 2 (it goes where
+            // slice q - 1 was) behind the first one, the advance to slice q + 3 behind one after the last load.
+            // (A tile's very first step starts its accumulators from zero: that step exists twice in the code.)
+            auto none = [] __device__(auto) __attribute__((always_inline)) {};
+            if constexpr (FP6) {
+                auto hook0 = [&] __device__(auto p_c) __attribute__((always_inline)) {
+                    if constexpr (decltype(p_c)::value == 0) issue_prepare(fill_off);
+                    if constexpr (decltype(p_c)::value == 14) issue_advance();
+                };
+                if (kt == 0) mfma_step(I<1>{}, f0, f1, cur_off, I<1>{}, I<0>{}, I<DMA>{}, I<2>{}, I<1>{}, hook0);
+                else mfma_step(I<0>{}, f0, f1, cur_off, I<1>{}, I<0>{}, I<DMA>{}, I<2>{}, I<1>{}, hook0);
+            } else {
+                auto hook0 = [&] __device__(auto p_c) __attribute__((always_inline)) {
+                    if constexpr (decltype(p_c)::value == 0) issue_prepare(fill_off);
+                };
+                auto hook2 = [&] __device__(auto p_c) __attribute__((always_inline)) {
+                    if constexpr (decltype(p_c)::value == 15) issue_advance();
+                };
+                if (kt == 0) mfma_step(I<1>{}, f0, f1, cur_off, I<1>{}, I<0>{}, I<4>{}, I<8>{}, I<2>{}, hook0);
+                else mfma_step(I<0>{}, f0, f1, cur_off, I<1>{}, I<0>{}, I<4>{}, I<8>{}, I<2>{}, hook0);
+                mfma_step(I<0>{}, f1, f0, cur_off, I<2>{}, I<4>{}, I<4>{}, I<8>{}, I<2>{}, none);
+                mfma_step(I<0>{}, f0, f1, cur_off, I<3>{}, I<8>{}, I<4>{}, I<8>{}, I<2>{}, hook2);
             }
-            issue_advance();
             // Publish slice q + 1: it has landed once at most the loads of slice q + 2 (just issued) are
             // outstanding, plus, right after a full tile's epilogue, that tile's stores.  Every fragment read of
             // slice q has been issued; once they are back (lgkmcnt) and everyone is here, buffer q % 3 is free.
@@ -399,9 +410,15 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
             __builtin_amdgcn_s_barrier();
             // the last step of slice q multiplies while step 0 of slice q + 1 is fetched (past the workgroup's
             // last slice: a stale but in-bounds buffer, never used)
-            load_frags(f0, (q + 1) % STAGES, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_step(f1, -1);
+            auto rotate = [&] __device__(auto p_c) __attribute__((always_inline)) {
+                if constexpr (decltype(p_c)::value == 15) {   // (the step's reads of nxt_off have all been issued)
+                    const uint32_t t = cur_off;
+                    cur_off = nxt_off;
+                    nxt_off = fill_off;
+                    fill_off = t;
+                }
+            };
+            mfma_step(I<0>{}, f1, f0, nxt_off, I<0>{}, I<0>{}, I<0>{}, I<0>{}, I<1>{}, rotate);
         }
 
         // ---- epilogue of tile comp_tile.  Accumulator register r = 4 g + e of MFMA tile (i, j) in lane l is
@@ -413,19 +430,18 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
         int m0, n0;
         tile_origin(comp_tile, tiles_m, tiles_n, group_n, BM, BN, m0, n0);
         ++tile_j;
-        comp_tile = __builtin_amdgcn_readfirstlane(s_tiles[tile_j & 7]);   // the next one (its loads are under way)
+        comp_tile = tile_number(tile_j);   // the next one (its loads are under way)
         const bool vec8 = (N & 7) == 0;
         const uint8_t *s_tile = smem + STAGES * STAGE + ((tile_j - 1) % 3) * SCALES;
         const float *s_xs = reinterpret_cast<const float *>(s_tile);
         const float *s_ws = s_xs + BM;
         const int32_t *s_rsum = reinterpret_cast<const int32_t *>(s_tile + OFF_RSUM);
-        // the integer accumulator, and sum q (c - z) = acc - z * rs with a 24-bit multiply (ranges: C ABI)
-        auto acc_int = [] __device__(auto a) {
-            if constexpr (FP6) return (int)(a * kFp6Unit);
-            else return (int)a >> SHIFT;
-        };
+        // sum q (c - z) = acc - z * rs with a 24-bit multiply (ranges: C ABI)
         auto unzero = [] __device__(int a, int z, int rs) { return a - __mul24(z, rs); };
-        uint8_t *stg = smem + ((q - 1) % STAGES) * STAGE + wave * 4096;   // the buffer of the slice consumed last
+        uint8_t *stg = smem + fill_off + wave * 4096;   // the buffer of the slice consumed last (next to be filled)
+#ifdef ABL_NO_EPI
+        if (M == -12345)
+#endif
         if (vec8 && !acc_out && m0 + BM <= M && n0 + BN <= N) {
             // ---- interior tile: no predicates; channel vectors fetched one register group ahead; the bf16 tile
             // is transposed through LDS, 32 tokens x 64 channels at a time, into whole-line streaming stores
@@ -459,61 +475,56 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                 };
                 ChannelVec cv[2];
                 fetch(cv[0], 0, 0);
-                int k = 0;
+                uint32_t pk[2][2];
+                // 64 units of 4 values: unit u = ((ip * TM + j) * 2 + ii) * 4 + (g + h), MFMA tile column i = 2 ip + ii,
+                // token block j, accumulator registers 4 (g + h) .. + 3; 8 units make a 32-token x 64-channel chunk
+                static_for<(TN / 2) * TM * 8>([&](auto u_c) __attribute__((always_inline)) {
+                    constexpr int U = decltype(u_c)::value, q = U & 3, h = U & 1, g = q - h, ii = (U >> 2) & 1;
+                    constexpr int j = (U >> 3) % TM, ip = U / (8 * TM), i = 2 * ip + ii;
+                    if constexpr (U + 1 < (TN / 2) * TM * 8) {   // the unit after this one: its channel vectors
+                        constexpr int UN = U + 1;
+                        fetch(cv[UN & 1], 2 * (UN / (8 * TM)) + ((UN >> 2) & 1), UN & 3);
+                    }
+                    const ChannelVec &c = cv[U & 1];
+                    const v4i raw = read_acc4<i * TM + j, q>();
+                    float o[4];
 #pragma unroll
-                for (int ip = 0; ip < TN / 2; ++ip) {
-#pragma unroll
-                    for (int j = 0; j < TM; ++j) {
-#pragma unroll
-                        for (int ii = 0; ii < 2; ++ii) {
-                            const int i = 2 * ip + ii;
-#pragma unroll
-                            for (int g = 0; g < 4; g += 2) {
-                                uint32_t pk[2][2];
-#pragma unroll
-                                for (int h = 0; h < 2; ++h, ++k) {
-                                    {   // the group after this one, in this loop nest's order
-                                        int gn = g + h + 1, iin = ii, jn = j, ipn = ip;
-                                        if (gn == 4) { gn = 0; if (++iin == 2) { iin = 0; if (++jn == TM) { jn = 0; ++ipn; } } }
-                                        if (ipn < TN / 2) fetch(cv[(k + 1) & 1], 2 * ipn + iin, gn);
-                                    }
-                                    const ChannelVec &c = cv[k & 1];
-                                    const int r = (g + h) * 4;
-                                    float o[4];
-#pragma unroll
-                                    for (int e = 0; e < 4; ++e) {
-                                        if constexpr (ZP) {
-                                            const int z = (int)(int8_t)(c.zq >> (8 * e));
-                                            if constexpr (FP6) o[e] = (float)unzero(acc_int(acc[i][j][r + e]), z, rsum[j]) * xs_l[j];
-                                            else o[e] = (float)unzero((int)acc[i][j][r + e], z * (1 << SHIFT), rsum[j]) * xs_l[j];
-                                        } else {
-                                            o[e] = (float)acc[i][j][r + e] * xs_l[j];
-                                        }
-                                    }
-                                    o[0] *= c.ws.x;
-                                    o[1] *= c.ws.y;
-                                    o[2] *= c.ws.z;
-                                    o[3] *= c.ws.w;
-                                    if (bias) {
-                                        o[0] += __uint_as_float(c.bb.x << 16);
-                                        o[1] += __uint_as_float(c.bb.x & 0xFFFF0000u);
-                                        o[2] += __uint_as_float(c.bb.y << 16);
-                                        o[3] += __uint_as_float(c.bb.y & 0xFFFF0000u);
-                                    }
-                                    pk[h][0] = pack_bf16x2(o[0], o[1]);
-                                    pk[h][1] = pack_bf16x2(o[2], o[3]);
-                                }
-#pragma unroll
-                                for (int d = 0; d < 2; ++d) {
-                                    auto sw = __builtin_amdgcn_permlane32_swap(pk[0][d], pk[1][d], false, false);
-                                    pk[0][d] = sw[0];
-                                    pk[1][d] = sw[1];
-                                }
-                                const int piece = ii * 4 + g + fhalf;   // 16-byte piece of the 64-channel row
-                                *reinterpret_cast<uint4 *>(stg + frow * 128 + ((piece ^ (frow & 7)) << 4)) =
-                                    make_uint4(pk[0][0], pk[0][1], pk[1][0], pk[1][1]);
-                            }
+                    for (int e = 0; e < 4; ++e) {
+                        if constexpr (ZP) {
+                            const int z = (int)(int8_t)(c.zq >> (8 * e));
+                            if constexpr (FP6) o[e] = (float)unzero((int)(__int_as_float(raw[e]) * kFp6Unit), z, rsum[j]) * xs_l[j];
+                            else o[e] = (float)unzero(raw[e], z * (1 << SHIFT), rsum[j]) * xs_l[j];
+                        } else {
+                            if constexpr (FP6) o[e] = __int_as_float(raw[e]) * xs_l[j];
+                            else o[e] = (float)raw[e] * xs_l[j];
                         }
+                    }
+                    o[0] *= c.ws.x;
+                    o[1] *= c.ws.y;
+                    o[2] *= c.ws.z;
+                    o[3] *= c.ws.w;
+                    if (bias) {
+                        o[0] += __uint_as_float(c.bb.x << 16);
+                        o[1] += __uint_as_float(c.bb.x & 0xFFFF0000u);
+                        o[2] += __uint_as_float(c.bb.y << 16);
+                        o[3] += __uint_as_float(c.bb.y & 0xFFFF0000u);
+                    }
+                    pk[h][0] = pack_bf16x2(o[0], o[1]);
+                    pk[h][1] = pack_bf16x2(o[2], o[3]);
+                    if constexpr (h == 1) {
+                        // lanes l and l + 32 hold channels (8 g' .. + 3) and (8 g' + 4 .. + 7): after the swap each lane
+                        // owns 8 consecutive channels
+#pragma unroll
+                        for (int d = 0; d < 2; ++d) {
+                            auto sw = __builtin_amdgcn_permlane32_swap(pk[0][d], pk[1][d], false, false);
+                            pk[0][d] = sw[0];
+                            pk[1][d] = sw[1];
+                        }
+                        const int piece = ii * 4 + g + fhalf;   // 16-byte piece of the 64-channel row
+                        *reinterpret_cast<uint4 *>(stg + frow * 128 + ((piece ^ (frow & 7)) << 4)) =
+                            make_uint4(pk[0][0], pk[0][1], pk[1][0], pk[1][1]);
+                    }
+                    if constexpr ((U & 7) == 7) {   // the chunk is staged: whole-line stores
                         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                         __builtin_amdgcn_wave_barrier();
                         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -528,7 +539,7 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                         for (int pass = 0; pass < 4; ++pass) store_streaming16(yb + (int64_t)pass * 8 * N, v[pass]);
                         __builtin_amdgcn_wave_barrier();   // the next chunk's LDS writes stay behind these reads
                     }
-                }
+                });
             };
             if (w_zero) interior(std::true_type{});
             else interior(std::false_type{});
@@ -538,89 +549,88 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
             int lane_s = lane;
             asm volatile("" : "+v"(lane_s));
             const int frow = lane_s & 31, fhalf = lane_s >> 5;
-#pragma unroll
-            for (int j = 0; j < TM; ++j) {
+            static_for<TM * TN>([&](auto t_c) __attribute__((always_inline)) {
+                constexpr int j = decltype(t_c)::value / TN, i = decltype(t_c)::value % TN;
                 const int m = m0 + wm + j * 32 + frow;
                 const bool m_ok = m < M;
                 const float xs = s_xs[wm + j * 32 + frow];
                 const int rs = w_zero ? s_rsum[wm + j * 32 + frow] : 0;
+                const int nb = n0 + wn + i * 32;   // this MFMA tile's first output channel
+                int a[16];
+                static_for<4>([&](auto g_c) __attribute__((always_inline)) {
+                    constexpr int g = decltype(g_c)::value;
+                    const v4i raw = read_acc4<i * TM + j, g>();
 #pragma unroll
-                for (int i = 0; i < TN; ++i) {
-                    const int nb = n0 + wn + i * 32;   // this MFMA tile's first output channel
-                    int a[16];
+                    for (int e = 0; e < 4; ++e) {
+                        const int n = nb + g * 8 + fhalf * 4 + e;
+                        if constexpr (FP6) a[g * 4 + e] = (int)(__int_as_float(raw[e]) * kFp6Unit);
+                        else a[g * 4 + e] = raw[e] >> SHIFT;
+                        if (w_zero && n < N) a[g * 4 + e] = unzero(a[g * 4 + e], (int)w_zero[n], rs);
+                    }
+                });
+                if (acc_out && m_ok) {
 #pragma unroll
-                    for (int g = 0; g < 4; ++g)
+                    for (int g = 0; g < 4; ++g) {
+                        const int n = nb + g * 8 + fhalf * 4;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (n + e < N) acc_out[(int64_t)m * N + n + e] = a[g * 4 + e];
+                    }
+                }
+                if (vec8) {
+                    uint32_t pk[4][2];
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int n = nb + g * 8 + fhalf * 4;
+                        float o[4];
+                        if (n < N) {  // N % 8 == 0 and n % 4 == 0: n + 3 < N as well
+                            const float4 ws = *reinterpret_cast<const float4 *>(s_ws + (n - n0));
+                            o[0] = (float)a[g * 4 + 0] * xs * ws.x;
+                            o[1] = (float)a[g * 4 + 1] * xs * ws.y;
+                            o[2] = (float)a[g * 4 + 2] * xs * ws.z;
+                            o[3] = (float)a[g * 4 + 3] * xs * ws.w;
+                            if (bias) {
+                                const uint2 bb = *reinterpret_cast<const uint2 *>(bias + n);
+                                o[0] += __uint_as_float(bb.x << 16);
+                                o[1] += __uint_as_float(bb.x & 0xFFFF0000u);
+                                o[2] += __uint_as_float(bb.y << 16);
+                                o[3] += __uint_as_float(bb.y & 0xFFFF0000u);
+                            }
+                        } else {
+                            o[0] = o[1] = o[2] = o[3] = 0.f;
+                        }
+                        pk[g][0] = pack_bf16x2(o[0], o[1]);
+                        pk[g][1] = pack_bf16x2(o[2], o[3]);
+                    }
+#pragma unroll
+                    for (int g = 0; g < 4; g += 2) {
+#pragma unroll
+                        for (int d = 0; d < 2; ++d) {
+                            auto r = __builtin_amdgcn_permlane32_swap(pk[g][d], pk[g + 1][d], false, false);
+                            pk[g][d] = r[0];
+                            pk[g + 1][d] = r[1];
+                        }
+                        const int n = nb + g * 8 + fhalf * 8;
+                        if (m_ok && n < N)
+                            *reinterpret_cast<uint4 *>(y + (int64_t)m * N + n) =
+                                make_uint4(pk[g][0], pk[g][1], pk[g + 1][0], pk[g + 1][1]);
+                    }
+                } else if (m_ok) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int n = nb + g * 8 + fhalf * 4;
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            const int n = nb + g * 8 + fhalf * 4 + e;
-                            a[g * 4 + e] = acc_int(acc[i][j][g * 4 + e]);
-                            if (w_zero && n < N) a[g * 4 + e] = unzero(a[g * 4 + e], (int)w_zero[n], rs);
-                        }
-                    if (acc_out && m_ok) {
-#pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            const int n = nb + g * 8 + fhalf * 4;
-#pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (n + e < N) acc_out[(int64_t)m * N + n + e] = a[g * 4 + e];
-                        }
-                    }
-                    if (vec8) {
-                        uint32_t pk[4][2];
-#pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            const int n = nb + g * 8 + fhalf * 4;
-                            float o[4];
-                            if (n < N) {  // N % 8 == 0 and n % 4 == 0: n + 3 < N as well
-                                const float4 ws = *reinterpret_cast<const float4 *>(s_ws + (n - n0));
-                                o[0] = (float)a[g * 4 + 0] * xs * ws.x;
-                                o[1] = (float)a[g * 4 + 1] * xs * ws.y;
-                                o[2] = (float)a[g * 4 + 2] * xs * ws.z;
-                                o[3] = (float)a[g * 4 + 3] * xs * ws.w;
-                                if (bias) {
-                                    const uint2 bb = *reinterpret_cast<const uint2 *>(bias + n);
-                                    o[0] += __uint_as_float(bb.x << 16);
-                                    o[1] += __uint_as_float(bb.x & 0xFFFF0000u);
-                                    o[2] += __uint_as_float(bb.y << 16);
-                                    o[3] += __uint_as_float(bb.y & 0xFFFF0000u);
-                                }
-                            } else {
-                                o[0] = o[1] = o[2] = o[3] = 0.f;
-                            }
-                            pk[g][0] = pack_bf16x2(o[0], o[1]);
-                            pk[g][1] = pack_bf16x2(o[2], o[3]);
-                        }
-#pragma unroll
-                        for (int g = 0; g < 4; g += 2) {
-#pragma unroll
-                            for (int d = 0; d < 2; ++d) {
-                                auto r = __builtin_amdgcn_permlane32_swap(pk[g][d], pk[g + 1][d], false, false);
-                                pk[g][d] = r[0];
-                                pk[g + 1][d] = r[1];
-                            }
-                            const int n = nb + g * 8 + fhalf * 8;
-                            if (m_ok && n < N)
-                                *reinterpret_cast<uint4 *>(y + (int64_t)m * N + n) =
-                                    make_uint4(pk[g][0], pk[g][1], pk[g + 1][0], pk[g + 1][1]);
-                        }
-                    } else if (m_ok) {
-#pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            const int n = nb + g * 8 + fhalf * 4;
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                if (n + e >= N) break;
-                                float o = (float)a[g * 4 + e] * xs * s_ws[n + e - n0];
-                                if (bias) o += __uint_as_float((uint32_t)bias[n + e] << 16);
-                                y[(int64_t)m * N + n + e] = (uint16_t)(pack_bf16x2(o, 0.f) & 0xFFFFu);
-                            }
+                            if (n + e >= N) break;
+                            float o = (float)a[g * 4 + e] * xs * s_ws[n + e - n0];
+                            if (bias) o += __uint_as_float((uint32_t)bias[n + e] << 16);
+                            y[(int64_t)m * N + n + e] = (uint16_t)(pack_bf16x2(o, 0.f) & 0xFFFFu);
                         }
                     }
                 }
-            }
+            });
         }
         if (comp_tile < 0) break;
-        clear_acc();
         // the staging buffer is the one the next slice's loads go to: nobody may issue them before everyone
         // has stored its part of the tile
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
