@@ -720,6 +720,10 @@ int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w
             default: return DVDQ_ERR_UNSUPPORTED;
         }
     }
+    // Variant 5 is the wide kernel of w4ax_gemm_wide.hip (int8 codes only): it pays when a tile has many K
+    // slices (4 % faster at K = 13824, slower below K = 4096), and is taken by itself from K = 8192 on when
+    // there are at least two rounds of 256 x 256 tiles.
+    if (g_variant < 0 && codes_format == DVDQ_CODES_INT8 && k / 128 >= 64 && ((M + 255) / 256) * ((N + 255) / 256) >= 512) v = 5;
     if (v == 5)
         return launch_w4ax_gemm_wide(reinterpret_cast<const uint8_t *>(codes), x_scale, w, w_scale, w_zero, code_rowsum, bias,
                                      M, N, K, false, y, acc_out, stream);

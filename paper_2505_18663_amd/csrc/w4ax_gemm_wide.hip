@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
     constexpr int STORES = TM * TN * 2;                      // 16-byte store instructions per wave per full tile
     static_assert(STAGE == 48 * 1024 && DMA == 12, "ring geometry");
     static_assert(DMA + STORES < 64 && (STAGES - 1) * DMA + 8 < 64, "vmcnt is 6 bits");
-    static_assert(NW * 4096 <= STAGE, "the epilogue stages 4 KB per wave in one ring buffer");
+    static_assert(NW * 8192 <= STAGE, "the epilogue stages 2 x 4 KB per wave in one ring buffer");
 
     extern __shared__ __align__(16) uint8_t smem[];
     const uint32_t smem_base = lds_address(smem);
@@ -225,9 +225,6 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
         issue_sa = smem_base + buf_off;
     };
     auto issue_one = [&] __device__(int idx) {
-#ifdef ABL_NO_DMA
-        if (issue_sa != 1) return;
-#endif
         if constexpr (FP6) {
             if (idx < 3)
                 lds_direct_load16(a_base + idx * 1024, lane16, issue_sa + (wave * A_DMA + idx) * 1024);
@@ -438,10 +435,7 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
         const int32_t *s_rsum = reinterpret_cast<const int32_t *>(s_tile + OFF_RSUM);
         // sum q (c - z) = acc - z * rs with a 24-bit multiply (ranges: C ABI)
         auto unzero = [] __device__(int a, int z, int rs) { return a - __mul24(z, rs); };
-        uint8_t *stg = smem + fill_off + wave * 4096;   // the buffer of the slice consumed last (next to be filled)
-#ifdef ABL_NO_EPI
-        if (M == -12345)
-#endif
+        uint8_t *stg = smem + fill_off + wave * 8192;   // in the buffer of the slice consumed last (next to be filled): two areas of 4 KB
         if (vec8 && !acc_out && m0 + BM <= M && n0 + BN <= N) {
             // ---- interior tile: no predicates; channel vectors fetched one register group ahead; the bf16 tile
             // is transposed through LDS, 32 tokens x 64 channels at a time, into whole-line streaming stores
@@ -476,6 +470,8 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                 ChannelVec cv[2];
                 fetch(cv[0], 0, 0);
                 uint32_t pk[2][2];
+                uint4 pend[4];            // a staged chunk on its way back from LDS, and where it goes
+                uint16_t *pend_y = y;
                 // 64 units of 4 values: unit u = ((ip * TM + j) * 2 + ii) * 4 + (g + h), MFMA tile column i = 2 ip + ii,
                 // token block j, accumulator registers 4 (g + h) .. + 3; 8 units make a 32-token x 64-channel chunk
                 static_for<(TN / 2) * TM * 8>([&](auto u_c) __attribute__((always_inline)) {
@@ -521,25 +517,33 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                             pk[1][d] = sw[1];
                         }
                         const int piece = ii * 4 + g + fhalf;   // 16-byte piece of the 64-channel row
-                        *reinterpret_cast<uint4 *>(stg + frow * 128 + ((piece ^ (frow & 7)) << 4)) =
+                        *reinterpret_cast<uint4 *>(stg + ((U >> 3) & 1) * 4096 + frow * 128 + ((piece ^ (frow & 7)) << 4)) =
                             make_uint4(pk[0][0], pk[0][1], pk[1][0], pk[1][1]);
                     }
-                    if constexpr ((U & 7) == 7) {   // the chunk is staged: whole-line stores
+                    // A staged chunk is read back right away (its LDS round trip then runs under the next chunk's
+                    // arithmetic; two staging areas alternate) and stored to memory half a chunk later.
+                    if constexpr ((U & 7) == 3 && U > 8) {
+#pragma unroll
+                        for (int pass = 0; pass < 4; ++pass) store_streaming16(pend_y + (int64_t)pass * 8 * N, pend[pass]);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if constexpr ((U & 7) == 7) {   // the chunk is staged: whole rows back, 8 lanes per 128-byte row
                         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                         __builtin_amdgcn_wave_barrier();
                         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                        uint16_t *yb = y + (int64_t)(m0 + wm + j * 32 + rd_row) * N + (n0 + wn + ip * 64 + rd_piece * 8);
-                        uint4 v[4];
+                        pend_y = y + (int64_t)(m0 + wm + j * 32 + rd_row) * N + (n0 + wn + ip * 64 + rd_piece * 8);
+                        const uint8_t *sg = stg + ((U >> 3) & 1) * 4096;
 #pragma unroll
                         for (int pass = 0; pass < 4; ++pass) {
                             const int row = pass * 8 + rd_row;
-                            v[pass] = *reinterpret_cast<const uint4 *>(stg + row * 128 + ((rd_piece ^ (row & 7)) << 4));
+                            pend[pass] = *reinterpret_cast<const uint4 *>(sg + row * 128 + ((rd_piece ^ (row & 7)) << 4));
                         }
-#pragma unroll
-                        for (int pass = 0; pass < 4; ++pass) store_streaming16(yb + (int64_t)pass * 8 * N, v[pass]);
-                        __builtin_amdgcn_wave_barrier();   // the next chunk's LDS writes stay behind these reads
+                        __builtin_amdgcn_wave_barrier();   // later LDS writes into this area stay behind these reads
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                 });
+#pragma unroll
+                for (int pass = 0; pass < 4; ++pass) store_streaming16(pend_y + (int64_t)pass * 8 * N, pend[pass]);   // the last chunk
             };
             if (w_zero) interior(std::true_type{});
             else interior(std::false_type{});
