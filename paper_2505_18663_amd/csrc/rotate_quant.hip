@@ -30,6 +30,8 @@
 // scale and into the reciprocal the codes are taken with.
 #include "dvdq_internal.h"
 
+#include <type_traits>
+
 namespace dvdq {
 namespace {
 
@@ -50,10 +52,10 @@ __device__ __forceinline__ float dpp_mov(float v) {
 // butterfly's difference; the caller tracks that sign and folds it into the quantizer.
 // (The compiler does not fuse a DPP move into an fma, so this is inline assembly.  The
 // leading s_nop covers the 2 wait states a DPP read needs after a VALU write of the same
-// register; the values must have been written by ordinary VALU instructions, never
-// directly by an MFMA, whose longer read-after-write distance only the compiler inserts.)
-#define DVDQ_FMAC_DPP8(CTRL)                                                                                   \
-    asm volatile("s_nop 1\n\t"                                                                                 \
+// register.  PRE is put in front of that: the first stage reads registers that an MFMA may have written
+// directly, whose longer read-after-write distance the compiler does not see through inline assembly.)
+#define DVDQ_FMAC_DPP8(PRE, CTRL)                                                                              \
+    asm volatile(PRE "s_nop 1\n\t"                                                                             \
                  "v_fmac_f32_dpp %0, %0, %8 " CTRL " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"              \
                  "v_fmac_f32_dpp %1, %1, %8 " CTRL " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"              \
                  "v_fmac_f32_dpp %2, %2, %8 " CTRL " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"              \
@@ -65,8 +67,11 @@ __device__ __forceinline__ float dpp_mov(float v) {
                  : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7]) \
                  : "v"(sign))
 
-__device__ __forceinline__ void stage_xor2(float (&v)[8], float sign) { DVDQ_FMAC_DPP8("quad_perm:[2,3,0,1]"); }
-__device__ __forceinline__ void stage_xor8(float (&v)[8], float sign) { DVDQ_FMAC_DPP8("row_ror:8"); }
+// (first of the lane-pairing stages: its values come straight from the 8-pass MFMAs, whose results a vector
+// instruction may read 12 wait states after the MFMA issued; 20 are kept)
+__device__ __forceinline__ void stage_xor1(float (&v)[8], float sign) { DVDQ_FMAC_DPP8("s_nop 15\n\ts_nop 1\n\t", "quad_perm:[1,0,3,2]"); }
+__device__ __forceinline__ void stage_xor2(float (&v)[8], float sign) { DVDQ_FMAC_DPP8("", "quad_perm:[2,3,0,1]"); }
+__device__ __forceinline__ void stage_xor8(float (&v)[8], float sign) { DVDQ_FMAC_DPP8("", "row_ror:8"); }
 
 // Butterfly stage over lanes l ^ 4 (no single DPP pattern): rows shifted left by 4 feed the
 // lanes with bit 2 clear (banks 0 and 2: own + partner), rows shifted right by 4 the others
@@ -79,6 +84,22 @@ __device__ __forceinline__ float stage_xor4_one(float v) {
                  : "=&v"(w)
                  : "v"(v));
     return w;
+}
+
+// Maximum of a non-negative value over the wave, the same in every lane: two quad permutes and two row
+// mirrors leave each 16-lane row's maximum in all its lanes, two row broadcasts carry it on into lane 63.
+__device__ __forceinline__ float wave_max(float a) {
+    auto with = [](float a, auto ctrl, auto row_mask) {
+        const int v = __builtin_bit_cast(int, a);
+        return fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, decltype(ctrl)::value, decltype(row_mask)::value, 0xF, false)));
+    };
+    a = with(a, std::integral_constant<int, 0xB1>{}, std::integral_constant<int, 0xF>{});    // quad_perm:[1,0,3,2]
+    a = with(a, std::integral_constant<int, 0x4E>{}, std::integral_constant<int, 0xF>{});    // quad_perm:[2,3,0,1]
+    a = with(a, std::integral_constant<int, 0x141>{}, std::integral_constant<int, 0xF>{});   // row_half_mirror
+    a = with(a, std::integral_constant<int, 0x140>{}, std::integral_constant<int, 0xF>{});   // row_mirror
+    a = with(a, std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xA>{});   // row_bcast:15 into rows 1, 3
+    a = with(a, std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xC>{});   // row_bcast:31 into rows 2, 3
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a), 63));
 }
 
 // entry (r, k) of the 32 x 32 matrix that applies H to the index bits in `mask` and the
@@ -134,25 +155,28 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
     }
     // butterfly signs of the lane-pairing stages (the lane with the stage's bit set takes the difference)
     const float s1 = (lane & 1) ? -1.f : 1.f, s2 = (lane & 2) ? -1.f : 1.f, s8 = (lane & 8) ? -1.f : 1.f;
-    // stages xor 2 and xor 8 leave MINUS the difference in the lane with the bit set
-    const float flip = (((LOG2B >= 7) && (lane & 2)) != ((LOG2B >= 8) && (lane & 8))) ? -1.f : 1.f;
+    // stages xor 1, xor 2 and xor 8 leave MINUS the difference in the lane with the bit set
+    const float flip = ((((LOG2B >= 6) && (lane & 1)) != 0) != (((LOG2B >= 7) && (lane & 2)) != ((LOG2B >= 8) && (lane & 8)))) ? -1.f : 1.f;
 
     // channel offsets of this lane's chunks; chunks at or past K are padding (zero in, nothing out)
     int k0[CPW];
 #pragma unroll
     for (int c = 0; c < CPW; ++c) k0[c] = (wsub + c * waves_per_row) * kUnit + chunk * 8;
 
+    // A row is read through a buffer descriptor of its own (base = the row, extent = its K bf16 values, or
+    // nothing for rows past M): chunks past the end come back as zeros with no branch around the loads, so the
+    // compiler can count the loads in flight and wait only for the row it needs while the next one is on its way.
+    // X is read exactly once: streaming loads keep it from displacing the codes this kernel writes (and the
+    // weights) from the caches the GEMM is about to read them from.
     auto load_row = [&] __device__(uint4 (&raw)[CPW], int64_t row) {
+        const bool ok = row < M;
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t *>(x) + (ok ? row : 0) * K, 0, ok ? K * 2 : 0, 0x00020000);
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
-            raw[c] = make_uint4(0, 0, 0, 0);
-            if (row < M && k0[c] < K) {
-                // X is read exactly once: a streaming load keeps it from displacing the codes this kernel
-                // writes (and the weights) from the caches the GEMM is about to read them from
-                typedef uint32_t v4u __attribute__((ext_vector_type(4)));
-                const v4u t = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(x + row * K + k0[c]));
-                raw[c] = make_uint4(t[0], t[1], t[2], t[3]);
-            }
+            typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+            const v4u t = __builtin_amdgcn_raw_buffer_load_b128(rsrc, k0[c] * 2, 0, 2 /* nt */);
+            raw[c] = make_uint4(t[0], t[1], t[2], t[3]);
         }
     };
 
@@ -163,18 +187,21 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
     // its chunks of a run in LDS and writes them as whole lines (16-byte stores scattered over 64 lines
     // per instruction make the whole kernel take twice as long).
     const int run = FMT == 2 ? via_lds : 1;
-    // row of wave row 0 in the workgroup's it-th iteration; wave row r is r * run rows further on
-    auto first_row_of = [&] __device__(int64_t it) {
-        const int64_t g = it / run;
-        return ((int64_t)blockIdx.x + g * gridDim.x) * (run * rows_per_wg) + (it - g * run);
-    };
-    int64_t it = 0;
-    int64_t row = first_row_of(0) + row_in_wg * run;
+    // The workgroup's iterations are numbered (g, turn): turn counts 0 .. run - 1 within group g, and wave row 0
+    // takes row (blockIdx.x + g * gridDim.x) * run * rows_per_wg + turn; wave row r is r * run rows further on.
+    // (Counted up by hand: a 64-bit division per iteration costs more than a hundred scalar instructions.)
+    const int64_t group_stride = (int64_t)gridDim.x * (run * rows_per_wg);
+    int64_t group_row = (int64_t)blockIdx.x * (run * rows_per_wg);   // first row of the current group
+    int turn = 0;                                                    // turn of the row being processed
+    int64_t row = group_row + row_in_wg * run;
     uint4 raw[CPW];
     load_row(raw, row);
     int slot = 0;
-    for (int64_t base = first_row_of(0); base < M; slot ^= 1) {
-        const int64_t next_base = first_row_of(++it);
+    for (int64_t base = group_row; base < M; slot ^= 1) {
+        const bool last_turn = turn == run - 1;
+        const int64_t next_group_row = last_turn ? group_row + group_stride : group_row;
+        const int next_turn = last_turn ? 0 : turn + 1;
+        const int64_t next_base = next_group_row + next_turn;
         uint4 nxt[CPW];
         load_row(nxt, next_base + row_in_wg * run);
         const bool row_ok = row < M;
@@ -204,10 +231,7 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
         }
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
-            if (LOG2B >= 6) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) v[c][i] = fmaf(v[c][i], s1, dpp_mov<0xB1>(v[c][i]));  // quad_perm [1,0,3,2]
-            }
+            if (LOG2B >= 6) stage_xor1(v[c], s1);
             if (LOG2B >= 7) stage_xor2(v[c], s2);
             if (LOG2B >= 8) stage_xor8(v[c], s8);
             if (LOG2B >= 9) {
@@ -217,8 +241,7 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
 #pragma unroll
             for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(v[c][i]));
         }
-#pragma unroll
-        for (int m = 1; m < kWave; m <<= 1) amax = fmaxf(amax, __shfl_xor(amax, m, kWave));
+        amax = wave_max(amax);
         if (waves_per_row > 1) {
             float *slots = s_amax + slot * (rows_per_wg * waves_per_row);
             if (lane == 0) slots[wave] = amax;
@@ -235,48 +258,62 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
         const float magic = 12582912.f;  // 1.5 * 2^23: adding it rounds to integer, ties to even
         int csum = 0;                    // this lane's share of the row's code sum (padding chunks hold zeros)
         if (FMT == 2) {
-            // FP6 container: code c as the E2M3 pattern (c < 0) << 5 | |c|.  The magnitude comes from the
-            // same fused multiply-add on absolute values (round-half-even is symmetric); the value's sign
-            // bit is or-ed in at bit 5, and the sign of the reciprocal (the same for all 8 values of a lane)
-            // flips the 8 sign positions at the end.  A lane's 8 fields are 48 bits; summing
-            // (magic + field) << 6 i and taking the magic's known contribution off once leaves the fields
-            // packed.  The bytes of the group's rows are put together in LDS in channel order.
+            // FP6 container: code c as the E2M3 pattern (c < 0) << 5 | |c|, a lane's 8 fields = 48 bits, made by
+            // the chip's packed f32 -> FP6 conversion.  The bytes of the group's rows are put together in LDS in
+            // channel order.
             constexpr int TURN_BYTES = CPW * 384 + 16;   // + 16: the 8 turns a quarter-wave reads back sit in different banks
-            const int turn = (int)((it - 1) % run);
             uint8_t *stage = reinterpret_cast<uint8_t *>(s_pack) + wave * (run * TURN_BYTES);
             uint8_t *sp = stage + turn * TURN_BYTES;
-            const uint32_t rsign = __float_as_uint(r) & 0x80000000u;
-            const uint32_t rflip_lo = rsign ? 0x20820820u : 0u;   // bits 5, 11, 17, 23, 29: the signs of fields 0..4
-            const uint32_t rflip_hi = rsign ? 0x8208u : 0u;       // bits 3, 9, 15 of the upper 16: fields 5..7
-            constexpr uint32_t MB = 0x4B400000u;   // bit pattern of the magic number
-            constexpr uint32_t LO_C = MB + (MB << 6) + (MB << 12) + (MB << 18) + (MB << 24) + (MB << 30);
-            constexpr uint32_t HI_C = (MB >> 2) + (MB << 4) + (MB << 10);
+            // q_i = rne(v_i * r) as a float, by the same single-rounding fused multiply-add as the other
+            // containers (so that all containers carry identical codes), then the packed conversion: exact
+            // integers -7 .. 7 divided by 8 (its scale operand) are E2M3 subnormals m / 8, whose patterns
+            // sign << 5 | m are the container's fields.  One conversion takes 32 values, field 2 i from element i
+            // of its first source and field 2 i + 1 from element i of its second: four chunks of this lane at a
+            // time, chunk g's even channels in elements 4 g .. 4 g + 3 of the first source and its odd channels
+            // in those of the second, so that chunk g comes out as bits 48 g .. 48 g + 47.  The instruction
+            // reads its sources while it writes its result, so the result must not share registers with them
+            // (the early-clobber output; the compiler's own builtin does not keep them apart).
+            typedef float v16f __attribute__((ext_vector_type(16)));
+            typedef uint32_t v6u __attribute__((ext_vector_type(6)));
+            // even chunks sit 4-byte aligned in the turn's bytes and store bytes 0-3 and 4-5, odd chunks (2 mod 4)
+            // store bytes 0-1 and 2-5
+            uint8_t *d = sp + chunk * 6;
+            uint32_t *d_word = reinterpret_cast<uint32_t *>(d + ((chunk & 1) ? 2 : 0));
+            uint16_t *d_half = reinterpret_cast<uint16_t *>(d + ((chunk & 1) ? 0 : 4));
+            const bool odd = chunk & 1;
+            float fsum = 0.f;   // code sums stay exact in fp32: at most 8 * CPW values of magnitude <= 127
 #pragma unroll
-            for (int c = 0; c < CPW; ++c) {
-                uint32_t t[8];
+            for (int c0 = 0; c0 < CPW; c0 += 4) {
+                // (elements past the lane's last chunk are don't-cares: left undefined, they cost no instruction)
+                const v4f none = {0.f, 0.f, 0.f, 0.f};
+                v16f qa = __builtin_shufflevector(none, none, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1);
+                v16f qb = qa;
 #pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    t[i] = __float_as_uint(fmaf(fabsf(v[c][i]), fabsf(r), magic)) | ((__float_as_uint(v[c][i]) >> 26) & 32u);
-                uint32_t lo = t[0] + (t[1] << 6) + (t[2] << 12) + (t[3] << 18) + (t[4] << 24) + (t[5] << 30) - LO_C;
-                uint32_t hi = ((t[5] >> 2) + (t[6] << 4) + (t[7] << 10) - HI_C) & 0xFFFFu;
-                lo ^= rflip_lo;
-                hi ^= rflip_hi;
-                if (code_rowsum) {
+                for (int g = 0; g < 4 && c0 + g < CPW; ++g) {
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const int mag = (int)(t[i] & 0xFu);
-                        csum += (((t[i] >> 5) & 1u) != (rsign >> 31)) ? -mag : mag;
+                    for (int i = 0; i < 4; ++i) {
+                        qa[4 * g + i] = fmaf(v[c0 + g][2 * i], r, magic) - magic;
+                        qb[4 * g + i] = fmaf(v[c0 + g][2 * i + 1], r, magic) - magic;
+                        if (code_rowsum) fsum += qa[4 * g + i] + qb[4 * g + i];
                     }
                 }
-                uint8_t *d = sp + c * 384 + chunk * 6;   // 4-byte aligned for even chunks, 2-byte for odd ones
-                if (chunk & 1) {
-                    *reinterpret_cast<uint16_t *>(d) = (uint16_t)lo;
-                    *reinterpret_cast<uint32_t *>(d + 2) = (lo >> 16) | (hi << 16);
-                } else {
-                    *reinterpret_cast<uint32_t *>(d) = lo;
-                    *reinterpret_cast<uint16_t *>(d + 4) = (uint16_t)hi;
+                v6u pk;
+                asm volatile("v_cvt_scalef32_2xpk16_fp6_f32 %0, %1, %2, %3\n\ts_nop 1" : "=&v"(pk) : "v"(qa), "v"(qb), "v"(8.0f));
+#pragma unroll
+                for (int g = 0; g < 4 && c0 + g < CPW; ++g) {
+                    // the chunk's three 16-bit pieces h0 h1 h2: an even chunk stores (h0 h1) and h2, an odd one h0 and (h1 h2)
+                    const uint32_t w0 = pk[3 * (g / 2) + (g & 1)], w1 = pk[3 * (g / 2) + (g & 1) + 1];
+                    uint32_t h01, h12, h0, h2;
+                    if (g & 1) {   // bits 16 .. 63 of (w0, w1)
+                        h01 = __builtin_amdgcn_alignbit(w1, w0, 16); h12 = w1; h0 = w0 >> 16; h2 = w1 >> 16;
+                    } else {       // bits 0 .. 47
+                        h01 = w0; h12 = __builtin_amdgcn_alignbit(w1, w0, 16); h0 = w0; h2 = w1;
+                    }
+                    d_word[(c0 + g) * 96] = odd ? h12 : h01;
+                    d_half[(c0 + g) * 192] = (uint16_t)(odd ? h0 : h2);
                 }
             }
+            if (code_rowsum) csum = (int)fsum;
             if (turn == run - 1 || next_base >= M) {
                 // the run is complete (or the rows are): chunk j of slice s of rows row0 .. row0 + run - 1 is the
                 // line [row / 32][s][j][row % 32][16 B]; neighbouring lanes take neighbouring rows.  Wave-private
@@ -284,18 +321,21 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                // (row0 is a multiple of `run`, a power of two <= 8: the run lies inside one 32-row block, so its
+                // address splits into a wave-uniform 64-bit base and a 32-bit offset per lane)
                 const int64_t row0 = row - turn;
                 const int slices = K >> 7;
+                const int run_log2 = __builtin_ctz(run);
+                uint8_t *run_base = reinterpret_cast<uint8_t *>(codes) + ((row0 >> 5) * slices) * 3072 + (row0 & 31) * 16;
+                const int rows_left = (int)min((int64_t)turn, M - 1 - row0);   // rows row0 .. row0 + rows_left exist
                 for (int idx0 = 0; idx0 < CPW * 24 * run; idx0 += kWave) {
                     const int idx = idx0 + lane;
-                    const int L = idx / run, rr = idx - L * run;          // chunk of the wave's units, turn
+                    const int L = idx >> run_log2, rr = idx & (run - 1);   // chunk of the wave's units, turn
                     const int c = L / 24, part = L - c * 24;
                     const int g = (wsub + c * waves_per_row) * 24 + part;  // 16-byte chunk of the row
                     const int slice = g / 6, j = g - slice * 6;
-                    const int64_t grow = row0 + rr;
-                    if (idx < CPW * 24 * run && rr <= turn && grow < M && slice < slices)
-                        *reinterpret_cast<uint4 *>(reinterpret_cast<uint8_t *>(codes) +
-                                                   ((grow >> 5) * slices + slice) * 3072 + j * 512 + (grow & 31) * 16) =
+                    if (idx < CPW * 24 * run && rr <= rows_left && slice < slices)
+                        *reinterpret_cast<uint4 *>(run_base + (uint32_t)(slice * 3072 + j * 512 + rr * 16)) =
                             *reinterpret_cast<const uint4 *>(stage + rr * TURN_BYTES + c * 384 + part * 16);
                 }
                 __builtin_amdgcn_wave_barrier();   // the next run's LDS writes stay behind these reads
@@ -397,6 +437,8 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
         for (int c = 0; c < CPW; ++c) raw[c] = nxt[c];
         base = next_base;
         row = next_base + row_in_wg * run;
+        group_row = next_group_row;
+        turn = next_turn;
     }
 }
 
