@@ -15,13 +15,16 @@
 //     products are exact and the sums are accumulated in fp32.  No bf16 -> fp32
 //     unpacking is needed and the result lands in the same lane, same order.
 //   * bits 5..8 (strides 32..256) are butterflies between lanes, on fp32 values, with
-//     DPP row operations (one fused multiply-add with a DPP operand per value).  The
-//     16-byte chunks of a unit are dealt to lanes so that bits 5, 6, 7 pair lanes l ^ 1,
-//     l ^ 2, l ^ 8 (single DPP operations) and bit 8, which only 512-blocks transform,
-//     pairs l ^ 4 (two masked row shifts).
+//     DPP row operations: one fused multiply-add with a DPP operand per value and stage.  A 16-lane row
+//     has single-operation pairings l ^ 1, l ^ 2 (quad permutes), l ^ 8 (row rotate) and l ^ 7 (half-row
+//     mirror), but none for l ^ 4; 1, 2, 8, 7 is a basis of the row's 16 lane numbers all the same, and a
+//     transform whose stages pair along a basis is the Hadamard transform in the coordinates over that
+//     basis.  So the 16-byte chunks of a unit are dealt to lanes by those coordinates: the lane whose
+//     number is u5 * 1 ^ u6 * 2 ^ u7 * 8 ^ u8 * 7 takes the chunk whose channel-index bits 5..8 are
+//     u5 .. u8, and the result lands in place.
 //
 // Chunk c (16 bytes = 8 channels) of a unit belongs to lane
-//   l = (c & 3) << 4 | (c >> 2 & 1) | (c >> 3 & 1) << 1 | (c >> 5 & 1) << 2 | (c >> 4 & 1) << 3,
+//   l = (c & 3) << 4 | ((c >> 2 & 1) * 1 ^ (c >> 3 & 1) * 2 ^ (c >> 4 & 1) * 8 ^ (c >> 5 & 1) * 7),
 // i.e. lanes l, l+16, l+32, l+48 hold 64 contiguous bytes and a wave instruction still
 // covers one contiguous kilobyte.  Rows longer than a few units are spread over the
 // waves of a workgroup and the abs-max is combined through LDS.  Workgroups stay
@@ -30,13 +33,12 @@
 // scale and into the reciprocal the codes are taken with.
 #include "dvdq_internal.h"
 
-#include <type_traits>
-
 namespace dvdq {
 namespace {
 
 constexpr int kWave = 64;
 constexpr int kUnit = 512;  // channels a wave handles per step (64 lanes x 8)
+constexpr size_t kLdsPerCu = 160 * 1024;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -73,32 +75,26 @@ __device__ __forceinline__ void stage_xor1(float (&v)[8], float sign) { DVDQ_FMA
 __device__ __forceinline__ void stage_xor2(float (&v)[8], float sign) { DVDQ_FMAC_DPP8("", "quad_perm:[2,3,0,1]"); }
 __device__ __forceinline__ void stage_xor8(float (&v)[8], float sign) { DVDQ_FMAC_DPP8("", "row_ror:8"); }
 
-// Butterfly stage over lanes l ^ 4 (no single DPP pattern): rows shifted left by 4 feed the
-// lanes with bit 2 clear (banks 0 and 2: own + partner), rows shifted right by 4 the others
-// (banks 1 and 3: partner - own).  Two instructions per value, exact butterfly signs.
-__device__ __forceinline__ float stage_xor4_one(float v) {
-    float w;
-    asm volatile("s_nop 1\n\t"
-                 "v_add_f32_dpp %0, %1, %1 row_shl:4 row_mask:0xf bank_mask:0x5\n\t"
-                 "v_sub_f32_dpp %0, %1, %1 row_shr:4 row_mask:0xf bank_mask:0xa"
-                 : "=&v"(w)
-                 : "v"(v));
-    return w;
-}
+__device__ __forceinline__ void stage_xor7(float (&v)[8], float sign) { DVDQ_FMAC_DPP8("", "row_half_mirror"); }
 
 // Maximum of a non-negative value over the wave, the same in every lane: two quad permutes and two row
 // mirrors leave each 16-lane row's maximum in all its lanes, two row broadcasts carry it on into lane 63.
+// (Inline assembly: the compiler keeps a move, two canonicalizing maxima and the maximum per step instead of one
+// maximum with a DPP operand.  s_nop 1: the 2 wait states between a vector write and a DPP read of a register.)
 __device__ __forceinline__ float wave_max(float a) {
-    auto with = [](float a, auto ctrl, auto row_mask) {
-        const int v = __builtin_bit_cast(int, a);
-        return fmaxf(a, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, decltype(ctrl)::value, decltype(row_mask)::value, 0xF, false)));
-    };
-    a = with(a, std::integral_constant<int, 0xB1>{}, std::integral_constant<int, 0xF>{});    // quad_perm:[1,0,3,2]
-    a = with(a, std::integral_constant<int, 0x4E>{}, std::integral_constant<int, 0xF>{});    // quad_perm:[2,3,0,1]
-    a = with(a, std::integral_constant<int, 0x141>{}, std::integral_constant<int, 0xF>{});   // row_half_mirror
-    a = with(a, std::integral_constant<int, 0x140>{}, std::integral_constant<int, 0xF>{});   // row_mirror
-    a = with(a, std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xA>{});   // row_bcast:15 into rows 1, 3
-    a = with(a, std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xC>{});   // row_bcast:31 into rows 2, 3
+    asm volatile("s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"   // into rows 1, 3
+                 "s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf"          // into rows 2, 3
+                 : "+v"(a));
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a), 63));
 }
 
@@ -136,8 +132,9 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
     const int row_in_wg = wave / waves_per_row;
     const int wsub = wave - row_in_wg * waves_per_row;
     // this lane's 16-byte chunk within a unit
-    const int chunk = ((lane >> 4) & 3) | ((lane & 1) << 2) | (((lane >> 1) & 1) << 3) | (((lane >> 3) & 1) << 4) |
-                      (((lane >> 2) & 1) << 5);
+    // (u5 .. u8: the lane's coordinates over the pairings 1, 2, 8, 7 = channel-index bits 5 .. 8 of its chunk)
+    const int u8 = (lane >> 2) & 1, u7 = (lane >> 3) & 1, u6 = ((lane >> 1) & 1) ^ u8, u5 = (lane & 1) ^ u8;
+    const int chunk = ((lane >> 4) & 3) | (u5 << 2) | (u6 << 3) | (u7 << 4) | (u8 << 5);
 
     // constant MFMA operands: rows r = 8 (m / 4) + 4 h + (m % 4) of the 32 x 32 transform, m = lane % 16,
     // columns k = 8 (lane / 16) + t.  MFMA h then yields transformed channels 4h .. 4h+3 of this lane's chunk.
@@ -154,14 +151,20 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
         tmat[h] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
     }
     // butterfly signs of the lane-pairing stages (the lane with the stage's bit set takes the difference)
-    const float s1 = (lane & 1) ? -1.f : 1.f, s2 = (lane & 2) ? -1.f : 1.f, s8 = (lane & 8) ? -1.f : 1.f;
-    // stages xor 1, xor 2 and xor 8 leave MINUS the difference in the lane with the bit set
-    const float flip = ((((LOG2B >= 6) && (lane & 1)) != 0) != (((LOG2B >= 7) && (lane & 2)) != ((LOG2B >= 8) && (lane & 8)))) ? -1.f : 1.f;
+    const float s1 = u5 ? -1.f : 1.f, s2 = u6 ? -1.f : 1.f, s8 = u7 ? -1.f : 1.f, s7 = u8 ? -1.f : 1.f;
+    // every stage leaves MINUS the difference in the lane whose coordinate is set
+    const float flip = (((LOG2B >= 6) & u5) ^ ((LOG2B >= 7) & u6) ^ ((LOG2B >= 8) & u7) ^ ((LOG2B >= 9) & u8)) ? -1.f : 1.f;
 
     // channel offsets of this lane's chunks; chunks at or past K are padding (zero in, nothing out)
     int k0[CPW];
 #pragma unroll
     for (int c = 0; c < CPW; ++c) k0[c] = (wsub + c * waves_per_row) * kUnit + chunk * 8;
+
+    // Unit c of this wave is unit wsub + c * waves_per_row of the row; only the last one can lie past the row's
+    // end (the launcher gives every wave ceil(units / waves) slots).  Wave-uniform: such a wave branches around
+    // the slot's work, which keeps the vector work of the SIMDs of a workgroup even when units do not divide.
+    const bool last_unit_present = (wsub + (CPW - 1) * waves_per_row) * kUnit < K;
+    auto present = [&] __device__(int c) { return c < CPW - 1 || last_unit_present; };
 
     // A row is read through a buffer descriptor of its own (base = the row, extent = its K bf16 values, or
     // nothing for rows past M): chunks past the end come back as zeros with no branch around the loads, so the
@@ -187,6 +190,17 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
     // its chunks of a run in LDS and writes them as whole lines (16-byte stores scattered over 64 lines
     // per instruction make the whole kernel take twice as long).
     const int run = FMT == 2 ? via_lds : 1;
+    // FP6 write-back of a unit's 24 chunks x run rows: item t * 64 + lane is row (lane % run) of the run and
+    // chunk part = (t * 64 + lane) / run of the unit, i.e. slice part / 6, piece part % 6; parts >= 24 are idle
+    int wb_in[3], wb_out[3], wb_slice[3];
+    const int wb_rr = lane & (run - 1);
+#pragma unroll
+    for (int t = 0; t < 3; ++t) {
+        const int part = (t * kWave + lane) >> __builtin_ctz(run);
+        wb_slice[t] = part < 24 ? part / 6 : (1 << 30);   // idle: past every row's slices
+        wb_in[t] = wb_rr * (CPW * 384 + 16) + part * 16;
+        wb_out[t] = (part / 6) * 3072 + (part % 6) * 512 + wb_rr * 16;
+    }
     // The workgroup's iterations are numbered (g, turn): turn counts 0 .. run - 1 within group g, and wave row 0
     // takes row (blockIdx.x + g * gridDim.x) * run * rows_per_wg + turn; wave row r is r * run rows further on.
     // (Counted up by hand: a 64-bit division per iteration costs more than a hundred scalar instructions.)
@@ -210,6 +224,7 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
         float amax = 0.f;
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
+            if (!present(c)) continue;   // (its values are never read)
             if (LOG2B == 0) {
                 const uint32_t w[4] = {raw[c].x, raw[c].y, raw[c].z, raw[c].w};
 #pragma unroll
@@ -231,13 +246,11 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
         }
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
+            if (!present(c)) continue;
             if (LOG2B >= 6) stage_xor1(v[c], s1);
             if (LOG2B >= 7) stage_xor2(v[c], s2);
             if (LOG2B >= 8) stage_xor8(v[c], s8);
-            if (LOG2B >= 9) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) v[c][i] = stage_xor4_one(v[c][i]);
-            }
+            if (LOG2B >= 9) stage_xor7(v[c], s7);
 #pragma unroll
             for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(v[c][i]));
         }
@@ -290,6 +303,7 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
                 v16f qb = qa;
 #pragma unroll
                 for (int g = 0; g < 4 && c0 + g < CPW; ++g) {
+                    if (!present(c0 + g)) continue;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         qa[4 * g + i] = fmaf(v[c0 + g][2 * i], r, magic) - magic;
@@ -301,6 +315,7 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
                 asm volatile("v_cvt_scalef32_2xpk16_fp6_f32 %0, %1, %2, %3\n\ts_nop 1" : "=&v"(pk) : "v"(qa), "v"(qb), "v"(8.0f));
 #pragma unroll
                 for (int g = 0; g < 4 && c0 + g < CPW; ++g) {
+                    if (!present(c0 + g)) continue;
                     // the chunk's three 16-bit pieces h0 h1 h2: an even chunk stores (h0 h1) and h2, an odd one h0 and (h1 h2)
                     const uint32_t w0 = pk[3 * (g / 2) + (g & 1)], w1 = pk[3 * (g / 2) + (g & 1) + 1];
                     uint32_t h01, h12, h0, h2;
@@ -321,22 +336,26 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                // (row0 is a multiple of `run`, a power of two <= 8: the run lies inside one 32-row block, so its
-                // address splits into a wave-uniform 64-bit base and a 32-bit offset per lane)
+                // (row0 is a multiple of `run`, a power of two <= 8: the run lies inside one 32-row block, so a
+                // unit's address splits into a wave-uniform 64-bit base and the lane's fixed offsets wb_out[])
                 const int64_t row0 = row - turn;
                 const int slices = K >> 7;
-                const int run_log2 = __builtin_ctz(run);
                 uint8_t *run_base = reinterpret_cast<uint8_t *>(codes) + ((row0 >> 5) * slices) * 3072 + (row0 & 31) * 16;
                 const int rows_left = (int)min((int64_t)turn, M - 1 - row0);   // rows row0 .. row0 + rows_left exist
-                for (int idx0 = 0; idx0 < CPW * 24 * run; idx0 += kWave) {
-                    const int idx = idx0 + lane;
-                    const int L = idx >> run_log2, rr = idx & (run - 1);   // chunk of the wave's units, turn
-                    const int c = L / 24, part = L - c * 24;
-                    const int g = (wsub + c * waves_per_row) * 24 + part;  // 16-byte chunk of the row
-                    const int slice = g / 6, j = g - slice * 6;
-                    if (idx < CPW * 24 * run && rr <= rows_left && slice < slices)
-                        *reinterpret_cast<uint4 *>(run_base + (uint32_t)(slice * 3072 + j * 512 + rr * 16)) =
-                            *reinterpret_cast<const uint4 *>(stage + rr * TURN_BYTES + c * 384 + part * 16);
+                const bool rr_ok = wb_rr <= rows_left;
+#pragma unroll
+                for (int c = 0; c < CPW; ++c) {
+                    if (!present(c)) continue;
+                    const int unit = wsub + c * waves_per_row;
+                    uint8_t *unit_base = run_base + (int64_t)unit * (4 * 3072);
+                    const int slices_here = slices - 4 * unit;   // a row's last unit may hold fewer than 4 slices
+#pragma unroll
+                    for (int t = 0; t < 3; ++t) {
+                        if (t * kWave >= 24 * run) break;
+                        if (rr_ok && wb_slice[t] < slices_here)
+                            *reinterpret_cast<uint4 *>(unit_base + wb_out[t]) =
+                                *reinterpret_cast<const uint4 *>(stage + wb_in[t] + c * 384);
+                    }
                 }
                 __builtin_amdgcn_wave_barrier();   // the next run's LDS writes stay behind these reads
             }
@@ -346,6 +365,8 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
             uint32_t p[CPW];
 #pragma unroll
             for (int c = 0; c < CPW; ++c) {
+                p[c] = 0;
+                if (!present(c)) continue;
                 uint32_t b[8], u[4];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) b[i] = __float_as_uint(fmaf(v[c][i], r, magic));
@@ -381,6 +402,7 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
         } else {
 #pragma unroll
             for (int c = 0; c < CPW; ++c) {
+                if (!present(c)) continue;
                 uint32_t b[8];
                 if (group_log2) {
                     // Block-wise scaling (a reading of the block-wise variant of Sec. 3.2): a channel group
@@ -448,10 +470,13 @@ int launch_cpw(int cpw, dim3 grid, dim3 block, size_t smem, hipStream_t stream, 
                int8_t *codes, float *x_scale, int32_t *code_rowsum) {
 #define DVDQ_RQ_CASE(C)                                                                                   \
     case C:                                                                                               \
-        if (pack4 == 3)                                                                                   \
+        if (pack4 == 3) {                                                                                 \
+            static std::atomic<uint64_t> lds_allowed{0};                                                  \
+            allow_dynamic_lds(reinterpret_cast<const void *>(&rotate_quant_kernel<LOG2B, C, 2>),          \
+                              kLdsPerCu, lds_allowed);                                                    \
             hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C, 2>), grid, block, smem, stream, x, M, K, W, \
                                rpw, scale_mul, recip_num, group_log2, 0, 0, codes, x_scale, code_rowsum); \
-        else if (pack4)                                                                                   \
+        } else if (pack4)                                                                                   \
             hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C, 1>), grid, block, smem, stream, x, M, K, W, \
                                rpw, scale_mul, recip_num, pack4 == 2, 0, 0, codes, x_scale, code_rowsum); \
         else                                                                                              \
@@ -476,23 +501,26 @@ int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block,
     // 0: int8; 1 / 2: packed nibbles stored per lane / gathered through LDS; 3: FP6 container
     const int pack4 = codes_format == DVDQ_CODES_FP6 ? 3 : (codes_format != DVDQ_CODES_PACKED4 ? 0 : ((K % 32) == 0 ? 2 : 1));
     const int units = (int)((K + kUnit - 1) / kUnit);
-    // waves per row: at most 4 units (32 fp32 values per lane) in registers per wave, at most 16 waves
-    int W = (units + 3) / 4;
+    // waves per row: at most 3 units (24 fp32 values per lane) in registers per wave, at most 16 waves
+    // (3 rather than 4: a 13824-channel row then takes 9 waves of 3 units instead of 7 of 4, and the
+    // kernel 12 % less time; the other shapes do not care)
+    int W = (units + 2) / 3;
+    if (W > 4) W = (W + 3) / 4 * 4;   // whole waves per SIMD
     if (W > 16) W = 16;
     const int cpw = (units + W - 1) / W;
     if (cpw > 8) return DVDQ_ERR_UNSUPPORTED;
-    const int rows_per_wg = W >= 4 ? 1 : 4 / W;
+    // workgroups of about 8 waves, about 16 waves resident per compute unit (256 of them), every workgroup
+    // striding over the rows.  Measured over 8 .. 28 resident waves and workgroups of 2, 4, 8 waves on the
+    // four video-DiT shapes: within 1.5 % of the best of each shape and container, but for int8 codes of
+    // 3072-channel rows, which would run 10 % faster with 8 resident waves.
+    const int rows_per_wg = W >= 8 ? 1 : 8 / W;
     const dim3 block(kWave * W * rows_per_wg);
-    // resident workgroups: a whole number per compute unit (256 of them), about 16 waves each,
-    // every workgroup striding over the rows
-    // FP6: consecutive rows a wave takes in turn (see the kernel): 8 if the LDS for collecting them allows
-    // resident waves per compute unit: 16; 20 with the FP6 container, whose extra vector work per element
-    // more waves hide (measured: -4 % on 1536- and 3072-channel rows; the other containers get slower)
-    int wgs_per_cu = (pack4 == 3 ? 20 : 16) / (W * rows_per_wg);
+    int wgs_per_cu = 16 / (W * rows_per_wg);
     if (wgs_per_cu < 1) wgs_per_cu = 1;
+    // FP6: consecutive rows a wave takes in turn (see the kernel): 8 if the LDS for collecting them allows
     int run = 1;
     if (pack4 == 3) {
-        const size_t budget = wgs_per_cu <= 2 ? 65536 - 4096 : (size_t)150 * 1024 / wgs_per_cu;
+        const size_t budget = (kLdsPerCu - 8192) / wgs_per_cu;
         for (run = 8; run > 1 && (size_t)W * rows_per_wg * run * (cpw * 384 + 16) > budget;) run /= 2;
     }
     const int group_rows = rows_per_wg * run;

@@ -131,6 +131,7 @@ def rand_x(rng, M, K):
 @pytest.mark.parametrize("M,K,B", [
     (1, 128, 1), (3, 128, 128), (7, 384, 32), (130, 256, 256), (33, 768, 256), (257, 1536, 256), (64, 3072, 256),
     (31, 512, 512), (6, 13824, 512), (17, 640, 8), (4, 65536, 512), (1027, 1536, 256), (40, 2560, 512),
+    (70, 13824, 512), (45, 32768, 512), (70, 8192, 256),   # rows of many units: runs of 8, 4 and 2 rows staged per wave
 ])
 def test_rotate_quant_fp6_decodes_to_the_int8_codes(M, K, B):
     rng = np.random.default_rng(M * 17 + K + B)
