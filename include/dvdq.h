@@ -16,13 +16,18 @@
  * Conventions shared by every entry point
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
  *     never allocates or frees device memory.  Its only state: the measurement hooks
- *     of dvdq_bench.h, and a fixed 32 KB array of device memory per GPU (part of the
- *     loaded code object) that the GEMM kernels use as tile counters, 64 bytes per
- *     stream: zero at load, and put back to zero by every kernel before it ends.
- *     Kernels of one stream run one after the other and therefore share a slot; up to
- *     512 streams per GPU get slots, further streams and launches under stream capture
- *     use fixed tile shares instead (same results).  A stream must not be destroyed
- *     while a GEMM it was given is still running and its handle be reused at once.
+ *     of dvdq_bench.h, the scratch array of dvdq_qlinear_static, and a fixed 32 KB array
+ *     of device memory per GPU (part of the loaded code object) that the GEMM kernels
+ *     use as tile counters, 64 bytes per stream.  No launch depends on what an earlier
+ *     one left in its counters: they are zeroed on the stream right before every GEMM
+ *     that counts in them (by the quantizer kernel of dvdq_qlinear, by a one-wave kernel
+ *     in front of a dvdq_w4ax_gemm), so a launch that never finished or a stray write
+ *     cannot make a later GEMM skip tiles.  Kernels of one stream run one after the
+ *     other and therefore share a slot; up to 512 streams per GPU hold slots at a time
+ *     (dvdq_release_stream gives one back), further streams and launches under stream
+ *     capture use fixed tile shares instead (same results; nothing extra is captured).
+ *     Two GEMMs must not run at the same time on one stream handle, which HIP rules out
+ *     as long as a handle is not used after its stream was destroyed.
  *   - `hip_stream` is the caller's hipStream_t (NULL = the default stream).  All
  *     work is enqueued on it; calls return without synchronizing.
  *   - Inputs are read-only; outputs must not overlap inputs or each other.
@@ -209,6 +214,13 @@ int dvdq_qlinear_static(const void *x_bf16, const uint8_t *w, const float *w_sca
                         const void *bias_bf16, int64_t M, int64_t N, int64_t K, int had_block, int act_bits,
                         int codes_format, int w_layout, void *y_bf16, void *hip_stream);
 size_t dvdq_static_workspace_bytes(void);
+
+/*
+ * Optional: forget a stream (on the current GPU) before it is destroyed, so that its
+ * counter slot can serve another stream.  Host-only bookkeeping, nothing is enqueued;
+ * using the stream again later simply assigns a slot again.  Unknown streams: no-op.
+ */
+int dvdq_release_stream(void *hip_stream);
 
 /*
  * One-time, offline: reorder canonical packed weights into the GEMM kernel's

@@ -40,15 +40,20 @@ int dvdq_bench_mfma_fp6(int iters, int data, int32_t *sink, double *ops_out, voi
 /* Tile-configuration sweeps: force the native-layout GEMMs to use tile variant `variant`
  * (INT8 matrix path: 1..4, see the dispatch tables in w4ax_gemm.hip, one per code container; shapes too
  * shallow in K for a variant's ring fall back to variant 2.  FP6 matrix path: 1..2, see w4a4_fp6_gemm.hip,
- * other values mean its own choice); -1 restores the library's own choice.  Process-wide, not
- * thread-safe, meant for benchmarking only. */
+ * other values mean its own choice); -1 restores the library's own choice.  Process-wide (an atomic
+ * that every launch reads once), meant for benchmarking only. */
 int dvdq_bench_set_gemm_variant(int variant);
 
 /* How the native-layout GEMM's persistent workgroups get their tiles: 0 = fixed equal shares,
  * -1 = the library's own choice (tiles drawn from per-stream counters, fixed shares while a
- * stream is being captured).  Results are identical either way.  Process-wide, not
- * thread-safe, meant for benchmarking only. */
+ * stream is being captured).  Results are identical either way.  Process-wide (an atomic that every
+ * launch reads once), meant for benchmarking only. */
 int dvdq_bench_set_gemm_schedule(int schedule);
+
+/* Robustness tests: overwrite every word of the current GPU's tile counters with `value`, in stream
+ * order on `hip_stream` (as a stray write or a launch that never finished would leave them).  GEMMs
+ * launched afterwards must still give the right result. */
+int dvdq_bench_fill_tile_counters(uint32_t value, void *hip_stream);
 
 #ifdef __cplusplus
 }

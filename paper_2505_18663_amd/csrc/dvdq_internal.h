@@ -12,11 +12,15 @@ namespace dvdq {
 // Launchers: arguments are already validated by the C-ABI layer in api.hip.
 // Each returns DVDQ_OK or DVDQ_ERR_HIP.
 int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block, int act_bits, int codes_format,
-                        int group_log2, int8_t *codes, float *x_scale, int32_t *code_rowsum, hipStream_t stream);
+                        int group_log2, int8_t *codes, float *x_scale, int32_t *code_rowsum, hipStream_t stream,
+                        unsigned *clear_words = nullptr);   // 16 words the kernel also zeroes: the tile counters of the GEMM behind it
+
+// counters_clear: whatever ran on the stream right before has zeroed the stream's tile counters (sched_slot)
 
 int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                      const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,
-                     int64_t K, int codes_format, int w_layout, uint16_t *y, int32_t *acc_out, hipStream_t stream);
+                     int64_t K, int codes_format, int w_layout, uint16_t *y, int32_t *acc_out, hipStream_t stream,
+                     bool counters_clear = false);
 
 int launch_w4ax_gemm_canonical(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                                const uint16_t *bias, int64_t M, int64_t N, int64_t K, uint16_t *y, int32_t *acc_out,
@@ -25,12 +29,13 @@ int launch_w4ax_gemm_canonical(const int8_t *codes, const float *x_scale, const 
 // W4A4 on the FP6 matrix path (w4a4_fp6_gemm.hip): codes and weights in the FP6 block-slice layouts
 int launch_w4a4_fp6_gemm(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                          const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,
-                         int64_t K, uint16_t *y, int32_t *acc_out, hipStream_t stream);
+                         int64_t K, uint16_t *y, int32_t *acc_out, hipStream_t stream, bool counters_clear = false);
 // One 4-wave workgroup per compute unit, 128 x 128 wave tiles, accumulators in AGPRs (w4ax_gemm_wide.hip):
 // int8 codes x native weights (fp6 = false) or FP6 codes x FP6 native weights (fp6 = true)
 int launch_w4ax_gemm_wide(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                           const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,
-                          int64_t K, bool fp6, uint16_t *y, int32_t *acc_out, hipStream_t stream);
+                          int64_t K, bool fp6, uint16_t *y, int32_t *acc_out, hipStream_t stream,
+                          bool counters_clear = false);
 size_t w4_native_fp6_bytes(int64_t N, int64_t K);
 size_t codes_fp6_bytes(int64_t M, int64_t K);
 int launch_w4_prepack_fp6(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, hipStream_t stream);
@@ -38,6 +43,9 @@ int launch_w4_prepack_fp6(const uint8_t *w_canonical, int64_t N, int64_t K, uint
 size_t w4_native_bytes(int64_t N, int64_t K);
 void set_gemm_variant(int v);  // benchmark sweeps only; -1 = choose by shape
 void set_gemm_schedule(int v); // benchmark only; 0 = fixed tile shares, -1 = drawn from counters where possible
+unsigned *sched_slot(hipStream_t stream);                   // the stream's tile-counter slot (16 words), or nullptr: fixed tile shares
+void release_sched_slot(hipStream_t stream);               // forget a stream's tile-counter slot (host bookkeeping only)
+int fill_sched_slots(uint32_t value, hipStream_t stream);  // robustness tests only: overwrite every tile counter
 
 int launch_w4_prepack(const uint8_t *w_canonical, int64_t N, int64_t K, uint8_t *w_native, hipStream_t stream);
 

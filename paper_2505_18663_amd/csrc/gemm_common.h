@@ -95,9 +95,47 @@ static __device__ __forceinline__ void tile_origin(int t, int tiles_m, int tiles
 }
 
 
-// The per-stream tile counters of the persistent kernels (defined in w4ax_gemm.hip): 16 words, the first
-// eight the XCDs' draw counters, the ninth the count of finished workgroups; nullptr = fixed shares.
-unsigned *sched_slot(hipStream_t stream);
+// ---- tile numbers of a persistent launch
+// Workgroup ids are dealt round-robin to the 8 XCDs, and the workgroups of one XCD work on one contiguous
+// run of tile numbers at a time.
+//   ctr != nullptr: XCD x owns tile numbers [x total / 8, (x + 1) total / 8) and its workgroups draw from them
+//     in order through one counter word (an atomic add).  The word is zero when the kernel starts: whatever
+//     runs on the stream right before the GEMM clears the slot (the quantizer kernel of the fused layer, or
+//     a one-wave kernel the GEMM's launcher puts in front), so no launch depends on what an earlier one --
+//     finished or not -- left behind, and nothing has to be put back at the end.
+//   ctr == nullptr: fixed shares, the j-th tile of workgroup b is number j * grid + (b % 8) * (grid / 8) + b / 8.
+struct TileSource {
+    int total, grid, xcd, first_tile, run_lo;
+    unsigned run_len;
+    unsigned *ctr;   // this XCD's counter
+
+    __device__ __forceinline__ TileSource(int tiles_m, int tiles_n, unsigned *sched) {
+        total = tiles_m * tiles_n;
+        grid = gridDim.x;   // a multiple of 8
+        xcd = blockIdx.x % 8;
+        first_tile = xcd * (grid / 8) + blockIdx.x / 8;
+        run_lo = (int)((int64_t)xcd * total / 8);
+        run_len = (unsigned)((int64_t)(xcd + 1) * total / 8) - (unsigned)run_lo;
+        ctr = sched ? sched + xcd : nullptr;
+    }
+    // the tile a draw's reply stands for (drawn mode), or the workgroup's ordinal-th tile (fixed shares); -1: none left
+    __device__ __forceinline__ int tile(unsigned reply, int ordinal) const {
+        if (ctr) return reply < run_len ? run_lo + (int)reply : -1;
+        const int t = first_tile + ordinal * grid;
+        return t < total ? t : -1;
+    }
+    // one further tile (one lane; drawn mode only).  The reply may be awaited as late as the caller likes.
+    __device__ __forceinline__ unsigned draw() const { return atomicAdd(ctr, 1u); }
+    // the workgroup's first two tiles (one lane; either mode)
+    __device__ __forceinline__ void first_two(int &t0, int &t1) const {
+        const unsigned v = ctr ? atomicAdd(ctr, 2u) : 0u;
+        t0 = tile(v, 0);
+        t1 = tile(v + 1u, 1);
+    }
+};
+
+// Enqueues the one-wave kernel that zeroes a counter slot (sched_slot; defined in w4ax_gemm.hip).
+int clear_sched_slot(unsigned *slot, hipStream_t stream);
 int gemm_variant();   // the benchmark hook's tile variant (-1: the kernels' own choice)
 
 }  // namespace dvdq

@@ -118,7 +118,9 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
     int group_log2,    // int8 container only: 0, or log2 of the channel group (7, 8, 9) of block-wise scaling
     int emax,          // block-wise scaling: largest power-of-two refinement of a group's step (8 - act_bits)
     int8_t *__restrict__ codes, float *__restrict__ x_scale,
-    int32_t *__restrict__ code_rowsum) {  // NULL, or [M]: sum of the row's codes (for weight zero-points)
+    int32_t *__restrict__ code_rowsum,    // NULL, or [M]: sum of the row's codes (for weight zero-points)
+    unsigned *__restrict__ clear_words) { // NULL, or 16 words to zero: the tile counters of the GEMM that follows on the stream
+    if (clear_words && blockIdx.x == 0 && threadIdx.x < 16) clear_words[threadIdx.x] = 0u;
     extern __shared__ float s_amax[];  // [2][rows_per_wg * waves_per_row], slots alternate per iteration
     // then [2][rows_per_wg * waves_per_row] per-wave code sums, then, 16-byte aligned,
     // [waves][CPW][64] dwords for gathering packed codes (via_lds), or [waves][rows in turn][CPW * 384 + 16] bytes for FP6
@@ -467,7 +469,7 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
 template <int LOG2B>
 int launch_cpw(int cpw, dim3 grid, dim3 block, size_t smem, hipStream_t stream, const uint16_t *x, int64_t M,
                int K, int W, int rpw, double scale_mul, float recip_num, int pack4, int group_log2, int emax,
-               int8_t *codes, float *x_scale, int32_t *code_rowsum) {
+               int8_t *codes, float *x_scale, int32_t *code_rowsum, unsigned *clear_words) {
 #define DVDQ_RQ_CASE(C)                                                                                   \
     case C:                                                                                               \
         if (pack4 == 3) {                                                                                 \
@@ -475,14 +477,14 @@ int launch_cpw(int cpw, dim3 grid, dim3 block, size_t smem, hipStream_t stream, 
             allow_dynamic_lds(reinterpret_cast<const void *>(&rotate_quant_kernel<LOG2B, C, 2>),          \
                               kLdsPerCu, lds_allowed);                                                    \
             hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C, 2>), grid, block, smem, stream, x, M, K, W, \
-                               rpw, scale_mul, recip_num, group_log2, 0, 0, codes, x_scale, code_rowsum); \
+                               rpw, scale_mul, recip_num, group_log2, 0, 0, codes, x_scale, code_rowsum, clear_words); \
         } else if (pack4)                                                                                   \
             hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C, 1>), grid, block, smem, stream, x, M, K, W, \
-                               rpw, scale_mul, recip_num, pack4 == 2, 0, 0, codes, x_scale, code_rowsum); \
+                               rpw, scale_mul, recip_num, pack4 == 2, 0, 0, codes, x_scale, code_rowsum, clear_words); \
         else                                                                                              \
             hipLaunchKernelGGL((rotate_quant_kernel<LOG2B, C, 0>), grid, block, smem, stream, x, M, K, W, \
                                rpw, scale_mul, recip_num, 0, group_log2, emax, codes, x_scale,            \
-                               code_rowsum);                                                              \
+                               code_rowsum, clear_words);                                                 \
         break;
     switch (cpw) {
         DVDQ_RQ_CASE(1) DVDQ_RQ_CASE(2) DVDQ_RQ_CASE(3) DVDQ_RQ_CASE(4)
@@ -496,7 +498,8 @@ int launch_cpw(int cpw, dim3 grid, dim3 block, size_t smem, hipStream_t stream, 
 }  // namespace
 
 int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block, int act_bits, int codes_format,
-                        int group_log2, int8_t *codes, float *x_scale, int32_t *code_rowsum, hipStream_t stream) {
+                        int group_log2, int8_t *codes, float *x_scale, int32_t *code_rowsum, hipStream_t stream,
+                        unsigned *clear_words) {
     const int emax = group_log2 ? 8 - act_bits : 0;
     // 0: int8; 1 / 2: packed nibbles stored per lane / gathered through LDS; 3: FP6 container
     const int pack4 = codes_format == DVDQ_CODES_FP6 ? 3 : (codes_format != DVDQ_CODES_PACKED4 ? 0 : ((K % 32) == 0 ? 2 : 1));
@@ -537,7 +540,7 @@ int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block,
 #define DVDQ_RQ_B(L)                                                                                        \
     case L:                                                                                                 \
         return launch_cpw<L>(cpw, grid, block, smem, stream, x, M, (int)K, W, rows_per_wg, scale_mul,       \
-                             recip_num, pack4, pack4 == 3 ? run : group_log2, emax, codes, x_scale, code_rowsum);
+                             recip_num, pack4, pack4 == 3 ? run : group_log2, emax, codes, x_scale, code_rowsum, clear_words);
     switch (log2_block) {
         DVDQ_RQ_B(0) DVDQ_RQ_B(1) DVDQ_RQ_B(2) DVDQ_RQ_B(3) DVDQ_RQ_B(4)
         DVDQ_RQ_B(5) DVDQ_RQ_B(6) DVDQ_RQ_B(7) DVDQ_RQ_B(8) DVDQ_RQ_B(9)

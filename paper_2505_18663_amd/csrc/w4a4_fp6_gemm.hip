@@ -77,62 +77,38 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_ker
     const int64_t w_slice_stride = (int64_t)G * kFp6Block;
     const int last_block = (M - 1) / 32;                         // code row blocks past it do not exist
 
-    // Persistent workgroups draw their tiles exactly as in the INT8 kernel (see there): per-XCD counters
-    // in sched[0..7], finished workgroups counted in sched[8], fixed shares when sched is null; tile
-    // numbers travel through an 8-entry ring in LDS.
-    const int total = tiles_m * tiles_n;
-    const int grid = gridDim.x;  // multiple of 8
-    const int xcd = blockIdx.x % 8;
-    const int first_tile = xcd * (grid / 8) + blockIdx.x / 8;
-    const int run_lo = (int)((int64_t)xcd * total / 8);
-    const unsigned run_len = (unsigned)((int64_t)(xcd + 1) * total / 8) - (unsigned)run_lo;
+    // Persistent workgroups draw their tiles exactly as in the INT8 kernel (see there, and TileSource): per-XCD
+    // counters, fixed shares when sched is null; tile numbers travel through an 8-entry ring in LDS.
+    const TileSource tiles(tiles_m, tiles_n, sched);
     typedef volatile __attribute__((address_space(3))) int lds_int;
     lds_int *s_tiles = (lds_int *)DVDQ_LDS(smem + STAGES * STAGE + 2 * SCALES);
     int draws = 0;
     unsigned drawn = 0;
     bool draw_pending = false;
     int draw_wait = 0;   // loop tops until the pending draw's reply is older than loads already awaited
-    auto tile_of_draw = [&] __device__(unsigned i, int ordinal) {
-        if (sched) return i < run_len ? run_lo + (int)i : -1;
-        const int t = first_tile + ordinal * grid;
-        return t < total ? t : -1;
-    };
     auto draw = [&] __device__() {
-        if (wave == 0 && sched && lane == 0) drawn = atomicAdd(sched + xcd, 1u);
+        if (wave == 0 && tiles.ctr && lane == 0) drawn = tiles.draw();
         ++draws;
         draw_pending = true;
         draw_wait = STAGES - 1;
     };
     auto publish_draw = [&] __device__() {   // before a workgroup barrier
         if (wave == 0) {
-            if (lane == 0) s_tiles[(draws - 1) & 7] = tile_of_draw(drawn, draws - 1);
+            if (lane == 0) s_tiles[(draws - 1) & 7] = tiles.tile(drawn, draws - 1);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
         draw_pending = false;
     };
-    auto leave = [&] __device__() {
-        if (sched && tid == 0) {
-            if (atomicAdd(sched + 8, 1u) == (unsigned)grid - 1) {
-#pragma unroll
-                for (int i = 0; i < 9; ++i) __hip_atomic_store(sched + i, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-    };
-    if (wave == 0) {
-        unsigned i = 0;
-        if (sched && lane == 0) i = atomicAdd(sched + xcd, 2u);
-        if (lane == 0) {
-            s_tiles[0] = tile_of_draw(i, 0);
-            s_tiles[1] = tile_of_draw(i + 1, 1);
-        }
+    if (wave == 0 && lane == 0) {
+        int t0, t1;
+        tiles.first_two(t0, t1);
+        s_tiles[0] = t0;
+        s_tiles[1] = t1;
     }
     draws = 2;
     __syncthreads();
     int comp_tile = __builtin_amdgcn_readfirstlane(s_tiles[0]);
-    if (comp_tile < 0) {   // (whole workgroup: nothing below is reached, no barrier is missed)
-        leave();
-        return;
-    }
+    if (comp_tile < 0) return;   // (whole workgroup: nothing below is reached, no barrier is missed)
 
     // ---- LDS-direct loads: every piece is 1 KB that is contiguous in memory and in LDS, so a lane's
     // offset is 16 * lane on both sides and the rest is wave-uniform.  Codes: this wave's row block of
@@ -496,7 +472,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_ker
         if (comp_tile < 0) break;
     }
     wait_vmcnt<0>();   // no LDS-direct load may still be in flight when the workgroup's LDS is released
-    leave();
 }
 
 namespace {
@@ -544,7 +519,7 @@ __global__ __launch_bounds__(256) void w4_prepack_fp6_kernel(const uint8_t *__re
 template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int OCC>
 int launch_fp6(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale, const int8_t *w_zero,
                const int32_t *code_rowsum, const uint16_t *bias, int M, int N, int K, uint16_t *y, int32_t *acc_out,
-               hipStream_t stream) {
+               hipStream_t stream, bool counters_clear) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     // column tiles are walked in groups of at most 16, so that workgroups at work at the same time share
     // weight panels in the L2s (2 to 16 measured within 3 % of each other)
@@ -559,8 +534,10 @@ int launch_fp6(const uint8_t *codes, const float *x_scale, const uint8_t *w, con
     auto k = w4a4_fp6_gemm_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, OCC>;
     static std::atomic<uint64_t> configured{0};
     allow_dynamic_lds(reinterpret_cast<const void *>(k), smem, configured);
+    unsigned *sched = sched_slot(stream);
+    if (sched && !counters_clear && clear_sched_slot(sched, stream) != DVDQ_OK) return DVDQ_ERR_HIP;
     hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), smem, stream, codes, x_scale, w, w_scale,
-                       w_zero, code_rowsum, bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n, sched_slot(stream));
+                       w_zero, code_rowsum, bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n, sched);
     return check_launch();
 }
 
@@ -568,8 +545,8 @@ int launch_fp6(const uint8_t *codes, const float *x_scale, const uint8_t *w, con
 
 int launch_w4a4_fp6_gemm(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                          const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,
-                         int64_t K, uint16_t *y, int32_t *acc_out, hipStream_t stream) {
-#define DVDQ_FP6_ARGS codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K, y, acc_out, stream
+                         int64_t K, uint16_t *y, int32_t *acc_out, hipStream_t stream, bool counters_clear) {
+#define DVDQ_FP6_ARGS codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K, y, acc_out, stream, counters_clear
     // Tile variants {tile M, tile N, waves M x N, ring depth, workgroups per compute unit}:
     //   1: two independent 4-wave workgroups per compute unit, 128 x 256 tiles, two buffers: while one
     //      converts and stores a tile the other multiplies;
@@ -586,7 +563,7 @@ int launch_w4a4_fp6_gemm(const uint8_t *codes, const float *x_scale, const uint8
     const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
     if (v != 1 && v != 2 && v != 3) v = big_tiles >= 512 ? (K / kBK >= 20 ? 3 : 2) : 1;
     if (K / kBK < 2 && v == 2) v = 1;
-    if (v == 3) return launch_w4ax_gemm_wide(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, M, N, K, true, y, acc_out, stream);
+    if (v == 3) return launch_w4ax_gemm_wide(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, M, N, K, true, y, acc_out, stream, counters_clear);
     if (v == 2) return launch_fp6<256, 256, 4, 2, 3, 1>(DVDQ_FP6_ARGS);
     return launch_fp6<128, 256, 2, 2, 2, 2>(DVDQ_FP6_ARGS);
 #undef DVDQ_FP6_ARGS

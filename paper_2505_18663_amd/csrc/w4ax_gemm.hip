@@ -27,6 +27,7 @@
 #include <mutex>
 #include <type_traits>
 #include <unordered_map>
+#include <vector>
 
 #include "gemm_common.h"
 
@@ -83,70 +84,43 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     const int64_t w_slice_stride = (int64_t)G * kGroupBytes;
     const int code_row_bytes = A4 ? K / 2 : K;
 
-    // Persistent workgroups take tiles until none is left.  Workgroup ids are dealt round-robin to
-    // the 8 XCDs, and the workgroups of one XCD work on one contiguous run of tile numbers at a time.
-    //   sched != nullptr: XCD x owns tile numbers [x total / 8, (x + 1) total / 8) and its workgroups
-    //     draw from them in order through the counter sched[x] (an atomic add).  The two workgroups
-    //     of a compute unit do not run at the same speed (the older one wins the issue arbitration),
-    //     so equal shares would leave the faster ones idle for the last tenth of the kernel.
-    //     sched[8] counts the workgroups that are done; the last one puts all nine words back to zero.
-    //   sched == nullptr: the j-th tile of workgroup b is number j * grid + (b % 8) * (grid / 8) + b / 8.
+    // Persistent workgroups take tiles until none is left: drawn per XCD through counters (sched), or in
+    // fixed shares (see TileSource).  The two workgroups of a compute unit do not run at the same speed (the
+    // older one wins the issue arbitration), so equal shares would leave the faster ones idle for the last
+    // tenth of the kernel.
     // The tile numbers a workgroup has drawn go through an 8-entry ring in LDS (s_tiles; -1 = no
     // tile left).  Wave 0 draws tile n + 2 while the loads of tile n are being enqueued and writes the
     // number into the ring one item later, before that item's barrier: the atomic's reply is then
     // older than loads the wave has already awaited, so the draw never stalls anything.
-    const int total = tiles_m * tiles_n;
-    const int grid = gridDim.x;  // multiple of 8
-    const int xcd = blockIdx.x % 8;
-    const int first_tile = xcd * (grid / 8) + blockIdx.x / 8;
-    const int run_lo = (int)((int64_t)xcd * total / 8);
-    const unsigned run_len = (unsigned)((int64_t)(xcd + 1) * total / 8) - (unsigned)run_lo;
+    const TileSource tiles(tiles_m, tiles_n, sched);
     typedef volatile __attribute__((address_space(3))) int lds_int;   // (explicitly LDS: a generic volatile access would be a flat one)
     lds_int *s_tiles = (lds_int *)DVDQ_LDS(smem + STAGES * STAGE + 2 * SCALES);
     int draws = 0;           // tiles drawn so far (the same in every wave)
     unsigned drawn = 0;      // wave 0, lane 0: reply of the draw not yet written into the ring
     bool draw_pending = false;
-    auto tile_of_draw = [&] __device__(unsigned i, int ordinal) {
-        if (sched) return i < run_len ? run_lo + (int)i : -1;
-        const int t = first_tile + ordinal * grid;
-        return t < total ? t : -1;
-    };
     auto draw = [&] __device__() {
-        if (wave == 0 && sched && lane == 0) drawn = atomicAdd(sched + xcd, 1u);
+        if (wave == 0 && tiles.ctr && lane == 0) drawn = tiles.draw();
         ++draws;
         draw_pending = true;
     };
     auto publish_draw = [&] __device__() {   // before a workgroup barrier
         if (wave == 0) {
-            if (lane == 0) s_tiles[(draws - 1) & 7] = tile_of_draw(drawn, draws - 1);
+            if (lane == 0) s_tiles[(draws - 1) & 7] = tiles.tile(drawn, draws - 1);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
         draw_pending = false;
     };
-    auto leave = [&] __device__() {          // every wave is past its last draw and its last load
-        if (sched && tid == 0) {
-            if (atomicAdd(sched + 8, 1u) == (unsigned)grid - 1) {
-#pragma unroll
-                for (int i = 0; i < 9; ++i) __hip_atomic_store(sched + i, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-    };
     // the first two tiles are drawn together
-    if (wave == 0) {
-        unsigned i = 0;
-        if (sched && lane == 0) i = atomicAdd(sched + xcd, 2u);
-        if (lane == 0) {
-            s_tiles[0] = tile_of_draw(i, 0);
-            s_tiles[1] = tile_of_draw(i + 1, 1);
-        }
+    if (wave == 0 && lane == 0) {
+        int t0, t1;
+        tiles.first_two(t0, t1);
+        s_tiles[0] = t0;
+        s_tiles[1] = t1;
     }
     draws = 2;
     __syncthreads();
     int comp_tile = __builtin_amdgcn_readfirstlane(s_tiles[0]);   // tile being multiplied
-    if (comp_tile < 0) {   // (whole workgroup: nothing below is reached, no barrier is missed)
-        leave();
-        return;
-    }
+    if (comp_tile < 0) return;   // (whole workgroup: nothing below is reached, no barrier is missed)
 
     // ---- LDS-direct load addressing: wave-uniform base pointer + per-lane 32-bit offset.
     // codes: load slot i of this wave fills ROWS_PER_DMA consecutive LDS rows of the stage;
@@ -584,7 +558,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
         if (comp_tile < 0) break;
     }
     wait_vmcnt<0>();   // no LDS-direct load may still be in flight when the workgroup's LDS is released
-    leave();
 }
 
 namespace {
@@ -617,21 +590,36 @@ __global__ __launch_bounds__(256) void w4_prepack_kernel(const uint8_t *__restri
     dst[o] = q;
 }
 
-int g_variant = -1;  // -1: pick by shape; set by the benchmark's sweep hook
-int g_schedule = -1; // -1: tiles drawn from counters where possible; 0: fixed shares (benchmark hook)
+std::atomic<int> g_variant{-1};   // -1: pick by shape; set by the benchmark's sweep hook
+std::atomic<int> g_schedule{-1};  // -1: tiles drawn from counters where possible; 0: fixed shares (benchmark hook)
 
-// Tile counters of the persistent kernel: one slot of 16 words per stream (kernels of one stream run
-// one after the other, and every kernel leaves its slot zero, as the module load did).
+// Tile counters of the persistent kernels: one slot of 16 words (the first 8 one per XCD; 64 bytes) per stream;
+// kernels of one stream run one after the other.  What a slot holds between launches does not matter (see
+// TileSource): it is cleared on the stream right before every kernel that counts in it.
 constexpr int kSchedSlots = 512;
-__device__ unsigned g_sched[kSchedSlots][16];
+__device__ __align__(64) unsigned g_sched[kSchedSlots][16];
+
+struct SchedTable {
+    unsigned *base = nullptr;
+    std::unordered_map<uint64_t, int> slot_of;   // stream handle -> slot
+    std::vector<int> free_slots;                 // released slots, reused before fresh ones
+    int fresh = 0;                               // slots never handed out yet
+};
+std::mutex g_sched_mu;
+SchedTable g_sched_table[64];
+
+__global__ void fill_sched_kernel(unsigned *p, unsigned value, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = value;
+}
 
 }  // namespace
 
-// The counter slot for a launch on `stream`, or nullptr (fixed shares) when the launch is being
-// captured into a graph -- the same node may later run in several graph instances at once, which
-// must not share counters -- or when all slots are taken.
+// The counter slot for a launch on `stream`, or nullptr (fixed shares): when the launch is being captured
+// into a graph -- the same node may later run in several graph instances at once, which must not share
+// counters -- or when all slots are taken.
 unsigned *sched_slot(hipStream_t stream) {
-    if (g_schedule == 0) return nullptr;
+    if (g_schedule.load(std::memory_order_relaxed) == 0) return nullptr;
     hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(stream, &cap) != hipSuccess) {
         (void)hipGetLastError();
@@ -640,25 +628,55 @@ unsigned *sched_slot(hipStream_t stream) {
     if (cap != hipStreamCaptureStatusNone) return nullptr;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
-    static std::mutex mu;
-    static unsigned *base[64] = {};
-    static std::unordered_map<uint64_t, int> slots[64];
-    std::lock_guard<std::mutex> lock(mu);
-    if (!base[dev]) {
+    std::lock_guard<std::mutex> lock(g_sched_mu);
+    SchedTable &t = g_sched_table[dev];
+    if (!t.base) {
         void *p = nullptr;
         if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_sched)) != hipSuccess) {
             (void)hipGetLastError();
             return nullptr;
         }
-        base[dev] = static_cast<unsigned *>(p);
+        t.base = static_cast<unsigned *>(p);
     }
-    auto &m = slots[dev];
-    auto it = m.find(reinterpret_cast<uint64_t>(stream));
-    if (it == m.end()) {
-        if ((int)m.size() >= kSchedSlots) return nullptr;
-        it = m.emplace(reinterpret_cast<uint64_t>(stream), (int)m.size()).first;
+    auto it = t.slot_of.find(reinterpret_cast<uint64_t>(stream));
+    if (it == t.slot_of.end()) {
+        int slot;
+        if (!t.free_slots.empty()) {
+            slot = t.free_slots.back();
+            t.free_slots.pop_back();
+        } else if (t.fresh < kSchedSlots) {
+            slot = t.fresh++;
+        } else {
+            return nullptr;
+        }
+        it = t.slot_of.emplace(reinterpret_cast<uint64_t>(stream), slot).first;
     }
-    return base[dev] + it->second * 16;
+    return t.base + it->second * 16;
+}
+
+int clear_sched_slot(unsigned *slot, hipStream_t stream) {
+    hipLaunchKernelGGL(fill_sched_kernel, dim3(1), dim3(64), 0, stream, slot, 0u, 16);
+    return check_launch();
+}
+
+int fill_sched_slots(uint32_t value, hipStream_t stream) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_sched)) != hipSuccess) return DVDQ_ERR_HIP;
+    const int n = kSchedSlots * 16;
+    hipLaunchKernelGGL(fill_sched_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, static_cast<unsigned *>(p), value, n);
+    return check_launch();
+}
+
+// Forget `stream` on the current device (its slot goes to the next stream that needs one).
+void release_sched_slot(hipStream_t stream) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return;
+    std::lock_guard<std::mutex> lock(g_sched_mu);
+    SchedTable &t = g_sched_table[dev];
+    auto it = t.slot_of.find(reinterpret_cast<uint64_t>(stream));
+    if (it == t.slot_of.end()) return;
+    t.free_slots.push_back(it->second);
+    t.slot_of.erase(it);
 }
 
 namespace {
@@ -666,7 +684,7 @@ namespace {
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int OCC, bool A4 = false>
 int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                   const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int M, int N, int K,
-                  uint16_t *y, int32_t *acc_out, hipStream_t stream) {
+                  uint16_t *y, int32_t *acc_out, hipStream_t stream, bool counters_clear) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     // column tiles per L2 sharing group: balanced groups of at most 16
     const int n_groups = (tiles_n + 15) / 16;
@@ -681,27 +699,29 @@ int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, c
     auto k = w4ax_gemm_native_kernel<BM, BN, BK, WAVES_M, WAVES_N, STAGES, OCC, A4>;
     static std::atomic<uint64_t> configured{0};   // one per template instantiation
     allow_dynamic_lds(reinterpret_cast<const void *>(k), smem, configured);
+    unsigned *sched = sched_slot(stream);
+    if (sched && !counters_clear && clear_sched_slot(sched, stream) != DVDQ_OK) return DVDQ_ERR_HIP;
     hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), smem, stream, codes, x_scale, w,
-                       w_scale, w_zero, code_rowsum, bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n,
-                       sched_slot(stream));
+                       w_scale, w_zero, code_rowsum, bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n, sched);
     return check_launch();
 }
 
 }  // namespace
 
-void set_gemm_variant(int v) { g_variant = v; }
-int gemm_variant() { return g_variant; }
-void set_gemm_schedule(int v) { g_schedule = v; }
+void set_gemm_variant(int v) { g_variant.store(v, std::memory_order_relaxed); }
+int gemm_variant() { return g_variant.load(std::memory_order_relaxed); }
+void set_gemm_schedule(int v) { g_schedule.store(v, std::memory_order_relaxed); }
 
 int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                      const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,
-                     int64_t K, int codes_format, int w_layout, uint16_t *y, int32_t *acc_out, hipStream_t stream) {
+                     int64_t K, int codes_format, int w_layout, uint16_t *y, int32_t *acc_out, hipStream_t stream,
+                     bool counters_clear) {
     if (w_layout == DVDQ_W_CANONICAL) {
         if (codes_format != DVDQ_CODES_INT8 || w_zero) return DVDQ_ERR_UNSUPPORTED;
         return launch_w4ax_gemm_canonical(codes, x_scale, w, w_scale, bias, M, N, K, y, acc_out, stream);
     }
     const int m = (int)M, n = (int)N, k = (int)K;
-#define DVDQ_GEMM_ARGS codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, m, n, k, y, acc_out, stream
+#define DVDQ_GEMM_ARGS codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, m, n, k, y, acc_out, stream, counters_clear
     // Tile variants: {tile M, tile N, K slice, waves M x N, ring depth, workgroups per compute unit}.
     // Variant 2 is the default for every shape: two independent 4-wave workgroups per compute unit,
     // each owning a 128 x 256 tile (64 x 128 per wave) with K slices of 128 through two buffers.  In
@@ -709,7 +729,8 @@ int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w
     // fastest: while one workgroup converts and stores its tile the other keeps the matrix cores busy,
     // which the one-workgroup 256 x 256 variants cannot do.  The others remain for sweeps; a shape with
     // fewer K slices than a variant's ring needs falls back to variant 2, which always qualifies.
-    int v = g_variant < 0 ? 2 : g_variant;
+    const int forced = gemm_variant();
+    int v = forced < 0 ? 2 : forced;
     if (codes_format == DVDQ_CODES_PACKED4) {
         if ((v == 1 && k / 128 < 2) || (v > 2 && k / 128 < 3)) v = 2;
         switch (v) {
@@ -723,10 +744,10 @@ int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w
     // Variant 5 is the wide kernel of w4ax_gemm_wide.hip (int8 codes only): it pays when a tile has many K
     // slices (4 % faster at K = 13824, slower below K = 4096), and is taken by itself from K = 8192 on when
     // there are at least two rounds of 256 x 256 tiles.
-    if (g_variant < 0 && codes_format == DVDQ_CODES_INT8 && k / 128 >= 64 && ((M + 255) / 256) * ((N + 255) / 256) >= 512) v = 5;
+    if (forced < 0 && codes_format == DVDQ_CODES_INT8 && k / 128 >= 64 && ((M + 255) / 256) * ((N + 255) / 256) >= 512) v = 5;
     if (v == 5)
         return launch_w4ax_gemm_wide(reinterpret_cast<const uint8_t *>(codes), x_scale, w, w_scale, w_zero, code_rowsum, bias,
-                                     M, N, K, false, y, acc_out, stream);
+                                     M, N, K, false, y, acc_out, stream, counters_clear);
     {
         const int bk = v == 4 ? 64 : 128, stages = v == 2 ? 2 : (v == 4 ? 4 : 3);
         if (k / bk < stages - 1) v = 2;

@@ -85,15 +85,10 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
 
     // ---- tiles: persistent workgroups, per-XCD runs of tile numbers drawn through counters (sched) or dealt
     // in fixed shares (sched == nullptr); numbers travel through an 8-entry ring in LDS.  See w4ax_gemm.hip.
-    const int total = tiles_m * tiles_n;
-    const int grid = gridDim.x;  // multiple of 8
-    const int xcd = blockIdx.x % 8;
-    const int first_tile = xcd * (grid / 8) + blockIdx.x / 8;
-    const int run_lo = (int)((int64_t)xcd * total / 8);
-    const unsigned run_len = (unsigned)((int64_t)(xcd + 1) * total / 8) - (unsigned)run_lo;
+    const TileSource tiles(tiles_m, tiles_n, sched);
     typedef volatile __attribute__((address_space(3))) int lds_int;
     lds_int *s_tiles = (lds_int *)DVDQ_LDS(smem + STAGES * STAGE + 3 * SCALES);
-    // Fixed shares (sched == nullptr): the ordinal-th tile of this workgroup is first_tile + ordinal * grid, which
+    // Fixed shares (no counters): the ordinal-th tile of this workgroup follows from its number alone, which
     // every wave computes for itself.  Drawn tiles (K / 128 >= 2): the number drawn while slice `draw_kt` of tile n
     // is issued belongs to tile n + 2; wave 0 writes it into the ring before the barrier after next (by then the
     // loads issued around the atomic have been awaited, so its reply is there), two barriers before it is
@@ -101,53 +96,37 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
     int published = 2;       // tile numbers written into the ring
     unsigned drawn = 0;      // wave 0, lane 0: reply of the pending draw
     int draw_wait = 0;       // barriers until the pending draw is written into the ring (0: none pending)
-    auto tile_of_ordinal = [&] __device__(int ordinal) {   // fixed shares
-        const int t = first_tile + ordinal * grid;
-        return t < total ? t : -1;
-    };
-    auto tile_of_draw = [&] __device__(unsigned i) { return i < run_len ? run_lo + (int)i : -1; };
     auto draw = [&] __device__() {
-        if (!sched) return;
-        if (wave == 0 && lane == 0) drawn = atomicAdd(sched + xcd, 1u);
+        if (!tiles.ctr) return;
+        if (wave == 0 && lane == 0) drawn = tiles.draw();
         draw_wait = 2;
     };
     auto before_barrier = [&] __device__() {   // every wave, before each workgroup barrier of the pipeline
         draw_wait = __builtin_amdgcn_readfirstlane(draw_wait);   // (wave-uniform: keep it in a scalar register)
         if (draw_wait > 0 && --draw_wait == 0) {
             if (wave == 0) {
-                if (lane == 0) s_tiles[published & 7] = tile_of_draw(drawn);
+                if (lane == 0) s_tiles[published & 7] = tiles.tile(drawn, 0);
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             }
             ++published;
         }
     };
-    auto leave = [&] __device__() {
-        if (sched && tid == 0) {
-            if (atomicAdd(sched + 8, 1u) == (unsigned)grid - 1) {
-#pragma unroll
-                for (int i = 0; i < 9; ++i) __hip_atomic_store(sched + i, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-    };
-    if (sched && wave == 0) {
-        unsigned i = 0;
+    if (tiles.ctr && wave == 0) {
         if (lane == 0) {
-            i = atomicAdd(sched + xcd, 2u);
-            s_tiles[0] = tile_of_draw(i);
-            s_tiles[1] = tile_of_draw(i + 1);
+            int t0, t1;
+            tiles.first_two(t0, t1);
+            s_tiles[0] = t0;
+            s_tiles[1] = t1;
         } else if (lane >= 2 && lane < 8) {
             s_tiles[lane] = -1;   // a ring entry read before it was written would end the workgroup's work, not misdirect it
         }
     }
     __syncthreads();
     auto tile_number = [&] __device__(int ordinal) {   // the ordinal-th tile of this workgroup (-1: none left)
-        return sched ? __builtin_amdgcn_readfirstlane(s_tiles[ordinal & 7]) : tile_of_ordinal(ordinal);
+        return tiles.ctr ? __builtin_amdgcn_readfirstlane(s_tiles[ordinal & 7]) : tiles.tile(0u, ordinal);
     };
     int comp_tile = tile_number(0);
-    if (comp_tile < 0) {   // (whole workgroup: nothing below is reached, no barrier is missed)
-        leave();
-        return;
-    }
+    if (comp_tile < 0) return;   // (whole workgroup: nothing below is reached, no barrier is missed)
 
     // ---- LDS-direct loads of one slice: 12 pieces of 1 KB per wave.
     // INT8 path, codes: piece i of wave v fills 8 consecutive LDS rows (128 B each) of the stage; LDS position p
@@ -641,7 +620,6 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
         __builtin_amdgcn_s_barrier();
     }
     wait_vmcnt<0>();   // no LDS-direct load may still be in flight when the workgroup's LDS is released
-    leave();
 }
 
 namespace {
@@ -649,7 +627,7 @@ namespace {
 template <bool FP6>
 int launch_wide(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale, const int8_t *w_zero,
                 const int32_t *code_rowsum, const uint16_t *bias, int M, int N, int K, uint16_t *y, int32_t *acc_out,
-                hipStream_t stream) {
+                hipStream_t stream, bool counters_clear) {
     constexpr int BM = 256, BN = 256, STAGES = 3;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int n_groups = (tiles_n + 15) / 16;   // column tiles per L2 sharing group: balanced groups of at most 16
@@ -661,9 +639,10 @@ int launch_wide(const uint8_t *codes, const float *x_scale, const uint8_t *w, co
     auto k = w4ax_gemm_wide_kernel<FP6>;
     static std::atomic<uint64_t> configured{0};
     allow_dynamic_lds(reinterpret_cast<const void *>(k), smem, configured);
+    unsigned *sched = K / kBK >= 2 ? sched_slot(stream) : nullptr;   // a tile draw takes two slices to come back
+    if (sched && !counters_clear && clear_sched_slot(sched, stream) != DVDQ_OK) return DVDQ_ERR_HIP;
     hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(256), smem, stream, codes, x_scale, w, w_scale, w_zero, code_rowsum,
-                       bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n,
-                       K / kBK >= 2 ? sched_slot(stream) : nullptr);   // a tile draw takes two slices to come back
+                       bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n, sched);
     return check_launch();
 }
 
@@ -671,12 +650,12 @@ int launch_wide(const uint8_t *codes, const float *x_scale, const uint8_t *w, co
 
 int launch_w4ax_gemm_wide(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                           const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,
-                          int64_t K, bool fp6, uint16_t *y, int32_t *acc_out, hipStream_t stream) {
+                          int64_t K, bool fp6, uint16_t *y, int32_t *acc_out, hipStream_t stream, bool counters_clear) {
     if (fp6)
         return launch_wide<true>(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K, y, acc_out,
-                                 stream);
+                                 stream, counters_clear);
     return launch_wide<false>(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K, y, acc_out,
-                              stream);
+                              stream, counters_clear);
 }
 
 }  // namespace dvdq

@@ -2,8 +2,9 @@
 per-stream counters in device memory (default) or take fixed equal shares (while a stream is being
 captured, or forced through the benchmark hook).  Which workgroup computes a tile must not show in
 the result: outputs are compared bit for bit between the two modes, over shapes with fewer tiles than
-workgroups, edge tiles, every tile variant, many launches in a row (the counters must be back at zero
-after every kernel) and launches on several streams at once (one counter slot per stream)."""
+workgroups, edge tiles, every tile variant, many launches in a row (no launch may depend on what the
+one before left in the counters), counters overwritten with garbage between launches, and launches on
+several streams at once (one counter slot per stream)."""
 import pytest
 import torch
 
@@ -81,9 +82,9 @@ def test_every_tile_variant_agrees_between_the_two_modes(variant, packed):
     assert torch.equal(y_fixed.view(torch.int16), y_drawn.view(torch.int16))
 
 
-def test_counters_are_back_at_zero_after_every_kernel():
-    """200 launches in a row on one stream, alternating between two shapes: a counter left dirty by one
-    kernel would make the next one skip or repeat tiles."""
+def test_many_launches_in_a_row_on_one_stream():
+    """200 launches in a row on one stream, alternating between two shapes: a launch that counted on from
+    where the one before stopped would skip or repeat tiles."""
     a = _operands(4096, 512, 2048, 4, True, seed=1)
     b = _operands(700, 256, 520, 6, False, seed=2)
     dvdq.bench_set_gemm_schedule(0)
@@ -166,3 +167,67 @@ def test_fp6_kernel_counters_and_streams(variant):
     torch.cuda.synchronize()
     for i, y in enumerate(outs):
         assert torch.equal(y.view(torch.int16), ya_ref.view(torch.int16)), f"stream {i}"
+
+
+@pytest.mark.parametrize("value", [0xFFFFF, 0xFFFFFFFF, 0x7FF00003, 0xFFF80000, 1])
+def test_gemms_do_not_depend_on_what_the_tile_counters_hold(value):
+    """Every counter word overwritten (as a launch that never finished, or a stray write, would leave it) before
+    each of several launches: the two-wave INT8 kernel, the wide INT8 kernel, both FP6 kernels, and the fused
+    layer, whose quantizer kernel is what clears the counters."""
+    s = torch.cuda.Stream()
+    i8 = _operands(4096, 512, 2048, 4, True, seed=21)
+    wide = _operands(2100, 384, 1300, 4, False, seed=22)
+    f6 = _fp6_operands(4100, 512, 2056, seed=23)
+    dvdq.bench_set_gemm_schedule(0)
+    ref_i8 = _gemm(i8, 4, True)
+    dvdq.bench_set_gemm_variant(5)
+    ref_wide = _gemm(wide, 4, False)
+    dvdq.bench_set_gemm_variant(3)
+    ref_f6w = _fp6_gemm(f6)
+    dvdq.bench_set_gemm_variant(-1)
+    ref_f6 = _fp6_gemm(f6)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(24)
+    x = torch.randn((3000, 512), device=DEV, generator=g).to(torch.bfloat16)
+    ref_layer, _ = dvdq.qlinear(x, f6[2], f6[3], 256, 4, dvdq.W_NATIVE_FP6, codes_format=dvdq.CODES_FP6)
+    dvdq.bench_set_gemm_schedule(-1)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        for rep in range(3):
+            dvdq.bench_fill_tile_counters(value, stream=s)
+            y_layer, _ = dvdq.qlinear(x, f6[2], f6[3], 256, 4, dvdq.W_NATIVE_FP6, codes_format=dvdq.CODES_FP6, stream=s)
+            dvdq.bench_fill_tile_counters(value, stream=s)
+            y = _gemm(i8, 4, True, stream=s)
+            dvdq.bench_fill_tile_counters(value + rep, stream=s)
+            dvdq.bench_set_gemm_variant(5)
+            yw = _gemm(wide, 4, False, stream=s)
+            dvdq.bench_fill_tile_counters(value, stream=s)
+            dvdq.bench_set_gemm_variant(3)
+            y6w = _fp6_gemm(f6, stream=s)
+            dvdq.bench_set_gemm_variant(-1)
+            dvdq.bench_fill_tile_counters(value ^ 5, stream=s)
+            y6 = _fp6_gemm(f6, stream=s)
+            s.synchronize()
+            assert torch.equal(y.view(torch.int16), ref_i8.view(torch.int16)), f"int8, round {rep}"
+            assert torch.equal(yw.view(torch.int16), ref_wide.view(torch.int16)), f"wide int8, round {rep}"
+            assert torch.equal(y6w.view(torch.int16), ref_f6w.view(torch.int16)), f"wide fp6, round {rep}"
+            assert torch.equal(y6.view(torch.int16), ref_f6.view(torch.int16)), f"fp6, round {rep}"
+            assert torch.equal(y_layer.view(torch.int16), ref_layer.view(torch.int16)), f"fused layer, round {rep}"
+    dvdq.release_stream(s)
+
+
+def test_a_released_stream_can_be_used_again():
+    ops = _operands(3000, 256, 1024, 4, True, seed=31)
+    dvdq.bench_set_gemm_schedule(0)
+    ref = _gemm(ops, 4, True)
+    dvdq.bench_set_gemm_schedule(-1)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    for rep in range(3):
+        for s in streams:
+            with torch.cuda.stream(s):
+                y = _gemm(ops, 4, True, stream=s)
+            s.synchronize()
+            assert torch.equal(y.view(torch.int16), ref.view(torch.int16))
+            dvdq.release_stream(s)
+            dvdq.release_stream(s)   # unknown by now: no-op
