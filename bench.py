@@ -66,6 +66,9 @@ def parse():
                     help="matrix path of 4-bit activations: FP6 (E2M3 patterns, default) or INT8 (packed nibbles)")
     ap.add_argument("--bufs", type=int, default=3, help="input/output buffer sets rotated through (cache defeat)")
     ap.add_argument("--cpu-seconds", type=float, default=8.0, help="CPU time aimed at per workload for the oracle leg")
+    ap.add_argument("--overlap-experiment", action="store_true",
+                    help="instead of the benchmark: time the layer with the quantizer of row panel p + 1 on a second stream "
+                         "beside the GEMM of panel p (W4A4 workloads 1 and 3), against the plain back-to-back call")
     return ap.parse_args()
 
 
@@ -380,6 +383,75 @@ class Bench:
         return out
 
 
+def overlap_experiment(torch, dvdq, di):
+    """Rotate/GEMM overlap by row panels: panel p + 1 is quantized on one stream while the GEMM of panel p runs on
+    another (same priority), the GEMM's persistent grid optionally shortened to leave compute units free.  Every
+    variant is checked bit for bit against the plain call; times are medians of event pairs around whole calls,
+    host launch work included on both sides."""
+    import itertools
+    dev = "cuda:0"
+
+    def med(fn, n=15, warm=4):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(n):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        return sorted(ts)[n // 2]
+
+    out = {}
+    main_stream = torch.cuda.current_stream()
+    sq, sg = torch.cuda.Stream(), torch.cuda.Stream()
+    for idx in (1, 3):
+        wl = di.WORKLOADS[idx]
+        M, K, N, B = wl.M, wl.K, wl.N, wl.had_block
+        g = torch.Generator(device=dev)
+        g.manual_seed(idx)
+        x = (torch.randn((M, K), device=dev, generator=g) *
+             torch.exp(0.5 * torch.randn((M, 1), device=dev, generator=g))).to(torch.bfloat16)
+        w = dvdq.w4_prepack_fp6(torch.randint(0, 256, (N, K // 2), device=dev, dtype=torch.uint8, generator=g))
+        ws = torch.rand((N,), device=dev, generator=g) * 0.01 + 1e-3
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        wsb = torch.empty(dvdq.qlinear_workspace_bytes(M, K, dvdq.CODES_FP6), dtype=torch.uint8, device=dev)
+        t0 = med(lambda: dvdq.qlinear(x, w, ws, B, 4, dvdq.W_NATIVE_FP6, y=y, workspace=wsb, codes_format=dvdq.CODES_FP6))
+        y_ref = y.clone()
+        entry = {"back_to_back_us": round(t0 * 1e3, 1), "panelled": []}
+        for panels, limit in itertools.product((2, 4, 8), (0, 496, 448, 384)):
+            rows = -(-(-(-M // panels)) // 256) * 256
+            bounds = [(r, min(M, r + rows)) for r in range(0, M, rows)]
+            cs = [torch.empty(dvdq.codes_bytes(b - a, K, dvdq.CODES_FP6), dtype=torch.uint8, device=dev) for a, b in bounds]
+            ss = [torch.empty((b - a,), dtype=torch.float32, device=dev) for a, b in bounds]
+
+            def panelled():
+                sq.wait_stream(main_stream)
+                sg.wait_stream(main_stream)
+                for (a, b), c, sc in zip(bounds, cs, ss):
+                    dvdq.rotate_quant(x[a:b], B, 4, codes=c, x_scale=sc, codes_format=dvdq.CODES_FP6, stream=sq)
+                    ev = torch.cuda.Event()
+                    ev.record(sq)
+                    sg.wait_event(ev)
+                    dvdq.w4ax_gemm(c, sc, w, ws, 4, dvdq.W_NATIVE_FP6, y=y[a:b], codes_format=dvdq.CODES_FP6, K=K, stream=sg)
+                main_stream.wait_stream(sg)
+                main_stream.wait_stream(sq)
+            dvdq.bench_set_gemm_grid_limit(limit)
+            y.zero_()
+            t = med(panelled)
+            same = bool(torch.equal(y.view(torch.int16), y_ref.view(torch.int16)))
+            dvdq.bench_set_gemm_grid_limit(0)
+            entry["panelled"].append({"panels": len(bounds), "gemm_workgroups_at_most": limit or "all", "us": round(t * 1e3, 1),
+                                      "vs_back_to_back": round(t / t0, 3), "identical": same})
+        out[wl.name] = entry
+        del x, w, y, wsb
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -394,6 +466,10 @@ def main():
     dvdq.lib()   # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
 
+    if args.overlap_experiment:
+        import dvdq_inputs as di
+        print(json.dumps({"experiment": "rotate/GEMM overlap by row panels on two streams", "results": overlap_experiment(torch, dvdq, di)}))
+        return
     b = Bench(args)
     which = [args.workload] if args.workload is not None else [1, 2, 3, 4]
     head_idx = HEADLINE if HEADLINE in which else which[-1]

@@ -50,6 +50,11 @@ int dvdq_bench_set_gemm_variant(int variant);
  * launch reads once), meant for benchmarking only. */
 int dvdq_bench_set_gemm_schedule(int schedule);
 
+/* Experiments that share the chip between kernels: let the persistent GEMMs launch at most `workgroups`
+ * workgroups (rounded down to a multiple of 8, at least 8) instead of filling every compute unit; 0 lifts the
+ * limit.  Results are identical.  Process-wide (an atomic that every launch reads once), benchmarking only. */
+int dvdq_bench_set_gemm_grid_limit(int workgroups);
+
 /* Robustness tests: overwrite every word of the current GPU's tile counters with `value`, in stream
  * order on `hip_stream` (as a stray write or a launch that never finished would leave them).  GEMMs
  * launched afterwards must still give the right result. */

@@ -16,7 +16,7 @@ import torch
 __all__ = [
     "DvdqError", "DvdqLibraryMissing", "lib", "library_path", "version", "status_string",
     "rotate_quant", "rotate_quant_blockwise", "w4ax_gemm", "qlinear", "qlinear_static", "static_workspace_bytes", "qlinear_workspace_bytes", "qlinear_scale_offset", "qlinear_rowsum_offset", "workspace_rowsum",
-    "w4_prepack", "w4_native_bytes", "w4_prepack_fp6", "w4_native_fp6_bytes", "codes_bytes", "bgr_quantize", "GbsController", "bench_copy", "bench_mfma_i8", "bench_mfma_fp6", "bench_set_gemm_variant", "bench_set_gemm_schedule", "bench_fill_tile_counters", "release_stream",
+    "w4_prepack", "w4_native_bytes", "w4_prepack_fp6", "w4_native_fp6_bytes", "codes_bytes", "bgr_quantize", "GbsController", "bench_copy", "bench_mfma_i8", "bench_mfma_fp6", "bench_set_gemm_variant", "bench_set_gemm_schedule", "bench_fill_tile_counters", "bench_set_gemm_grid_limit", "release_stream",
     "W_CANONICAL", "W_NATIVE", "W_NATIVE_FP6", "CODES_INT8", "CODES_PACKED4", "CODES_FP6", "BGR_LISTING", "BGR_BEST_OF_ALL", "EXPORTED_SYMBOLS",
 ]
 
@@ -28,7 +28,7 @@ EXPORTED_SYMBOLS = (
     "dvdq_rotate_quant", "dvdq_rotate_quant_blockwise", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_qlinear_workspace_bytes",
     "dvdq_qlinear_scale_offset", "dvdq_qlinear_rowsum_offset", "dvdq_qlinear_static", "dvdq_static_workspace_bytes", "dvdq_w4_prepack", "dvdq_w4_native_bytes", "dvdq_w4_prepack_fp6",
     "dvdq_w4_native_fp6_bytes", "dvdq_codes_bytes", "dvdq_status_string",
-    "dvdq_version", "dvdq_gbs_workspace_bytes", "dvdq_gbs_reset", "dvdq_gbs_step", "dvdq_bgr_quantize", "dvdq_bench_copy", "dvdq_bench_mfma_i8", "dvdq_bench_mfma_fp6", "dvdq_bench_set_gemm_variant", "dvdq_bench_set_gemm_schedule", "dvdq_bench_fill_tile_counters", "dvdq_release_stream",
+    "dvdq_version", "dvdq_gbs_workspace_bytes", "dvdq_gbs_reset", "dvdq_gbs_step", "dvdq_bgr_quantize", "dvdq_bench_copy", "dvdq_bench_mfma_i8", "dvdq_bench_mfma_fp6", "dvdq_bench_set_gemm_variant", "dvdq_bench_set_gemm_schedule", "dvdq_bench_fill_tile_counters", "dvdq_bench_set_gemm_grid_limit", "dvdq_release_stream",
 )
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -101,6 +101,8 @@ def lib() -> C.CDLL:
     L.dvdq_bench_set_gemm_schedule.restype = i32
     L.dvdq_bench_fill_tile_counters.argtypes = [C.c_uint32, C.c_void_p]
     L.dvdq_bench_fill_tile_counters.restype = i32
+    L.dvdq_bench_set_gemm_grid_limit.argtypes = [i32]
+    L.dvdq_bench_set_gemm_grid_limit.restype = i32
     L.dvdq_release_stream.argtypes = [C.c_void_p]
     L.dvdq_release_stream.restype = i32
     for f in ("dvdq_rotate_quant", "dvdq_rotate_quant_blockwise", "dvdq_w4ax_gemm", "dvdq_qlinear", "dvdq_w4_prepack", "dvdq_version",
@@ -463,6 +465,11 @@ def bench_set_gemm_variant(variant: int) -> None:
 def bench_set_gemm_schedule(schedule: int) -> None:
     """0: fixed tile shares; -1: the library's own choice (tiles drawn from counters)."""
     _check(lib().dvdq_bench_set_gemm_schedule(int(schedule)), "dvdq_bench_set_gemm_schedule")
+
+
+def bench_set_gemm_grid_limit(workgroups: int) -> None:
+    """At most `workgroups` workgroups per persistent GEMM launch (0: fill the chip).  Same results."""
+    _check(lib().dvdq_bench_set_gemm_grid_limit(int(workgroups)), "dvdq_bench_set_gemm_grid_limit")
 
 
 def bench_fill_tile_counters(value: int, stream=None) -> None:

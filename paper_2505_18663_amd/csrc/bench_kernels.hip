@@ -179,6 +179,12 @@ int dvdq_bench_set_gemm_schedule(int schedule) {
     return DVDQ_OK;
 }
 
+int dvdq_bench_set_gemm_grid_limit(int workgroups) {
+    if (workgroups < 0) return DVDQ_ERR_UNSUPPORTED;
+    dvdq::set_gemm_grid_limit(workgroups);
+    return DVDQ_OK;
+}
+
 int dvdq_bench_fill_tile_counters(uint32_t value, void *hip_stream) {
     return dvdq::fill_sched_slots(value, static_cast<hipStream_t>(hip_stream));
 }

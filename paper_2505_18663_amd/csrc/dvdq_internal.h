@@ -43,6 +43,8 @@ int launch_w4_prepack_fp6(const uint8_t *w_canonical, int64_t N, int64_t K, uint
 size_t w4_native_bytes(int64_t N, int64_t K);
 void set_gemm_variant(int v);  // benchmark sweeps only; -1 = choose by shape
 void set_gemm_schedule(int v); // benchmark only; 0 = fixed tile shares, -1 = drawn from counters where possible
+void set_gemm_grid_limit(int v); // benchmark only; 0 = persistent grids fill the chip, else at most v workgroups
+int limited_grid(int grid);
 unsigned *sched_slot(hipStream_t stream);                   // the stream's tile-counter slot (16 words), or nullptr: fixed tile shares
 void release_sched_slot(hipStream_t stream);               // forget a stream's tile-counter slot (host bookkeeping only)
 int fill_sched_slots(uint32_t value, hipStream_t stream);  // robustness tests only: overwrite every tile counter

@@ -529,6 +529,7 @@ int launch_fp6(const uint8_t *codes, const float *x_scale, const uint8_t *w, con
     const int total = tiles_m * tiles_n;
     int grid = 256 * OCC;
     if (total < grid) grid = (total + 7) / 8 * 8;
+    grid = limited_grid(grid);
     const size_t smem = (size_t)STAGES * (BM / 32 + BN / 32) * kFp6Block + 2 * ((BM + BN) * 4 + BN * 2 + BM * 4 + BN) +
                         8 * sizeof(int);
     auto k = w4a4_fp6_gemm_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, OCC>;

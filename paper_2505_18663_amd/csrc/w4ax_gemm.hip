@@ -592,6 +592,7 @@ __global__ __launch_bounds__(256) void w4_prepack_kernel(const uint8_t *__restri
 
 std::atomic<int> g_variant{-1};   // -1: pick by shape; set by the benchmark's sweep hook
 std::atomic<int> g_schedule{-1};  // -1: tiles drawn from counters where possible; 0: fixed shares (benchmark hook)
+std::atomic<int> g_grid_limit{0}; // 0: persistent grids fill the chip; else at most this many workgroups (benchmark hook)
 
 // Tile counters of the persistent kernels: one slot of 16 words (the first 8 one per XCD; 64 bytes) per stream;
 // kernels of one stream run one after the other.  What a slot holds between launches does not matter (see
@@ -693,6 +694,7 @@ int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, c
     // persistent: OCC workgroups per compute unit (256 CUs), grid a multiple of the 8 XCDs
     int grid = 256 * OCC;
     if (total < grid) grid = (total + 7) / 8 * 8;
+    grid = limited_grid(grid);
     // the ring, then two tiles' epilogue vectors (scales, bias, code sums, zero-points; see the kernel)
     const size_t smem = (size_t)STAGES * (BM * (A4 ? BK / 2 : BK) + BN * BK / 2) +
                         2 * ((BM + BN) * 4 + BN * 2 + BM * 4 + BN) + 8 * sizeof(int);   // + the ring of tile numbers
@@ -711,6 +713,12 @@ int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, c
 void set_gemm_variant(int v) { g_variant.store(v, std::memory_order_relaxed); }
 int gemm_variant() { return g_variant.load(std::memory_order_relaxed); }
 void set_gemm_schedule(int v) { g_schedule.store(v, std::memory_order_relaxed); }
+void set_gemm_grid_limit(int v) { g_grid_limit.store(v, std::memory_order_relaxed); }
+int limited_grid(int grid) {
+    const int limit = g_grid_limit.load(std::memory_order_relaxed);
+    if (limit <= 0 || grid <= limit) return grid;
+    return limit < 8 ? 8 : limit / 8 * 8;
+}
 
 int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                      const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,

@@ -635,6 +635,7 @@ int launch_wide(const uint8_t *codes, const float *x_scale, const uint8_t *w, co
     const int total = tiles_m * tiles_n;
     int grid = 256;
     if (total < grid) grid = (total + 7) / 8 * 8;
+    grid = limited_grid(grid);
     const size_t smem = (size_t)STAGES * 48 * 1024 + 3 * ((BM + BN) * 4 + BN * 2 + BM * 4 + BN) + 8 * sizeof(int);
     auto k = w4ax_gemm_wide_kernel<FP6>;
     static std::atomic<uint64_t> configured{0};
