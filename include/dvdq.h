@@ -169,7 +169,7 @@ int dvdq_rotate_quant_blockwise(const void *x_bf16, int64_t M, int64_t K, int ha
  *   acc_out   out  int32 [M, N] or NULL; when given, receives the raw accumulators
  *                  (parity hook; costs extra bandwidth)
  *
- * K must be a multiple of 64 (DVDQ_ERR_SHAPE), and of 128 with the native layout
+ * K must be a multiple of 32 (DVDQ_ERR_SHAPE), and of 128 with the native layouts
  * (DVDQ_ERR_UNSUPPORTED otherwise).  Any M >= 1, N >= 1; ragged tiles are handled inside.
  */
 int dvdq_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,

@@ -69,7 +69,7 @@ int check_gemm(const void *codes, const void *x_scale, const void *w, const void
                const void *code_rowsum, const void *bias, int64_t M, int64_t N, int64_t K, int act_bits,
                int codes_format, int w_layout, const void *y, const void *acc_out) {
     if (!codes || !x_scale || !w || !w_scale || !y || (w_zero && !code_rowsum)) return DVDQ_ERR_NULL;
-    if (M < 1 || N < 1 || K < 1 || (K % 64) != 0) return DVDQ_ERR_SHAPE;
+    if (M < 1 || N < 1 || K < 1 || (K % 32) != 0) return DVDQ_ERR_SHAPE;
     if (!bits_ok(act_bits) ||
         (w_layout != DVDQ_W_CANONICAL && w_layout != DVDQ_W_NATIVE && w_layout != DVDQ_W_NATIVE_FP6))
         return DVDQ_ERR_UNSUPPORTED;

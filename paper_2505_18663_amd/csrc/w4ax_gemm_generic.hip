@@ -75,19 +75,23 @@ __global__ __launch_bounds__(256) void w4ax_gemm_canonical_kernel(
 
     // global -> register staging
     uint4 ra[A_LOADS], rw[W_LOADS];
-    const int KT = K / kBK;
+    // K is a multiple of 32: the last slice may be half a slice, whose missing channels are zero codes and
+    // zero weights (they add nothing to the exact integer sums)
+    const int KT = (K + kBK - 1) / kBK;
     auto load_slice = [&](int kt) {
 #pragma unroll
         for (int i = 0; i < A_LOADS; ++i) {
             const int idx = tid + i * 256, row = idx >> 2, chunk = idx & 3;
             const int gm = min(m0 + row, M - 1);
-            ra[i] = *reinterpret_cast<const uint4 *>(codes + (int64_t)gm * K + kt * kBK + chunk * 16);
+            const int k = kt * kBK + chunk * 16;
+            ra[i] = k < K ? *reinterpret_cast<const uint4 *>(codes + (int64_t)gm * K + k) : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
         for (int i = 0; i < W_LOADS; ++i) {
             const int idx = tid + i * 256, row = idx >> 1, half = idx & 1;
             const int gn = min(n0 + row, N - 1);
-            rw[i] = *reinterpret_cast<const uint4 *>(w + (int64_t)gn * (K / 2) + kt * (kBK / 2) + half * 16);
+            const int k = kt * kBK + half * 32;
+            rw[i] = k < K ? *reinterpret_cast<const uint4 *>(w + (int64_t)gn * (K / 2) + k / 2) : make_uint4(0, 0, 0, 0);
         }
     };
     auto store_slice = [&](int buf) {

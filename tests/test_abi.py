@@ -69,7 +69,7 @@ def test_gemm_argument_errors():
     assert f(None, FAKE, FAKE, FAKE, None, None, None, 4, 8, 64, 4, 0, 0, FAKE, None, None) == 1
     assert f(FAKE, FAKE, FAKE, FAKE, None, None, None, 4, 8, 64, 4, 0, 0, None, None, None) == 1
     assert f(FAKE, FAKE, FAKE, FAKE, None, None, None, 4, 0, 64, 4, 0, 0, FAKE, None, None) == 2
-    assert f(FAKE, FAKE, FAKE, FAKE, None, None, None, 4, 8, 96, 4, 0, 0, FAKE, None, None) == 2     # K % 64
+    assert f(FAKE, FAKE, FAKE, FAKE, None, None, None, 4, 8, 80, 4, 0, 0, FAKE, None, None) == 2     # K % 32
     assert f(FAKE, FAKE, FAKE, FAKE, None, None, None, 4, 8, 64, 3, 0, 0, FAKE, None, None) == 3
     assert f(FAKE, FAKE, FAKE, FAKE, None, None, None, 4, 8, 64, 4, 0, 7, FAKE, None, None) == 3     # layout
     assert f(FAKE, FAKE, FAKE, FAKE, None, None, None, 4, 8, 64 * 4096, 8, 0, 0, FAKE, None, None) == 3   # accumulator bound

@@ -126,6 +126,9 @@ def rand_gemm_inputs(rng, M, N, K, bits):
     (513, 260, 1536, 4, "native", True),
     (256, 768, 13824, 4, "native", False),     # deepest K of the workloads
     (70, 300, 704, 8, "canonical", True),
+    (90, 130, 32, 4, "canonical", False),      # K multiples of 32 that are not multiples of 64: half a last slice
+    (200, 260, 96, 6, "canonical", True),
+    (33, 513, 1120, 8, "canonical", False),
 ])
 def test_gemm_int32_exact_and_bf16_epilogue(M, N, K, bits, layout, use_bias):
     rng = np.random.default_rng(M + 7 * N + 13 * K + bits)
@@ -217,3 +220,21 @@ def test_qlinear_tiny_config_compositional(idx):
         assert torch.equal(y2, y)
         if np.array_equal(codes_g, ref["codes"]) and np.array_equal(scale_g, ref["x_scale"]):
             check_y(bits_of(y), ref["y"], wl.name + " direct")
+
+
+@pytest.mark.parametrize("M,K,N,B,bits", [(77, 96, 130, 32, 4), (300, 1120, 200, 32, 6), (64, 160, 64, 1, 8)])
+def test_qlinear_with_k_a_multiple_of_32_only(M, K, N, B, bits):
+    """the whole layer where K is no multiple of 64 (weights in the canonical layout): as above"""
+    rng = np.random.default_rng(M + K + N)
+    xb = rand_x(rng, M, K)
+    _, wc, _, ws = rand_gemm_inputs(rng, M, N, K, bits)
+    wp = di.pack_w4(wc)
+    x_dev, w_dev, ws_dev = to_bf16(xb), dev(wp), dev(ws)
+    y, wsp = dvdq.qlinear(x_dev, w_dev, ws_dev, B, bits, dvdq.W_CANONICAL)
+    torch.cuda.synchronize()
+    codes_g, scale_g = dvdq.workspace_views(wsp, M, K)
+    codes_g, scale_g = codes_g.cpu().numpy(), scale_g.cpu().numpy()
+    ref = oracle.qlinear(xb, wp, ws, B, bits)
+    check_codes_and_scales(codes_g, scale_g, ref["codes"], ref["x_scale"], oracle.rotate(xb, B), bits, f"K{K}",
+                           allow_fp32_ties=B <= 8)
+    check_y(bits_of(y), oracle.w4ax_gemm(codes_g, scale_g, wp, ws), f"K{K}")
