@@ -20,9 +20,11 @@
  *     of device memory per GPU (part of the loaded code object) that the GEMM kernels
  *     use as tile counters, 64 bytes per stream.  No launch depends on what an earlier
  *     one left in its counters: they are zeroed on the stream right before every GEMM
- *     that counts in them (by the quantizer kernel of dvdq_qlinear, by a one-wave kernel
- *     in front of a dvdq_w4ax_gemm), so a launch that never finished or a stray write
- *     cannot make a later GEMM skip tiles.  Kernels of one stream run one after the
+ *     that counts in them (by the quantizer kernel when that is what the library enqueued
+ *     last on the stream, as in dvdq_qlinear; else by a one-wave kernel in front of the
+ *     GEMM), so a launch that never finished or a stray write cannot make a later GEMM
+ *     skip tiles.  Calls on one stream from several host threads must be ordered by the
+ *     caller, as for any stream.  Kernels of one stream run one after the
  *     other and therefore share a slot; up to 512 streams per GPU hold slots at a time
  *     (dvdq_release_stream gives one back), further streams and launches under stream
  *     capture use fixed tile shares instead (same results; nothing extra is captured).

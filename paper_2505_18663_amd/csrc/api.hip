@@ -184,18 +184,16 @@ int dvdq_qlinear(const void *x_bf16, const uint8_t *w, const float *w_scale, con
     if (rc != DVDQ_OK) return rc;
     if (workspace_bytes < dvdq_qlinear_workspace_bytes(M, K, codes_format)) return DVDQ_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    // the quantizer kernel also zeroes the tile counters the GEMM behind it draws from
-    unsigned *counters = w_layout == DVDQ_W_CANONICAL ? nullptr : dvdq::sched_slot(stream);
     rc = dvdq::launch_rotate_quant(static_cast<const uint16_t *>(x_bf16), M, K, log2b, act_bits, codes_format, 0,
-                                   codes, x_scale, rowsum, stream, counters);
+                                   codes, x_scale, rowsum, stream);
     if (rc != DVDQ_OK) return rc;
     if (w_layout == DVDQ_W_NATIVE_FP6)
         return dvdq::launch_w4a4_fp6_gemm(reinterpret_cast<const uint8_t *>(codes), x_scale, w, w_scale, w_zero, rowsum,
                                           static_cast<const uint16_t *>(bias_bf16), M, N, K,
-                                          static_cast<uint16_t *>(y_bf16), nullptr, stream, counters != nullptr);
+                                          static_cast<uint16_t *>(y_bf16), nullptr, stream);
     return dvdq::launch_w4ax_gemm(codes, x_scale, w, w_scale, w_zero, rowsum,
                                   static_cast<const uint16_t *>(bias_bf16), M, N, K, codes_format, w_layout,
-                                  static_cast<uint16_t *>(y_bf16), nullptr, stream, counters != nullptr);
+                                  static_cast<uint16_t *>(y_bf16), nullptr, stream);
 }
 
 size_t dvdq_static_workspace_bytes(void) { return DVDQ_STATIC_WORKSPACE_BYTES; }

@@ -100,9 +100,10 @@ static __device__ __forceinline__ void tile_origin(int t, int tiles_m, int tiles
 // run of tile numbers at a time.
 //   ctr != nullptr: XCD x owns tile numbers [x total / 8, (x + 1) total / 8) and its workgroups draw from them
 //     in order through one counter word (an atomic add).  The word is zero when the kernel starts: whatever
-//     runs on the stream right before the GEMM clears the slot (the quantizer kernel of the fused layer, or
-//     a one-wave kernel the GEMM's launcher puts in front), so no launch depends on what an earlier one --
-//     finished or not -- left behind, and nothing has to be put back at the end.
+//     runs on the stream right before the GEMM clears the slot (the quantizer kernel, if that is what the
+//     library enqueued last on the stream, else a one-wave kernel the GEMM's launcher puts in front), so no
+//     launch depends on what an earlier one -- finished or not -- left behind, and nothing has to be put back
+//     at the end.
 //   ctr == nullptr: fixed shares, the j-th tile of workgroup b is number j * grid + (b % 8) * (grid / 8) + b / 8.
 struct TileSource {
     int total, grid, xcd, first_tile, run_lo;

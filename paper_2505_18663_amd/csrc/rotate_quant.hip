@@ -498,8 +498,9 @@ int launch_cpw(int cpw, dim3 grid, dim3 block, size_t smem, hipStream_t stream, 
 }  // namespace
 
 int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block, int act_bits, int codes_format,
-                        int group_log2, int8_t *codes, float *x_scale, int32_t *code_rowsum, hipStream_t stream,
-                        unsigned *clear_words) {
+                        int group_log2, int8_t *codes, float *x_scale, int32_t *code_rowsum, hipStream_t stream) {
+    // the kernel also zeroes the tile counters of the stream: a GEMM enqueued next needs no clearing kernel of its own
+    unsigned *clear_words = sched_slot_to_clear(stream);
     const int emax = group_log2 ? 8 - act_bits : 0;
     // 0: int8; 1 / 2: packed nibbles stored per lane / gathered through LDS; 3: FP6 container
     const int pack4 = codes_format == DVDQ_CODES_FP6 ? 3 : (codes_format != DVDQ_CODES_PACKED4 ? 0 : ((K % 32) == 0 ? 2 : 1));
@@ -537,16 +538,19 @@ int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block,
     const double norm = 1.0 / sqrt((double)(1 << log2_block));
     const double scale_mul = norm / qmax;
     const float recip_num = (float)norm;
+    int rc = DVDQ_ERR_UNSUPPORTED;
 #define DVDQ_RQ_B(L)                                                                                        \
     case L:                                                                                                 \
-        return launch_cpw<L>(cpw, grid, block, smem, stream, x, M, (int)K, W, rows_per_wg, scale_mul,       \
-                             recip_num, pack4, pack4 == 3 ? run : group_log2, emax, codes, x_scale, code_rowsum, clear_words);
+        rc = launch_cpw<L>(cpw, grid, block, smem, stream, x, M, (int)K, W, rows_per_wg, scale_mul,       \
+                             recip_num, pack4, pack4 == 3 ? run : group_log2, emax, codes, x_scale, code_rowsum, clear_words); \
+        break;
     switch (log2_block) {
         DVDQ_RQ_B(0) DVDQ_RQ_B(1) DVDQ_RQ_B(2) DVDQ_RQ_B(3) DVDQ_RQ_B(4)
         DVDQ_RQ_B(5) DVDQ_RQ_B(6) DVDQ_RQ_B(7) DVDQ_RQ_B(8) DVDQ_RQ_B(9)
     }
 #undef DVDQ_RQ_B
-    return DVDQ_ERR_UNSUPPORTED;
+    if (rc == DVDQ_OK && clear_words) sched_slot_cleared(stream);
+    return rc;
 }
 
 }  // namespace dvdq

@@ -519,7 +519,7 @@ __global__ __launch_bounds__(256) void w4_prepack_fp6_kernel(const uint8_t *__re
 template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int OCC>
 int launch_fp6(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale, const int8_t *w_zero,
                const int32_t *code_rowsum, const uint16_t *bias, int M, int N, int K, uint16_t *y, int32_t *acc_out,
-               hipStream_t stream, bool counters_clear) {
+               hipStream_t stream) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     // column tiles are walked in groups of at most 16, so that workgroups at work at the same time share
     // weight panels in the L2s (2 to 16 measured within 3 % of each other)
@@ -535,8 +535,9 @@ int launch_fp6(const uint8_t *codes, const float *x_scale, const uint8_t *w, con
     auto k = w4a4_fp6_gemm_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, OCC>;
     static std::atomic<uint64_t> configured{0};
     allow_dynamic_lds(reinterpret_cast<const void *>(k), smem, configured);
-    unsigned *sched = sched_slot(stream);
-    if (sched && !counters_clear && clear_sched_slot(sched, stream) != DVDQ_OK) return DVDQ_ERR_HIP;
+    bool is_clear = false;
+    unsigned *sched = sched_slot(stream, &is_clear);
+    if (sched && !is_clear && clear_sched_slot(sched, stream) != DVDQ_OK) return DVDQ_ERR_HIP;
     hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), smem, stream, codes, x_scale, w, w_scale,
                        w_zero, code_rowsum, bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n, sched);
     return check_launch();
@@ -546,8 +547,8 @@ int launch_fp6(const uint8_t *codes, const float *x_scale, const uint8_t *w, con
 
 int launch_w4a4_fp6_gemm(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                          const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,
-                         int64_t K, uint16_t *y, int32_t *acc_out, hipStream_t stream, bool counters_clear) {
-#define DVDQ_FP6_ARGS codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K, y, acc_out, stream, counters_clear
+                         int64_t K, uint16_t *y, int32_t *acc_out, hipStream_t stream) {
+#define DVDQ_FP6_ARGS codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K, y, acc_out, stream
     // Tile variants {tile M, tile N, waves M x N, ring depth, workgroups per compute unit}:
     //   1: two independent 4-wave workgroups per compute unit, 128 x 256 tiles, two buffers: while one
     //      converts and stores a tile the other multiplies;
@@ -564,7 +565,7 @@ int launch_w4a4_fp6_gemm(const uint8_t *codes, const float *x_scale, const uint8
     const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
     if (v != 1 && v != 2 && v != 3) v = big_tiles >= 512 ? (K / kBK >= 20 ? 3 : 2) : 1;
     if (K / kBK < 2 && v == 2) v = 1;
-    if (v == 3) return launch_w4ax_gemm_wide(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, M, N, K, true, y, acc_out, stream, counters_clear);
+    if (v == 3) return launch_w4ax_gemm_wide(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, M, N, K, true, y, acc_out, stream);
     if (v == 2) return launch_fp6<256, 256, 4, 2, 3, 1>(DVDQ_FP6_ARGS);
     return launch_fp6<128, 256, 2, 2, 2, 2>(DVDQ_FP6_ARGS);
 #undef DVDQ_FP6_ARGS

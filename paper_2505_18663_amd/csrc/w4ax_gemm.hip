@@ -605,6 +605,7 @@ struct SchedTable {
     std::unordered_map<uint64_t, int> slot_of;   // stream handle -> slot
     std::vector<int> free_slots;                 // released slots, reused before fresh ones
     int fresh = 0;                               // slots never handed out yet
+    bool clear[kSchedSlots] = {};                // the last library kernel enqueued on the slot's stream zeroes the slot
 };
 std::mutex g_sched_mu;
 SchedTable g_sched_table[64];
@@ -616,10 +617,10 @@ __global__ void fill_sched_kernel(unsigned *p, unsigned value, int n) {
 
 }  // namespace
 
-// The counter slot for a launch on `stream`, or nullptr (fixed shares): when the launch is being captured
-// into a graph -- the same node may later run in several graph instances at once, which must not share
-// counters -- or when all slots are taken.
-unsigned *sched_slot(hipStream_t stream) {
+// The counter slot of `stream`, or nullptr (fixed shares): when the stream is being captured into a graph
+// -- the same node may later run in several graph instances at once, which must not share counters -- or
+// when all slots are taken.  *index: the slot's number.
+static unsigned *slot_of_stream(hipStream_t stream, int *dev_out, int *index) {
     if (g_schedule.load(std::memory_order_relaxed) == 0) return nullptr;
     hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(stream, &cap) != hipSuccess) {
@@ -629,7 +630,6 @@ unsigned *sched_slot(hipStream_t stream) {
     if (cap != hipStreamCaptureStatusNone) return nullptr;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
-    std::lock_guard<std::mutex> lock(g_sched_mu);
     SchedTable &t = g_sched_table[dev];
     if (!t.base) {
         void *p = nullptr;
@@ -650,9 +650,41 @@ unsigned *sched_slot(hipStream_t stream) {
         } else {
             return nullptr;
         }
+        t.clear[slot] = false;
         it = t.slot_of.emplace(reinterpret_cast<uint64_t>(stream), slot).first;
     }
+    *dev_out = dev;
+    *index = it->second;
     return t.base + it->second * 16;
+}
+
+// For a GEMM about to be enqueued on `stream`: its counter slot (or nullptr: fixed shares), and whether the
+// library kernel enqueued last on the stream zeroes it (a quantizer; then the GEMM needs no clearing kernel
+// of its own).  The GEMM leaves the slot dirty.  (Calls on one stream are in the caller's order, as the
+// stream's own semantics require.)
+unsigned *sched_slot(hipStream_t stream, bool *is_clear) {
+    std::lock_guard<std::mutex> lock(g_sched_mu);
+    int dev = 0, index = 0;
+    *is_clear = false;
+    unsigned *slot = slot_of_stream(stream, &dev, &index);
+    if (slot) {
+        *is_clear = g_sched_table[dev].clear[index];
+        g_sched_table[dev].clear[index] = false;
+    }
+    return slot;
+}
+
+// For a quantizer about to be enqueued on `stream`: the 16 words it should zero (or nullptr), and, once it
+// is enqueued, the note that it does.
+unsigned *sched_slot_to_clear(hipStream_t stream) {
+    std::lock_guard<std::mutex> lock(g_sched_mu);
+    int dev = 0, index = 0;
+    return slot_of_stream(stream, &dev, &index);
+}
+void sched_slot_cleared(hipStream_t stream) {
+    std::lock_guard<std::mutex> lock(g_sched_mu);
+    int dev = 0, index = 0;
+    if (slot_of_stream(stream, &dev, &index)) g_sched_table[dev].clear[index] = true;
 }
 
 int clear_sched_slot(unsigned *slot, hipStream_t stream) {
@@ -665,6 +697,11 @@ int fill_sched_slots(uint32_t value, hipStream_t stream) {
     if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_sched)) != hipSuccess) return DVDQ_ERR_HIP;
     const int n = kSchedSlots * 16;
     hipLaunchKernelGGL(fill_sched_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, static_cast<unsigned *>(p), value, n);
+    {
+        std::lock_guard<std::mutex> lock(g_sched_mu);
+        for (auto &t : g_sched_table)
+            for (bool &c : t.clear) c = false;
+    }
     return check_launch();
 }
 
@@ -685,7 +722,7 @@ namespace {
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int STAGES, int OCC, bool A4 = false>
 int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                   const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int M, int N, int K,
-                  uint16_t *y, int32_t *acc_out, hipStream_t stream, bool counters_clear) {
+                  uint16_t *y, int32_t *acc_out, hipStream_t stream) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     // column tiles per L2 sharing group: balanced groups of at most 16
     const int n_groups = (tiles_n + 15) / 16;
@@ -701,8 +738,9 @@ int launch_native(const int8_t *codes, const float *x_scale, const uint8_t *w, c
     auto k = w4ax_gemm_native_kernel<BM, BN, BK, WAVES_M, WAVES_N, STAGES, OCC, A4>;
     static std::atomic<uint64_t> configured{0};   // one per template instantiation
     allow_dynamic_lds(reinterpret_cast<const void *>(k), smem, configured);
-    unsigned *sched = sched_slot(stream);
-    if (sched && !counters_clear && clear_sched_slot(sched, stream) != DVDQ_OK) return DVDQ_ERR_HIP;
+    bool is_clear = false;
+    unsigned *sched = sched_slot(stream, &is_clear);
+    if (sched && !is_clear && clear_sched_slot(sched, stream) != DVDQ_OK) return DVDQ_ERR_HIP;
     hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), smem, stream, codes, x_scale, w,
                        w_scale, w_zero, code_rowsum, bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n, sched);
     return check_launch();
@@ -722,14 +760,13 @@ int limited_grid(int grid) {
 
 int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                      const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,
-                     int64_t K, int codes_format, int w_layout, uint16_t *y, int32_t *acc_out, hipStream_t stream,
-                     bool counters_clear) {
+                     int64_t K, int codes_format, int w_layout, uint16_t *y, int32_t *acc_out, hipStream_t stream) {
     if (w_layout == DVDQ_W_CANONICAL) {
         if (codes_format != DVDQ_CODES_INT8 || w_zero) return DVDQ_ERR_UNSUPPORTED;
         return launch_w4ax_gemm_canonical(codes, x_scale, w, w_scale, bias, M, N, K, y, acc_out, stream);
     }
     const int m = (int)M, n = (int)N, k = (int)K;
-#define DVDQ_GEMM_ARGS codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, m, n, k, y, acc_out, stream, counters_clear
+#define DVDQ_GEMM_ARGS codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, m, n, k, y, acc_out, stream
     // Tile variants: {tile M, tile N, K slice, waves M x N, ring depth, workgroups per compute unit}.
     // Variant 2 is the default for every shape: two independent 4-wave workgroups per compute unit,
     // each owning a 128 x 256 tile (64 x 128 per wave) with K slices of 128 through two buffers.  In
@@ -755,7 +792,7 @@ int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w
     if (forced < 0 && codes_format == DVDQ_CODES_INT8 && k / 128 >= 64 && ((M + 255) / 256) * ((N + 255) / 256) >= 512) v = 5;
     if (v == 5)
         return launch_w4ax_gemm_wide(reinterpret_cast<const uint8_t *>(codes), x_scale, w, w_scale, w_zero, code_rowsum, bias,
-                                     M, N, K, false, y, acc_out, stream, counters_clear);
+                                     M, N, K, false, y, acc_out, stream);
     {
         const int bk = v == 4 ? 64 : 128, stages = v == 2 ? 2 : (v == 4 ? 4 : 3);
         if (k / bk < stages - 1) v = 2;

@@ -627,7 +627,7 @@ namespace {
 template <bool FP6>
 int launch_wide(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale, const int8_t *w_zero,
                 const int32_t *code_rowsum, const uint16_t *bias, int M, int N, int K, uint16_t *y, int32_t *acc_out,
-                hipStream_t stream, bool counters_clear) {
+                hipStream_t stream) {
     constexpr int BM = 256, BN = 256, STAGES = 3;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int n_groups = (tiles_n + 15) / 16;   // column tiles per L2 sharing group: balanced groups of at most 16
@@ -640,8 +640,10 @@ int launch_wide(const uint8_t *codes, const float *x_scale, const uint8_t *w, co
     auto k = w4ax_gemm_wide_kernel<FP6>;
     static std::atomic<uint64_t> configured{0};
     allow_dynamic_lds(reinterpret_cast<const void *>(k), smem, configured);
-    unsigned *sched = K / kBK >= 2 ? sched_slot(stream) : nullptr;   // a tile draw takes two slices to come back
-    if (sched && !counters_clear && clear_sched_slot(sched, stream) != DVDQ_OK) return DVDQ_ERR_HIP;
+    bool is_clear = false;
+    unsigned *sched = sched_slot(stream, &is_clear);
+    if (K / kBK < 2) sched = nullptr;   // a tile draw takes two slices to come back
+    if (sched && !is_clear && clear_sched_slot(sched, stream) != DVDQ_OK) return DVDQ_ERR_HIP;
     hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(256), smem, stream, codes, x_scale, w, w_scale, w_zero, code_rowsum,
                        bias, M, N, K, y, acc_out, tiles_m, tiles_n, group_n, sched);
     return check_launch();
@@ -651,12 +653,12 @@ int launch_wide(const uint8_t *codes, const float *x_scale, const uint8_t *w, co
 
 int launch_w4ax_gemm_wide(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                           const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,
-                          int64_t K, bool fp6, uint16_t *y, int32_t *acc_out, hipStream_t stream, bool counters_clear) {
+                          int64_t K, bool fp6, uint16_t *y, int32_t *acc_out, hipStream_t stream) {
     if (fp6)
         return launch_wide<true>(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K, y, acc_out,
-                                 stream, counters_clear);
+                                 stream);
     return launch_wide<false>(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K, y, acc_out,
-                              stream, counters_clear);
+                              stream);
 }
 
 }  // namespace dvdq
