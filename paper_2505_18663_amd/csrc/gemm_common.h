@@ -1,5 +1,6 @@
 // Device helpers shared by the persistent GEMM kernels (INT8 matrix path in w4ax_gemm.hip, FP6 matrix
-// path in w4a4_fp6_gemm.hip): LDS-direct loads, hand-kept vmcnt waits, streaming stores, tile order.
+// path in w4a4_fp6_gemm.hip, both operand types with one wave per SIMD in w4ax_gemm_wide.hip): LDS-direct
+// loads, hand-kept vmcnt waits, streaming stores, tile order, tile draws.
 #pragma once
 #include "dvdq_internal.h"
 
