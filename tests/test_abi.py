@@ -169,6 +169,9 @@ def test_bench_helpers_argument_errors():
     assert L.dvdq_bench_mfma_fp6(0, 1, FAKE, None, None) == 2
     assert L.dvdq_bench_mfma_fp6(4, 1, None, None, None) == 1
     assert L.dvdq_bench_mfma_fp6(4, -1, FAKE, None, None) == 3
+    assert L.dvdq_bench_set_gemm_grid_limit(-8) == 3
+    assert L.dvdq_bench_set_gemm_grid_limit(0) == 0
+    assert L.dvdq_bench_set_gemm_schedule(2) == 3
 
 
 def test_binding_refuses_cpu_tensors():
