@@ -105,10 +105,10 @@ def profile_traffic(workload_name):
     return rows, rel
 
 
-def first_match(rows, pattern):
+def first_match(rows, pattern, want_name=False):
     for name, v in rows.items():
         if re.match(pattern, name):
-            return v
+            return name if want_name else v
     return None
 
 
@@ -267,13 +267,16 @@ class Bench:
         gemm_traffic = first_match(traffic, r"dvdq::(w4a4_fp6_gemm_kernel<|w4ax_gemm_wide_kernel<true>)" if use_fp6 else
                                    (r"dvdq::w4ax_gemm_native_kernel<.*, true>" if p["fmt_name"] == "packed4" else
                                     r"dvdq::(w4ax_gemm_native_kernel<.*, false>|w4ax_gemm_wide_kernel<false>)"))
+        gemm_symbol = first_match(traffic, r"dvdq::(w4a4_fp6_gemm_kernel<|w4ax_gemm_wide_kernel<true>)" if use_fp6 else
+                                  (r"dvdq::w4ax_gemm_native_kernel<.*, true>" if p["fmt_name"] == "packed4" else
+                                   r"dvdq::(w4ax_gemm_native_kernel<.*, false>|w4ax_gemm_wide_kernel<false>)"), want_name=True)
         rq_traffic = first_match(traffic, r"dvdq::rotate_quant_kernel<\d+, \d+, %d>" % {"int8": 0, "packed4": 1, "fp6": 2}[p["fmt_name"]])
         entry = {
             "workload": wl.name, "M": M, "K": K, "N": N, "had_block": B, "act_bits": bits,
             "matrix_path": p["matrix_path"], "codes_format": p["fmt_name"], "dtype": p["dtype"],
             "ms_per_step": round(t_step * 1e3, 4), "value": round(tops, 2), "unit": "TOP/s",
             "frac_int8_mfma_peak": round(tops / INT8_MFMA_PEAK_TOPS, 4),
-            "roofline": {"kernel": p["kernel"], "bound": "mfma", "achieved": round(gemm_tops, 2), "peak": p["peak"],
+            "roofline": {"kernel": p["kernel"], "kernel_symbol": gemm_symbol, "bound": "mfma", "achieved": round(gemm_tops, 2), "peak": p["peak"],
                          "unit": "TOP/s", "frac": round(gemm_tops / p["peak"], 4), "traffic": gemm_traffic,
                          "traffic_source": src,
                          "avg_launch_ms": round(r["gemm_avg"], 4), "median_launch_ms": round(r["gemm_med"], 4),
