@@ -8,6 +8,7 @@ namespace dvdq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kBK = 128;      // K slice (bytes of int8 codes per row)
 constexpr int kGroup = 32;    // weight rows per native-layout group
@@ -135,6 +136,259 @@ struct TileSource {
         t1 = tile(v + 1u, 1);
     }
 };
+
+// ---- epilogues of the two-waves-per-SIMD kernels (INT8 matrix path and FP6 matrix path)
+// Both kernels end a tile the same way; what differs is how an accumulator register turns into the integer sum
+// of code products, which an accumulator policy states:
+//   AccI32<SHIFT>: int32 registers holding 2^SHIFT times the sum (the widened operands' factor);
+//   AccF32x64:     fp32 registers holding the sum / 64 exactly (FP6 values are codes / 8).
+// Accumulator register r = 4 g + e of MFMA tile (i, j) in lane l is
+//   n = n0 + wn + 32 i + 8 g + 4 (l / 32) + e,   m = m0 + wm + 32 j + (l % 32).
+// With weight zero-points, sum q (c - z) = acc - z * rs (rs the token's code sum) is taken with a 24-bit
+// multiply: operands and product are in range (checked by the C ABI), so it is exact.
+template <int SHIFT>
+struct AccI32 {
+    typedef v16i vec;
+    // factor folded into the token scale (a power of two: exact)
+    static __device__ __forceinline__ constexpr float fold(bool) { return 1.f / (float)(1 << SHIFT); }
+    template <bool ZP>
+    static __device__ __forceinline__ float scaled(int a, int z, int rs, float xs_folded) {
+        if constexpr (ZP) a -= __mul24(z * (1 << SHIFT), rs);
+        return (float)a * xs_folded;
+    }
+    // per-element path: the register's integer (still times 2^SHIFT), its zero-point term, the plain sum
+    static __device__ __forceinline__ int integer(int a) { return a; }
+    static __device__ __forceinline__ int unzero(int v, int z, int rs) { return v - __mul24(z * (1 << SHIFT), rs); }
+    static __device__ __forceinline__ int sum(int v) { return v >> SHIFT; }
+    static __device__ __forceinline__ constexpr float edge_fold() { return 1.f / (float)(1 << SHIFT); }
+};
+
+struct AccF32x64 {
+    typedef v16f vec;
+    // without zero-points the token scale times 64 multiplies the fp32 accumulator directly
+    static __device__ __forceinline__ constexpr float fold(bool zp) { return zp ? 1.f : 64.f; }
+    template <bool ZP>
+    static __device__ __forceinline__ float scaled(float a, int z, int rs, float xs_folded) {
+        if constexpr (ZP) return (float)((int)(a * 64.f) - __mul24(z, rs)) * xs_folded;
+        else return a * xs_folded;
+    }
+    static __device__ __forceinline__ int integer(float a) { return (int)(a * 64.f); }
+    static __device__ __forceinline__ int unzero(int v, int z, int rs) { return v - __mul24(z, rs); }
+    static __device__ __forceinline__ int sum(int v) { return v; }
+    static __device__ __forceinline__ constexpr float edge_fold() { return 1.f; }
+};
+
+// LDS image of a tile's epilogue vectors (staged by LDS-direct loads with the tile's first slice): token scales
+// fp32 [BM], channel scales fp32 [BN], bias bf16 [BN], code sums int32 [BM], zero-points int8 [BN]
+template <int BM, int BN>
+struct TileVectors {
+    static constexpr int OFF_BIAS = (BM + BN) * 4, OFF_RSUM = OFF_BIAS + BN * 2, OFF_ZERO = OFF_RSUM + BM * 4;
+    static constexpr int BYTES = OFF_ZERO + BN;
+};
+
+// Interior tile (whole tile inside M x N, N a multiple of 8): no predicates, every vector the epilogue needs
+// comes from LDS, one row pointer per lane.  The bf16 tile goes through LDS so that every store instruction
+// writes whole 128-byte lines: in the accumulator layout a lane owns one token and 8 consecutive channels per
+// register group, so a direct store touches 32 token rows with 32 bytes each.  32 tokens x 64 channels at a
+// time are staged in `stg` (this wave's 4 KB of the ring buffer whose slice was consumed last: after the
+// barrier no wave reads it any more, and the next loads into it are only issued after the next K loop's first
+// barrier; 16-byte pieces, piece index xor-ed with the row against bank conflicts) and read back with 8 lanes
+// per token row.  A lane's channel vectors (4 channel scales, bias, zero-points) for register group g of MFMA
+// tile column i are fetched one group ahead of their use: a read issued where its value is needed would
+// expose the LDS latency once per group, 32 times per tile.  The accumulators are left at zero.
+template <class P, int BM, int BN, int TM, int TN, bool ZP>
+static __device__ __forceinline__ void epilogue_interior(typename P::vec (&acc)[TN][TM], const uint8_t *s_tile, bool has_bias,
+                                                         int lane, int wm, int wn, uint8_t *stg, uint16_t *y, int m0,
+                                                         int n0, int N) {
+    typedef TileVectors<BM, BN> TV;
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const float *s_xs = reinterpret_cast<const float *>(s_tile);
+    const float *ws_l = s_xs + BM + wn + fhalf * 4;
+    const int32_t *s_rsum = reinterpret_cast<const int32_t *>(s_tile + TV::OFF_RSUM);
+    const uint32_t *bias_l = reinterpret_cast<const uint32_t *>(s_tile + TV::OFF_BIAS) + (wn + fhalf * 4) / 2;
+    const uint32_t *zero_l = reinterpret_cast<const uint32_t *>(s_tile + TV::OFF_ZERO) + (wn + fhalf * 4) / 4;
+    float xs_l[TM];
+    int rsum[TM];
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+        xs_l[j] = s_xs[wm + j * 32 + frow] * P::fold(ZP);
+        rsum[j] = ZP ? s_rsum[wm + j * 32 + frow] : 0;
+    }
+    const int rd_row = lane >> 3, rd_piece = lane & 7;
+    struct ChannelVec { float4 ws; uint2 bb; uint32_t zq; };
+    auto fetch = [&] __device__(ChannelVec &cv, int i, int g) {
+        const int c = i * 32 + g * 8;
+        cv.ws = *reinterpret_cast<const float4 *>(ws_l + c);
+        if (has_bias) cv.bb = *reinterpret_cast<const uint2 *>(bias_l + c / 2);
+        if constexpr (ZP) cv.zq = zero_l[c / 4];
+    };
+    ChannelVec cv[2];   // group k of the tile's groups lives in cv[k & 1]
+    fetch(cv[0], 0, 0);
+    int k = 0;
+#pragma unroll
+    for (int ip = 0; ip < TN / 2; ++ip) {
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+#pragma unroll
+            for (int ii = 0; ii < 2; ++ii) {
+                const int i = 2 * ip + ii;
+#pragma unroll
+                for (int g = 0; g < 4; g += 2) {
+                    uint32_t pk[2][2];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h, ++k) {
+                        {   // the group after this one, in this loop nest's order
+                            int gn = g + h + 1, iin = ii, jn = j, ipn = ip;
+                            if (gn == 4) { gn = 0; if (++iin == 2) { iin = 0; if (++jn == TM) { jn = 0; ++ipn; } } }
+                            if (ipn < TN / 2) fetch(cv[(k + 1) & 1], 2 * ipn + iin, gn);
+                        }
+                        const ChannelVec &c = cv[k & 1];
+                        const int r = (g + h) * 4;
+                        float o[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            o[e] = P::template scaled<ZP>(acc[i][j][r + e], (int)(int8_t)(c.zq >> (8 * e)), rsum[j], xs_l[j]);
+                            acc[i][j][r + e] = 0;
+                        }
+                        o[0] *= c.ws.x;
+                        o[1] *= c.ws.y;
+                        o[2] *= c.ws.z;
+                        o[3] *= c.ws.w;
+                        if (has_bias) {
+                            o[0] += __uint_as_float(c.bb.x << 16);
+                            o[1] += __uint_as_float(c.bb.x & 0xFFFF0000u);
+                            o[2] += __uint_as_float(c.bb.y << 16);
+                            o[3] += __uint_as_float(c.bb.y & 0xFFFF0000u);
+                        }
+                        pk[h][0] = pack_bf16x2(o[0], o[1]);
+                        pk[h][1] = pack_bf16x2(o[2], o[3]);
+                    }
+                    // lanes l and l+32 hold channels (8g .. 8g+3) and (8g+4 .. 8g+7): swap the upper half
+                    // of group g with the lower half of group g+1 so each lane owns 8 consecutive channels
+#pragma unroll
+                    for (int d = 0; d < 2; ++d) {
+                        auto sw = __builtin_amdgcn_permlane32_swap(pk[0][d], pk[1][d], false, false);
+                        pk[0][d] = sw[0];
+                        pk[1][d] = sw[1];
+                    }
+                    const int piece = ii * 4 + g + fhalf;   // 16-byte piece of the 64-channel row
+                    *reinterpret_cast<uint4 *>(stg + frow * 128 + ((piece ^ (frow & 7)) << 4)) =
+                        make_uint4(pk[0][0], pk[0][1], pk[1][0], pk[1][1]);
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            uint16_t *yb = y + (int64_t)(m0 + wm + j * 32 + rd_row) * N + (n0 + wn + ip * 64 + rd_piece * 8);
+            uint4 v[4];
+#pragma unroll
+            for (int pass = 0; pass < 4; ++pass) {
+                const int row = pass * 8 + rd_row;
+                v[pass] = *reinterpret_cast<const uint4 *>(stg + row * 128 + ((rd_piece ^ (row & 7)) << 4));
+            }
+#pragma unroll
+            for (int pass = 0; pass < 4; ++pass) store_streaming16(yb + (int64_t)pass * 8 * N, v[pass]);
+            __builtin_amdgcn_wave_barrier();   // the next chunk's LDS writes stay behind these reads
+        }
+    }
+}
+
+// Edge tiles, N not a multiple of 8, or the accumulator hook: predicated per element, through the integer
+// accumulator (same values and rounding order as the interior path).  The accumulators are left at zero.
+template <class P, int BM, int BN, int TM, int TN>
+static __device__ __forceinline__ void epilogue_edge(typename P::vec (&acc)[TN][TM], const uint8_t *s_tile, const uint16_t *bias,
+                                                     const int8_t *w_zero, int lane, int wm, int wn, uint16_t *y,
+                                                     int32_t *acc_out, int m0, int n0, int M, int N) {
+    typedef TileVectors<BM, BN> TV;
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const float *s_xs = reinterpret_cast<const float *>(s_tile);
+    const float *s_ws = s_xs + BM;
+    const int32_t *s_rsum = reinterpret_cast<const int32_t *>(s_tile + TV::OFF_RSUM);
+    const bool vec8 = (N & 7) == 0;
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+        const int m = m0 + wm + j * 32 + frow;
+        const bool m_ok = m < M;
+        const float xs = s_xs[wm + j * 32 + frow] * P::edge_fold();
+        const int rs = w_zero ? s_rsum[wm + j * 32 + frow] : 0;
+#pragma unroll
+        for (int i = 0; i < TN; ++i) {
+            const int nb = n0 + wn + i * 32;   // this MFMA tile's first output channel
+            int a[16];
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    // (channels past N: some valid zero-point, for values that are never stored)
+                    const int z = w_zero ? (int)w_zero[min(nb + g * 8 + fhalf * 4 + e, N - 1)] : 0;
+                    a[g * 4 + e] = P::unzero(P::integer(acc[i][j][g * 4 + e]), z, rs);
+                    acc[i][j][g * 4 + e] = 0;
+                }
+            if (acc_out && m_ok) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = nb + g * 8 + fhalf * 4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (n + e < N) acc_out[(int64_t)m * N + n + e] = P::sum(a[g * 4 + e]);
+                }
+            }
+            if (vec8) {
+                uint32_t pk[4][2];
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = nb + g * 8 + fhalf * 4;
+                    float o[4];
+                    if (n < N) {  // N % 8 == 0 and n % 4 == 0: n + 3 < N as well
+                        const float4 ws = *reinterpret_cast<const float4 *>(s_ws + (n - n0));
+                        o[0] = (float)a[g * 4 + 0] * xs * ws.x;
+                        o[1] = (float)a[g * 4 + 1] * xs * ws.y;
+                        o[2] = (float)a[g * 4 + 2] * xs * ws.z;
+                        o[3] = (float)a[g * 4 + 3] * xs * ws.w;
+                        if (bias) {
+                            const uint2 bb = *reinterpret_cast<const uint2 *>(bias + n);
+                            o[0] += __uint_as_float(bb.x << 16);
+                            o[1] += __uint_as_float(bb.x & 0xFFFF0000u);
+                            o[2] += __uint_as_float(bb.y << 16);
+                            o[3] += __uint_as_float(bb.y & 0xFFFF0000u);
+                        }
+                    } else {
+                        o[0] = o[1] = o[2] = o[3] = 0.f;
+                    }
+                    pk[g][0] = pack_bf16x2(o[0], o[1]);
+                    pk[g][1] = pack_bf16x2(o[2], o[3]);
+                }
+                // lanes l and l+32 hold channels (8g .. 8g+3) and (8g+4 .. 8g+7): swap the upper half of
+                // group g with the lower half of group g+1 so each lane owns 8 consecutive channels
+#pragma unroll
+                for (int g = 0; g < 4; g += 2) {
+#pragma unroll
+                    for (int d = 0; d < 2; ++d) {
+                        auto r = __builtin_amdgcn_permlane32_swap(pk[g][d], pk[g + 1][d], false, false);
+                        pk[g][d] = r[0];
+                        pk[g + 1][d] = r[1];
+                    }
+                    const int n = nb + g * 8 + fhalf * 8;
+                    if (m_ok && n < N)
+                        *reinterpret_cast<uint4 *>(y + (int64_t)m * N + n) =
+                            make_uint4(pk[g][0], pk[g][1], pk[g + 1][0], pk[g + 1][1]);
+                }
+            } else if (m_ok) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = nb + g * 8 + fhalf * 4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (n + e >= N) break;
+                        float o = (float)a[g * 4 + e] * xs * s_ws[n + e - n0];
+                        if (bias) o += __uint_as_float((uint32_t)bias[n + e] << 16);
+                        y[(int64_t)m * N + n + e] = (uint16_t)(pack_bf16x2(o, 0.f) & 0xFFFFu);
+                    }
+                }
+            }
+        }
+    }
+}
 
 // Enqueues the one-wave kernel that zeroes a counter slot (sched_slot; defined in w4ax_gemm.hip).
 int clear_sched_slot(unsigned *slot, hipStream_t stream);

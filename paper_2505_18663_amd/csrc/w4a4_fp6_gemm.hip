@@ -31,7 +31,6 @@ namespace dvdq {
 namespace {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
-typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kFp6RowBytes = kBK * 6 / 8;              // 96: one row's codes of one K slice
 constexpr int kFp6Block = kGroup * kFp6RowBytes;       // 3072: 32 rows of one K slice
@@ -57,8 +56,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_ker
     static_assert(GROUPS * DMA_PER_GROUP >= DMA, "not every load of an item would be issued");
     // one tile's epilogue vectors in LDS: token scales, channel scales (fp32), bias (bf16), and for
     // weights with zero-points the tokens' code sums (int32) and the channels' zero-points (int8)
-    constexpr int OFF_BIAS = (BM + BN) * 4, OFF_RSUM = OFF_BIAS + BN * 2, OFF_ZERO = OFF_RSUM + BM * 4;
-    constexpr int SCALES = OFF_ZERO + BN;
+    typedef TileVectors<BM, BN> TV;
+    constexpr int OFF_BIAS = TV::OFF_BIAS, OFF_RSUM = TV::OFF_RSUM, OFF_ZERO = TV::OFF_ZERO, SCALES = TV::BYTES;
     constexpr int STORES = TM * TN * 2;                  // 16-byte store instructions per wave per full tile
     static_assert(BM / 32 == NW, "one block of code rows per wave");
     static_assert(W_DMA >= 1 && W_DMA * 1024 * NW == W_STAGE, "weight tile does not split over the waves");
@@ -259,215 +258,26 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_ker
         if (++kt < KT) continue;
         __builtin_amdgcn_s_setprio(0);
 
-        // ---- epilogue of tile comp_tile.  Accumulator register r = 4 g + e of MFMA tile (i, j) in lane l is
-        //   n = n0 + wn + 32 i + 8 g + 4 (l / 32) + e,   m = m0 + wm + 32 j + (l % 32),  value = integer sum / 64.
+        // ---- epilogue of tile comp_tile (shared with the INT8 kernel: see epilogue_interior / epilogue_edge; here
+        // the fp32 accumulators hold the integer sum / 64, exactly: see the top of this file)
         int m0, n0;
         tile_origin(comp_tile, tiles_m, tiles_n, group_n, BM, BN, m0, n0);
         kt = 0;
         ++tile_j;
         comp_tile = __builtin_amdgcn_readfirstlane(s_tiles[tile_j & 7]);   // the next one (its loads are under way)
-        const bool vec8 = (N & 7) == 0;
         const uint8_t *s_tile = smem + STAGES * STAGE + ((tile_j - 1) & 1) * SCALES;
-        const float *s_xs = reinterpret_cast<const float *>(s_tile);
-        const float *s_ws = s_xs + BM;
-        const int32_t *s_rsum = reinterpret_cast<const int32_t *>(s_tile + OFF_RSUM);
-        // the integer accumulator (exact: see the top of this file), then sum q (c - z) = acc - z * rs with a
-        // 24-bit multiply (operands and product in range: checked by the C ABI)
-        auto acc_int = [] __device__(float a) { return (int)(a * kFp6Unit); };
-        auto unzero = [] __device__(int a, int z, int rs) { return a - __mul24(z, rs); };
-        if (vec8 && !acc_out && m0 + BM <= M && n0 + BN <= N) {
-            // ---- interior tile: no predicates, channel vectors fetched one register group ahead, bf16 tile
-            // transposed through this wave's 4 KB of the ring buffer that was consumed last, whole-line
-            // non-temporal stores (the INT8 kernel's epilogue; same arithmetic, same rounding order).
+        // Lane-dependent addresses of the epilogue are derived from a lane number the compiler cannot trace
+        // back: computed here once per tile instead of being kept (and spilled) across the K loop.
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));
+        if ((N & 7) == 0 && !acc_out && m0 + BM <= M && n0 + BN <= N) {
             if (KT >= STAGES) store_credit = STAGES - 1;
-            auto interior = [&] __device__(auto has_zero) __attribute__((always_inline)) {
-                constexpr bool ZP = decltype(has_zero)::value;
-                // Lane-dependent addresses of the epilogue are derived from a lane number the compiler cannot
-                // trace back: computed here once per tile instead of being kept (and spilled) across the K loop.
-                int lane_e = lane;
-                asm volatile("" : "+v"(lane_e));
-                const int frow = lane_e & 31, fhalf = lane_e >> 5;
-                const float *ws_l = s_ws + wn + fhalf * 4;
-                const uint32_t *bias_l = reinterpret_cast<const uint32_t *>(s_tile + OFF_BIAS) + (wn + fhalf * 4) / 2;
-                const uint32_t *zero_l = reinterpret_cast<const uint32_t *>(s_tile + OFF_ZERO) + (wn + fhalf * 4) / 4;
-                float xs_l[TM];   // token scale; times 64 where it multiplies the fp32 accumulator directly
-                int rsum[TM];
-#pragma unroll
-                for (int j = 0; j < TM; ++j) {
-                    xs_l[j] = s_xs[wm + j * 32 + frow] * (ZP ? 1.f : kFp6Unit);
-                    rsum[j] = ZP ? s_rsum[wm + j * 32 + frow] : 0;
-                }
-                uint8_t *stg = smem + (q % STAGES) * STAGE + wave * 4096;
-                const int rd_row = lane_e >> 3, rd_piece = lane_e & 7;
-                struct ChannelVec { float4 ws; uint2 bb; uint32_t zq; };
-                auto fetch = [&] __device__(ChannelVec &cv, int i, int g) {
-                    const int c = i * 32 + g * 8;
-                    cv.ws = *reinterpret_cast<const float4 *>(ws_l + c);
-                    if (bias) cv.bb = *reinterpret_cast<const uint2 *>(bias_l + c / 2);
-                    if constexpr (ZP) cv.zq = zero_l[c / 4];
-                };
-                ChannelVec cv[2];
-                fetch(cv[0], 0, 0);
-                int k = 0;
-#pragma unroll
-                for (int ip = 0; ip < TN / 2; ++ip) {
-#pragma unroll
-                    for (int j = 0; j < TM; ++j) {
-#pragma unroll
-                        for (int ii = 0; ii < 2; ++ii) {
-                            const int i = 2 * ip + ii;
-#pragma unroll
-                            for (int g = 0; g < 4; g += 2) {
-                                uint32_t pk[2][2];
-#pragma unroll
-                                for (int h = 0; h < 2; ++h, ++k) {
-                                    {   // the group after this one, in this loop nest's order
-                                        int gn = g + h + 1, iin = ii, jn = j, ipn = ip;
-                                        if (gn == 4) { gn = 0; if (++iin == 2) { iin = 0; if (++jn == TM) { jn = 0; ++ipn; } } }
-                                        if (ipn < TN / 2) fetch(cv[(k + 1) & 1], 2 * ipn + iin, gn);
-                                    }
-                                    const ChannelVec &c = cv[k & 1];
-                                    const int r = (g + h) * 4;
-                                    float o[4];
-#pragma unroll
-                                    for (int e = 0; e < 4; ++e) {
-                                        if constexpr (ZP)
-                                            o[e] = (float)unzero(acc_int(acc[i][j][r + e]), (int)(int8_t)(c.zq >> (8 * e)), rsum[j]) * xs_l[j];
-                                        else
-                                            o[e] = acc[i][j][r + e] * xs_l[j];
-                                        acc[i][j][r + e] = 0.f;
-                                    }
-                                    o[0] *= c.ws.x;
-                                    o[1] *= c.ws.y;
-                                    o[2] *= c.ws.z;
-                                    o[3] *= c.ws.w;
-                                    if (bias) {
-                                        o[0] += __uint_as_float(c.bb.x << 16);
-                                        o[1] += __uint_as_float(c.bb.x & 0xFFFF0000u);
-                                        o[2] += __uint_as_float(c.bb.y << 16);
-                                        o[3] += __uint_as_float(c.bb.y & 0xFFFF0000u);
-                                    }
-                                    pk[h][0] = pack_bf16x2(o[0], o[1]);
-                                    pk[h][1] = pack_bf16x2(o[2], o[3]);
-                                }
-#pragma unroll
-                                for (int d = 0; d < 2; ++d) {
-                                    auto sw = __builtin_amdgcn_permlane32_swap(pk[0][d], pk[1][d], false, false);
-                                    pk[0][d] = sw[0];
-                                    pk[1][d] = sw[1];
-                                }
-                                const int piece = ii * 4 + g + fhalf;   // 16-byte piece of the 64-channel row
-                                *reinterpret_cast<uint4 *>(stg + frow * 128 + ((piece ^ (frow & 7)) << 4)) =
-                                    make_uint4(pk[0][0], pk[0][1], pk[1][0], pk[1][1]);
-                            }
-                        }
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
-                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                        uint16_t *yb = y + (int64_t)(m0 + wm + j * 32 + rd_row) * N + (n0 + wn + ip * 64 + rd_piece * 8);
-                        uint4 v[4];
-#pragma unroll
-                        for (int pass = 0; pass < 4; ++pass) {
-                            const int row = pass * 8 + rd_row;
-                            v[pass] = *reinterpret_cast<const uint4 *>(stg + row * 128 + ((rd_piece ^ (row & 7)) << 4));
-                        }
-#pragma unroll
-                        for (int pass = 0; pass < 4; ++pass) store_streaming16(yb + (int64_t)pass * 8 * N, v[pass]);
-                        __builtin_amdgcn_wave_barrier();   // the next chunk's LDS writes stay behind these reads
-                    }
-                }
-            };
+            uint8_t *stg = smem + (q % STAGES) * STAGE + wave * 4096;
             __builtin_amdgcn_s_barrier();   // every wave is done reading the last slice: its buffer stages the tile
-            if (w_zero) interior(std::true_type{});
-            else interior(std::false_type{});
-            if (comp_tile < 0) break;
-            continue;
-        }
-        // ---- edge tiles, N not a multiple of 8, or the accumulator hook: predicated per element, through
-        // the integer accumulator (same values and rounding order as the interior path)
-        int lane_s = lane;   // (as in the interior path: keeps this path's addresses out of the K loop's registers)
-        asm volatile("" : "+v"(lane_s));
-        const int frow = lane_s & 31, fhalf = lane_s >> 5;
-#pragma unroll
-        for (int j = 0; j < TM; ++j) {
-            const int m = m0 + wm + j * 32 + frow;
-            const bool m_ok = m < M;
-            const float xs = s_xs[wm + j * 32 + frow];
-            const int rs = w_zero ? s_rsum[wm + j * 32 + frow] : 0;
-#pragma unroll
-            for (int i = 0; i < TN; ++i) {
-                const int nb = n0 + wn + i * 32;   // this MFMA tile's first output channel
-                int a[16];
-#pragma unroll
-                for (int g = 0; g < 4; ++g)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int n = nb + g * 8 + fhalf * 4 + e;
-                        a[g * 4 + e] = acc_int(acc[i][j][g * 4 + e]);
-                        if (w_zero && n < N) a[g * 4 + e] = unzero(a[g * 4 + e], (int)w_zero[n], rs);
-                        acc[i][j][g * 4 + e] = 0.f;
-                    }
-                if (acc_out && m_ok) {
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int n = nb + g * 8 + fhalf * 4;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (n + e < N) acc_out[(int64_t)m * N + n + e] = a[g * 4 + e];
-                    }
-                }
-                if (vec8) {
-                    uint32_t pk[4][2];
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int n = nb + g * 8 + fhalf * 4;
-                        float o[4];
-                        if (n < N) {  // N % 8 == 0 and n % 4 == 0: n + 3 < N as well
-                            const float4 ws = *reinterpret_cast<const float4 *>(s_ws + (n - n0));
-                            o[0] = (float)a[g * 4 + 0] * xs * ws.x;
-                            o[1] = (float)a[g * 4 + 1] * xs * ws.y;
-                            o[2] = (float)a[g * 4 + 2] * xs * ws.z;
-                            o[3] = (float)a[g * 4 + 3] * xs * ws.w;
-                            if (bias) {
-                                const uint2 bb = *reinterpret_cast<const uint2 *>(bias + n);
-                                o[0] += __uint_as_float(bb.x << 16);
-                                o[1] += __uint_as_float(bb.x & 0xFFFF0000u);
-                                o[2] += __uint_as_float(bb.y << 16);
-                                o[3] += __uint_as_float(bb.y & 0xFFFF0000u);
-                            }
-                        } else {
-                            o[0] = o[1] = o[2] = o[3] = 0.f;
-                        }
-                        pk[g][0] = pack_bf16x2(o[0], o[1]);
-                        pk[g][1] = pack_bf16x2(o[2], o[3]);
-                    }
-#pragma unroll
-                    for (int g = 0; g < 4; g += 2) {
-#pragma unroll
-                        for (int d = 0; d < 2; ++d) {
-                            auto r = __builtin_amdgcn_permlane32_swap(pk[g][d], pk[g + 1][d], false, false);
-                            pk[g][d] = r[0];
-                            pk[g + 1][d] = r[1];
-                        }
-                        const int n = nb + g * 8 + fhalf * 8;
-                        if (m_ok && n < N)
-                            *reinterpret_cast<uint4 *>(y + (int64_t)m * N + n) =
-                                make_uint4(pk[g][0], pk[g][1], pk[g + 1][0], pk[g + 1][1]);
-                    }
-                } else if (m_ok) {
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int n = nb + g * 8 + fhalf * 4;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            if (n + e >= N) break;
-                            float o = (float)a[g * 4 + e] * xs * s_ws[n + e - n0];
-                            if (bias) o += __uint_as_float((uint32_t)bias[n + e] << 16);
-                            y[(int64_t)m * N + n + e] = (uint16_t)(pack_bf16x2(o, 0.f) & 0xFFFFu);
-                        }
-                    }
-                }
-            }
+            if (w_zero) epilogue_interior<AccF32x64, BM, BN, TM, TN, true>(acc, s_tile, bias != nullptr, lane_e, wm, wn, stg, y, m0, n0, N);
+            else epilogue_interior<AccF32x64, BM, BN, TM, TN, false>(acc, s_tile, bias != nullptr, lane_e, wm, wn, stg, y, m0, n0, N);
+        } else {
+            epilogue_edge<AccF32x64, BM, BN, TM, TN>(acc, s_tile, bias, w_zero, lane_e, wm, wn, y, acc_out, m0, n0, M, N);
         }
         if (comp_tile < 0) break;
     }

@@ -60,8 +60,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
     constexpr int AHEAD = STAGES >= 3 ? 1 : 0;
     // one tile's epilogue vectors in LDS: token scales, channel scales (fp32), bias (bf16), and for
     // weights with zero-points the tokens' code sums (int32) and the channels' zero-points (int8)
-    constexpr int OFF_BIAS = (BM + BN) * 4, OFF_RSUM = OFF_BIAS + BN * 2, OFF_ZERO = OFF_RSUM + BM * 4;
-    constexpr int SCALES = OFF_ZERO + BN;
+    typedef TileVectors<BM, BN> TV;
+    constexpr int OFF_BIAS = TV::OFF_BIAS, OFF_RSUM = TV::OFF_RSUM, OFF_ZERO = TV::OFF_ZERO, SCALES = TV::BYTES;
     constexpr int SHIFT = A4 ? 8 : 4;                    // log2 of the factor the widened operands carry
     constexpr int STORES = TM * TN * 2;                  // 16-byte store instructions per wave per full tile
     static_assert((STAGES - 2 - AHEAD) * DMA + STORES < 64, "store-aware wait exceeds vmcnt");
@@ -337,223 +337,27 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
         if (++kt < KT) continue;
         __builtin_amdgcn_s_setprio(0);   // the epilogue yields issue slots to the other workgroup's K loop
 
-        // ---- epilogue of tile tile_j.  Accumulator register r = 4 g + e of MFMA tile (i, j) in lane l is
-        //   n = n0 + wn + 32 i + 8 g + 4 (l / 32) + e,   m = m0 + wm + 32 j + (l % 32),  value 16 * acc.
+        // ---- epilogue of tile tile_j (shared with the FP6 kernel: see epilogue_interior / epilogue_edge; here the
+        // accumulators hold 2^SHIFT times the sum of code products)
         int m0, n0;
         tile_origin(comp_tile, tiles_m, tiles_n, group_n, BM, BN, m0, n0);
         kt = 0;
         ++tile_j;
         comp_tile = __builtin_amdgcn_readfirstlane(s_tiles[tile_j & 7]);   // the next one (its loads are under way)
-        const bool vec8 = (N & 7) == 0;
-        const float *s_xs = reinterpret_cast<const float *>(smem + STAGES * STAGE + ((tile_j - 1) & 1) * SCALES);
-        const float *s_ws = s_xs + BM;
-        constexpr float kUnwiden = 1.f / (float)(1 << SHIFT);  // the factor 16 of the widened weights (and codes)
         const uint8_t *s_tile = smem + STAGES * STAGE + ((tile_j - 1) & 1) * SCALES;
-        const int32_t *s_rsum = reinterpret_cast<const int32_t *>(s_tile + OFF_RSUM);
-        // accumulator of channel zero-point z and token code sum rs: sum q (c - z) = acc - z * rs, all times
-        // 2^SHIFT.  zs = z << SHIFT and rs fit 24 bits and the product fits 32 (checked by the C ABI), so the
-        // 24-bit multiply is exact.
-        auto unzero = [] __device__(int a, int zs, int rs) { return a - __mul24(zs, rs); };
-        if (vec8 && !acc_out && m0 + BM <= M && n0 + BN <= N) {
-            // ---- interior tile: no predicates, every vector the epilogue needs comes from LDS up front,
-            // one row pointer per lane.  Every lane of every wave stores all its values, so the number of
-            // stores is exact (see the store-aware wait above).
+        typedef AccI32<SHIFT> Acc;
+        if ((N & 7) == 0 && !acc_out && m0 + BM <= M && n0 + BN <= N) {
+            // Interior tile: every lane of every wave stores all its values, so the number of stores is exact
+            // (see the store-aware wait above).
             if (KT >= STAGES) store_credit = STAGES - 1 - AHEAD;
+            uint8_t *stg = smem + (q % STAGES) * STAGE + wave * 4096;
+            __builtin_amdgcn_s_barrier();   // every wave is done reading the last slice: its buffer stages the tile
             // Two specializations, with and without weight zero-points, chosen once per tile: inside the
             // unrolled loops a run-time test of the pointer would cost a branch per element.
-            auto interior = [&] __device__(auto has_zero) __attribute__((always_inline)) {
-                constexpr bool ZP = decltype(has_zero)::value;
-                const float *ws_l = s_ws + wn + fhalf * 4;
-                const uint32_t *bias_l = reinterpret_cast<const uint32_t *>(s_tile + OFF_BIAS) + (wn + fhalf * 4) / 2;
-                const uint32_t *zero_l = reinterpret_cast<const uint32_t *>(s_tile + OFF_ZERO) + (wn + fhalf * 4) / 4;
-                float xs16[TM];
-                int rsum[TM];
-#pragma unroll
-                for (int j = 0; j < TM; ++j) {
-                    xs16[j] = s_xs[wm + j * 32 + frow] * kUnwiden;
-                    rsum[j] = ZP ? s_rsum[wm + j * 32 + frow] : 0;
-                }
-                // The bf16 tile goes through LDS so that every store instruction writes whole 128-byte lines:
-                // in the accumulator layout a lane owns one token and 8 consecutive channels per register
-                // group, so a direct store touches 32 token rows with 32 bytes each.  32 tokens x 64 channels
-                // at a time are staged (16-byte pieces, piece index xor-ed with the row against bank
-                // conflicts) and read back with 8 lanes per token row.  The space is this wave's 4 KB of the
-                // ring buffer whose slice was consumed last: after the barrier no wave reads it any more, and
-                // the next loads into it are only issued after the next K loop's first barrier.
-                uint8_t *stg = smem + (q % STAGES) * STAGE + wave * 4096;
-                const int rd_row = lane >> 3, rd_piece = lane & 7;
-                // A lane's channel vectors (4 channel scales, bias, zero-points) for register group g of MFMA
-                // tile column i are fetched one group ahead of their use: a read issued where its value is
-                // needed would expose the LDS latency once per group, 32 times per tile.
-                struct ChannelVec { float4 ws; uint2 bb; uint32_t zq; };
-                auto fetch = [&] __device__(ChannelVec &cv, int i, int g) {
-                    const int c = i * 32 + g * 8;
-                    cv.ws = *reinterpret_cast<const float4 *>(ws_l + c);
-                    if (bias) cv.bb = *reinterpret_cast<const uint2 *>(bias_l + c / 2);
-                    if constexpr (ZP) cv.zq = zero_l[c / 4];
-                };
-                ChannelVec cv[2];   // group k of the tile's 8 TM TN / 2 ... groups lives in cv[k & 1]
-                fetch(cv[0], 0, 0);
-                int k = 0;
-#pragma unroll
-                for (int ip = 0; ip < TN / 2; ++ip) {
-#pragma unroll
-                    for (int j = 0; j < TM; ++j) {
-#pragma unroll
-                        for (int ii = 0; ii < 2; ++ii) {
-                            const int i = 2 * ip + ii;
-#pragma unroll
-                            for (int g = 0; g < 4; g += 2) {
-                                uint32_t pk[2][2];
-#pragma unroll
-                                for (int h = 0; h < 2; ++h, ++k) {
-                                    {   // the group after this one, in this loop nest's order
-                                        int gn = g + h + 1, iin = ii, jn = j, ipn = ip;
-                                        if (gn == 4) { gn = 0; if (++iin == 2) { iin = 0; if (++jn == TM) { jn = 0; ++ipn; } } }
-                                        if (ipn < TN / 2) fetch(cv[(k + 1) & 1], 2 * ipn + iin, gn);
-                                    }
-                                    const ChannelVec &c = cv[k & 1];
-                                    const int r = (g + h) * 4;
-                                    float o[4];
-#pragma unroll
-                                    for (int e = 0; e < 4; ++e) {
-                                        int a = acc[i][j][r + e];
-                                        if constexpr (ZP) a = unzero(a, (int)(int8_t)(c.zq >> (8 * e)) * (1 << SHIFT), rsum[j]);
-                                        o[e] = (float)a * xs16[j];
-                                        acc[i][j][r + e] = 0;
-                                    }
-                                    o[0] *= c.ws.x;
-                                    o[1] *= c.ws.y;
-                                    o[2] *= c.ws.z;
-                                    o[3] *= c.ws.w;
-                                    if (bias) {
-                                        o[0] += __uint_as_float(c.bb.x << 16);
-                                        o[1] += __uint_as_float(c.bb.x & 0xFFFF0000u);
-                                        o[2] += __uint_as_float(c.bb.y << 16);
-                                        o[3] += __uint_as_float(c.bb.y & 0xFFFF0000u);
-                                    }
-                                    pk[h][0] = pack_bf16x2(o[0], o[1]);
-                                    pk[h][1] = pack_bf16x2(o[2], o[3]);
-                                }
-                                // lanes l and l+32 hold channels (8g .. 8g+3) and (8g+4 .. 8g+7): swap the upper half
-                                // of group g with the lower half of group g+1 so each lane owns 8 consecutive channels
-#pragma unroll
-                                for (int d = 0; d < 2; ++d) {
-                                    auto sw = __builtin_amdgcn_permlane32_swap(pk[0][d], pk[1][d], false, false);
-                                    pk[0][d] = sw[0];
-                                    pk[1][d] = sw[1];
-                                }
-                                const int piece = ii * 4 + g + fhalf;   // 16-byte piece of the 64-channel row
-                                *reinterpret_cast<uint4 *>(stg + frow * 128 + ((piece ^ (frow & 7)) << 4)) =
-                                    make_uint4(pk[0][0], pk[0][1], pk[1][0], pk[1][1]);
-                            }
-                        }
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
-                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                        uint16_t *yb = y + (int64_t)(m0 + wm + j * 32 + rd_row) * N + (n0 + wn + ip * 64 + rd_piece * 8);
-                        uint4 v[4];
-#pragma unroll
-                        for (int pass = 0; pass < 4; ++pass) {
-                            const int row = pass * 8 + rd_row;
-                            v[pass] = *reinterpret_cast<const uint4 *>(stg + row * 128 + ((rd_piece ^ (row & 7)) << 4));
-                        }
-#pragma unroll
-                        for (int pass = 0; pass < 4; ++pass) store_streaming16(yb + (int64_t)pass * 8 * N, v[pass]);
-                        __builtin_amdgcn_wave_barrier();   // the next chunk's LDS writes stay behind these reads
-                    }
-                }
-            };
-            __builtin_amdgcn_s_barrier();   // every wave is done reading the last slice: its buffer stages the tile
-            if (w_zero) interior(std::true_type{});
-            else interior(std::false_type{});
-            if (comp_tile < 0) break;
-            continue;
-        }
-        // ---- edge tiles, N not a multiple of 8, or the accumulator hook: predicated per element
-#pragma unroll
-        for (int j = 0; j < TM; ++j) {
-            const int m = m0 + wm + j * 32 + frow;
-            const bool m_ok = m < M;
-            const float xs16 = s_xs[wm + j * 32 + frow] * kUnwiden;
-#pragma unroll
-            for (int i = 0; i < TN; ++i) {
-                const int nb = n0 + wn + i * 32;   // this MFMA tile's first output channel
-                if (w_zero) {   // remove the zero-point term from the accumulators in place
-                    const int rs = s_rsum[wm + j * 32 + frow];
-#pragma unroll
-                    for (int g = 0; g < 4; ++g)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int n = nb + g * 8 + fhalf * 4 + e;
-                            if (n < N) acc[i][j][g * 4 + e] = unzero(acc[i][j][g * 4 + e], (int)w_zero[n] * (1 << SHIFT), rs);
-                        }
-                }
-                if (acc_out && m_ok) {
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int n = nb + g * 8 + fhalf * 4;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (n + e < N) acc_out[(int64_t)m * N + n + e] = acc[i][j][g * 4 + e] >> SHIFT;
-                    }
-                }
-                if (vec8) {
-                    uint32_t pk[4][2];
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int n = nb + g * 8 + fhalf * 4;
-                        float o[4];
-                        if (n < N) {  // N % 8 == 0 and n % 4 == 0: n + 3 < N as well
-                            const float4 ws = *reinterpret_cast<const float4 *>(s_ws + (n - n0));
-                            o[0] = (float)acc[i][j][g * 4 + 0] * xs16 * ws.x;
-                            o[1] = (float)acc[i][j][g * 4 + 1] * xs16 * ws.y;
-                            o[2] = (float)acc[i][j][g * 4 + 2] * xs16 * ws.z;
-                            o[3] = (float)acc[i][j][g * 4 + 3] * xs16 * ws.w;
-                            if (bias) {
-                                const uint2 bb = *reinterpret_cast<const uint2 *>(bias + n);
-                                o[0] += __uint_as_float(bb.x << 16);
-                                o[1] += __uint_as_float(bb.x & 0xFFFF0000u);
-                                o[2] += __uint_as_float(bb.y << 16);
-                                o[3] += __uint_as_float(bb.y & 0xFFFF0000u);
-                            }
-                        } else {
-                            o[0] = o[1] = o[2] = o[3] = 0.f;
-                        }
-                        pk[g][0] = pack_bf16x2(o[0], o[1]);
-                        pk[g][1] = pack_bf16x2(o[2], o[3]);
-                    }
-                    // lanes l and l+32 hold channels (8g .. 8g+3) and (8g+4 .. 8g+7): swap the upper
-                    // half of tile g with the lower half of tile g+1 so each lane owns 8 consecutive channels
-#pragma unroll
-                    for (int g = 0; g < 4; g += 2) {
-#pragma unroll
-                        for (int d = 0; d < 2; ++d) {
-                            auto r = __builtin_amdgcn_permlane32_swap(pk[g][d], pk[g + 1][d], false, false);
-                            pk[g][d] = r[0];
-                            pk[g + 1][d] = r[1];
-                        }
-                        const int n = nb + g * 8 + fhalf * 8;
-                        if (m_ok && n < N)
-                            *reinterpret_cast<uint4 *>(y + (int64_t)m * N + n) =
-                                make_uint4(pk[g][0], pk[g][1], pk[g + 1][0], pk[g + 1][1]);
-                    }
-                } else if (m_ok) {
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int n = nb + g * 8 + fhalf * 4;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            if (n + e >= N) break;
-                            float o = (float)acc[i][j][g * 4 + e] * xs16 * s_ws[n + e - n0];
-                            if (bias) o += __uint_as_float((uint32_t)bias[n + e] << 16);
-                            y[(int64_t)m * N + n + e] = (uint16_t)(pack_bf16x2(o, 0.f) & 0xFFFFu);
-                        }
-                    }
-                }
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-            }
+            if (w_zero) epilogue_interior<Acc, BM, BN, TM, TN, true>(acc, s_tile, bias != nullptr, lane, wm, wn, stg, y, m0, n0, N);
+            else epilogue_interior<Acc, BM, BN, TM, TN, false>(acc, s_tile, bias != nullptr, lane, wm, wn, stg, y, m0, n0, N);
+        } else {
+            epilogue_edge<Acc, BM, BN, TM, TN>(acc, s_tile, bias, w_zero, lane, wm, wn, y, acc_out, m0, n0, M, N);
         }
         if (comp_tile < 0) break;
     }

@@ -31,7 +31,6 @@ namespace {
 
 typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v6i __attribute__((ext_vector_type(6)));
-typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kFp6Block = kGroup * kBK * 6 / 8;   // 3072: 32 rows of one K slice as E2M3 patterns
 
