@@ -54,6 +54,16 @@ static __device__ __forceinline__ void lds_direct_load16(const void *sbase, uint
                  : "memory");
 }
 
+// Follow-up of lds_direct_load16 with the same M0: the instruction offset OFF is added to the global address
+// and to the LDS address alike (checked on the hardware), so a run of loads whose source and destination
+// advance by the same number of bytes needs one M0 and one base address.  No other M0 write may stand
+// between it and the load that set M0 (the kernels that use it check their assembly for that).
+template <int OFF>
+static __device__ __forceinline__ void lds_direct_load16_more(const void *sbase, uint32_t voff) {
+    static_assert(OFF > 0 && OFF < 4096, "13-bit signed instruction offset");
+    asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" : : "v"(voff), "s"(sbase), "n"(OFF) : "memory");
+}
+
 // chunk swizzle of a code row in LDS (see the kernel).  A 16-byte read is served 16 lanes = 16 rows at a
 // time by the 64 banks (256 bytes), and rows 128 bytes apart alternate between the two halves of the
 // banks: the 8 rows of a half take 8 different chunk slots with (row >> 1) & 7.  With 64-byte rows four

@@ -17,10 +17,21 @@
 // step, whose fragments are already in registers).
 //
 // Ring: three buffers of one 128-channel slice of both operands (48 KB).  In iteration q the waves multiply
-// slice q, slice q+1 is landing and the loads of slice q+2 are dealt out between the MFMA groups; the
-// barrier of iteration q publishes slice q+1 and frees buffer q % 3 for slice q+3.  Everything else --
-// LDS-direct loads with hand-kept vmcnt, persistent workgroups drawing tiles per XCD, tile scales staged in
-// LDS, whole-line epilogue through the ring buffer that was consumed last -- follows w4ax_gemm.hip.
+// slice q, slice q+1 is landing and the loads of slice q+2 are dealt out between the MFMAs; the barrier of
+// iteration q publishes slice q+1 and frees buffer q % 3 for slice q+3.  Everything else -- LDS-direct loads
+// with hand-kept vmcnt, persistent workgroups drawing tiles per XCD, tile scales staged in LDS, whole-line
+// epilogue through the ring buffer that was consumed last -- follows w4ax_gemm.hip.
+//
+// What the single wave per SIMD is sensitive to (measured with shader-clock timestamps around the steps and
+// with register-only loops): an FP6 MFMA occupies the pipe for 32 clocks and the wave issues about six other
+// instructions in that time; whatever else stands between two MFMAs delays the second.  Hence: a run of
+// LDS-direct loads shares one M0 and one base address and moves by the instruction offset (which applies to
+// the global and to the LDS address alike) instead of three scalar instructions per load; the per-slice
+// bookkeeping has a branch-free common path and is dealt out over several MFMA slots; and, on the FP6 path,
+// the twelve loads of a slice are spread over both steps of an iteration (the path from L2 into LDS moves 64
+// bytes per clock and compute unit, a slice is 48 KB, a step is 512 clocks: twelve loads within one step back
+// up and hold the MFMAs behind them).  Together: 1980 -> 1360 clocks per slice on K = 13824 (1024 would be
+// the matrix pipe alone).
 #include <type_traits>
 
 #include "gemm_common.h"
@@ -45,6 +56,7 @@ __device__ __forceinline__ void static_for(F &&f) {
 }
 
 #include "wide_acc.inc"
+
 
 }  // namespace
 
@@ -102,7 +114,7 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
     };
     auto before_barrier = [&] __device__() {   // every wave, before each workgroup barrier of the pipeline
         draw_wait = __builtin_amdgcn_readfirstlane(draw_wait);   // (wave-uniform: keep it in a scalar register)
-        if (draw_wait > 0 && --draw_wait == 0) {
+        if (__builtin_expect(draw_wait > 0, 0) && --draw_wait == 0) {
             if (wave == 0) {
                 if (lane == 0) s_tiles[published & 7] = tiles.tile(drawn, 0);
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -133,7 +145,7 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
     // Weights: the tile's slice is one linear run of the native buffer (16 KB).
     // FP6 path: a 32-row block of codes of one slice is 3 KB contiguous in memory and in LDS (blocks past the last
     // one repeat it; their rows are never stored); the tile's weight slice is one 24 KB run.
-    const uint32_t lane16 = lane * 16;
+    const uint32_t lane16 = lane * 16, lane16_hi = lane16 + 4096;
     int a_row[FP6 ? 1 : A_DMA];
     uint32_t a_voff[FP6 ? 1 : A_DMA];
     if constexpr (!FP6) {
@@ -143,26 +155,28 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
     const uint8_t *a_base = codes, *a_base2 = codes;   // FP6: the wave's two code blocks of the slice being issued
     const uint8_t *w_base = w;
     int issue_tile = 0, issue_kt = 0;
-    bool issue_live = true;
+    int issue_live = 1;   // (wave-uniform, kept in a scalar register)
     const int draw_kt = KT > 1 ? 1 : 0;
-    uint32_t issue_sa = 0;
+    uint32_t issue_sa_a = 0, issue_sa_w = 0;   // LDS addresses of this wave's first code piece and first weight piece
     auto issue_prepare = [&] __device__(uint32_t buf_off) {
         int issue_no = -1;
-        if (issue_live && issue_kt == 0) {
-            issue_no = tile_number(issue_tile);
-            issue_live = issue_no >= 0;
+        if (__builtin_expect((issue_kt <= draw_kt ? issue_live : 0) != 0, 0)) {   // (a tile's first slice or two: off the common path)
+            if (issue_kt == 0) {
+                issue_no = tile_number(issue_tile);
+                issue_live = __builtin_amdgcn_readfirstlane(issue_no >= 0 ? 1 : 0);
+            }
+            if (issue_live && issue_kt == draw_kt) draw();
         }
-        if (issue_live && issue_kt == draw_kt) draw();
-        if (issue_no >= 0) {
+        if (__builtin_expect(issue_no >= 0, 0)) {
             int m0, n0;
             tile_origin(issue_no, tiles_m, tiles_n, group_n, BM, BN, m0, n0);
             if constexpr (FP6) {
                 a_base = uniform_ptr(codes + (int64_t)min(m0 / 32 + 2 * wave, last_block) * KT * kFp6Block);
                 a_base2 = uniform_ptr(codes + (int64_t)min(m0 / 32 + 2 * wave + 1, last_block) * KT * kFp6Block);
-                w_base = uniform_ptr(w + (int64_t)(n0 / kGroup) * kFp6Block);
+                w_base = uniform_ptr(w + (int64_t)(n0 / kGroup) * kFp6Block + wave * W_DMA * 1024);
             } else {
                 a_base = uniform_ptr(codes + (int64_t)m0 * K);
-                w_base = uniform_ptr(w + (int64_t)(n0 / kGroup) * kGroupBytes);
+                w_base = uniform_ptr(w + (int64_t)(n0 / kGroup) * kGroupBytes + wave * W_DMA * 1024);
 #pragma unroll
                 for (int i = 0; i < A_DMA; ++i) {
                     const int row = min(a_row[i], M - 1 - m0);
@@ -200,40 +214,57 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                 }
             }
         }
-        issue_sa = smem_base + buf_off;
+        issue_sa_a = smem_base + buf_off + wave * A_DMA * 1024;
+        issue_sa_w = smem_base + buf_off + A_STAGE + wave * W_DMA * 1024;
     };
-    auto issue_one = [&] __device__(int idx) {
+    // Piece idx of the wave's 12.  Pieces whose source and destination both advance by 1 KB share M0 and the base
+    // address and differ in the instruction offset: the FP6 path sets M0 four times per slice (first and second
+    // code block, weight pieces 0-3 and 4-5), the INT8 path once per code piece and once for its four weight pieces.
+    auto issue_one = [&] __device__(auto idx_c) __attribute__((always_inline)) {
+        constexpr int idx = decltype(idx_c)::value;
         if constexpr (FP6) {
-            if (idx < 3)
-                lds_direct_load16(a_base + idx * 1024, lane16, issue_sa + (wave * A_DMA + idx) * 1024);
-            else if (idx < A_DMA)
-                lds_direct_load16(a_base2 + (idx - 3) * 1024, lane16, issue_sa + (wave * A_DMA + idx) * 1024);
-            else
-                lds_direct_load16(w_base + (wave * W_DMA + idx - A_DMA) * 1024, lane16,
-                                  issue_sa + A_STAGE + (wave * W_DMA + idx - A_DMA) * 1024);
+            if constexpr (idx == 0) lds_direct_load16(a_base, lane16, issue_sa_a);
+            else if constexpr (idx < 3) lds_direct_load16_more<idx * 1024>(a_base, lane16);
+            else if constexpr (idx == 3) lds_direct_load16(a_base2, lane16, issue_sa_a + 3072);
+            else if constexpr (idx < A_DMA) lds_direct_load16_more<(idx - 3) * 1024>(a_base2, lane16);
+            else if constexpr (idx == A_DMA) lds_direct_load16(w_base, lane16, issue_sa_w);
+            else if constexpr (idx < A_DMA + 4) lds_direct_load16_more<(idx - A_DMA) * 1024>(w_base, lane16);
+            else if constexpr (idx == A_DMA + 4) lds_direct_load16(w_base, lane16_hi, issue_sa_w + 4096);
+            else lds_direct_load16_more<(idx - A_DMA - 4) * 1024>(w_base, lane16_hi);
         } else {
-            if (idx < A_DMA)
-                lds_direct_load16(a_base, a_voff[idx], issue_sa + (wave * A_DMA + idx) * 1024);
-            else
-                lds_direct_load16(w_base + (wave * W_DMA + idx - A_DMA) * 1024, lane16,
-                                  issue_sa + A_STAGE + (wave * W_DMA + idx - A_DMA) * 1024);
+            if constexpr (idx < A_DMA) lds_direct_load16(a_base, a_voff[idx], issue_sa_a + idx * 1024);
+            else if constexpr (idx == A_DMA) lds_direct_load16(w_base, lane16, issue_sa_w);
+            else lds_direct_load16_more<(idx - A_DMA) * 1024>(w_base, lane16);
+        }
+    };
+    // To the next slice of the tile, or to slice 0 of the next tile, whose addresses issue_prepare sets (or none:
+    // stay on this slice).  Without branches: it runs once per slice between two MFMAs.
+    // In three parts, so that each fits in the shadow of one MFMA (a wave issues about six other instructions
+    // while an FP6 MFMA occupies the pipe; what does not fit delays the next MFMA).  The empty asm statements pin
+    // each part where it is called: the compiler would otherwise sink it to the barrier behind the step.
+    int adv_more = 0;
+    auto issue_advance_part = [&] __device__(auto part_c) __attribute__((always_inline)) {
+        constexpr int PART = decltype(part_c)::value;
+        if constexpr (PART == 0) {
+            // (wave-uniform values the compiler would otherwise keep in vector registers and test lane by lane)
+            adv_more = __builtin_amdgcn_readfirstlane(issue_kt + 1 < KT ? issue_live : 0);
+            const int a_step = adv_more ? (FP6 ? kFp6Block : A_ROW) : 0;
+            a_base += a_step;
+            if constexpr (FP6) a_base2 += a_step;
+            asm volatile("" : "+s"(adv_more), "+s"(a_base), "+s"(a_base2));
+        } else if constexpr (PART == 1) {
+            w_base += adv_more ? w_slice_stride : (int64_t)0;
+            asm volatile("" : "+s"(w_base));
+        } else {
+            issue_tile = __builtin_amdgcn_readfirstlane(issue_tile + issue_live - adv_more);
+            issue_kt = __builtin_amdgcn_readfirstlane(adv_more ? issue_kt + 1 : 0);
+            asm volatile("" : "+s"(issue_kt), "+s"(issue_tile));
         }
     };
     auto issue_advance = [&] __device__() {
-        if (!issue_live) return;
-        if (issue_kt + 1 < KT) {
-            if constexpr (FP6) {
-                a_base += kFp6Block;
-                a_base2 += kFp6Block;
-            } else {
-                a_base += A_ROW;
-            }
-            w_base += w_slice_stride;
-            ++issue_kt;
-        } else {   // next: slice 0 of the next tile, whose addresses issue_prepare sets (or none: stay on this slice)
-            issue_kt = 0;
-            ++issue_tile;
-        }
+        issue_advance_part(I<0>{});
+        issue_advance_part(I<1>{});
+        issue_advance_part(I<2>{});
     };
 
     // ---- fragments.  MFMA operand row = lane % 32, K half = lane / 32.
@@ -317,9 +348,15 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
             if constexpr (FP6) mfma_fp6_acc<P, FIRST, false>(cur.w[i], cur.a[j]);
             else mfma_i8_acc<P, FIRST, j == 0>(fw_cur, cur.a[j]);
             hook(p_c);   // the caller's bookkeeping for this slot (scalar work in the MFMA's shadow)
-            if constexpr (P < PARTS) load_part(nxt, nxt_off, s_nxt_c, p_c);
+            // (FP6: a fragment's head and tail behind one MFMA, so the set is complete -- and the wait before the
+            // slice barrier over -- half a step before the step ends)
+            if constexpr (FP6 && 2 * P < PARTS) {
+                load_part(nxt, nxt_off, s_nxt_c, I<2 * P>{});
+                load_part(nxt, nxt_off, s_nxt_c, I<2 * P + 1>{});
+            }
+            if constexpr (!FP6 && P < PARTS) load_part(nxt, nxt_off, s_nxt_c, p_c);
             if constexpr (DMA_N > 0 && P >= DMA_FROM && (P - DMA_FROM) % DMA_EVERY == 0 && (P - DMA_FROM) / DMA_EVERY < DMA_N)
-                issue_one(DMA0 + (P - DMA_FROM) / DMA_EVERY);
+                issue_one(I<DMA0 + (P - DMA_FROM) / DMA_EVERY>{});
             if constexpr (!FP6 && j == TM - 1) {   // the next group's widened weights (the next step's first group after the last)
                 if constexpr (i + 1 < TN) fw_cur = widen(cur.w[i + 1]);
                 else fw_cur = widen(nxt.w[0]);
@@ -331,8 +368,7 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
 #pragma unroll
     for (int st = 0; st < STAGES - 1; ++st) {
         issue_prepare(st * STAGE);
-#pragma unroll
-        for (int d = 0; d < DMA; ++d) issue_one(d);
+        static_for<DMA>([&](auto d_c) __attribute__((always_inline)) { issue_one(d_c); });
         issue_advance();
     }
     wait_vmcnt<DMA>();
@@ -353,12 +389,25 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
             // (A tile's very first step starts its accumulators from zero: that step exists twice in the code.)
             auto none = [] __device__(auto) __attribute__((always_inline)) {};
             if constexpr (FP6) {
-                auto hook0 = [&] __device__(auto p_c) __attribute__((always_inline)) {
-                    if constexpr (decltype(p_c)::value == 0) issue_prepare(fill_off);
-                    if constexpr (decltype(p_c)::value == 14) issue_advance();
-                };
-                if (kt == 0) mfma_step(I<1>{}, f0, f1, cur_off, I<1>{}, I<0>{}, I<DMA>{}, I<2>{}, I<1>{}, hook0);
-                else mfma_step(I<0>{}, f0, f1, cur_off, I<1>{}, I<0>{}, I<DMA>{}, I<2>{}, I<1>{}, hook0);
+                // The path from L2 into LDS takes 64 bytes per clock and compute unit: the 48 KB of a slice cannot be
+                // requested within one step (16 MFMAs, 512 clocks) without the load instructions backing up and
+                // holding the MFMAs behind them.  So pieces 0-5 of slice q + 2 went out behind the last step of slice
+                // q - 1 (its buffer was free from that slice's barrier on) and pieces 6-11 go out here, one every
+                // other MFMA.  Only a tile's first slice issues all twelve here: the step behind a tile's last slice
+                // issues nothing, because the epilogue stages the tile in that buffer.
+                if (kt == 0) {
+                    auto hook = [&] __device__(auto p_c) __attribute__((always_inline)) {
+                        if constexpr (decltype(p_c)::value == 0) issue_prepare(fill_off);
+                        if constexpr (decltype(p_c)::value == 14) issue_advance();
+                    };
+                    mfma_step(I<1>{}, f0, f1, cur_off, I<1>{}, I<0>{}, I<DMA>{}, I<2>{}, I<1>{}, hook);
+                } else {
+                    auto hook = [&] __device__(auto p_c) __attribute__((always_inline)) {
+                        if constexpr (decltype(p_c)::value >= 12 && decltype(p_c)::value <= 14)
+                            issue_advance_part(I<decltype(p_c)::value - 12>{});
+                    };
+                    mfma_step(I<0>{}, f0, f1, cur_off, I<1>{}, I<DMA / 2>{}, I<DMA / 2>{}, I<1>{}, I<2>{}, hook);
+                }
             } else {
                 auto hook0 = [&] __device__(auto p_c) __attribute__((always_inline)) {
                     if constexpr (decltype(p_c)::value == 0) issue_prepare(fill_off);
@@ -374,7 +423,7 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
             // Publish slice q + 1: it has landed once at most the loads of slice q + 2 (just issued) are
             // outstanding, plus, right after a full tile's epilogue, that tile's stores.  Every fragment read of
             // slice q has been issued; once they are back (lgkmcnt) and everyone is here, buffer q % 3 is free.
-            if (store_credit > 0) {
+            if (__builtin_expect(store_credit > 0, 0)) {
                 wait_vmcnt<DMA + STORES>();
                 store_credit = 0;
             } else {
@@ -393,7 +442,18 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                     fill_off = t;
                 }
             };
-            mfma_step(I<0>{}, f1, f0, nxt_off, I<0>{}, I<0>{}, I<0>{}, I<0>{}, I<1>{}, rotate);
+            if (FP6 && kt + 1 < KT) {
+                // FP6 path, not the tile's last slice: the barrier has freed the buffer of slice q, which takes slice
+                // q + 3; its addresses (and, at a tile's start, the tile's vectors and the next draw) behind the first
+                // MFMA, its pieces 0-5 behind every other MFMA from the third on
+                auto early = [&] __device__(auto p_c) __attribute__((always_inline)) {
+                    if constexpr (decltype(p_c)::value == 0) issue_prepare(cur_off);
+                    rotate(p_c);
+                };
+                mfma_step(I<0>{}, f1, f0, nxt_off, I<0>{}, I<0>{}, I<DMA / 2>{}, I<2>{}, I<2>{}, early);
+            } else {
+                mfma_step(I<0>{}, f1, f0, nxt_off, I<0>{}, I<0>{}, I<0>{}, I<0>{}, I<1>{}, rotate);
+            }
         }
 
         // ---- epilogue of tile comp_tile.  Accumulator register r = 4 g + e of MFMA tile (i, j) in lane l is
