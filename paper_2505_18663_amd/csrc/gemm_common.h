@@ -196,7 +196,8 @@ struct TileVectors {
     static constexpr int BYTES = OFF_ZERO + BN;
 };
 
-// Interior tile (whole tile inside M x N, N a multiple of 8): no predicates, every vector the epilogue needs
+// Interior tile (whole tile inside M x N, N a multiple of 8; specialized on zero-points and, where the caller
+// can afford the code, on bias: a run-time test inside the unrolled loops costs a branch per register group): no predicates, every vector the epilogue needs
 // comes from LDS, one row pointer per lane.  The bf16 tile goes through LDS so that every store instruction
 // writes whole 128-byte lines: in the accumulator layout a lane owns one token and 8 consecutive channels per
 // register group, so a direct store touches 32 token rows with 32 bytes each.  32 tokens x 64 channels at a
@@ -206,10 +207,15 @@ struct TileVectors {
 // per token row.  A lane's channel vectors (4 channel scales, bias, zero-points) for register group g of MFMA
 // tile column i are fetched one group ahead of their use: a read issued where its value is needed would
 // expose the LDS latency once per group, 32 times per tile.  The accumulators are left at zero.
-template <class P, int BM, int BN, int TM, int TN, bool ZP>
+// BIAS: 1 / 0 = with / without bias, fixed at compile time; -1 = `has_bias` decides at run time (for kernels
+// whose register budget does not survive four inlined copies of this function).
+template <class P, int BM, int BN, int TM, int TN, bool ZP, int BIAS>
 static __device__ __forceinline__ void epilogue_interior(typename P::vec (&acc)[TN][TM], const uint8_t *s_tile, bool has_bias,
                                                          int lane, int wm, int wn, uint8_t *stg, uint16_t *y, int m0,
                                                          int n0, int N) {
+    // (scale, then add the bias, each rounded: a fused multiply-add would differ from the per-element path in the last bit)
+#pragma clang fp contract(off)
+    if constexpr (BIAS >= 0) has_bias = BIAS != 0;
     typedef TileVectors<BM, BN> TV;
     const int frow = lane & 31, fhalf = lane >> 5;
     const float *s_xs = reinterpret_cast<const float *>(s_tile);

@@ -274,8 +274,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_ker
             if (KT >= STAGES) store_credit = STAGES - 1;
             uint8_t *stg = smem + (q % STAGES) * STAGE + wave * 4096;
             __builtin_amdgcn_s_barrier();   // every wave is done reading the last slice: its buffer stages the tile
-            if (w_zero) epilogue_interior<AccF32x64, BM, BN, TM, TN, true>(acc, s_tile, bias != nullptr, lane_e, wm, wn, stg, y, m0, n0, N);
-            else epilogue_interior<AccF32x64, BM, BN, TM, TN, false>(acc, s_tile, bias != nullptr, lane_e, wm, wn, stg, y, m0, n0, N);
+            if (w_zero) {
+                if (bias) epilogue_interior<AccF32x64, BM, BN, TM, TN, true, 1>(acc, s_tile, true, lane_e, wm, wn, stg, y, m0, n0, N);
+                else epilogue_interior<AccF32x64, BM, BN, TM, TN, true, 0>(acc, s_tile, true, lane_e, wm, wn, stg, y, m0, n0, N);
+            } else {
+                if (bias) epilogue_interior<AccF32x64, BM, BN, TM, TN, false, 1>(acc, s_tile, true, lane_e, wm, wn, stg, y, m0, n0, N);
+                else epilogue_interior<AccF32x64, BM, BN, TM, TN, false, 0>(acc, s_tile, true, lane_e, wm, wn, stg, y, m0, n0, N);
+            }
         } else {
             epilogue_edge<AccF32x64, BM, BN, TM, TN>(acc, s_tile, bias, w_zero, lane_e, wm, wn, y, acc_out, m0, n0, M, N);
         }

@@ -352,10 +352,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
             if (KT >= STAGES) store_credit = STAGES - 1 - AHEAD;
             uint8_t *stg = smem + (q % STAGES) * STAGE + wave * 4096;
             __builtin_amdgcn_s_barrier();   // every wave is done reading the last slice: its buffer stages the tile
-            // Two specializations, with and without weight zero-points, chosen once per tile: inside the
-            // unrolled loops a run-time test of the pointer would cost a branch per element.
-            if (w_zero) epilogue_interior<Acc, BM, BN, TM, TN, true>(acc, s_tile, bias != nullptr, lane, wm, wn, stg, y, m0, n0, N);
-            else epilogue_interior<Acc, BM, BN, TM, TN, false>(acc, s_tile, bias != nullptr, lane, wm, wn, stg, y, m0, n0, N);
+            // Two specializations, with and without weight zero-points, chosen once per tile (with four, bias as
+            // well, this kernel spills).
+            if (w_zero) epilogue_interior<Acc, BM, BN, TM, TN, true, -1>(acc, s_tile, bias != nullptr, lane, wm, wn, stg, y, m0, n0, N);
+            else epilogue_interior<Acc, BM, BN, TM, TN, false, -1>(acc, s_tile, bias != nullptr, lane, wm, wn, stg, y, m0, n0, N);
         } else {
             epilogue_edge<Acc, BM, BN, TM, TN>(acc, s_tile, bias, w_zero, lane, wm, wn, y, acc_out, m0, n0, M, N);
         }

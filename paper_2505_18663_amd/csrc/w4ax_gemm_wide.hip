@@ -478,8 +478,12 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
             // ---- interior tile: no predicates; channel vectors fetched one register group ahead; the bf16 tile
             // is transposed through LDS, 32 tokens x 64 channels at a time, into whole-line streaming stores
             if (KT >= 2) store_credit = 1;
-            auto interior = [&] __device__(auto has_zero) __attribute__((always_inline)) {
-                constexpr bool ZP = decltype(has_zero)::value;
+            // Four specializations (zero-points, bias), chosen once per tile: inside the unrolled units a run-time
+            // test costs a branch each, and a lone wave per SIMD pays every taken branch with an idle front end.
+            auto interior = [&] __device__(auto has_zero, auto has_bias) __attribute__((always_inline)) {
+                // (scale, then add the bias, each rounded: a fused multiply-add would differ from the per-element path in the last bit)
+#pragma clang fp contract(off)
+                constexpr bool ZP = decltype(has_zero)::value, BIAS = decltype(has_bias)::value;
                 int lane_e = lane;   // (keeps the epilogue's lane-dependent addresses out of the K loop's registers)
                 asm volatile("" : "+v"(lane_e));
                 const int frow = lane_e & 31, fhalf = lane_e >> 5;
@@ -502,11 +506,12 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                 auto fetch = [&] __device__(ChannelVec &cv, int i, int g) {
                     const int c = i * 32 + g * 8;
                     cv.ws = *reinterpret_cast<const float4 *>(ws_l + c);
-                    if (bias) cv.bb = *reinterpret_cast<const uint2 *>(bias_l + c / 2);
+                    if constexpr (BIAS) cv.bb = *reinterpret_cast<const uint2 *>(bias_l + c / 2);
                     if constexpr (ZP) cv.zq = zero_l[c / 4];
                 };
-                ChannelVec cv[2];
-                fetch(cv[0], 0, 0);
+                // The 8 channel vectors of a pair of MFMA tile columns serve all TM token blocks: fetched once per pair
+                // into registers (the operand fragments' registers are free here), not once per unit.
+                ChannelVec cv[8];
                 uint32_t pk[2][2];
                 uint4 pend[4];            // a staged chunk on its way back from LDS, and where it goes
                 uint16_t *pend_y = y;
@@ -515,11 +520,11 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                 static_for<(TN / 2) * TM * 8>([&](auto u_c) __attribute__((always_inline)) {
                     constexpr int U = decltype(u_c)::value, q = U & 3, h = U & 1, g = q - h, ii = (U >> 2) & 1;
                     constexpr int j = (U >> 3) % TM, ip = U / (8 * TM), i = 2 * ip + ii;
-                    if constexpr (U + 1 < (TN / 2) * TM * 8) {   // the unit after this one: its channel vectors
-                        constexpr int UN = U + 1;
-                        fetch(cv[UN & 1], 2 * (UN / (8 * TM)) + ((UN >> 2) & 1), UN & 3);
+                    if constexpr (U % (8 * TM) == 0) {
+#pragma unroll
+                        for (int v = 0; v < 8; ++v) fetch(cv[v], 2 * ip + (v >> 2), v & 3);
                     }
-                    const ChannelVec &c = cv[U & 1];
+                    const ChannelVec &c = cv[ii * 4 + q];
                     const v4i raw = read_acc4<i * TM + j, q>();
                     float o[4];
 #pragma unroll
@@ -537,7 +542,7 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                     o[1] *= c.ws.y;
                     o[2] *= c.ws.z;
                     o[3] *= c.ws.w;
-                    if (bias) {
+                    if constexpr (BIAS) {
                         o[0] += __uint_as_float(c.bb.x << 16);
                         o[1] += __uint_as_float(c.bb.x & 0xFFFF0000u);
                         o[2] += __uint_as_float(c.bb.y << 16);
@@ -583,8 +588,13 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
 #pragma unroll
                 for (int pass = 0; pass < 4; ++pass) store_streaming16(pend_y + (int64_t)pass * 8 * N, pend[pass]);   // the last chunk
             };
-            if (w_zero) interior(std::true_type{});
-            else interior(std::false_type{});
+            if (w_zero) {
+                if (bias) interior(std::true_type{}, std::true_type{});
+                else interior(std::true_type{}, std::false_type{});
+            } else {
+                if (bias) interior(std::false_type{}, std::true_type{});
+                else interior(std::false_type{}, std::false_type{});
+            }
         } else {
             // ---- edge tiles, N not a multiple of 8, or the accumulator hook: predicated per element, through the
             // integer accumulator (same values and rounding order as the interior path)
