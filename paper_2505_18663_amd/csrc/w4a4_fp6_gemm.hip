@@ -131,7 +131,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_ker
             int m0, n0;
             tile_origin(issue_no, tiles_m, tiles_n, group_n, BM, BN, m0, n0);
             a_base = uniform_ptr(codes + (int64_t)min(m0 / 32 + wave, last_block) * KT * kFp6Block);
-            w_base = uniform_ptr(w + (int64_t)(n0 / kGroup) * kFp6Block);
+            w_base = uniform_ptr(w + (int64_t)(n0 / kGroup) * kFp6Block + wave * W_DMA * 1024);   // (this wave's pieces)
             const uint32_t sc = smem_base + STAGES * STAGE + (issue_tile & 1) * SCALES;
 #pragma unroll
             for (int j = 0; j < (BM + BN) / 64; ++j) {
@@ -162,12 +162,26 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4a4_fp6_gemm_ker
         }
         issue_sa = smem_base + buf * STAGE;
     };
-    auto issue_one = [&] __device__(int idx) {
-        if (idx < A_DMA)
-            lds_direct_load16(a_base + idx * 1024, lane16, issue_sa + (wave * A_DMA + idx) * 1024);
-        else
-            lds_direct_load16(w_base + (wave * W_DMA + idx - A_DMA) * 1024, lane16,
-                              issue_sa + A_STAGE + (wave * W_DMA + idx - A_DMA) * 1024);
+    // Piece idx of the wave's DMA (a constant wherever it is called: the switch folds away).  The code pieces and
+    // the weight pieces are runs whose source and destination both advance by 1 KB: the first of a run sets M0,
+    // the others reuse it and move by the instruction offset (weight pieces 4 .. through a second lane offset).
+    static_assert(A_DMA == 3 && W_DMA <= 8, "piece runs");
+    const uint32_t lane16_hi = lane16 + 4096;
+    auto issue_one = [&] __device__(int idx) __attribute__((always_inline)) {
+        const uint32_t sa_a = issue_sa + wave * A_DMA * 1024, sa_w = issue_sa + A_STAGE + wave * W_DMA * 1024;
+        switch (idx) {
+            case 0: lds_direct_load16(a_base, lane16, sa_a); break;
+            case 1: lds_direct_load16_more<1024>(a_base, lane16); break;
+            case 2: lds_direct_load16_more<2048>(a_base, lane16); break;
+            case 3: lds_direct_load16(w_base, lane16, sa_w); break;
+            case 4: lds_direct_load16_more<1024>(w_base, lane16); break;
+            case 5: lds_direct_load16_more<2048>(w_base, lane16); break;
+            case 6: lds_direct_load16_more<3072>(w_base, lane16); break;
+            case 7: lds_direct_load16(w_base, lane16_hi, sa_w + 4096); break;
+            case 8: lds_direct_load16_more<1024>(w_base, lane16_hi); break;
+            case 9: lds_direct_load16_more<2048>(w_base, lane16_hi); break;
+            default: lds_direct_load16_more<3072>(w_base, lane16_hi); break;
+        }
     };
     auto issue_advance = [&] __device__() {
         if (!issue_live) return;

@@ -198,12 +198,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void w4ax_gemm_native_
         }
         issue_sa = smem_base + buf * STAGE;
     };
-    auto issue_one = [&] __device__(int idx) {
-        if (idx < A_DMA)
+    // (idx is a constant wherever this is called.  With 128-channel slices the weight pieces of a wave are one
+    // run in memory and in LDS: the first sets M0, the others reuse it and move by the instruction offset; the
+    // loops below issue a wave's pieces in ascending order, weight pieces last, so nothing comes between them.)
+    auto issue_one = [&] __device__(int idx) __attribute__((always_inline)) {
+        if (idx < A_DMA) {
             lds_direct_load16(a_base, a_voff[idx], issue_sa + (wave * A_DMA + idx) * 1024);
-        else
+        } else if (W_PIECE != 1024 || W_DMA > 4 || idx == A_DMA) {
             lds_direct_load16(w_base + (wave * W_DMA + idx - A_DMA) * W_PIECE, lane16,
                               issue_sa + A_STAGE + (wave * W_DMA + idx - A_DMA) * 1024);
+        } else {
+            const uint8_t *run = w_base + wave * W_DMA * 1024;
+            switch (idx - A_DMA) {
+                case 1: lds_direct_load16_more<1024>(run, lane16); break;
+                case 2: lds_direct_load16_more<2048>(run, lane16); break;
+                default: lds_direct_load16_more<3072>(run, lane16); break;
+            }
+        }
     };
     auto issue_advance = [&] __device__() {
         if (!issue_live) return;
