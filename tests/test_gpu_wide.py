@@ -19,6 +19,7 @@ def _library_defaults():
     yield
     dvdq.bench_set_gemm_schedule(-1)
     dvdq.bench_set_gemm_variant(-1)
+    dvdq.bench_set_gemm_grid_limit(0)
 
 
 def _case(M, K, N, bits, seed, fp6):
@@ -124,3 +125,21 @@ def test_wide_kernel_many_launches_in_a_row(fp6):
             torch.cuda.synchronize()
             assert torch.equal(ya.view(torch.int16), ya_ref.view(torch.int16)), f"iteration {it}"
             assert torch.equal(yb.view(torch.int16), yb_ref.view(torch.int16)), f"iteration {it}"
+
+
+@pytest.mark.parametrize("fp6", [False, True])
+@pytest.mark.parametrize("K", [128, 256, 384, 640, 1152])
+def test_wide_kernel_with_few_workgroups_walking_many_tiles(K, fp6):
+    """8 and 24 workgroups for 20 x 5 tiles: every workgroup goes through several tiles in a row (tile draws or fixed
+    shares, the load pipeline across tile boundaries, the epilogue's staging buffer) at one to nine K slices per tile"""
+    c = _case(5000, K, 1160, 4, 500 + K, fp6)
+    wide = WIDE_FP6 if fp6 else WIDE_INT8
+    extra = dict(bias=c["bias"]) if K % 256 else {}
+    y_ref = _run(c, -1, **extra)
+    for limit in (8, 24):
+        dvdq.bench_set_gemm_grid_limit(limit)
+        for schedule in (0, -1):
+            print(f"wide K{K} fp6={fp6} workgroups {limit} schedule {schedule}", flush=True)
+            y = _run(c, wide, schedule, **extra)
+            assert torch.equal(y.view(torch.int16), y_ref.view(torch.int16)), (K, limit, schedule)
+    dvdq.bench_set_gemm_grid_limit(0)
