@@ -430,8 +430,9 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                 wait_vmcnt<DMA>();
             }
             before_barrier();
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            __builtin_amdgcn_s_barrier();
+            // (the barrier itself stands inside both branches below: the branch is then taken in the shadow of the
+            // step's last MFMA, not between the barrier's release and the next step's first MFMA; the comments in
+            // the asm statements keep the compiler from merging the two copies again)
             // the last step of slice q multiplies while step 0 of slice q + 1 is fetched (past the workgroup's
             // last slice: a stale but in-bounds buffer, never used)
             auto rotate = [&] __device__(auto p_c) __attribute__((always_inline)) {
@@ -443,6 +444,8 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                 }
             };
             if (FP6 && kt + 1 < KT) {
+                asm volatile("; slice barrier, loads follow\n\ts_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
                 // FP6 path, not the tile's last slice: the barrier has freed the buffer of slice q, which takes slice
                 // q + 3; its addresses (and, at a tile's start, the tile's vectors and the next draw) behind the first
                 // MFMA, its pieces 0-5 behind every other MFMA from the third on
@@ -452,6 +455,8 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                 };
                 mfma_step(I<0>{}, f1, f0, nxt_off, I<0>{}, I<0>{}, I<DMA / 2>{}, I<2>{}, I<2>{}, early);
             } else {
+                asm volatile("; slice barrier\n\ts_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
                 mfma_step(I<0>{}, f1, f0, nxt_off, I<0>{}, I<0>{}, I<0>{}, I<0>{}, I<1>{}, rotate);
             }
         }
