@@ -294,6 +294,6 @@ const char *dvdq_status_string(int status) {
     }
 }
 
-int dvdq_version(void) { return 220; }
+int dvdq_version(void) { return 230; }
 
 }  // extern "C"
