@@ -47,8 +47,13 @@ static __device__ __forceinline__ void wait_vmcnt() {
 // outstanding LDS-direct loads (it cannot tell the ring buffers apart), which
 // serializes the pipeline.  Completion is awaited by hand (wait_vmcnt) before the
 // workgroup barrier that publishes a buffer.
+// (The wait states cover two hazards the compiler cannot see inside the statement: M0 written by the s_mov
+// needs one before an LDS-direct load, and a scalar register written by a vector instruction -- a base address
+// the compiler has just reloaded with v_readlane or made uniform with v_readfirstlane -- needs five before a
+// vector memory instruction reads it: the load would otherwise go to whatever address the register pair held
+// before.)
 static __device__ __forceinline__ void lds_direct_load16(const void *sbase, uint32_t voff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 3\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
                  : "v"(voff), "s"(sbase), "s"(lds_base)
                  : "memory");
@@ -57,7 +62,9 @@ static __device__ __forceinline__ void lds_direct_load16(const void *sbase, uint
 // Follow-up of lds_direct_load16 with the same M0: the instruction offset OFF is added to the global address
 // and to the LDS address alike (checked on the hardware), so a run of loads whose source and destination
 // advance by the same number of bytes needs one M0 and one base address.  No other M0 write may stand
-// between it and the load that set M0 (the kernels that use it check their assembly for that).
+// between it and the load that set M0, and the base address must not have been written by a vector instruction
+// within the last five wait states (it is the register pair the run's first load used; tests/test_kernel_asm.py
+// checks both on the kernels' assembly).
 template <int OFF>
 static __device__ __forceinline__ void lds_direct_load16_more(const void *sbase, uint32_t voff) {
     static_assert(OFF > 0 && OFF < 4096, "13-bit signed instruction offset");
@@ -73,7 +80,7 @@ static __device__ __forceinline__ int swz_bk(int row) { return BK == 128 ? ((row
 
 // Same, 4 bytes per lane (LDS address lds_base + 4 * lane): used for the per-tile scale vectors.
 static __device__ __forceinline__ void lds_direct_load4(const void *sbase, uint32_t voff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 3\n\tglobal_load_lds_dword %0, %1"
                  :
                  : "v"(voff), "s"(sbase), "s"(lds_base)
                  : "memory");

@@ -17,8 +17,10 @@
 // step, whose fragments are already in registers).
 //
 // Ring: three buffers of one 128-channel slice of both operands (48 KB).  In iteration q the waves multiply
-// slice q, slice q+1 is landing and the loads of slice q+2 are dealt out between the MFMAs; the barrier of
-// iteration q publishes slice q+1 and frees buffer q % 3 for slice q+3.  Everything else -- LDS-direct loads
+// slice q, slice q+1 is landing and loads of slice q+2 are dealt out between the MFMAs (INT8 path: all twelve
+// per wave; FP6 path: its second half, the first half having gone out behind the last step of slice q-1, and
+// behind the last step of slice q the first half of slice q+3); the barrier of iteration q publishes slice
+// q+1 and frees buffer q % 3 for slice q+3.  Everything else -- LDS-direct loads
 // with hand-kept vmcnt, persistent workgroups drawing tiles per XCD, tile scales staged in LDS, whole-line
 // epilogue through the ring buffer that was consumed last -- follows w4ax_gemm.hip.
 //
@@ -383,9 +385,9 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
     int store_credit = 0, tile_j = 0;
     for (;;) {
         for (int kt = 0; kt < KT; ++kt) {
-            // Steps 0 .. last - 1 of slice q, the loads of slice q + 2 dealt out between their MFMAs.  The scalar
-            // bookkeeping of the load pipeline stands behind MFMAs as well: the addresses of slice q + 2 (it goes where
-            // slice q - 1 was) behind the first one, the advance to slice q + 3 behind one after the last load.
+            // Steps 0 .. last - 1 of slice q, loads of slice q + 2 dealt out between their MFMAs.  The scalar
+            // bookkeeping of the load pipeline stands behind MFMAs as well: the addresses of a slice (it goes where
+            // slice q - 1 was) behind the MFMA before its first load, the advance to the next behind MFMAs after its last.
             // (A tile's very first step starts its accumulators from zero: that step exists twice in the code.)
             auto none = [] __device__(auto) __attribute__((always_inline)) {};
             if constexpr (FP6) {
