@@ -583,7 +583,7 @@ int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w
     const int m = (int)M, n = (int)N, k = (int)K;
 #define DVDQ_GEMM_ARGS codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, m, n, k, y, acc_out, stream
     // Tile variants: {tile M, tile N, K slice, waves M x N, ring depth, workgroups per compute unit}.
-    // Variant 2 is the default for every shape: two independent 4-wave workgroups per compute unit,
+    // Variant 2 is the default of the two-wave kernels for every shape: two independent 4-wave workgroups per compute unit,
     // each owning a 128 x 256 tile (64 x 128 per wave) with K slices of 128 through two buffers.  In
     // interleaved sweeps over the DiT shapes (K = 1536 ... 13824) it was fastest or within 1 % of the
     // fastest: while one workgroup converts and stores its tile the other keeps the matrix cores busy,
@@ -601,10 +601,11 @@ int launch_w4ax_gemm(const int8_t *codes, const float *x_scale, const uint8_t *w
             default: return DVDQ_ERR_UNSUPPORTED;
         }
     }
-    // Variant 5 is the wide kernel of w4ax_gemm_wide.hip (int8 codes only): it pays when a tile has many K
-    // slices (4 % faster at K = 13824, slower below K = 4096), and is taken by itself from K = 8192 on when
-    // there are at least two rounds of 256 x 256 tiles.
-    if (forced < 0 && codes_format == DVDQ_CODES_INT8 && k / 128 >= 64 && ((M + 255) / 256) * ((N + 255) / 256) >= 512) v = 5;
+    // Variant 5 is the wide kernel of w4ax_gemm_wide.hip (int8 codes only).  Measured on the DiT shapes it is 2 %
+    // (K = 1536) to 6 % (K = 3072) faster than variant 2 and level with it at K = 13824; it is taken by itself when
+    // a tile has at least 12 K slices and there are at least two rounds of 256 x 256 tiles (fewer tiles are dealt
+    // out more evenly in variant 2's 128 x 256 pieces).
+    if (forced < 0 && codes_format == DVDQ_CODES_INT8 && k / 128 >= 12 && ((M + 255) / 256) * ((N + 255) / 256) >= 512) v = 5;
     if (v == 5)
         return launch_w4ax_gemm_wide(reinterpret_cast<const uint8_t *>(codes), x_scale, w, w_scale, w_zero, code_rowsum, bias,
                                      M, N, K, false, y, acc_out, stream);

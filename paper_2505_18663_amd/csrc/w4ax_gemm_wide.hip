@@ -102,19 +102,30 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
     typedef volatile __attribute__((address_space(3))) int lds_int;
     lds_int *s_tiles = (lds_int *)DVDQ_LDS(smem + STAGES * STAGE + 3 * SCALES);
     // Fixed shares (no counters): the ordinal-th tile of this workgroup follows from its number alone, which
-    // every wave computes for itself.  Drawn tiles (K / 128 >= 2): the number drawn while slice `draw_kt` of tile n
-    // is issued belongs to tile n + 2; wave 0 writes it into the ring before the barrier after next (by then the
-    // loads issued around the atomic have been awaited, so its reply is there), two barriers before it is
-    // read.  Draws are at least two slices apart, so at most one is pending.
+    // every wave computes for itself.  Drawn tiles (K / 128 >= 2), two protocols:
+    // FP6 path: the number drawn while slice `draw_kt` of tile n is issued belongs to tile n + 2; wave 0 writes it
+    //   into the ring before the barrier after next (by then the loads issued around the atomic have been
+    //   awaited, so its reply is there), two barriers before it is read.  Draws are at least two slices apart,
+    //   so at most one is pending.
+    // INT8 path: the number of tile n + 2 is drawn by wave 0 at the start of the epilogue of tile n and written
+    //   into the ring in front of that tile's first stores; the workgroup barrier that closes the epilogue makes
+    //   it visible; it is first read when slice 0 of tile n + 2 is issued, during tile n + 1.
+    // Why two: a reply that stays pending across loop iterations lives in a register the compiler may copy, and
+    // it waits for every outstanding vector memory operation of the wave in front of such a copy.  In the INT8
+    // kernel it put one into the K loop (5 % of the kernel's time); in the FP6 kernel it does not (a test on the
+    // assembly watches that), and there the epilogue protocol costs more than it saves: wave 0 waits for the
+    // reply about a thousand clocks into every epilogue, 10 % on tiles of twelve slices.
+    constexpr bool DRAW_IN_EPILOGUE = !FP6;
     int published = 2;       // tile numbers written into the ring
     unsigned drawn = 0;      // wave 0, lane 0: reply of the pending draw
     int draw_wait = 0;       // barriers until the pending draw is written into the ring (0: none pending)
     auto draw = [&] __device__() {
-        if (!tiles.ctr) return;
+        if (DRAW_IN_EPILOGUE || !tiles.ctr) return;
         if (wave == 0 && lane == 0) drawn = tiles.draw();
         draw_wait = 2;
     };
     auto before_barrier = [&] __device__() {   // every wave, before each workgroup barrier of the pipeline
+        if constexpr (DRAW_IN_EPILOGUE) return;
         draw_wait = __builtin_amdgcn_readfirstlane(draw_wait);   // (wave-uniform: keep it in a scalar register)
         if (__builtin_expect(draw_wait > 0, 0) && --draw_wait == 0) {
             if (wave == 0) {
@@ -473,6 +484,14 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
         tile_origin(comp_tile, tiles_m, tiles_n, group_n, BM, BN, m0, n0);
         ++tile_j;
         comp_tile = tile_number(tile_j);   // the next one (its loads are under way)
+        // INT8 path: the number of the tile after next, requested now and written into the ring in front of this
+        // tile's first stores (behind them the compiler's wait for the reply would be the stores' round trip)
+        const bool drawer = DRAW_IN_EPILOGUE && tiles.ctr && comp_tile >= 0 && wave == 0 && lane == 0;
+        unsigned draw_reply = 0;
+        if (drawer) draw_reply = tiles.draw();
+        auto publish_draw = [&] __device__() {
+            if (drawer) s_tiles[(tile_j + 1) & 7] = tiles.tile(draw_reply, 0);
+        };
         const bool vec8 = (N & 7) == 0;
         const uint8_t *s_tile = smem + STAGES * STAGE + ((tile_j - 1) % 3) * SCALES;
         const float *s_xs = reinterpret_cast<const float *>(s_tile);
@@ -572,6 +591,7 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                     }
                     // A staged chunk is read back right away (its LDS round trip then runs under the next chunk's
                     // arithmetic; two staging areas alternate) and stored to memory half a chunk later.
+                    if constexpr (U == 11) publish_draw();
                     if constexpr ((U & 7) == 3 && U > 8) {
 #pragma unroll
                         for (int pass = 0; pass < 4; ++pass) store_streaming16(pend_y + (int64_t)pass * 8 * N, pend[pass]);
@@ -688,10 +708,11 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                     }
                 }
             });
+            publish_draw();
         }
         if (comp_tile < 0) break;
         // the staging buffer is the one the next slice's loads go to: nobody may issue them before everyone
-        // has stored its part of the tile
+        // has stored its part of the tile (the same barrier makes a ring entry written in the epilogue visible)
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
     }

@@ -143,9 +143,8 @@ def test_loads_that_reuse_m0_follow_the_load_that_set_it(kernels):
     assert chained > 0
 
 
-# kernels the default dispatch takes on the benchmark's workloads (the INT8 wide kernel, taken only for int8 codes
-# with K >= 8192, is known to carry one such wait in its loop and is reported, not asserted)
-HOT = ("w4ax_gemm_wide_kernelILb1", "w4a4_fp6_gemm_kernel", "w4ax_gemm_native_kernel")
+# every persistent GEMM kernel of the three files
+HOT = ("w4ax_gemm_wide_kernel", "w4a4_fp6_gemm_kernel", "w4ax_gemm_native_kernel")
 
 
 def test_no_wait_for_all_memory_operations_inside_the_k_loops(kernels):
