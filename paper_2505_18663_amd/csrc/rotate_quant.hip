@@ -310,7 +310,17 @@ __global__ __launch_bounds__(1024) void rotate_quant_kernel(
                     for (int i = 0; i < 4; ++i) {
                         qa[4 * g + i] = fmaf(v[c0 + g][2 * i], r, magic) - magic;
                         qb[4 * g + i] = fmaf(v[c0 + g][2 * i + 1], r, magic) - magic;
-                        if (code_rowsum) fsum += qa[4 * g + i] + qb[4 * g + i];
+                    }
+                }
+                if (code_rowsum) {
+                    // (the empty volatile statement keeps the additions inside this branch: without it the
+                    // compiler adds in every launch and selects afterwards, a tenth of the loop's vector work)
+                    asm volatile("" : "+v"(fsum));
+#pragma unroll
+                    for (int g = 0; g < 4 && c0 + g < CPW; ++g) {
+                        if (!present(c0 + g)) continue;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) fsum += qa[4 * g + i] + qb[4 * g + i];
                     }
                 }
                 v6u pk;

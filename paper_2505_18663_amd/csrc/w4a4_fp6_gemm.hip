@@ -387,12 +387,13 @@ int launch_w4a4_fp6_gemm(const uint8_t *codes, const float *x_scale, const uint8
     //      no second workgroup hides its epilogue.  Taken when there are at least two rounds of such tiles
     //      and K is deep enough for the ring; the benchmark hook can force either.
     //   3: the wide kernel of w4ax_gemm_wide.hip: one 4-wave workgroup, 256 x 256 tiles, 128 x 128 wave tiles with
-    //      the accumulators in AGPRs: a third fewer LDS fragment bytes per MFMA, but nothing hides a tile's
-    //      epilogue, so it pays when a tile has many K slices (measured on the DiT shapes: 4 % faster at
-    //      K = 3072, 8 % at K = 13824, 7 % slower at K = 1536).
+    //      the accumulators in AGPRs: a third fewer LDS fragment bytes per MFMA and a K slice in 60 % of
+    //      variant 2's time, but a larger fixed cost per tile (nothing hides its epilogue), so it pays from
+    //      ten K slices on (whole layer steps on a 32760 x 4608 output, variant 3 against variant 2: 14 %
+    //      slower at K = 512, 5 % at 768, equal at 1024, 3 % faster at 1280, 7 % at 1536, 8 % at 2048).
     int v = gemm_variant();
     const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
-    if (v != 1 && v != 2 && v != 3) v = big_tiles >= 512 ? (K / kBK >= 20 ? 3 : 2) : 1;
+    if (v != 1 && v != 2 && v != 3) v = big_tiles >= 512 ? (K / kBK >= 10 ? 3 : 2) : 1;
     if (K / kBK < 2 && v == 2) v = 1;
     if (v == 3) return launch_w4ax_gemm_wide(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, M, N, K, true, y, acc_out, stream);
     if (v == 2) return launch_fp6<256, 256, 4, 2, 3, 1>(DVDQ_FP6_ARGS);
