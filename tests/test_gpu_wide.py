@@ -143,3 +143,22 @@ def test_wide_kernel_with_few_workgroups_walking_many_tiles(K, fp6):
             y = _run(c, wide, schedule, **extra)
             assert torch.equal(y.view(torch.int16), y_ref.view(torch.int16)), (K, limit, schedule)
     dvdq.bench_set_gemm_grid_limit(0)
+
+
+@pytest.mark.parametrize("K", [1152, 1280])
+def test_default_dispatch_around_the_fp6_wide_kernel_threshold(K):
+    """512 tiles of 256 x 256 (two rounds of them on the chip): below ten K slices the library takes the 8-wave FP6
+    kernel by itself, from ten on the wide one.  Whatever it takes must equal both kernels forced, bit for bit, and
+    the integer contraction of the oracle on a sample of token rows."""
+    M, N = 4096, 8192
+    print(f"dispatch threshold K{K}", flush=True)
+    c = _case(M, K, N, 4, 9000 + K, True)
+    y_default, acc = _run(c, -1, want_acc=True)
+    rows = np.r_[0:24, 2040:2056, M - 24:M]
+    acc_or = oracle.int_gemm(c["codes"][rows], c["wc"])
+    assert np.array_equal(acc.cpu().numpy()[rows].astype(np.int64), acc_or)
+    y_plain = _run(c, -1)
+    assert torch.equal(y_plain.view(torch.int16), y_default.view(torch.int16))
+    for variant in (1, 2, WIDE_FP6):
+        y = _run(c, variant)
+        assert torch.equal(y.view(torch.int16), y_plain.view(torch.int16)), f"variant {variant}"
