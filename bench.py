@@ -264,12 +264,12 @@ class Bench:
         rq_gbps = rq_bytes / (r["rq_avg"] * 1e-3) / 1e9
         traffic, src = profile_traffic(wl.name)
         # (whichever kernel the library's dispatch took for this shape: the summary holds the kernels of this workload's run)
-        gemm_traffic = first_match(traffic, r"dvdq::(w4a4_fp6_gemm_kernel<|w4ax_gemm_wide_kernel<true>)" if use_fp6 else
+        gemm_traffic = first_match(traffic, r"dvdq::(w4a4_fp6_gemm_kernel<|w4ax_gemm_wide_kernel<true, )" if use_fp6 else
                                    (r"dvdq::w4ax_gemm_native_kernel<.*, true>" if p["fmt_name"] == "packed4" else
-                                    r"dvdq::(w4ax_gemm_native_kernel<.*, false>|w4ax_gemm_wide_kernel<false>)"))
-        gemm_symbol = first_match(traffic, r"dvdq::(w4a4_fp6_gemm_kernel<|w4ax_gemm_wide_kernel<true>)" if use_fp6 else
+                                    r"dvdq::(w4ax_gemm_native_kernel<.*, false>|w4ax_gemm_wide_kernel<false, )"))
+        gemm_symbol = first_match(traffic, r"dvdq::(w4a4_fp6_gemm_kernel<|w4ax_gemm_wide_kernel<true, )" if use_fp6 else
                                   (r"dvdq::w4ax_gemm_native_kernel<.*, true>" if p["fmt_name"] == "packed4" else
-                                   r"dvdq::(w4ax_gemm_native_kernel<.*, false>|w4ax_gemm_wide_kernel<false>)"), want_name=True)
+                                   r"dvdq::(w4ax_gemm_native_kernel<.*, false>|w4ax_gemm_wide_kernel<false, )"), want_name=True)
         rq_traffic = first_match(traffic, r"dvdq::rotate_quant_kernel<\d+, \d+, %d>" % {"int8": 0, "packed4": 1, "fp6": 2}[p["fmt_name"]])
         entry = {
             "workload": wl.name, "M": M, "K": K, "N": N, "had_block": B, "act_bits": bits,

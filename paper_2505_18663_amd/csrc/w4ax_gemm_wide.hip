@@ -22,7 +22,12 @@
 // behind the last step of slice q the first half of slice q+3); the barrier of iteration q publishes slice
 // q+1 and frees buffer q % 3 for slice q+3.  Everything else -- LDS-direct loads
 // with hand-kept vmcnt, persistent workgroups drawing tiles per XCD, tile scales staged in LDS, whole-line
-// epilogue through the ring buffer that was consumed last -- follows w4ax_gemm.hip.
+// epilogue through the ring buffer that was consumed last -- follows w4ax_gemm.hip.  The epilogue stages 4 KB
+// per wave in the weight half of that buffer; on the FP6 path (tiles of three slices or more) its code half is
+// filled meanwhile with the first half of the next tile's slice 2, so that the loads cross a tile boundary in the
+// same order as inside a tile and a tile's first step issues six loads, not twelve, behind the stores of the
+// tile before (measured per tile on K = 1536: 970 of 27300 clocks less on 32 workgroups, 1280 of 28600 on the
+// whole chip, where the output of all compute units leaves at once and the loads queue behind it).
 //
 // What the single wave per SIMD is sensitive to (measured with shader-clock timestamps around the steps and
 // with register-only loops): an FP6 MFMA occupies the pipe for 32 clocks and the wave issues about six other
@@ -62,7 +67,11 @@ __device__ __forceinline__ void static_for(F &&f) {
 
 }  // namespace
 
-template <bool FP6>
+// ACROSS (FP6 path, tiles of three K slices or more): the load pipeline runs across tile boundaries exactly as
+// inside a tile.  A kernel of its own rather than a run-time flag: with both orders in one loop the compiler copies
+// registers at the loop's edges, among them the pending reply of the tile draw, and waits for every outstanding
+// load in front of such a copy.
+template <bool FP6, bool ACROSS>
 __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
     const uint8_t *__restrict__ codes, const float *__restrict__ x_scale, const uint8_t *__restrict__ w,
     const float *__restrict__ w_scale, const int8_t *__restrict__ w_zero, const int32_t *__restrict__ code_rowsum,
@@ -82,7 +91,8 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
     constexpr int STORES = TM * TN * 2;                      // 16-byte store instructions per wave per full tile
     static_assert(STAGE == 48 * 1024 && DMA == 12, "ring geometry");
     static_assert(DMA + STORES < 64 && (STAGES - 1) * DMA + 8 < 64, "vmcnt is 6 bits");
-    static_assert(NW * 8192 <= STAGE, "the epilogue stages 2 x 4 KB per wave in one ring buffer");
+    static_assert(FP6 || !ACROSS, "the INT8 path issues a slice's loads in one piece");
+    static_assert(NW * 4096 <= W_STAGE, "the epilogue stages 4 KB per wave in the weight half of one ring buffer");
 
     extern __shared__ __align__(16) uint8_t smem[];
     const uint32_t smem_base = lds_address(smem);
@@ -235,14 +245,18 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
     // code block, weight pieces 0-3 and 4-5), the INT8 path once per code piece and once for its four weight pieces.
     auto issue_one = [&] __device__(auto idx_c) __attribute__((always_inline)) {
         constexpr int idx = decltype(idx_c)::value;
+        // (the LDS addresses are wave-uniform, but short of scalar registers the compiler may keep them in a vector
+        // register across a step and would then hand that register to the load's scalar operand: the explicit
+        // first-lane read makes it a scalar again, and is nothing where the value already is one)
+        auto sa = [] __device__(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); };
         if constexpr (FP6) {
-            if constexpr (idx == 0) lds_direct_load16(a_base, lane16, issue_sa_a);
+            if constexpr (idx == 0) lds_direct_load16(a_base, lane16, sa(issue_sa_a));
             else if constexpr (idx < 3) lds_direct_load16_more<idx * 1024>(a_base, lane16);
-            else if constexpr (idx == 3) lds_direct_load16(a_base2, lane16, issue_sa_a + 3072);
+            else if constexpr (idx == 3) lds_direct_load16(a_base2, lane16, sa(issue_sa_a + 3072));
             else if constexpr (idx < A_DMA) lds_direct_load16_more<(idx - 3) * 1024>(a_base2, lane16);
-            else if constexpr (idx == A_DMA) lds_direct_load16(w_base, lane16, issue_sa_w);
+            else if constexpr (idx == A_DMA) lds_direct_load16(w_base, lane16, sa(issue_sa_w));
             else if constexpr (idx < A_DMA + 4) lds_direct_load16_more<(idx - A_DMA) * 1024>(w_base, lane16);
-            else if constexpr (idx == A_DMA + 4) lds_direct_load16(w_base, lane16_hi, issue_sa_w + 4096);
+            else if constexpr (idx == A_DMA + 4) lds_direct_load16(w_base, lane16_hi, sa(issue_sa_w + 4096));
             else lds_direct_load16_more<(idx - A_DMA - 4) * 1024>(w_base, lane16_hi);
         } else {
             if constexpr (idx < A_DMA) lds_direct_load16(a_base, a_voff[idx], issue_sa_a + idx * 1024);
@@ -393,6 +407,11 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
 
     // LDS byte offsets of the ring buffers holding slice q (being multiplied), q + 1 and q + 2 (being issued)
     uint32_t cur_off = 0, nxt_off = STAGE, fill_off = 2 * STAGE;
+    // ACROSS: the first half of slice 2 is under way before the loop, like the halves issued behind a slice's last step
+    if constexpr (ACROSS) {
+        issue_prepare(fill_off);
+        static_for<DMA / 2>([&](auto d_c) __attribute__((always_inline)) { issue_one(d_c); });
+    }
     int store_credit = 0, tile_j = 0;
     for (;;) {
         for (int kt = 0; kt < KT; ++kt) {
@@ -406,9 +425,17 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                 // requested within one step (16 MFMAs, 512 clocks) without the load instructions backing up and
                 // holding the MFMAs behind them.  So pieces 0-5 of slice q + 2 went out behind the last step of slice
                 // q - 1 (its buffer was free from that slice's barrier on) and pieces 6-11 go out here, one every
-                // other MFMA.  Only a tile's first slice issues all twelve here: the step behind a tile's last slice
-                // issues nothing, because the epilogue stages the tile in that buffer.
-                if (kt == 0) {
+                // other MFMA.  Across a tile boundary too (ACROSS): the epilogue stages the tile in the weight half of
+                // the buffer that pieces 0-5, code blocks, are landing in meanwhile.  Tiles of one or two slices keep the
+                // older order (nothing behind the tile's last slice, all twelve pieces here in its first): there a
+                // slice-2 position is where the tile draws and tile numbers are read, timed by the barriers in between.
+                if (kt == 0 && ACROSS) {
+                    auto hook = [&] __device__(auto p_c) __attribute__((always_inline)) {
+                        if constexpr (decltype(p_c)::value >= 12 && decltype(p_c)::value <= 14)
+                            issue_advance_part(I<decltype(p_c)::value - 12>{});
+                    };
+                    mfma_step(I<1>{}, f0, f1, cur_off, I<1>{}, I<DMA / 2>{}, I<DMA / 2>{}, I<1>{}, I<2>{}, hook);
+                } else if (kt == 0) {
                     auto hook = [&] __device__(auto p_c) __attribute__((always_inline)) {
                         if constexpr (decltype(p_c)::value == 0) issue_prepare(fill_off);
                         if constexpr (decltype(p_c)::value == 14) issue_advance();
@@ -456,10 +483,10 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                     fill_off = t;
                 }
             };
-            if (FP6 && kt + 1 < KT) {
+            if (FP6 && (ACROSS || kt + 1 < KT)) {
                 asm volatile("; slice barrier, loads follow\n\ts_waitcnt lgkmcnt(0)" ::: "memory");
                 __builtin_amdgcn_s_barrier();
-                // FP6 path, not the tile's last slice: the barrier has freed the buffer of slice q, which takes slice
+                // FP6 path (tiles of one or two slices: not behind the tile's last slice): the barrier has freed the buffer of slice q, which takes slice
                 // q + 3; its addresses (and, at a tile's start, the tile's vectors and the next draw) behind the first
                 // MFMA, its pieces 0-5 behind every other MFMA from the third on
                 auto early = [&] __device__(auto p_c) __attribute__((always_inline)) {
@@ -499,7 +526,9 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
         const int32_t *s_rsum = reinterpret_cast<const int32_t *>(s_tile + OFF_RSUM);
         // sum q (c - z) = acc - z * rs with a 24-bit multiply (ranges: C ABI)
         auto unzero = [] __device__(int a, int z, int rs) { return a - __mul24(z, rs); };
-        uint8_t *stg = smem + fill_off + wave * 8192;   // in the buffer of the slice consumed last (next to be filled): two areas of 4 KB
+        // staging: 4 KB per wave in the weight half of the buffer of the slice consumed last (next to be filled; on
+        // the FP6 path its code half is already being filled with the next tile's slice 2 while the epilogue runs)
+        uint8_t *stg = smem + fill_off + A_STAGE + wave * 4096;
         if (vec8 && !acc_out && m0 + BM <= M && n0 + BN <= N) {
             // ---- interior tile: no predicates; channel vectors fetched one register group ahead; the bf16 tile
             // is transposed through LDS, 32 tokens x 64 channels at a time, into whole-line streaming stores
@@ -586,11 +615,12 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                             pk[1][d] = sw[1];
                         }
                         const int piece = ii * 4 + g + fhalf;   // 16-byte piece of the 64-channel row
-                        *reinterpret_cast<uint4 *>(stg + ((U >> 3) & 1) * 4096 + frow * 128 + ((piece ^ (frow & 7)) << 4)) =
+                        *reinterpret_cast<uint4 *>(stg + frow * 128 + ((piece ^ (frow & 7)) << 4)) =
                             make_uint4(pk[0][0], pk[0][1], pk[1][0], pk[1][1]);
                     }
                     // A staged chunk is read back right away (its LDS round trip then runs under the next chunk's
-                    // arithmetic; two staging areas alternate) and stored to memory half a chunk later.
+                    // arithmetic; a wave's LDS instructions execute in order, so the next chunk's writes into the
+                    // same area stay behind these reads) and stored to memory half a chunk later.
                     if constexpr (U == 11) publish_draw();
                     if constexpr ((U & 7) == 3 && U > 8) {
 #pragma unroll
@@ -602,7 +632,7 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
                         __builtin_amdgcn_wave_barrier();
                         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                         pend_y = y + (int64_t)(m0 + wm + j * 32 + rd_row) * N + (n0 + wn + ip * 64 + rd_piece * 8);
-                        const uint8_t *sg = stg + ((U >> 3) & 1) * 4096;
+                        const uint8_t *sg = stg;
 #pragma unroll
                         for (int pass = 0; pass < 4; ++pass) {
                             const int row = pass * 8 + rd_row;
@@ -721,7 +751,7 @@ __global__ __launch_bounds__(256, 1) void w4ax_gemm_wide_kernel(
 
 namespace {
 
-template <bool FP6>
+template <bool FP6, bool ACROSS>
 int launch_wide(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale, const int8_t *w_zero,
                 const int32_t *code_rowsum, const uint16_t *bias, int M, int N, int K, uint16_t *y, int32_t *acc_out,
                 hipStream_t stream) {
@@ -734,7 +764,7 @@ int launch_wide(const uint8_t *codes, const float *x_scale, const uint8_t *w, co
     if (total < grid) grid = (total + 7) / 8 * 8;
     grid = limited_grid(grid);
     const size_t smem = (size_t)STAGES * 48 * 1024 + 3 * ((BM + BN) * 4 + BN * 2 + BM * 4 + BN) + 8 * sizeof(int);
-    auto k = w4ax_gemm_wide_kernel<FP6>;
+    auto k = w4ax_gemm_wide_kernel<FP6, ACROSS>;
     static std::atomic<uint64_t> configured{0};
     allow_dynamic_lds(reinterpret_cast<const void *>(k), smem, configured);
     bool is_clear = false;
@@ -751,11 +781,14 @@ int launch_wide(const uint8_t *codes, const float *x_scale, const uint8_t *w, co
 int launch_w4ax_gemm_wide(const uint8_t *codes, const float *x_scale, const uint8_t *w, const float *w_scale,
                           const int8_t *w_zero, const int32_t *code_rowsum, const uint16_t *bias, int64_t M, int64_t N,
                           int64_t K, bool fp6, uint16_t *y, int32_t *acc_out, hipStream_t stream) {
+    if (fp6 && K / kBK >= 3)
+        return launch_wide<true, true>(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K, y,
+                                       acc_out, stream);
     if (fp6)
-        return launch_wide<true>(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K, y, acc_out,
-                                 stream);
-    return launch_wide<false>(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K, y, acc_out,
-                              stream);
+        return launch_wide<true, false>(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K, y,
+                                        acc_out, stream);
+    return launch_wide<false, false>(codes, x_scale, w, w_scale, w_zero, code_rowsum, bias, (int)M, (int)N, (int)K, y, acc_out,
+                                     stream);
 }
 
 }  // namespace dvdq
