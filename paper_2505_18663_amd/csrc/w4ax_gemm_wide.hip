@@ -757,7 +757,22 @@ int launch_wide(const uint8_t *codes, const float *x_scale, const uint8_t *w, co
                 hipStream_t stream) {
     constexpr int BM = 256, BN = 256, STAGES = 3;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    const int n_groups = (tiles_n + 15) / 16;   // column tiles per L2 sharing group: balanced groups of at most 16
+    // Column tiles per L2 sharing group (the 32 workgroups of an XCD then work on about 32 / group_n token panels
+    // x group_n channel panels at a time, so a width near 6 pulls the fewest panels through the XCD's L2).
+    // Measured on the DiT shapes (whole layer steps): groups of 12, 18 or 20 columns cost 4-9 % against groups of
+    // 5-10; equal groups that split the columns among the 8 XCDs' tile ranges evenly (1, 2, 4 or 8 groups) are as
+    // fast as any width in that range, groups of unequal width (7, 7, 6 of 20 columns; 5, 5, 2 of 12) lose 2-5 %
+    // again; between 5 and 10 columns of 20 the time is the same and the L2 fetches differ by a fifth.  So: that
+    // many equal groups of at most 10 columns, the width nearest 6, where the column count allows it; else balanced
+    // groups of at most 16.
+    int n_groups = (tiles_n + 15) / 16;
+    for (int g = 1, best = 1 << 30; g <= 8; g *= 2) {
+        const int width = tiles_n / g, off = width > 6 ? width - 6 : 6 - width;
+        if (tiles_n % g == 0 && width <= 10 && off < best) {
+            best = off;
+            n_groups = g;
+        }
+    }
     const int group_n = (tiles_n + n_groups - 1) / n_groups;
     const int total = tiles_m * tiles_n;
     int grid = 256;
