@@ -515,19 +515,24 @@ int launch_rotate_quant(const uint16_t *x, int64_t M, int64_t K, int log2_block,
     // 0: int8; 1 / 2: packed nibbles stored per lane / gathered through LDS; 3: FP6 container
     const int pack4 = codes_format == DVDQ_CODES_FP6 ? 3 : (codes_format != DVDQ_CODES_PACKED4 ? 0 : ((K % 32) == 0 ? 2 : 1));
     const int units = (int)((K + kUnit - 1) / kUnit);
-    // waves per row: at most 3 units (24 fp32 values per lane) in registers per wave, at most 16 waves
-    // (3 rather than 4: a 13824-channel row then takes 9 waves of 3 units instead of 7 of 4, and the
-    // kernel 12 % less time; the other shapes do not care)
-    int W = (units + 2) / 3;
+    // Waves per row: at most 4 units (32 fp32 values per lane) in registers per wave, never 3 waves, whole waves
+    // per SIMD beyond 4, at most 16.  Workgroups of 8 waves, of 16 once a row takes 8 (two such rows then share a
+    // workgroup and its barrier), 16 waves resident per compute unit (256 of them), every workgroup striding over
+    // the rows.  Swept with the kernel timed where the layer runs it, between two GEMMs, over units per wave
+    // (3 .. 8) and workgroups of 8 and 16 waves, rows of 2048 .. 16384 channels, both containers: rows of 4, 8 and
+    // 16 units are 6-17 % faster as one, two and four waves of 4 units than in waves of 3 or fewer; 12 units are
+    // 4 % slower as three waves of 4 than as four of 3; a 13824-channel row (27 units) takes 225 us per launch as
+    // eight waves of 3-4 units in 16-wave workgroups, 238 in 8-wave workgroups, 252 as twelve waves of 2-3 units
+    // (an earlier state of this rule, chosen from launches timed back to back).  Resident waves (8 .. 28) and
+    // smaller workgroups stay within 2 % of this on the video-DiT shapes.
+    int W = (units + 3) / 4;
+    if (W == 3) W = 4;
     if (W > 4) W = (W + 3) / 4 * 4;   // whole waves per SIMD
     if (W > 16) W = 16;
     const int cpw = (units + W - 1) / W;
     if (cpw > 8) return DVDQ_ERR_UNSUPPORTED;
-    // workgroups of about 8 waves, about 16 waves resident per compute unit (256 of them), every workgroup
-    // striding over the rows.  Measured over 8 .. 28 resident waves and workgroups of 2, 4, 8 waves on the
-    // four video-DiT shapes: within 1.5 % of the best of each shape and container, but for int8 codes of
-    // 3072-channel rows, which would run 10 % faster with 8 resident waves.
-    const int rows_per_wg = W >= 8 ? 1 : 8 / W;
+    const int wg_waves = W >= 8 ? 16 : 8;
+    const int rows_per_wg = W >= wg_waves ? 1 : wg_waves / W;
     const dim3 block(kWave * W * rows_per_wg);
     int wgs_per_cu = 16 / (W * rows_per_wg);
     if (wgs_per_cu < 1) wgs_per_cu = 1;
